@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Benchmark of the QUIK linear layer on one MI355X.
+
+A step is one pass of the whole hot path (split + quantize, INT GEMM,
+dequantization epilogue, fp16 outlier GEMM) over one synthetic batch, through the
+C ABI (`quik_linear`, two kernel launches).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, MI355X data sheet (5.0 POP/s)
+PEAK_HBM_GBS = 8000.0
+
+
+def _event_ms(fn, iters, torch):
+    """Average duration of fn() in ms over `iters` back-to-back launches, measured with
+    HIP events recorded on the stream the kernels are launched on (torch's current one)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def cpu_baseline(inp, shp, budget_s=15.0):
+    """The oracle as it stands, on this host's cores, on a bounded sample of token rows
+    (tokens are independent, so a row sample is a faithful fraction of the workload)."""
+    import numpy as np
+    import oracle
+    rows = min(64, shp.T)
+    t0 = time.perf_counter()
+    oracle.linear(inp.x[:rows], inp.outlier_idx, shp.bits, inp.w_packed, inp.w_scale, inp.w_out)
+    probe = time.perf_counter() - t0
+    # the probe includes the per-call weight unpack; size the sample for ~budget_s
+    rows = int(max(8, min(shp.T, rows * budget_s / max(probe, 1e-3))))
+    t0 = time.perf_counter()
+    oracle.linear(inp.x[:rows], inp.outlier_idx, shp.bits, inp.w_packed, inp.w_scale, inp.w_out)
+    dt = time.perf_counter() - t0
+    tops = 2.0 * rows * shp.K * shp.N / dt / 1e12
+    return {"value": tops, "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {rows} of {shp.T} token rows x all {shp.N} outputs, "
+                      f"whole layer incl. weight unpack, {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="llama7b_up")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fp16", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU only: the layer shards over tokens with no "
+              "communication, so runs on several GPUs are not part of this build (use --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2310_09259_amd import api, synth
+
+    api.load()                      # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    shp = synth.CONFIGS[args.workload]
+    inp = synth.make_inputs(shp)
+    dev = "cuda"
+    x = torch.from_numpy(inp.x).to(dev)
+    idx = torch.from_numpy(inp.outlier_idx).to(dev) if shp.n_out else None
+    w_q = torch.from_numpy(inp.w_packed).to(dev)
+    w_scale = torch.from_numpy(inp.w_scale).to(dev)
+    w_out = torch.from_numpy(inp.w_out).to(dev) if shp.n_out else None
+    w_red = api.quik_weight_reduce(w_q, w_scale, shp.K_b, shp.bits)
+    T, K, N, K_b, n_out, bits = shp.T, shp.K, shp.N, shp.K_b, shp.n_out, shp.bits
+    ws = torch.empty(api.quik_workspace_bytes(T, K, N, n_out, bits), dtype=torch.uint8, device=dev)
+    y = torch.empty((T, N), dtype=torch.float16, device=dev)
+
+    def step():
+        api.quik_linear(x, idx, bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations (HIP events on the launch stream), same buffers
+    xq, scale, zero, x_out = api.quik_quantize(x, idx, bits)
+    q_out = (xq, scale, zero, x_out)
+    it = max(20, args.steps // 2)
+    ms_quant = _event_ms(lambda: api.quik_quantize(x, idx, bits, out=q_out), it, torch)
+    ms_gemm = _event_ms(lambda: api.quik_gemm_dequant(xq, scale, zero, x_out if n_out else None, K_b,
+                                                      bits, w_q, w_scale, w_red, w_out, out=y), it, torch)
+    ms_layer_ev = _event_ms(step, it, torch)
+
+    ms_fp16 = None
+    if not args.no_fp16:
+        wf = (torch.randn((N, K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
+        for _ in range(10):
+            torch.nn.functional.linear(x, wf)
+        ms_fp16 = _event_ms(lambda: torch.nn.functional.linear(x, wf), it, torch)
+        del wf
+
+    ops_layer = 2.0 * T * K * N
+    ops_int = 2.0 * T * K_b * N
+    tops = ops_layer / (ms_step * 1e-3) / 1e12
+    gemm_tops = ops_int / (ms_gemm * 1e-3) / 1e12
+    quant_bytes = T * (2 * K + K_b * bits // 8 + 2 * n_out + 8)
+    out = {
+        "metric": "QUIK linear TOPS (whole layer: quantize + INT4 GEMM + dequant + fp16 outliers)",
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": f"int{bits} operands on int8 MFMA, int32 accumulate, fp16 outliers",
+        "data": "synthetic",
+        "config": {"workload": f"{shp.name}: T={T} K={K} N={N} n_out={n_out} bits={bits}",
+                   "launches_per_step": 2},
+        "frac_int8_mfma_peak_layer": tops / PEAK_INT8_TOPS,
+        "speedup_vs_fp16_gemm": (ms_fp16 / ms_layer_ev) if ms_fp16 else None,
+        "fp16_gemm_ms": ms_fp16,
+        "kernels_ms": {"quik_quantize": ms_quant, "quik_gemm_dequant": ms_gemm,
+                       "quik_linear_events": ms_layer_ev},
+        "quantize_hbm": {"algorithmic_bytes": quant_bytes,
+                         "achieved_GBs": quant_bytes / (ms_quant * 1e-3) / 1e9,
+                         "frac": quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (INT GEMM + dequant + outlier GEMM)",
+                     "achieved": gemm_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": gemm_tops / PEAK_INT8_TOPS, "traffic": None,
+                     "algorithmic_ops_per_launch": ops_int},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, shp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

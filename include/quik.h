@@ -1,0 +1,186 @@
+/*
+ * quik.h -- C ABI of the MI355X (gfx950) QUIK hybrid-quantized linear layer.
+ *
+ * The library computes the forward pass of one QUIK linear layer, "QUIK Matmul"
+ * (arXiv 2310.09259, Section 3.3, Algorithm 1), for a batch of T tokens:
+ *
+ *   1. split the input columns into n_out outlier columns (kept in fp16) and
+ *      K_b = K - n_out base columns, and quantize the base part per token,
+ *      asymmetrically, to signed `bits`-bit integers in a packed format
+ *      (Algorithm 1, "split" and "Quantization");
+ *   2. multiply the packed activations with the packed, offline-quantized
+ *      weights using integer matrix cores with INT32 accumulation ("INTmatmul");
+ *   3. dequantize in the GEMM epilogue with the per-token and per-output-channel
+ *      scales and the zero-point correction of Eq. (1) ("Dequantization") and add
+ *      the fp16 product of the outlier columns ("FPmatmul", final add).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller, unless a
+ *     parameter is explicitly called "host".  The library never allocates,
+ *     frees or keeps a pointer.  `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).  Calls enqueue work on `stream` and return;
+ *     they do not synchronize.
+ *   - Matrices are row-major.  Leading dimensions ("ld...") are row strides, in
+ *     ELEMENTS for fp16 / int32 matrices and in BYTES for packed integer
+ *     matrices.
+ *   - Packed integers: bits = 4 stores two two's-complement nibbles per byte,
+ *     element 2p in bits 0..3 and element 2p+1 in bits 4..7 of byte p; bits = 8
+ *     stores one signed byte per element.  Quantized activations lie in
+ *     [-2^(bits-1), 2^(bits-1) - 1], weights likewise.
+ *   - Base columns keep their ascending original order; outlier column j of
+ *     x_out and w_out corresponds to input column outlier_idx[j].
+ *   - Return value: QUIK_OK (0) or a negative quik_status.  When an error is
+ *     returned nothing has been enqueued.  Arguments are validated on the host;
+ *     the contents of device buffers (for example the index list) are not, but
+ *     no index value can make a kernel access memory outside the buffers
+ *     described here: out-of-range or repeated indices only give unspecified
+ *     VALUES.
+ *   - Limits: bits in {4, 8}; K, ldx multiples of 8; n_out a multiple of 8,
+ *     0 <= n_out < K; K_b * bits a multiple of 8; K <= 32768; all input base
+ *     pointers 16-byte aligned; ldq, ldw multiples of 16 bytes; ldo, ldwo
+ *     multiples of 8 elements; y and ldy are unconstrained (ldy >= N).
+ *   - Thread safety: no global mutable state; calls on different streams are
+ *     independent.
+ */
+#ifndef QUIK_H_
+#define QUIK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QUIK_OK = 0,
+    QUIK_EINVAL = -1,       /* a size or flag is out of range or inconsistent      */
+    QUIK_ENULL = -2,        /* a required pointer is NULL                           */
+    QUIK_EALIGN = -3,       /* a pointer or leading dimension is not aligned        */
+    QUIK_EUNSUPPORTED = -4, /* valid in the paper's terms, not built here           */
+    QUIK_EWORKSPACE = -5,   /* workspace too small                                  */
+    QUIK_ELAUNCH = -6       /* the HIP runtime refused a launch                     */
+} quik_status;
+
+/* Library version (monotonic integer). */
+int quik_version(void);
+
+/* Static, human-readable name of a status code. */
+const char *quik_status_string(int status);
+
+/*
+ * Canonical row stride in bytes of a packed matrix with K_b elements per row:
+ * K_b * bits / 8 rounded up to a multiple of 16.  Returns 0 on invalid input.
+ */
+int quik_packed_row_bytes(int K_b, int bits);
+
+/*
+ * Bytes of device workspace quik_linear needs for a [T, K] input with n_out
+ * outlier columns: packed activations [T, quik_packed_row_bytes], per-token
+ * scale and zero (fp32 each) and the fp16 outlier block [T, n_out], each region
+ * aligned to 256 bytes.  Returns 0 on invalid input.  N is accepted for
+ * symmetry and does not change the result.
+ */
+size_t quik_workspace_bytes(int T, int K, int N, int n_out, int bits);
+
+/*
+ * Fused split + per-token asymmetric quantization (Algorithm 1, "split" and
+ * function "Quantization"; fusion as in Section 3.4, "Quantization Fusion").
+ *
+ * For every token t: zero[t] = min and scale[t] = (max - min) / (2^bits - 1)
+ * over the BASE columns only (scale = 1 for a constant row); every base element
+ * becomes q = clamp(rne((x - zero) * (1 / scale)), 0, 2^bits - 1) - 2^(bits-1),
+ * evaluated in IEEE binary32 with a once-per-token correctly rounded reciprocal,
+ * and is stored packed; outlier columns are copied bit for bit to x_out.
+ *
+ *   x            in   fp16 [T, ldx], ldx >= K
+ *   outlier_idx  in   int32 [n_out], unique, in [0, K); may be NULL if n_out = 0
+ *   xq           out  packed [T, ldq bytes], ldq >= K_b*bits/8; bytes of each row
+ *                     past the packed data up to ldq are written as zero
+ *   scale, zero  out  fp32 [T]
+ *   x_out        out  fp16 [T, ldo], ldo >= n_out; may be NULL if n_out = 0
+ */
+int quik_quantize(const void *x, int T, int K, int ldx,
+                  const int32_t *outlier_idx, int n_out, int bits,
+                  void *xq, int ldq, float *scale, float *zero,
+                  void *x_out, int ldo, void *stream);
+
+/*
+ * wReduced (Section 3.3, text after Eq. (1)): the static per-output-channel
+ * term of the zero-point correction,
+ *   w_reduced[n] = float(w_scale[n]) * float(sum_k w_q[n, k]),  k < K_b.
+ * Offline preparation, not part of the timed path.
+ *
+ *   w_q        in   packed [N, ldw bytes]
+ *   w_scale    in   fp16 [N]
+ *   w_reduced  out  fp32 [N]
+ */
+int quik_weight_reduce(const void *w_q, int ldw, const void *w_scale,
+                       int N, int K_b, int bits, float *w_reduced, void *stream);
+
+/*
+ * Integer GEMM + dequantization epilogue + outlier GEMM (Algorithm 1,
+ * "INTmatmul", function "Dequantization", "FPmatmul" and the final add; the
+ * epilogue fusion of Section 3.4):
+ *
+ *   acc[t,n] = sum_{k<K_b} xq[t,k] * w_q[n,k]                       (INT32, exact)
+ *   y[t,n]   = acc * scale[t] * w_scale[n]
+ *            + (zero[t] + 2^(bits-1) * scale[t]) * w_reduced[n]
+ *            + sum_{j<n_out} x_out[t,j] * w_out[n,j]  (+ bias[n])   -> fp16
+ *
+ * Floating point is binary32 with fp16 inputs to the outlier product; y is
+ * rounded once to fp16.
+ *
+ *   xq       in  packed [T, ldq bytes]; bytes of a row between K_b*bits/8 and
+ *                ldq MUST be zero (quik_quantize writes them so)
+ *   scale, zero  in  fp32 [T]
+ *   x_out    in  fp16 [T, ldo]        (ignored if n_out = 0, may be NULL)
+ *   w_q      in  packed [N, ldw bytes]; pad bytes may hold anything
+ *   w_scale  in  fp16 [N];  w_reduced in fp32 [N]
+ *   w_out    in  fp16 [N, ldwo]       (ignored if n_out = 0, may be NULL)
+ *   bias     in  fp16 [N] or NULL
+ *   y        out fp16 [T, ldy], ldy >= N
+ * K_b must be below 131072 (INT32 headroom of the 4-bit path).
+ */
+int quik_gemm_dequant(const void *xq, int ldq, const float *scale, const float *zero,
+                      const void *x_out, int ldo, int T, int K_b, int n_out, int bits,
+                      const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
+                      const void *w_out, int ldwo, const void *bias, int N,
+                      void *y, int ldy, void *stream);
+
+/*
+ * Test hook: the same integer K-loop as quik_gemm_dequant, writing the exact
+ * INT32 accumulators instead of running the epilogue ("INTmatmul" alone).
+ *   acc  out  int32 [T, ldacc], ldacc >= N
+ */
+int quik_int_gemm(const void *xq, int ldq, const void *w_q, int ldw,
+                  int T, int N, int K_b, int bits, int32_t *acc, int ldacc, void *stream);
+
+/*
+ * The whole layer: quik_quantize into `workspace`, then quik_gemm_dequant
+ * (Algorithm 1, "QUIK Matmul").  Two kernel launches on `stream`.
+ *
+ *   x            in   fp16 [T, ldx]
+ *   outlier_idx  in   int32 [n_out]
+ *   w_q, w_scale, w_reduced, w_out, bias: as in quik_gemm_dequant
+ *   y            out  fp16 [T, ldy]
+ *   workspace    device scratch of at least quik_workspace_bytes(...) bytes,
+ *                256-byte aligned; contents after the call: packed activations,
+ *                scale, zero, x_out (layout private to the library)
+ */
+int quik_linear(const void *x, int T, int K, int ldx,
+                const int32_t *outlier_idx, int n_out, int bits,
+                const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
+                const void *w_out, int ldwo, const void *bias, int N,
+                void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Host-side validator for an outlier index list (HOST pointer): returns QUIK_OK
+ * if all n_out entries are unique and inside [0, K), QUIK_EINVAL otherwise.
+ */
+int quik_check_outlier_idx_host(const int32_t *outlier_idx_host, int n_out, int K);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUIK_H_ */

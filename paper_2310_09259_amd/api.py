@@ -1,0 +1,188 @@
+"""Thin Python binding of the C ABI in include/quik.h (argument marshalling only).
+
+torch is used for device memory and for the current HIP stream; every step of
+the layer runs in the library's own kernels.  There is no CPU fallback: if the
+shared library is missing, loading it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libquik.so")
+
+_lib = None
+
+
+class QuikError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def load() -> C.CDLL:
+    """Load libquik.so (built in-tree by paper_2310_09259_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2310_09259_amd.build` "
+                "(there is no fallback path)")
+        lib = C.CDLL(LIB_PATH)
+        vp, i, f = C.c_void_p, C.c_int, C.c_void_p
+        lib.quik_version.restype = i
+        lib.quik_status_string.restype = C.c_char_p
+        lib.quik_status_string.argtypes = [i]
+        lib.quik_packed_row_bytes.restype = i
+        lib.quik_packed_row_bytes.argtypes = [i, i]
+        lib.quik_workspace_bytes.restype = C.c_size_t
+        lib.quik_workspace_bytes.argtypes = [i, i, i, i, i]
+        lib.quik_quantize.restype = i
+        lib.quik_quantize.argtypes = [vp, i, i, i, vp, i, i, vp, i, f, f, vp, i, vp]
+        lib.quik_weight_reduce.restype = i
+        lib.quik_weight_reduce.argtypes = [vp, i, vp, i, i, i, f, vp]
+        lib.quik_gemm_dequant.restype = i
+        lib.quik_gemm_dequant.argtypes = [vp, i, f, f, vp, i, i, i, i, i, vp, i, vp, f, vp, i, vp, i,
+                                          vp, i, vp]
+        lib.quik_int_gemm.restype = i
+        lib.quik_int_gemm.argtypes = [vp, i, vp, i, i, i, i, i, vp, i, vp]
+        lib.quik_linear.restype = i
+        lib.quik_linear.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
+                                    C.c_size_t, vp]
+        lib.quik_check_outlier_idx_host.restype = i
+        lib.quik_check_outlier_idx_host.argtypes = [vp, i, i]
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise QuikError(rc, where)
+
+
+def _dev(t, dtype, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if t.dim() > 1 and t.stride(-1) != 1:
+        raise ValueError(f"{name} must be contiguous along its last dimension")
+    return t
+
+
+def quik_version() -> int:
+    return load().quik_version()
+
+
+def status_string(status: int) -> str:
+    return load().quik_status_string(status).decode()
+
+
+def quik_packed_row_bytes(K_b: int, bits: int) -> int:
+    return load().quik_packed_row_bytes(K_b, bits)
+
+
+def quik_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int) -> int:
+    return load().quik_workspace_bytes(T, K, N, n_out, bits)
+
+
+def quik_check_outlier_idx_host(idx_host, K: int) -> int:
+    import numpy as np
+    a = np.ascontiguousarray(idx_host, dtype=np.int32)
+    return load().quik_check_outlier_idx_host(a.ctypes.data_as(C.c_void_p), int(a.size), K)
+
+
+def quik_quantize(x, outlier_idx, bits: int, out=None):
+    """x fp16 [T,K] -> (xq uint8 [T,ldq], scale f32 [T], zero f32 [T], x_out f16 [T,n_out])."""
+    x = _dev(x, torch.float16, "x")
+    T, K = x.shape
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    if n_out:
+        _dev(outlier_idx, torch.int32, "outlier_idx")
+    K_b = K - n_out
+    ldq = quik_packed_row_bytes(K_b, bits)
+    if ldq <= 0:
+        raise QuikError(-1, "quik_packed_row_bytes")
+    if out is None:
+        xq = torch.empty((T, ldq), dtype=torch.uint8, device=x.device)
+        scale = torch.empty(T, dtype=torch.float32, device=x.device)
+        zero = torch.empty(T, dtype=torch.float32, device=x.device)
+        x_out = torch.empty((T, n_out), dtype=torch.float16, device=x.device)
+    else:
+        xq, scale, zero, x_out = out
+    rc = load().quik_quantize(_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out,
+                              bits, _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero),
+                              _ptr(x_out) if n_out else None, x_out.stride(0) if n_out else 0,
+                              _stream())
+    _check(rc, "quik_quantize")
+    return xq, scale, zero, x_out
+
+
+def quik_weight_reduce(w_q, w_scale, K_b: int, bits: int):
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    w_scale = _dev(w_scale, torch.float16, "w_scale")
+    N = w_q.shape[0]
+    out = torch.empty(N, dtype=torch.float32, device=w_q.device)
+    rc = load().quik_weight_reduce(_ptr(w_q), w_q.stride(0), _ptr(w_scale), N, K_b, bits, _ptr(out),
+                                   _stream())
+    _check(rc, "quik_weight_reduce")
+    return out
+
+
+def quik_gemm_dequant(xq, scale, zero, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced, w_out,
+                      bias=None, out=None):
+    xq = _dev(xq, torch.uint8, "xq")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, N = xq.shape[0], w_q.shape[0]
+    n_out = 0 if x_out is None else int(x_out.shape[1])
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=xq.device)
+    rc = load().quik_gemm_dequant(
+        _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
+        x_out.stride(0) if n_out else 0, T, K_b, n_out, bits, _ptr(w_q), w_q.stride(0), _ptr(w_scale),
+        _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias),
+        N, _ptr(y), y.stride(0), _stream())
+    _check(rc, "quik_gemm_dequant")
+    return y
+
+
+def quik_int_gemm(xq, w_q, K_b: int, bits: int):
+    xq = _dev(xq, torch.uint8, "xq")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, N = xq.shape[0], w_q.shape[0]
+    acc = torch.empty((T, N), dtype=torch.int32, device=xq.device)
+    rc = load().quik_int_gemm(_ptr(xq), xq.stride(0), _ptr(w_q), w_q.stride(0), T, N, K_b, bits,
+                              _ptr(acc), acc.stride(0), _stream())
+    _check(rc, "quik_int_gemm")
+    return acc
+
+
+def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, bias=None, out=None,
+                workspace=None):
+    """Whole layer.  Returns y fp16 [T, N]."""
+    x = _dev(x, torch.float16, "x")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, K = x.shape
+    N = w_q.shape[0]
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    need = quik_workspace_bytes(T, K, N, n_out, bits)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
+    rc = load().quik_linear(
+        _ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(w_q),
+        w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None,
+        w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
+        workspace.numel(), _stream())
+    _check(rc, "quik_linear")
+    return y

@@ -1,0 +1,202 @@
+// C ABI of the library: argument validation and kernel dispatch.  See include/quik.h
+// for the contract of every entry point.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "quik.h"
+#include "quik_kernels.h"
+
+namespace {
+
+constexpr int kMaxK = 32768;
+constexpr int kMaxKb = 131072;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t up256(size_t v) { return (v + 255u) & ~size_t(255); }
+
+struct WorkspaceLayout {
+    size_t xq, scale, zero, x_out, total;
+    int ldq;
+};
+
+bool workspace_layout(int T, int K, int n_out, int bits, WorkspaceLayout* w) {
+    if (T <= 0 || K <= 0 || n_out < 0 || n_out >= K || (bits != 4 && bits != 8)) return false;
+    int ldq = quik_packed_row_bytes(K - n_out, bits);
+    if (ldq <= 0) return false;
+    w->ldq = ldq;
+    w->xq = 0;
+    w->scale = up256((size_t)T * ldq);
+    w->zero = w->scale + up256((size_t)T * sizeof(float));
+    w->x_out = w->zero + up256((size_t)T * sizeof(float));
+    w->total = w->x_out + up256((size_t)T * (n_out ? n_out : 1) * 2);
+    return true;
+}
+
+int check_quantize(const void* x, int T, int K, int ldx, const int32_t* idx, int n_out, int bits,
+                   void* xq, int ldq, float* scale, float* zero, void* x_out, int ldo) {
+    if (bits != 4 && bits != 8) return QUIK_EINVAL;
+    if (T <= 0 || K <= 0 || n_out < 0 || n_out >= K || ldx < K) return QUIK_EINVAL;
+    const int K_b = K - n_out;
+    if ((K_b * bits) % 8) return QUIK_EINVAL;
+    if (ldq < K_b * bits / 8) return QUIK_EINVAL;
+    if (n_out > 0 && ldo < n_out) return QUIK_EINVAL;
+    if (!x || !xq || !scale || !zero) return QUIK_ENULL;
+    if (n_out > 0 && (!idx || !x_out)) return QUIK_ENULL;
+    if (K > kMaxK) return QUIK_EUNSUPPORTED;
+    if (K % 8 || n_out % 8) return QUIK_EUNSUPPORTED;
+    if (ldx % 8 || ldq % 16 || (n_out > 0 && ldo % 8)) return QUIK_EALIGN;
+    if (!aligned16(x) || !aligned16(xq) || (n_out > 0 && !aligned16(x_out))) return QUIK_EALIGN;
+    if ((reinterpret_cast<uintptr_t>(scale) & 3u) || (reinterpret_cast<uintptr_t>(zero) & 3u))
+        return QUIK_EALIGN;
+    return QUIK_OK;
+}
+
+int check_gemm(const void* xq, int ldq, const void* x_out, int ldo, int T, int K_b, int n_out,
+               int bits, const void* w_q, int ldw, const void* w_out, int ldwo, int N) {
+    if (bits != 4 && bits != 8) return QUIK_EINVAL;
+    if (T <= 0 || N <= 0 || K_b <= 0 || n_out < 0) return QUIK_EINVAL;
+    if ((K_b * bits) % 8) return QUIK_EINVAL;
+    const int row_bytes = K_b * bits / 8;
+    if (ldq < row_bytes || ldw < row_bytes) return QUIK_EINVAL;
+    if (n_out > 0 && (ldo < n_out || ldwo < n_out)) return QUIK_EINVAL;
+    if (!xq || !w_q) return QUIK_ENULL;
+    if (n_out > 0 && (!x_out || !w_out)) return QUIK_ENULL;
+    if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
+    if (n_out % 8) return QUIK_EUNSUPPORTED;
+    if (ldq % 16 || ldw % 16) return QUIK_EALIGN;
+    if (n_out > 0 && (ldo % 8 || ldwo % 8)) return QUIK_EALIGN;
+    if (!aligned16(xq) || !aligned16(w_q)) return QUIK_EALIGN;
+    if (n_out > 0 && (!aligned16(x_out) || !aligned16(w_out))) return QUIK_EALIGN;
+    return QUIK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int quik_version(void) { return 1; }
+
+const char* quik_status_string(int status) {
+    switch (status) {
+        case QUIK_OK: return "QUIK_OK";
+        case QUIK_EINVAL: return "QUIK_EINVAL: size or flag out of range";
+        case QUIK_ENULL: return "QUIK_ENULL: required pointer is NULL";
+        case QUIK_EALIGN: return "QUIK_EALIGN: pointer or leading dimension misaligned";
+        case QUIK_EUNSUPPORTED: return "QUIK_EUNSUPPORTED: shape outside the built limits";
+        case QUIK_EWORKSPACE: return "QUIK_EWORKSPACE: workspace too small";
+        case QUIK_ELAUNCH: return "QUIK_ELAUNCH: HIP launch failed";
+        default: return "unknown quik status";
+    }
+}
+
+int quik_packed_row_bytes(int K_b, int bits) {
+    if (K_b <= 0 || (bits != 4 && bits != 8) || K_b >= kMaxKb) return 0;
+    if ((K_b * bits) % 8) return 0;
+    return ((K_b * bits / 8) + 15) & ~15;
+}
+
+size_t quik_workspace_bytes(int T, int K, int N, int n_out, int bits) {
+    (void)N;
+    WorkspaceLayout w;
+    if (!workspace_layout(T, K, n_out, bits, &w)) return 0;
+    return w.total;
+}
+
+int quik_quantize(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out,
+                  int bits, void* xq, int ldq, float* scale, float* zero, void* x_out, int ldo,
+                  void* stream) {
+    int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo);
+    if (rc != QUIK_OK) return rc;
+    quik::QuantizeArgs a{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo};
+    return quik::launch_quantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
+                                                                                   : QUIK_ELAUNCH;
+}
+
+int quik_weight_reduce(const void* w_q, int ldw, const void* w_scale, int N, int K_b, int bits,
+                       float* w_reduced, void* stream) {
+    if (bits != 4 && bits != 8) return QUIK_EINVAL;
+    if (N <= 0 || K_b <= 0 || (K_b * bits) % 8 || ldw < K_b * bits / 8) return QUIK_EINVAL;
+    if (!w_q || !w_scale || !w_reduced) return QUIK_ENULL;
+    if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
+    quik::WeightReduceArgs a{w_q, ldw, w_scale, N, K_b, bits, w_reduced};
+    return quik::launch_weight_reduce(a, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUIK_OK
+               : QUIK_ELAUNCH;
+}
+
+int quik_gemm_dequant(const void* xq, int ldq, const float* scale, const float* zero,
+                      const void* x_out, int ldo, int T, int K_b, int n_out, int bits,
+                      const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
+                      const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy,
+                      void* stream) {
+    int rc = check_gemm(xq, ldq, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_out, ldwo, N);
+    if (rc != QUIK_OK) return rc;
+    if (ldy < N) return QUIK_EINVAL;
+    if (!scale || !zero || !w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    quik::GemmArgs a{};
+    a.xq = xq; a.ldq = ldq; a.scale = scale; a.zero = zero; a.x_out = x_out; a.ldo = ldo;
+    a.T = T; a.K_b = K_b; a.n_out = n_out; a.bits = bits;
+    a.w_q = w_q; a.ldw = ldw; a.w_scale = w_scale; a.w_reduced = w_reduced;
+    a.w_out = w_out; a.ldwo = ldwo; a.bias = bias; a.N = N;
+    a.y = y; a.ldy = ldy; a.acc = nullptr; a.ldacc = 0;
+    return quik::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
+                                                                               : QUIK_ELAUNCH;
+}
+
+int quik_int_gemm(const void* xq, int ldq, const void* w_q, int ldw, int T, int N, int K_b,
+                  int bits, int32_t* acc, int ldacc, void* stream) {
+    int rc = check_gemm(xq, ldq, nullptr, 0, T, K_b, 0, bits, w_q, ldw, nullptr, 0, N);
+    if (rc != QUIK_OK) return rc;
+    if (ldacc < N) return QUIK_EINVAL;
+    if (!acc) return QUIK_ENULL;
+    quik::GemmArgs a{};
+    a.xq = xq; a.ldq = ldq; a.T = T; a.K_b = K_b; a.n_out = 0; a.bits = bits;
+    a.w_q = w_q; a.ldw = ldw; a.N = N; a.y = nullptr; a.acc = acc; a.ldacc = ldacc;
+    return quik::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
+                                                                               : QUIK_ELAUNCH;
+}
+
+int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out,
+                int bits, const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
+                const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy,
+                void* workspace, size_t workspace_bytes, void* stream) {
+    WorkspaceLayout w;
+    if (!workspace_layout(T, K, n_out, bits, &w)) return QUIK_EINVAL;
+    if (!workspace) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUIK_EALIGN;
+    if (workspace_bytes < w.total) return QUIK_EWORKSPACE;
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    void* xq = base + w.xq;
+    float* scale = reinterpret_cast<float*>(base + w.scale);
+    float* zero = reinterpret_cast<float*>(base + w.zero);
+    void* x_out = base + w.x_out;
+    const int K_b = K - n_out;
+    // validate both stages before anything is enqueued
+    int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, w.ldq, scale, zero, x_out, n_out);
+    if (rc != QUIK_OK) return rc;
+    rc = check_gemm(xq, w.ldq, x_out, n_out, T, K_b, n_out, bits, w_q, ldw, w_out, ldwo, N);
+    if (rc != QUIK_OK) return rc;
+    if (ldy < N) return QUIK_EINVAL;
+    if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, w.ldq, scale, zero, x_out, n_out, stream);
+    if (rc != QUIK_OK) return rc;
+    return quik_gemm_dequant(xq, w.ldq, scale, zero, x_out, n_out, T, K_b, n_out, bits, w_q, ldw,
+                             w_scale, w_reduced, w_out, ldwo, bias, N, y, ldy, stream);
+}
+
+int quik_check_outlier_idx_host(const int32_t* idx, int n_out, int K) {
+    if (n_out < 0 || K <= 0 || n_out >= K) return QUIK_EINVAL;
+    if (n_out > 0 && !idx) return QUIK_ENULL;
+    std::vector<bool> seen((size_t)K, false);
+    for (int j = 0; j < n_out; ++j) {
+        if (idx[j] < 0 || idx[j] >= K || seen[idx[j]]) return QUIK_EINVAL;
+        seen[idx[j]] = true;
+    }
+    return QUIK_OK;
+}
+
+}  // extern "C"

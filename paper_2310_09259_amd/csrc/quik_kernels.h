@@ -1,0 +1,56 @@
+// Internal launch interfaces between the C ABI (quik_api.hip) and the kernels.
+// Everything here is private to the shared library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace quik {
+
+struct QuantizeArgs {
+    const void* x;        // fp16 [T, ldx]
+    int T, K, ldx;
+    const int32_t* idx;   // [n_out]
+    int n_out, bits;
+    void* xq;             // packed [T, ldq bytes]
+    int ldq;
+    float* scale;         // [T]
+    float* zero;          // [T]
+    void* x_out;          // fp16 [T, ldo]
+    int ldo;
+};
+
+struct GemmArgs {
+    const void* xq;       // packed [T, ldq bytes]
+    int ldq;
+    const float* scale;   // [T]
+    const float* zero;    // [T]
+    const void* x_out;    // fp16 [T, ldo]
+    int ldo;
+    int T, K_b, n_out, bits;
+    const void* w_q;      // packed [N, ldw bytes]
+    int ldw;
+    const void* w_scale;  // fp16 [N]
+    const float* w_reduced;
+    const void* w_out;    // fp16 [N, ldwo]
+    int ldwo;
+    const void* bias;     // fp16 [N] or null
+    int N;
+    void* y;              // fp16 [T, ldy]   (epilogue mode)
+    int ldy;
+    int32_t* acc;         // int32 [T, ldacc] (raw-accumulator mode, y == null)
+    int ldacc;
+};
+
+struct WeightReduceArgs {
+    const void* w_q;
+    int ldw;
+    const void* w_scale;
+    int N, K_b, bits;
+    float* w_reduced;
+};
+
+hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
+
+}  // namespace quik

@@ -1,0 +1,303 @@
+// Fused split + per-token quantization kernel for gfx950 (Algorithm 1, "split" and
+// "Quantization"; fusion as in Section 3.4 of arXiv 2310.09259).
+//
+// One group of TPR threads owns one token row.  The row is read from HBM exactly
+// once with 128-bit loads and kept in registers; the three passes of the paper's
+// fused kernel (min/max over the non-outlier elements, quantization of the
+// non-outliers, moving the outliers) all run from those registers or from cache.
+//
+// Outlier columns are described by a bitmask over the K columns plus an exclusive
+// prefix count per 32-column word, both built once per workgroup in LDS.  A thread
+// that holds columns [k0, k0+8) derives from them which of its elements are base
+// columns and the position of its first base element in the packed output row.
+// Its (at most 8) quantized codes are squeezed into one 32/64-bit value and OR-ed
+// into an LDS image of the packed row at an arbitrary bit offset, so the packed
+// row leaves the CU as full, aligned 128-bit stores.
+//
+// Bit exactness: binary32 arithmetic, one IEEE division and one IEEE reciprocal
+// per row, a subtract and a multiply per element (never contracted), v_rndne.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "quik_kernels.h"
+
+namespace quik {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+union Chunk {          // 8 fp16 values = one 128-bit load
+    uint4 u;
+    __half h[8];
+};
+
+// Builds mask[w] (bit b set <=> column 32w+b is an outlier) and pre[w] (number of
+// outlier columns below 32w) for w < nwords.  Indices outside [0, K) are ignored.
+__device__ void build_outlier_map(const int32_t* __restrict__ idx, int n_out, int K, int nwords,
+                                  uint32_t* mask, uint32_t* pre, uint32_t* wave_tot) {
+    const int tid = threadIdx.x;
+    for (int w = tid; w < nwords; w += kBlock) mask[w] = 0u;
+    __syncthreads();
+    for (int j = tid; j < n_out; j += kBlock) {
+        int c = idx[j];
+        if (c >= 0 && c < K) atomicOr(&mask[c >> 5], 1u << (c & 31));
+    }
+    __syncthreads();
+    // exclusive scan of popcounts; each thread owns `per` consecutive words
+    const int per = (nwords + kBlock - 1) / kBlock;
+    const int w0 = tid * per;
+    uint32_t local = 0;
+    for (int i = 0; i < per; ++i)
+        if (w0 + i < nwords) local += __popc(mask[w0 + i]);
+    uint32_t incl = local;
+    const int lane = tid & 63, wv = tid >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t n = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += n;
+    }
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    uint32_t offs = 0;
+    for (int i = 0; i < wv; ++i) offs += wave_tot[i];
+    uint32_t run = offs + incl - local;
+    for (int i = 0; i < per; ++i)
+        if (w0 + i < nwords) {
+            pre[w0 + i] = run;
+            run += __popc(mask[w0 + i]);
+        }
+    __syncthreads();
+}
+
+template <int BITS>
+__device__ __forceinline__ int quantize_one(__half h, float mn, float inv) {
+    constexpr float kL = (float)((1 << BITS) - 1);
+    float d = __half2float(h) - mn;
+    float u = d * inv;
+    float r = __builtin_rintf(u);
+    r = fminf(fmaxf(r, 0.0f), kL);
+    return (int)r - (1 << (BITS - 1));
+}
+
+// Squeezes the base elements of one chunk together and ORs them into the LDS row
+// image at element position base0.  Elements at positions >= K_b are dropped.
+template <int BITS>
+__device__ __forceinline__ void emit_chunk(const Chunk& c, uint32_t m8, int base0, int K_b,
+                                           float mn, float inv, uint32_t* stage) {
+    if (base0 >= K_b) return;
+    int room = K_b - base0;                       // >= 1
+    if constexpr (BITS == 4) {
+        uint32_t w = 0;
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t q = (uint32_t)quantize_one<4>(c.h[i], mn, inv) & 0xFu;
+            bool keep = !((m8 >> i) & 1u);
+            w |= keep ? (q << (4 * cnt)) : 0u;
+            cnt += keep ? 1 : 0;
+        }
+        if (room < 8) w &= (1u << (4 * room)) - 1u;
+        uint32_t bit = (uint32_t)base0 * 4u;
+        uint32_t wi = bit >> 5, sh = bit & 31u;
+        uint32_t lo = w << sh;
+        uint32_t hi = sh ? (w >> (32u - sh)) : 0u;
+        if (lo) atomicOr(&stage[wi], lo);
+        if (hi) atomicOr(&stage[wi + 1], hi);
+    } else {
+        uint64_t w = 0;
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint64_t q = (uint64_t)((uint32_t)quantize_one<8>(c.h[i], mn, inv) & 0xFFu);
+            bool keep = !((m8 >> i) & 1u);
+            w |= keep ? (q << (8 * cnt)) : 0ull;
+            cnt += keep ? 1 : 0;
+        }
+        if (room < 8) w &= (1ull << (8 * room)) - 1ull;
+        uint32_t bit = (uint32_t)base0 * 8u;
+        uint32_t wi = bit >> 5, sh = bit & 31u;
+        uint64_t lo64 = w << sh;
+        uint32_t p0 = (uint32_t)lo64, p1 = (uint32_t)(lo64 >> 32);
+        uint32_t p2 = sh ? (uint32_t)(w >> (64u - sh)) : 0u;
+        if (p0) atomicOr(&stage[wi], p0);
+        if (p1) atomicOr(&stage[wi + 1], p1);
+        if (p2) atomicOr(&stage[wi + 2], p2);
+    }
+}
+
+// NCH > 0: the row is cached in NCH 128-bit registers per thread (K <= TPR*8*NCH).
+// NCH == 0: any K; the second pass re-reads the row (from cache).
+template <int BITS, int TPR, int NCH>
+__global__ __launch_bounds__(kBlock) void quantize_kernel(
+    const __half* __restrict__ x, int T, int K, int ldx, const int32_t* __restrict__ idx, int n_out,
+    uint8_t* __restrict__ xq, int ldq, float* __restrict__ scale, float* __restrict__ zero,
+    __half* __restrict__ x_out, int ldo) {
+    constexpr int RPB = kBlock / TPR;             // rows per workgroup iteration
+    extern __shared__ __align__(16) uint32_t lds[];
+    const int nwords = (K + 31) >> 5;
+    uint32_t* mask = lds;
+    uint32_t* pre = mask + nwords;
+    float* red = reinterpret_cast<float*>(pre + nwords);       // [2 * 4] wave partials
+    uint32_t* wave_tot = reinterpret_cast<uint32_t*>(red + 8); // [4]
+    uint32_t* stage_all = wave_tot + 4;                        // RPB rows of ldq bytes
+    // keep the row images 16-byte aligned
+    stage_all = reinterpret_cast<uint32_t*>((reinterpret_cast<uintptr_t>(stage_all) + 15) & ~(uintptr_t)15);
+
+    build_outlier_map(idx, n_out, K, nwords, mask, pre, wave_tot);
+
+    const int tid = threadIdx.x;
+    const int g = tid / TPR, lt = tid % TPR;
+    const int K_b = K - n_out;
+    const int ldq_words = ldq >> 2;
+    uint32_t* stage = stage_all + (size_t)g * ldq_words;
+    const int nrowblk = (T + RPB - 1) / RPB;
+    const int nch_rt = (K + TPR * 8 - 1) / (TPR * 8);          // chunks per thread (runtime form)
+
+    for (int rb = blockIdx.x; rb < nrowblk; rb += gridDim.x) {
+        const int t = rb * RPB + g;
+        const bool valid = t < T;
+        const __half* row = x + (size_t)(valid ? t : 0) * ldx;
+
+        for (int i = lt; i < ldq_words; i += TPR) stage[i] = 0u;
+
+        // ---- pass 1: load once, min/max over base columns
+        float mn = __builtin_inff(), mx = -__builtin_inff();
+        Chunk cache[NCH > 0 ? NCH : 1];
+        auto scan_chunk = [&](const Chunk& c, int k0) {
+            uint32_t m8 = (mask[k0 >> 5] >> (k0 & 31)) & 0xFFu;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float f = __half2float(c.h[i]);
+                bool keep = !((m8 >> i) & 1u);
+                mn = keep ? fminf(mn, f) : mn;
+                mx = keep ? fmaxf(mx, f) : mx;
+            }
+        };
+        if constexpr (NCH > 0) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                int k0 = (c * TPR + lt) * 8;
+                if (valid && k0 < K) {
+                    cache[c].u = *reinterpret_cast<const uint4*>(row + k0);
+                } else {
+                    cache[c].u = make_uint4(0, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                int k0 = (c * TPR + lt) * 8;
+                if (valid && k0 < K) scan_chunk(cache[c], k0);
+            }
+        } else {
+            for (int c = 0; c < nch_rt; ++c) {
+                int k0 = (c * TPR + lt) * 8;
+                if (valid && k0 < K) {
+                    Chunk ch;
+                    ch.u = *reinterpret_cast<const uint4*>(row + k0);
+                    scan_chunk(ch, k0);
+                }
+            }
+        }
+        mn = wave_min(mn);
+        mx = wave_max(mx);
+        if constexpr (TPR > 64) {
+            const int wv = tid >> 6;
+            if ((tid & 63) == 0) { red[wv] = mn; red[4 + wv] = mx; }
+            __syncthreads();
+            mn = fminf(fminf(red[0], red[1]), fminf(red[2], red[3]));
+            mx = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+        } else {
+            __syncthreads();                       // row image zeroed by all lanes
+        }
+        mn = mn + 0.0f;                            // -0 -> +0
+        const float range = mx - mn;
+        const float s = (range == 0.0f) ? 1.0f : range / (float)((1 << BITS) - 1);
+        const float inv = 1.0f / s;
+        if (valid && lt == 0) { scale[t] = s; zero[t] = mn; }
+
+        // ---- pass 2: quantize the base elements into the LDS row image
+        auto quant_chunk = [&](const Chunk& c, int k0) {
+            uint32_t word = mask[k0 >> 5];
+            uint32_t below = pre[k0 >> 5] + __popc(word & ((1u << (k0 & 31)) - 1u));
+            uint32_t m8 = (word >> (k0 & 31)) & 0xFFu;
+            emit_chunk<BITS>(c, m8, k0 - (int)below, K_b, mn, inv, stage);
+        };
+        if constexpr (NCH > 0) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                int k0 = (c * TPR + lt) * 8;
+                if (valid && k0 < K) quant_chunk(cache[c], k0);
+            }
+        } else {
+            for (int c = 0; c < nch_rt; ++c) {
+                int k0 = (c * TPR + lt) * 8;
+                if (valid && k0 < K) {
+                    Chunk ch;
+                    ch.u = *reinterpret_cast<const uint4*>(row + k0);
+                    quant_chunk(ch, k0);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- write the packed row (including its zero padding up to ldq)
+        if (valid) {
+            uint4* dst = reinterpret_cast<uint4*>(xq + (size_t)t * ldq);
+            const uint4* src = reinterpret_cast<const uint4*>(stage);
+            for (int i = lt; i < (ldq >> 4); i += TPR) dst[i] = src[i];
+            // ---- pass 3: move the outlier columns
+            for (int j = lt; j < n_out; j += TPR) {
+                int c = idx[j];
+                __half v = (c >= 0 && c < K) ? row[c] : __ushort_as_half((unsigned short)0);
+                x_out[(size_t)t * ldo + j] = v;
+            }
+        }
+        __syncthreads();                           // before the next iteration clears the image
+    }
+}
+
+template <int BITS, int TPR, int NCH>
+hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
+    constexpr int RPB = kBlock / TPR;
+    const int nwords = (a.K + 31) >> 5;
+    size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
+    int nrowblk = (a.T + RPB - 1) / RPB;
+    int grid = nrowblk < 4096 ? nrowblk : 4096;
+    hipLaunchKernelGGL((quantize_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
+                       (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
+                       a.scale, a.zero, (__half*)a.x_out, a.ldo);
+    return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t dispatch(const QuantizeArgs& a, hipStream_t stream) {
+    const int K = a.K;
+    if (K <= 64 * 8 * 1) return launch<BITS, 64, 1>(a, stream);
+    if (K <= 64 * 8 * 2) return launch<BITS, 64, 2>(a, stream);
+    if (K <= 64 * 8 * 4) return launch<BITS, 64, 4>(a, stream);
+    if (K <= 64 * 8 * 8) return launch<BITS, 64, 8>(a, stream);
+    if (K <= 256 * 8 * 4) return launch<BITS, 256, 4>(a, stream);
+    if (K <= 256 * 8 * 8) return launch<BITS, 256, 8>(a, stream);
+    return launch<BITS, 256, 0>(a, stream);
+}
+
+}  // namespace
+
+hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
+    return a.bits == 4 ? dispatch<4>(a, stream) : dispatch<8>(a, stream);
+}
+
+}  // namespace quik

@@ -1,0 +1,92 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and turns bad arguments into error codes before any launch.
+No kernel is launched here, so no GPU is needed."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2310_09259_amd", "libquik.so")
+HDR = os.path.join(ROOT, "include", "quik.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2310_09259_amd import build
+        build.build()
+    lib = C.CDLL(LIB)
+    lib.quik_workspace_bytes.restype = C.c_size_t
+    lib.quik_status_string.restype = C.c_char_p
+    return lib
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = sorted(set(re.findall(r"\b(quik_[a-z0-9_]+)\s*\(", open(HDR).read())))
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_sizes_and_strings(lib):
+    assert lib.quik_version() >= 1
+    assert lib.quik_packed_row_bytes(480, 4) == 240
+    assert lib.quik_packed_row_bytes(488, 4) == 256
+    assert lib.quik_packed_row_bytes(480, 8) == 480
+    assert lib.quik_packed_row_bytes(481, 4) == 0           # odd count cannot be nibble-packed
+    assert lib.quik_packed_row_bytes(16, 5) == 0
+    ws = lib.quik_workspace_bytes(2048, 4096, 11008, 256, 4)
+    assert ws >= 2048 * 1920 + 2 * 2048 * 4 + 2048 * 256 * 2 and ws % 256 == 0
+    assert lib.quik_workspace_bytes(0, 4096, 1, 0, 4) == 0
+    assert lib.quik_workspace_bytes(16, 64, 1, 64, 4) == 0   # no base column left
+    assert b"OK" in lib.quik_status_string(0)
+    for code in range(-6, 0):
+        assert lib.quik_status_string(code).startswith(b"QUIK_E")
+
+
+def test_outlier_index_validator(lib):
+    def chk(lst, K):
+        a = np.asarray(lst, np.int32)
+        return lib.quik_check_outlier_idx_host(a.ctypes.data_as(C.c_void_p), len(lst), K)
+    assert chk([3, 1, 7], 8) == 0
+    assert chk([3, 3], 8) == -1
+    assert chk([8], 8) == -1
+    assert chk([-1], 8) == -1
+
+
+def test_bad_arguments_are_rejected_before_launch(lib):
+    p = C.c_void_p(0x1000)          # never dereferenced: validation fails first
+    u = C.c_void_p(0x1004)          # misaligned
+    null = C.c_void_p(0)
+    q = lib.quik_quantize
+    # (x, T, K, ldx, idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo, stream)
+    assert q(p, 4, 64, 64, p, 8, 5, p, 32, p, p, p, 8, null) == -1        # bits
+    assert q(p, 0, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -1        # T
+    assert q(p, 4, 64, 64, p, 64, 4, p, 32, p, p, p, 64, null) == -1      # n_out == K
+    assert q(p, 4, 64, 32, p, 8, 4, p, 32, p, p, p, 8, null) == -1        # ldx < K
+    assert q(p, 4, 64, 64, p, 8, 4, p, 16, p, p, p, 8, null) == -1        # ldq too small
+    assert q(null, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -2     # x NULL
+    assert q(p, 4, 64, 64, null, 8, 4, p, 32, p, p, p, 8, null) == -2     # idx NULL with n_out
+    assert q(u, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -3        # x misaligned
+    assert q(p, 4, 64, 64, p, 8, 4, p, 40, p, p, p, 8, null) == -3        # ldq % 16
+    assert q(p, 4, 60, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -4        # K % 8
+    assert q(p, 4, 64, 64, p, 4, 4, p, 32, p, p, p, 8, null) == -4        # n_out % 8
+    assert q(p, 4, 65536, 65536, p, 8, 4, p, 32768, p, p, p, 8, null) == -4   # K too large
+    g = lib.quik_gemm_dequant
+    # (xq, ldq, scale, zero, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_scale, w_red, w_out, ldwo,
+    #  bias, N, y, ldy, stream)
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 16, p, p, p, 8, null, 8, p, 8, null) == -1   # ldw small
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, null, 8, null) == -2
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, p, 4, null) == -1   # ldy < N
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, u, 32, p, p, p, 8, null, 8, p, 8, null) == -3   # w_q align
+    lin = lib.quik_linear
+    lin.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
+                    C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+                    C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    need = lib.quik_workspace_bytes(4, 64, 8, 8, 4)
+    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, C.c_void_p(0x1000), need - 1,
+               null) == -5
+    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, null, need, null) == -2

@@ -1,0 +1,228 @@
+"""GPU-vs-oracle parity through the C ABI (run with -m gpu on an MI355X).
+
+Bars: packed activations, scale, zero, outlier block and INT32 accumulators are
+bit-exact; the fp16 output is within 5e-3 of the oracle's binary32 result
+(|y - y_ref| <= 5e-3 * max(|y_ref|, 1e-3 * max|y_ref|) element by element).
+"""
+import numpy as np
+import pytest
+
+from paper_2310_09259_amd import synth
+from tests.util import expected_xq, output_within_tolerance, to_dev, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2310_09259_amd import api as _api
+    _api.load()
+    return _api
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _quantize_case(api, oracle, x, idx, bits):
+    import torch
+    T, K = x.shape
+    xd = to_dev(x)
+    idxd = to_dev(idx) if idx.size else None
+    xq, scale, zero, x_out = api.quik_quantize(xd, idxd, bits)
+    _sync()
+    q, s, z, xo = oracle.quantize(x, idx, bits)
+    want = expected_xq(oracle, q, bits, xq.shape[1])
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32)), "scale"
+    assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32)), "zero"
+    got = xq.cpu().numpy()
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"xq differs at {len(bad)} bytes, first {bad[:5].tolist()}")
+    if idx.size:
+        assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16)), "x_out"
+
+
+# T, K, n_out, bits: covers every row-caching variant of the kernel (K <= 512,
+# 1024, 2048, 4096 with one wave per row; <= 8192, <= 16384 with a workgroup per
+# row; the uncached form above), ragged T, n_out = 0, and a packed row length that
+# is not a multiple of 16 bytes (K_b = 488 -> 244 bytes -> zero padding to 256).
+QUANT_SHAPES = [
+    (16, 512, 32, 4), (37, 512, 24, 4), (5, 1024, 64, 4), (33, 2048, 128, 4),
+    (64, 4096, 256, 4), (19, 5120, 256, 4), (9, 11008, 256, 4), (3, 20480, 256, 4),
+    (16, 512, 0, 4), (7, 64, 8, 4), (1, 8, 0, 4),
+    (16, 512, 32, 8), (21, 4096, 256, 8), (6, 11008, 256, 8), (3, 20480, 128, 8), (11, 520, 24, 8),
+]
+
+
+@pytest.mark.parametrize("T,K,n_out,bits", QUANT_SHAPES)
+def test_quantize_is_bit_exact(api, oracle, T, K, n_out, bits):
+    shp = synth.LayerShape("q", T, K, 8, n_out, bits, seed=1000 + T + K + n_out + bits)
+    inp = synth.make_inputs(shp)
+    _quantize_case(api, oracle, inp.x, inp.outlier_idx, bits)
+
+
+def test_quantize_unsorted_indices_and_degenerate_rows(api, oracle):
+    rng = np.random.default_rng(5)
+    T, K = 12, 1024
+    x = rng.standard_normal((T, K)).astype(np.float16)
+    x[0, :] = np.float16(2.5)                   # constant row
+    x[1, :] = np.float16(-0.0)                  # all minus zero
+    x[2, :] = np.float16(0.0)
+    x[2, 17] = np.float16(6.0e-8)               # smallest subnormal as the whole range
+    x[3, :] = np.float16(65504.0)
+    x[3, 5] = np.float16(-65504.0)              # full fp16 span
+    idx = rng.permutation(K)[:40].astype(np.int32)          # unsorted
+    _quantize_case(api, oracle, x, idx, 4)
+    _quantize_case(api, oracle, x, idx, 8)
+    # exact .5 ties: integer grid + halves, scale exactly 1
+    xt = (rng.integers(0, 30, size=(4, 512)) / 2.0).astype(np.float16)
+    xt[:, 0] = 0
+    xt[:, 1] = 15
+    xt = np.clip(xt, 0, 15)
+    _quantize_case(api, oracle, xt, np.zeros(0, np.int32), 4)
+
+
+# T, N, K_b, bits: several tiles in both directions with ragged edges, K tails that
+# are not a multiple of the K stage, a single row/column, the deepest test K.
+INT_GEMM_SHAPES = [
+    (16, 512, 480, 4), (200, 300, 992, 4), (129, 257, 3840, 4), (1, 1, 32, 4), (130, 64, 96, 4),
+    (16, 512, 480, 8), (150, 140, 1000, 8), (257, 129, 4864, 8),
+]
+
+
+@pytest.mark.parametrize("T,N,K_b,bits", INT_GEMM_SHAPES)
+def test_int32_accumulators_are_bit_exact(api, oracle, T, N, K_b, bits):
+    import torch
+    rng = np.random.default_rng(T * 7 + N * 3 + K_b + bits)
+    half = 1 << (bits - 1)
+    q = rng.integers(-half, half, size=(T, K_b)).astype(np.int8)
+    w = rng.integers(-half, half, size=(N, K_b)).astype(np.int8)
+    q[0, :] = -half
+    w[0, :] = -half                              # largest possible accumulator
+    ld = api.quik_packed_row_bytes(K_b, bits)
+    xq = to_dev(expected_xq(oracle, q, bits, ld))
+    # weight pad bytes may hold anything: fill them with 0xFF to prove it
+    wp = np.full((N, ld), 0xFF, np.uint8)
+    wp[:, : K_b * bits // 8] = oracle.pack(w, bits)
+    acc = api.quik_int_gemm(xq, to_dev(wp), K_b, bits)
+    _sync()
+    want = oracle.int_gemm(q, w, bits)
+    got = acc.cpu().numpy()
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"{len(bad)} accumulators differ, first {bad[:5].tolist()}: "
+                             f"{got[tuple(bad[0])]} vs {want[tuple(bad[0])]}")
+
+
+@pytest.mark.parametrize("N,K_b,bits", [(37, 480, 4), (300, 3840, 4), (129, 1000, 8)])
+def test_weight_reduce_is_bit_exact(api, oracle, N, K_b, bits):
+    rng = np.random.default_rng(N + K_b)
+    wp = rng.integers(0, 256, size=(N, K_b * bits // 8), dtype=np.uint8)
+    sw = rng.uniform(0.005, 0.02, N).astype(np.float16)
+    ld = api.quik_packed_row_bytes(K_b, bits)
+    buf = np.full((N, ld), 0xFF, np.uint8)
+    buf[:, : wp.shape[1]] = wp
+    got = api.quik_weight_reduce(to_dev(buf), to_dev(sw), K_b, bits)
+    _sync()
+    want = oracle.weight_reduce(oracle.unpack(wp, K_b, bits), sw)
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def _linear_case(api, oracle, shp, bias=False, gain=40.0):
+    inp = synth.make_inputs(shp, outlier_gain=gain)
+    d = upload(inp)
+    b = None
+    if bias:
+        b = np.random.default_rng(1).standard_normal(shp.N).astype(np.float16)
+    ref = oracle.linear(inp.x, inp.outlier_idx, shp.bits, inp.w_packed, inp.w_scale, inp.w_out, bias=b)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
+    y = api.quik_linear(d["x"], d["idx"], shp.bits, d["w_q"], d["w_scale"], w_red, d["w_out"],
+                        bias=to_dev(b) if bias else None)
+    _sync()
+    assert np.array_equal(w_red.cpu().numpy().view(np.uint32), ref.w_reduced.view(np.uint32))
+    ok, worst = output_within_tolerance(y.cpu().numpy(), ref.y)
+    assert ok, f"fp16 output outside 5e-3 (worst error / tolerance = {worst:.2f})"
+    assert worst > 0                                   # not a trivially equal array
+    return inp, d, ref, w_red
+
+
+LINEAR_SHAPES = [
+    synth.CONFIGS["tiny"],
+    synth.LayerShape("ragged", 150, 1024, 200, 64, 4, seed=31),
+    synth.LayerShape("multi_tile", 260, 2048, 390, 128, 4, seed=32),
+    synth.LayerShape("no_outliers", 64, 512, 256, 0, 4, seed=33),
+    synth.LayerShape("n_out_24", 40, 520, 136, 24, 4, seed=34),
+    synth.LayerShape("one_token", 1, 4096, 512, 256, 4, seed=35),
+    synth.LayerShape("w8a8", 130, 1024, 260, 64, 8, seed=36),
+    synth.LayerShape("w8a8_tiny", 16, 512, 512, 32, 8, seed=37),
+]
+
+
+@pytest.mark.parametrize("shp", LINEAR_SHAPES, ids=lambda s: s.name)
+def test_linear_matches_oracle(api, oracle, shp):
+    _linear_case(api, oracle, shp)
+
+
+def test_linear_with_bias(api, oracle):
+    _linear_case(api, oracle, synth.LayerShape("bias", 70, 512, 130, 32, 4, seed=41), bias=True)
+
+
+def test_stages_called_separately_agree_with_the_fused_entry_point(api, oracle):
+    shp = synth.LayerShape("stages", 100, 1024, 160, 64, 4, seed=42)
+    inp, d, ref, w_red = _linear_case(api, oracle, shp)
+    xq, scale, zero, x_out = api.quik_quantize(d["x"], d["idx"], 4)
+    y2 = api.quik_gemm_dequant(xq, scale, zero, x_out, shp.K_b, 4, d["w_q"], d["w_scale"], w_red,
+                               d["w_out"])
+    acc = api.quik_int_gemm(xq, d["w_q"], shp.K_b, 4)
+    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
+    _sync()
+    assert np.array_equal(y1.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
+    assert np.array_equal(acc.cpu().numpy(), ref.acc)
+
+
+def test_strided_input_and_output(api, oracle):
+    """Leading dimensions larger than the logical width (views into wider buffers)."""
+    import torch
+    shp = synth.LayerShape("strided", 50, 512, 72, 32, 4, seed=43)
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    ref = oracle.linear(inp.x, inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
+    xbig = torch.full((shp.T, shp.K + 64), 777.0, dtype=torch.float16, device="cuda")
+    xbig[:, : shp.K] = d["x"]
+    ybig = torch.full((shp.T, shp.N + 24), -5.0, dtype=torch.float16, device="cuda")
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    api.quik_linear(xbig[:, : shp.K], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"],
+                    out=ybig[:, : shp.N])
+    _sync()
+    yh = ybig.cpu().numpy()
+    ok, worst = output_within_tolerance(yh[:, : shp.N], ref.y)
+    assert ok, worst
+    assert np.all(yh[:, shp.N:] == -5.0)               # nothing written outside the view
+
+
+def test_full_size_llama7b_up_projection_on_sampled_tokens(api, oracle):
+    """The benchmark workload at full size (T=2048, K=4096, N=11008, 256 outliers):
+    quantization checked in full, accumulators and output on sampled token rows
+    (tokens are independent, so the oracle is run on those rows alone)."""
+    shp = synth.CONFIGS["llama7b_up"]
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    xq, scale, zero, x_out = api.quik_quantize(d["x"], d["idx"], 4)
+    y = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
+    acc = api.quik_int_gemm(xq, d["w_q"], shp.K_b, 4)
+    _sync()
+    q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, 4)
+    assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, q, 4, xq.shape[1]))
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
+    assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32))
+    assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16))
+    sel = np.array([0, 1, 31, 32, 127, 128, 777, 1023, 1024, 1500, 2046, 2047])
+    ref = oracle.linear(inp.x[sel], inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
+    assert np.array_equal(acc.cpu().numpy()[sel], ref.acc)
+    ok, worst = output_within_tolerance(y.cpu().numpy()[sel], ref.y)
+    assert ok, worst
