@@ -16,7 +16,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes",
+    "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes", "-Wno-inline-asm",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 

@@ -2,21 +2,36 @@
 // (Algorithm 1 of arXiv 2310.09259: "INTmatmul", "Dequantization", "FPmatmul" and
 // the final add; epilogue fusion as in Section 3.4).
 //
-// gfx950 has no 4-bit integer MFMA, so packed nibbles travel HBM -> LDS -> VGPR
-// still packed and are widened in registers: for a 32-bit word w holding eight
-// two's-complement nibbles, (w & 0xF0F0F0F0) and ((w << 4) & 0xF0F0F0F0) are two
-// int8x4 vectors holding 16x the odd and 16x the even nibbles.  Doing the same to
-// both operands makes every product 256x too large, exactly; the INT32 accumulator
-// is shifted right by 8 at the end.  A dot product does not care in which order k
-// is visited as long as both operands agree, so the odd/even split needs no
-// re-interleaving.  Headroom: K_b * 64 * 256 < 2^31 requires K_b < 131072.
+// Data path.  gfx950 has no 4-bit integer MFMA, so packed nibbles travel
+// HBM -> LDS -> VGPR still packed and are widened in registers: for a 32-bit word
+// w holding eight two's-complement nibbles, (w & 0xF0F0F0F0) and
+// ((w << 4) & 0xF0F0F0F0) are two int8x4 vectors holding 16x the odd and 16x the
+// even nibbles.  Doing the same to both operands makes every product exactly 256x
+// too large; the factor is removed in the epilogue (arithmetic shift for the raw
+// accumulators, an exact power-of-two fold into the scale for the dequantized
+// output).  A dot product does not care in which order k is visited as long as
+// both operands agree, so the odd/even split needs no re-interleaving.  Headroom:
+// K_b * 64 * 256 < 2^31 requires K_b < 131072.
 //
 // MFMA shape: v_mfma_i32_32x32x32_i8.  First operand = activations (32 token
 // rows), second = weights (32 output channels).  Lane l supplies row/column l%32
 // and the k-group l/32; it receives output column l%32 and rows
 // 8*(r/4) + 4*(l/32) + r%4 in accumulator register r.  The fp16 outlier product
 // uses v_mfma_f32_32x32x16_f16, whose accumulator has the same layout, so the
-// dequantized tile is simply the C operand of the outlier loop.
+// dequantized tile is simply the C operand of the outlier stages.
+//
+// Pipeline.  A workgroup of four waves owns a BM x BN output tile.  Operand panels
+// are copied global -> LDS without passing through registers (buffer_load ... lds,
+// 16 bytes per lane, BKB bytes of every row per stage, NST stage buffers).  Rows
+// beyond T / N and bytes beyond the row end are out of range for the buffer
+// descriptor and arrive as zeros.  The 16-byte slots of a row are XOR-swizzled so
+// that the 32 rows a ds_read_b128 touches fall into distinct banks.  The int4
+// stages and the fp16 outlier stages run through the same stage ring.  Inside a
+// wave the work is software pipelined three deep and the order is pinned with
+// scheduling barriers: while the MFMAs of sub-step q issue, the packed words of
+// sub-step q+1 are widened and the LDS reads of sub-step q+2 are in flight.
+// One workgroup barrier per stage; right after it the stage buffer it has just
+// freed is refilled, the DMA instructions spread between MFMAs.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -31,9 +46,11 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void* lds_ptr;
 
 constexpr int kThreads = 256;
 constexpr int kXcds = 8;
+constexpr uint32_t kOob = 0x80000000u;     // byte offset beyond any descriptor range
 
 // Maps the hardware workgroup id (dealt round-robin over the 8 XCDs) to a logical
 // tile id such that each XCD works on a contiguous range of logical tiles and so
@@ -45,89 +62,171 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int nblk) {
     return start + local;
 }
 
-template <int BITS>
-__device__ __forceinline__ void widen(const uint4& w, v4i& op0, v4i& op1) {
-    if constexpr (BITS == 4) {
-        constexpr uint32_t M = 0xF0F0F0F0u;
-        op0 = v4i{(int)((w.x << 4) & M), (int)(w.x & M), (int)((w.y << 4) & M), (int)(w.y & M)};
-        op1 = v4i{(int)((w.z << 4) & M), (int)(w.z & M), (int)((w.w << 4) & M), (int)(w.w & M)};
-    } else {
-        op0 = v4i{(int)w.x, (int)w.y, (int)w.z, (int)w.w};
-        op1 = op0;
-    }
+// Raw buffer descriptor over [p, p + bytes): loads beyond the range return zero.
+__device__ __forceinline__ v4i make_rsrc(const void* p, size_t bytes) {
+    uint32_t n = bytes > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)bytes;
+    uint64_t q = (uint64_t)(uintptr_t)p;
+    v4i r = v4i{(int)(uint32_t)q, (int)(uint32_t)(q >> 32), (int)n, 0x00020000};
+    r[0] = __builtin_amdgcn_readfirstlane(r[0]);
+    r[1] = __builtin_amdgcn_readfirstlane(r[1]);
+    r[2] = __builtin_amdgcn_readfirstlane(r[2]);
+    return r;
 }
 
-// BM x BN output tile per workgroup, WM x WN waves, BKB bytes of every packed row
-// per LDS stage.  RAW: write INT32 accumulators instead of running the epilogue.
-template <int BITS, int BM, int BN, int WM, int WN, int BKB, bool RAW>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs a) {
-    static_assert(WM * WN == 4, "four waves per workgroup");
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // MFMA tiles per wave
-    constexpr int CPR = BKB / 16;                         // 16-byte chunks per row per stage
-    constexpr int LDS_STRIDE = BKB + 16;                  // padded row stride (bank spread)
-    constexpr int A_CHUNKS = BM * CPR / kThreads, B_CHUNKS = BN * CPR / kThreads;
-    static_assert(BM * CPR % kThreads == 0 && BN * CPR % kThreads == 0, "tile/threads mismatch");
-    constexpr int KSUB = BKB / 32;                        // 32-byte sub-steps per stage
-    constexpr int SHIFT = (BITS == 4) ? 8 : 0;
+// 16 bytes per lane, global -> LDS at lds_base + lane*16, source = rsrc.base + voff + soff.
+// Issued as inline asm so that the compiler's wait-count insertion does not serialise
+// it against LDS reads of other stage buffers; completion is tracked by hand (vmcnt).
+// Extra vector-memory operations the compiler does not know about can only make its
+// own waits more conservative, because the counter retires in order.
+__device__ __forceinline__ void dma16(v4i rsrc, uint32_t lds_base, uint32_t voff, uint32_t soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) { return (uint32_t)(uintptr_t)(lds_ptr)(p); }
 
-    __shared__ __align__(16) uint8_t lds_a[2][BM * LDS_STRIDE];
-    __shared__ __align__(16) uint8_t lds_b[2][BN * LDS_STRIDE];
-    __shared__ float lds_sa[BM];   // scaleAct per tile row
-    __shared__ float lds_sh[BM];   // zeroAct + halfRange * scaleAct per tile row
+// XOR swizzle of the 16-byte slot index inside a stage row of BKB bytes.
+template <int BKB> __device__ __forceinline__ int swz(int r) {
+    if constexpr (BKB == 64) return (r >> 2) & 3;
+    else return (r >> 1) & 7;
+}
+template <int N> __device__ __forceinline__ void wait_vm() {   // s_waitcnt vmcnt(N) only
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// BM x BN output tile per workgroup, WM x WN waves, BKB bytes of every packed row per
+// stage, NST stage buffers.  RAW: write INT32 accumulators instead of running the epilogue.
+template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, bool RAW>
+__global__ __launch_bounds__(kThreads, OCC) void gemm_kernel(GemmArgs a) {
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int CPR = BKB / 16, RPI = 64 / CPR;
+    constexpr int A_INSTR = BM / RPI / 4, B_INSTR = BN / RPI / 4;
+    constexpr int LPS = A_INSTR + B_INSTR;
+    constexpr int KSUB = BKB / 32;
+    constexpr int SHIFT = (BITS == 4) ? 8 : 0;
+    constexpr int A_BYTES = BM * BKB, B_BYTES = BN * BKB, ST_BYTES = A_BYTES + B_BYTES;
+    constexpr int NF = TM + TN;
+    constexpr int HALVES = (BITS == 4) ? 2 : 1;          // MFMAs per output tile per sub-step
+    constexpr int SLOTS = TM * TN * HALVES;
+    constexpr int WORDS = NF * 4;
+    constexpr int BAR_KS = KSUB - 2;                     // stage barrier sits before this sub-step
+    static_assert(KSUB % 2 == 0 && NST >= 2, "");
+
+    __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES];
+    __shared__ __align__(16) float lds_sa[BM];
+    __shared__ __align__(16) float lds_sh[BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int wm = wave_u / WN, wn = wave_u % WN;
     const int l32 = lane & 31, g = lane >> 5;
 
     const int tiles_m = (a.T + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const int id = xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n);
     const int t0 = (id % tiles_m) * BM, n0 = (id / tiles_m) * BN;
 
-    const uint8_t* __restrict__ gA = static_cast<const uint8_t*>(a.xq);
-    const uint8_t* __restrict__ gB = static_cast<const uint8_t*>(a.w_q);
     const int row_bytes = a.K_b * BITS / 8;
-    const int nk = (row_bytes + BKB - 1) / BKB;
+    const int nk_int = (row_bytes + BKB - 1) / BKB;
+    const int fp_bytes = a.n_out * 2;
+    const int nk_fp = RAW ? 0 : (fp_bytes + BKB - 1) / BKB;
+    const int nk = nk_int + nk_fp;
+    const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
+
+    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * a.ldq, (size_t)(a.T - t0) * a.ldq);
+    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * a.ldw, (size_t)(a.N - n0) * a.ldw);
+    const v4i rAf = make_rsrc(a.n_out ? (const uint8_t*)a.x_out + (size_t)t0 * lda_fp : (const uint8_t*)a.xq,
+                              a.n_out ? (size_t)(a.T - t0) * lda_fp : 0);
+    const v4i rBf = make_rsrc(a.n_out ? (const uint8_t*)a.w_out + (size_t)n0 * ldb_fp : (const uint8_t*)a.xq,
+                              a.n_out ? (size_t)(a.N - n0) * ldb_fp : 0);
+
+    const int lrow = lane / CPR, lslot = lane % CPR;
+    const uint32_t lds_base = lds_addr(lds);
+    uint32_t voA[A_INSTR], voB[B_INSTR];
+    int chA[A_INSTR], chB[B_INSTR], rwA[A_INSTR], rwB[B_INSTR];
+#pragma unroll
+    for (int i = 0; i < A_INSTR; ++i) {
+        int row = (wave_u * A_INSTR + i) * RPI + lrow;
+        int c = (lslot ^ swz<BKB>(row)) * 16;
+        rwA[i] = row; chA[i] = c;
+        voA[i] = (uint32_t)(row * a.ldq + c);
+    }
+#pragma unroll
+    for (int i = 0; i < B_INSTR; ++i) {
+        int row = (wave_u * B_INSTR + i) * RPI + lrow;
+        int c = (lslot ^ swz<BKB>(row)) * 16;
+        rwB[i] = row; chB[i] = c;
+        voB[i] = (uint32_t)(row * a.ldw + c);
+    }
+    const uint32_t m0A = lds_base + wave_u * A_INSTR * 1024;
+    const uint32_t m0B = lds_base + A_BYTES + wave_u * B_INSTR * 1024;
+
+    // DMA instruction d of a full (unguarded) int stage
+    auto issue_one = [&](int s, int d) {
+        const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
+        const uint32_t so = (uint32_t)s * BKB;
+        if (d < A_INSTR) dma16(rA, m0A + sb + d * 1024, voA[d < A_INSTR ? d : 0], so);
+        else dma16(rB, m0B + sb + (d - A_INSTR) * 1024, voB[d >= A_INSTR ? d - A_INSTR : 0], so);
+    };
+    // any stage: K tail of the int part, fp16 part, or past the end (all lanes out of range)
+    auto issue_any = [&](int s) {
+        const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
+        const bool fp = s >= nk_int;
+        const int koff = (fp ? s - nk_int : s) * BKB;
+        const int lima = s < nk ? (fp ? fp_bytes : a.ldq) : 0, limb = s < nk ? (fp ? fp_bytes : a.ldw) : 0;
+        const int lda = fp ? lda_fp : a.ldq, ldb = fp ? ldb_fp : a.ldw;
+        const v4i ra_ = fp ? rAf : rA;
+        const v4i rb_ = fp ? rBf : rB;
+#pragma unroll
+        for (int i = 0; i < A_INSTR; ++i) {
+            uint32_t vo = (koff + chA[i] < lima) ? (uint32_t)(rwA[i] * lda + koff + chA[i]) : kOob;
+            dma16(ra_, m0A + sb + i * 1024, vo, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_INSTR; ++i) {
+            uint32_t vo = (koff + chB[i] < limb) ? (uint32_t)(rwB[i] * ldb + koff + chB[i]) : kOob;
+            dma16(rb_, m0B + sb + i * 1024, vo, 0);
+        }
+    };
+
+    // ---- prologue: fill every stage buffer
+#pragma unroll
+    for (int s = 0; s < NST; ++s) issue_any(s);
 
     if constexpr (!RAW) {
         for (int r = tid; r < BM; r += kThreads) {
             int t = t0 + r;
             float s = (t < a.T) ? a.scale[t] : 0.0f;
             float z = (t < a.T) ? a.zero[t] : 0.0f;
-            lds_sa[r] = s;
-            lds_sh[r] = z + (float)(1 << (BITS - 1)) * s;
+            lds_sa[r] = s;                                    // scaleAct
+            lds_sh[r] = z + (float)(1 << (BITS - 1)) * s;     // zeroAct + halfRange * scaleAct
         }
     }
 
-    // global -> register staging of one K stage
-    uint4 ga[A_CHUNKS], gb[B_CHUNKS];
-    auto load_stage = [&](int kt) {
+    uint32_t rd[NF][KSUB];
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            int c = tid + i * kThreads, r = c / CPR, ch = c % CPR;
-            int t = min(t0 + r, a.T - 1);
-            int off = kt * BKB + ch * 16;
-            ga[i] = (off < a.ldq) ? *reinterpret_cast<const uint4*>(gA + (size_t)t * a.ldq + off)
-                                  : make_uint4(0, 0, 0, 0);
-        }
+    for (int f = 0; f < NF; ++f) {
+        int r = (f < TM) ? (wm * TM * 32 + f * 32 + l32) : (wn * TN * 32 + (f - TM) * 32 + l32);
+        uint32_t base = (f < TM ? 0 : A_BYTES) + r * BKB;
 #pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            int c = tid + i * kThreads, r = c / CPR, ch = c % CPR;
-            int n = min(n0 + r, a.N - 1);
-            int off = kt * BKB + ch * 16;
-            gb[i] = (off < a.ldw) ? *reinterpret_cast<const uint4*>(gB + (size_t)n * a.ldw + off)
-                                  : make_uint4(0, 0, 0, 0);
-        }
+        for (int ks = 0; ks < KSUB; ++ks) rd[f][ks] = base + (((ks * 2 + g) ^ swz<BKB>(r)) << 4);
+    }
+
+    uint4 R[2][NF];
+    v4i U[2][NF][HALVES];
+
+    auto read_frag = [&](int set, int f, const uint8_t* stage, int ks) {
+        R[set][f] = *reinterpret_cast<const uint4*>(stage + rd[f][ks]);
     };
-    auto store_stage = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            int c = tid + i * kThreads, r = c / CPR, ch = c % CPR;
-            *reinterpret_cast<uint4*>(&lds_a[buf][r * LDS_STRIDE + ch * 16]) = ga[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            int c = tid + i * kThreads, r = c / CPR, ch = c % CPR;
-            *reinterpret_cast<uint4*>(&lds_b[buf][r * LDS_STRIDE + ch * 16]) = gb[i];
+    auto widen_word = [&](int set, int w) {
+        const int f = w >> 2, k = w & 3;
+        const uint32_t x = (k == 0) ? R[set][f].x : (k == 1) ? R[set][f].y : (k == 2) ? R[set][f].z : R[set][f].w;
+        if constexpr (BITS == 4) {
+            constexpr uint32_t M = 0xF0F0F0F0u;
+            U[set][f][k >> 1][(k & 1) * 2] = (int)((x << 4) & M);
+            U[set][f][k >> 1][(k & 1) * 2 + 1] = (int)(x & M);
+        } else {
+            U[set][f][0][k] = (int)x;
         }
     };
 
@@ -139,44 +238,64 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_stage(kt + 1);
-        const uint8_t* pa = &lds_a[buf][(wm * TM * 32 + l32) * LDS_STRIDE + g * 16];
-        const uint8_t* pb = &lds_b[buf][(wn * TN * 32 + l32) * LDS_STRIDE + g * 16];
-#pragma unroll
-        for (int ks = 0; ks < KSUB; ++ks) {
-            v4i a0[TM], a1[TM], b0[TN], b1[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                uint4 w = *reinterpret_cast<const uint4*>(pa + i * 32 * LDS_STRIDE + ks * 32);
-                widen<BITS>(w, a0[i], a1[i]);
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                uint4 w = *reinterpret_cast<const uint4*>(pb + j * 32 * LDS_STRIDE + ks * 32);
-                widen<BITS>(w, b0[j], b1[j]);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0[i], b0[j], acc[i][j], 0, 0, 0);
-                    if constexpr (BITS == 4)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1[i], b1[j], acc[i][j], 0, 0, 0);
-                }
-        }
-        if (kt + 1 < nk) store_stage(buf ^ 1);
+    // stage barrier of iteration s: stage s+1 has landed for everybody, and nobody reads stage s any more
+    auto stage_barrier = [&]() {
+        wait_vm<(NST - 2) * LPS>();
         __syncthreads();
-    }
+    };
 
-    // ---- epilogue
+    // sub-step ks of stage s.  PLAIN: the DMA into the freed buffer is a full int stage and is spread over
+    // the MFMA slots that follow the barrier; otherwise it is issued in one go.
+    auto substep = [&](int s, int ks, bool plain) {
+        const int par = ks & 1;
+        if (ks == BAR_KS) {
+            stage_barrier();
+            if (!plain) issue_any(s + NST);
+        }
+        const int ts = (ks + 2 < KSUB) ? s : s + 1, tks = (ks + 2) % KSUB;
+        const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < SLOTS; ++m) {
+            const int h = m / (TM * TN), ij = m % (TM * TN), i = ij / TN, j = ij % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(U[par][i][h], U[par][TM + j][h], acc[i][j], 0, 0, 0);
+            if (plain && ks == BAR_KS) {
+                constexpr int PER = (SLOTS >= LPS) ? SLOTS / LPS : 1;
+                if (m % PER == 0 && m / PER < LPS) issue_one(s + NST, m / PER);
+                if (SLOTS < LPS && m == SLOTS - 1)
+                    for (int d = SLOTS; d < LPS; ++d) issue_one(s + NST, d);
+            }
+#pragma unroll
+            for (int w = 0; w < WORDS; ++w)
+                if (w * SLOTS / WORDS == m) widen_word(par ^ 1, w);
+            if (m < NF) read_frag(par, m, tgt, tks);
+            if (SLOTS < NF && m == SLOTS - 1)
+                for (int f = SLOTS; f < NF; ++f) read_frag(par, f, tgt, tks);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    wait_vm<(NST - 1) * LPS>();          // stage 0 landed
+    __syncthreads();
+#pragma unroll
+    for (int f = 0; f < NF; ++f) { read_frag(0, f, lds, 0); read_frag(1, f, lds, 1); }
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) widen_word(0, w);
+
+    int s = 0;
+    for (; s + NST < nk_int - 1; ++s) {
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) substep(s, ks, true);
+    }
+    for (; s < nk_int; ++s) {
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) substep(s, ks, false);
+    }
+    // here: R[0] / R[1] hold raw sub-steps 0 / 1 of stage nk_int (fp16 data)
+
     const int tw = t0 + wm * TM * 32, nw = n0 + wn * TN * 32;
     if constexpr (RAW) {
+        wait_vm<0>();                      // drain the look-ahead DMA before the wave ends
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -188,77 +307,89 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmArgs a) {
                     if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = acc[i][j][r] >> SHIFT;
                 }
             }
-    } else {
-        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
-        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
-        v16f cf[TM][TN];
+        return;
+    }
+    const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
+    const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+    v16f cf[TM][TN];
+    {
+        float sw[TN], wr[TN], bv[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             int n = min(nw + j * 32 + l32, a.N - 1);
-            float sw = __half2float(wsc[n]);
-            float wr = a.w_reduced[n];
-            float bv = bias ? __half2float(bias[n]) : 0.0f;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int lr = wm * TM * 32 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    float v = (float)(acc[i][j][r] >> SHIFT);
-                    cf[i][j][r] = v * (lds_sa[lr] * sw) + (lds_sh[lr] * wr + bv);
-                }
+            sw[j] = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));   // exact power-of-two fold of the >> SHIFT
+            bv[j] = bias ? __half2float(bias[n]) : 0.0f;
+            wr[j] = a.w_reduced[n];
         }
-        // fp16 outlier product accumulated on top of the dequantized tile
-        const __half* __restrict__ xo = static_cast<const __half*>(a.x_out);
-        const __half* __restrict__ wo = static_cast<const __half*>(a.w_out);
-        for (int ko = 0; ko < a.n_out; ko += 16) {
-            const int kk = ko + g * 8;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int lr = wm * TM * 32 + i * 32 + 8 * rq + 4 * g;
+                const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
+                const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
+                const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const int r = rq * 4 + rr;
+                        float v = (float)acc[i][j][r];
+                        cf[i][j][r] = __builtin_fmaf(v, sa_[rr] * sw[j], __builtin_fmaf(sh_[rr], wr[j], bv[j]));
+                    }
+            }
+    }
+
+    for (; s < nk; ++s) {
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) {
+            const int par = ks & 1;
+            if (ks == BAR_KS) { stage_barrier(); issue_any(s + NST); }
+            const int ts = (ks + 2 < KSUB) ? s : s + 1, tks = (ks + 2) % KSUB;
+            const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
             v8h fa[TM], fb[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int t = min(tw + i * 32 + l32, a.T - 1);
-                uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(xo + (size_t)t * a.ldo + kk)
-                                         : make_uint4(0, 0, 0, 0);
-                fa[i] = __builtin_bit_cast(v8h, w);
-            }
+            for (int i = 0; i < TM; ++i) fa[i] = __builtin_bit_cast(v8h, R[par][i]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int n = min(nw + j * 32 + l32, a.N - 1);
-                uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(wo + (size_t)n * a.ldwo + kk)
-                                         : make_uint4(0, 0, 0, 0);
-                fb[j] = __builtin_bit_cast(v8h, w);
-            }
+            for (int j = 0; j < TN; ++j) fb[j] = __builtin_bit_cast(v8h, R[par][TM + j]);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) read_frag(par, f, tgt, tks);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], cf[i][j], 0, 0, 0);
         }
-        __half* __restrict__ y = static_cast<__half*>(a.y);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int n = nw + j * 32 + l32;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int t = tw + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (t < a.T && n < a.N) y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
-                }
-            }
     }
+
+    wait_vm<0>();                          // drain the look-ahead DMA before the wave ends
+    __half* __restrict__ y = static_cast<__half*>(a.y);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int n = nw + j * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int t = tw + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                if (t < a.T && n < a.N) y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+            }
+        }
 }
 
-template <int BITS, int BM, int BN, int WM, int WN, int BKB, bool RAW>
+template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, bool RAW>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_kernel<BITS, BM, BN, WM, WN, BKB, RAW>), dim3(tiles), dim3(kThreads), 0,
-                       stream, a);
+    hipLaunchKernelGGL((gemm_kernel<BITS, BM, BN, WM, WN, BKB, NST, OCC, RAW>), dim3(tiles),
+                       dim3(kThreads), 0, stream, a);
     return hipGetLastError();
 }
 
 template <int BITS, bool RAW>
 hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
-    return launch_cfg<BITS, 128, 128, 2, 2, 64, RAW>(a, stream);
+    // 128 x 128 tiles, 128-byte stage rows (full cache lines per row), two stage buffers,
+    // two workgroups per CU.
+    return launch_cfg<BITS, 128, 128, 2, 2, 128, 2, 2, RAW>(a, stream);
 }
 
 // one wave per output channel; lanes stride over the packed row
