@@ -22,6 +22,8 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, MI355X data sheet (5.0 POP/s)
 PEAK_HBM_GBS = 8000.0
+# profiles/gemm_kernel_llama7b_up.md: (112406 KiB * 2.0 + 46389 KiB * 1.0) * 1024
+TRAFFIC_BYTES = {"llama7b_up": int((112406 * 2.0 + 46389) * 1024)}
 
 
 def _event_ms(fn, iters, torch):
@@ -64,6 +66,9 @@ def main():
     ap.add_argument("--workload", default="llama7b_up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain device-to-device copy of 256 MiB (a kernel of known "
+                         "traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU only: the layer shards over tokens with no "
@@ -112,6 +117,14 @@ def main():
                                                       bits, w_q, w_scale, w_red, w_out, out=y), it, torch)
     ms_layer_ev = _event_ms(step, it, torch)
 
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_fp16 = None
     if not args.no_fp16:
         wf = (torch.randn((N, K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
@@ -143,7 +156,11 @@ def main():
                          "frac": quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel (INT GEMM + dequant + outlier GEMM)",
                      "achieved": gemm_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                     "frac": gemm_tops / PEAK_INT8_TOPS, "traffic": None,
+                     "frac": gemm_tops / PEAK_INT8_TOPS,
+                     # HBM-side bytes per launch from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+                     # (factors from a 256 MiB copy; see profiles/), measured for the default
+                     # workload only
+                     "traffic": TRAFFIC_BYTES.get(args.workload),
                      "algorithmic_ops_per_launch": ops_int},
     }
     if not args.no_cpu_baseline:
