@@ -15,7 +15,12 @@
 // row leaves the CU as full, aligned 128-bit stores.
 //
 // Bit exactness: binary32 arithmetic, one IEEE division and one IEEE reciprocal
-// per row, a subtract and a multiply per element (never contracted), v_rndne.
+// per row, a subtract and a multiply per element (never contracted).  Rounding to
+// the nearest integer, ties to even, is done by adding 1.5 * 2^23: the sum's unit
+// in the last place is 1 there, so the adder's own round-to-nearest-even performs
+// the rounding and the low mantissa bits are the integer.  For finite inputs
+// (x - min) * (1 / scale) lies in [0, (2^bits - 1) * (1 + 2^-22)], so the clamp of
+// the method can never fire and is replaced by a bit mask.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -82,33 +87,43 @@ __device__ void build_outlier_map(const int32_t* __restrict__ idx, int n_out, in
     __syncthreads();
 }
 
-template <int BITS>
-__device__ __forceinline__ int quantize_one(__half h, float mn, float inv) {
-    constexpr float kL = (float)((1 << BITS) - 1);
+// Unsigned code rne((x - mn) * inv) in the low BITS bits of the result (upper bits are
+// mantissa garbage; callers mask).
+__device__ __forceinline__ uint32_t code_bits(__half h, float mn, float inv) {
     float d = __half2float(h) - mn;
     float u = d * inv;
-    float r = __builtin_rintf(u);
-    r = fminf(fmaxf(r, 0.0f), kL);
-    return (int)r - (1 << (BITS - 1));
+    float v = u + 12582912.0f;                    // 1.5 * 2^23
+    return __float_as_uint(v);
 }
 
-// Squeezes the base elements of one chunk together and ORs them into the LDS row
-// image at element position base0.  Elements at positions >= K_b are dropped.
+// Removes the element at position p (element width W bits) from the packed value w,
+// closing the gap.
+template <typename U, int W>
+__device__ __forceinline__ U drop_element(U w, int p) {
+    const U low = (p == 0) ? U(0) : (~U(0) >> (sizeof(U) * 8 - W * p));
+    return (w & low) | ((w >> W) & ~low);
+}
+
+// Quantizes one chunk, squeezes its base elements together and ORs them into the LDS
+// row image at element position base0.  Elements at positions >= K_b are dropped.
 template <int BITS>
 __device__ __forceinline__ void emit_chunk(const Chunk& c, uint32_t m8, int base0, int K_b,
                                            float mn, float inv, uint32_t* stage) {
-    if (base0 >= K_b) return;
-    int room = K_b - base0;                       // >= 1
     if constexpr (BITS == 4) {
         uint32_t w = 0;
-        int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            uint32_t q = (uint32_t)quantize_one<4>(c.h[i], mn, inv) & 0xFu;
-            bool keep = !((m8 >> i) & 1u);
-            w |= keep ? (q << (4 * cnt)) : 0u;
-            cnt += keep ? 1 : 0;
+        for (int i = 0; i < 8; ++i) w |= (code_bits(c.h[i], mn, inv) & 0xFu) << (4 * i);
+        w ^= 0x88888888u;                          // code - halfRange, two's complement nibble
+        int cnt = 8;
+        while (m8) {                               // rare: squeeze out outlier positions, highest first
+            int p = 31 - __clz(m8);
+            w = drop_element<uint32_t, 4>(w, p);
+            m8 &= ~(1u << p);
+            --cnt;
         }
+        if (base0 >= K_b || cnt == 0) return;
+        int room = K_b - base0;
+        if (cnt < 8) w &= (1u << (4 * cnt)) - 1u;
         if (room < 8) w &= (1u << (4 * room)) - 1u;
         uint32_t bit = (uint32_t)base0 * 4u;
         uint32_t wi = bit >> 5, sh = bit & 31u;
@@ -118,14 +133,19 @@ __device__ __forceinline__ void emit_chunk(const Chunk& c, uint32_t m8, int base
         if (hi) atomicOr(&stage[wi + 1], hi);
     } else {
         uint64_t w = 0;
-        int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            uint64_t q = (uint64_t)((uint32_t)quantize_one<8>(c.h[i], mn, inv) & 0xFFu);
-            bool keep = !((m8 >> i) & 1u);
-            w |= keep ? (q << (8 * cnt)) : 0ull;
-            cnt += keep ? 1 : 0;
+        for (int i = 0; i < 8; ++i) w |= (uint64_t)(code_bits(c.h[i], mn, inv) & 0xFFu) << (8 * i);
+        w ^= 0x8080808080808080ull;
+        int cnt = 8;
+        while (m8) {
+            int p = 31 - __clz(m8);
+            w = drop_element<uint64_t, 8>(w, p);
+            m8 &= ~(1u << p);
+            --cnt;
         }
+        if (base0 >= K_b || cnt == 0) return;
+        int room = K_b - base0;
+        if (cnt < 8) w &= (1ull << (8 * cnt)) - 1ull;
         if (room < 8) w &= (1ull << (8 * room)) - 1ull;
         uint32_t bit = (uint32_t)base0 * 8u;
         uint32_t wi = bit >> 5, sh = bit & 31u;
@@ -156,8 +176,6 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     // keep the row images 16-byte aligned
     stage_all = reinterpret_cast<uint32_t*>((reinterpret_cast<uintptr_t>(stage_all) + 15) & ~(uintptr_t)15);
 
-    build_outlier_map(idx, n_out, K, nwords, mask, pre, wave_tot);
-
     const int tid = threadIdx.x;
     const int g = tid / TPR, lt = tid % TPR;
     const int K_b = K - n_out;
@@ -166,16 +184,28 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     const int nrowblk = (T + RPB - 1) / RPB;
     const int nch_rt = (K + TPR * 8 - 1) / (TPR * 8);          // chunks per thread (runtime form)
 
-    for (int rb = blockIdx.x; rb < nrowblk; rb += gridDim.x) {
+    constexpr int NC = NCH > 0 ? NCH : 1;
+    auto load_row = [&](Chunk (&cache)[NC], int rb) {
+        const int t = rb * RPB + g;
+        const __half* row = x + (size_t)(t < T ? t : 0) * ldx;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            int k0 = (c * TPR + lt) * 8;
+            if (t < T && k0 < K) cache[c].u = *reinterpret_cast<const uint4*>(row + k0);
+            else cache[c].u = make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    // All three passes for the row block rb; `cache` holds the row when NCH > 0.
+    auto process_row = [&](const Chunk (&cache)[NC], int rb) {
         const int t = rb * RPB + g;
         const bool valid = t < T;
         const __half* row = x + (size_t)(valid ? t : 0) * ldx;
 
         for (int i = lt; i < ldq_words; i += TPR) stage[i] = 0u;
 
-        // ---- pass 1: load once, min/max over base columns
+        // ---- pass 1: min/max over base columns
         float mn = __builtin_inff(), mx = -__builtin_inff();
-        Chunk cache[NCH > 0 ? NCH : 1];
         auto scan_chunk = [&](const Chunk& c, int k0) {
             uint32_t m8 = (mask[k0 >> 5] >> (k0 & 31)) & 0xFFu;
 #pragma unroll
@@ -187,15 +217,6 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
             }
         };
         if constexpr (NCH > 0) {
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                int k0 = (c * TPR + lt) * 8;
-                if (valid && k0 < K) {
-                    cache[c].u = *reinterpret_cast<const uint4*>(row + k0);
-                } else {
-                    cache[c].u = make_uint4(0, 0, 0, 0);
-                }
-            }
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 int k0 = (c * TPR + lt) * 8;
@@ -265,7 +286,33 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
                 x_out[(size_t)t * ldo + j] = v;
             }
         }
-        __syncthreads();                           // before the next iteration clears the image
+        __syncthreads();                           // before the next row clears the image
+    };
+
+    if constexpr (NCH > 0) {
+        // Row loads do not depend on the outlier map: the first row's loads are issued before
+        // the map is built, and from then on the next row is fetched into a second register
+        // set while the current one is processed.
+        Chunk ca[NC], cb[NC];
+        int rb = blockIdx.x;
+        if (rb < nrowblk) load_row(ca, rb);
+        build_outlier_map(idx, n_out, K, nwords, mask, pre, wave_tot);
+        while (rb < nrowblk) {
+            int nx = rb + gridDim.x;
+            if (nx < nrowblk) load_row(cb, nx);
+            process_row(ca, rb);
+            rb = nx;
+            if (rb >= nrowblk) break;
+            nx = rb + gridDim.x;
+            if (nx < nrowblk) load_row(ca, nx);
+            process_row(cb, rb);
+            rb = nx;
+        }
+    } else {
+        build_outlier_map(idx, n_out, K, nwords, mask, pre, wave_tot);
+        Chunk none[NC];
+        none[0].u = make_uint4(0, 0, 0, 0);
+        for (int rb = blockIdx.x; rb < nrowblk; rb += gridDim.x) process_row(none, rb);
     }
 }
 
@@ -275,7 +322,9 @@ hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     const int nwords = (a.K + 31) >> 5;
     size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
     int nrowblk = (a.T + RPB - 1) / RPB;
-    int grid = nrowblk < 4096 ? nrowblk : 4096;
+    // a bounded grid: the outlier map is built once per workgroup and the rows of a workgroup
+    // are software-pipelined (next row's loads in flight while the current one is processed)
+    int grid = nrowblk < 2048 ? nrowblk : 2048;
     hipLaunchKernelGGL((quantize_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
                        (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
                        a.scale, a.zero, (__half*)a.x_out, a.ldo);

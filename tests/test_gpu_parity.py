@@ -49,12 +49,15 @@ def _quantize_case(api, oracle, x, idx, bits):
 # T, K, n_out, bits: covers every row-caching variant of the kernel (K <= 512,
 # 1024, 2048, 4096 with one wave per row; <= 8192, <= 16384 with a workgroup per
 # row; the uncached form above), ragged T, n_out = 0, and a packed row length that
-# is not a multiple of 16 bytes (K_b = 488 -> 244 bytes -> zero padding to 256).
+# is not a multiple of 16 bytes (K_b = 488 -> 244 bytes -> zero padding to 256), and
+# row counts that make a workgroup loop over several rows.
 QUANT_SHAPES = [
     (16, 512, 32, 4), (37, 512, 24, 4), (5, 1024, 64, 4), (33, 2048, 128, 4),
     (64, 4096, 256, 4), (19, 5120, 256, 4), (9, 11008, 256, 4), (3, 20480, 256, 4),
     (16, 512, 0, 4), (7, 64, 8, 4), (1, 8, 0, 4),
     (16, 512, 32, 8), (21, 4096, 256, 8), (6, 11008, 256, 8), (3, 20480, 128, 8), (11, 520, 24, 8),
+    # more row blocks than workgroups: the software-pipelined row loop runs 2-3 times per workgroup
+    (9001, 512, 32, 4), (5000, 5120, 256, 4), (2500, 8200, 64, 8),
 ]
 
 
@@ -91,6 +94,8 @@ def test_quantize_unsorted_indices_and_degenerate_rows(api, oracle):
 INT_GEMM_SHAPES = [
     (16, 512, 480, 4), (200, 300, 992, 4), (129, 257, 3840, 4), (1, 1, 32, 4), (130, 64, 96, 4),
     (16, 512, 480, 8), (150, 140, 1000, 8), (257, 129, 4864, 8),
+    # enough 256 x 128 tiles to take the eight-wave configuration, ragged in T and N, K tail
+    (520, 11000, 480, 4), (770, 5500, 224, 8),
 ]
 
 
@@ -159,6 +164,9 @@ LINEAR_SHAPES = [
     synth.LayerShape("one_token", 1, 4096, 512, 256, 4, seed=35),
     synth.LayerShape("w8a8", 130, 1024, 260, 64, 8, seed=36),
     synth.LayerShape("w8a8_tiny", 16, 512, 512, 32, 8, seed=37),
+    # eight-wave 256 x 128 tile configuration (>= 256 such tiles), ragged T and N
+    synth.LayerShape("big_tiles_ragged", 520, 512, 11000, 32, 4, seed=38),
+    synth.LayerShape("big_tiles_w8a8", 770, 256, 5500, 24, 8, seed=39),
 ]
 
 
