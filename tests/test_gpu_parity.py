@@ -212,25 +212,37 @@ def test_strided_input_and_output(api, oracle):
     assert np.all(yh[:, shp.N:] == -5.0)               # nothing written outside the view
 
 
-def test_full_size_llama7b_up_projection_on_sampled_tokens(api, oracle):
-    """The benchmark workload at full size (T=2048, K=4096, N=11008, 256 outliers):
-    quantization checked in full, accumulators and output on sampled token rows
-    (tokens are independent, so the oracle is run on those rows alone)."""
-    shp = synth.CONFIGS["llama7b_up"]
+FULL_SIZE = ["llama7b_up", "llama7b_down", "llama7b_down_w8a8", "llama13b_qkv_t16",
+             "llama13b_qkv_t128", "llama13b_qkv_t1024", "llama13b_qkv_t4096", "llama70b_up"]
+
+
+@pytest.mark.parametrize("name", FULL_SIZE)
+def test_full_size_workloads_on_sampled_tokens(api, oracle, name):
+    """Every benchmark workload at full size, in the launch configuration bench.py times:
+    quantization checked in full, accumulators and output on sampled token rows (tokens are
+    independent, so the oracle is run on those rows alone)."""
+    import torch
+    shp = synth.CONFIGS[name]
+    bits = shp.bits
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
-    xq, scale, zero, x_out = api.quik_quantize(d["x"], d["idx"], 4)
-    y = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
-    acc = api.quik_int_gemm(xq, d["w_q"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, bits)
+    xq, scale, zero, x_out = api.quik_quantize(d["x"], d["idx"], bits)
+    y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
-    q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, 4)
-    assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, q, 4, xq.shape[1]))
+    q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, bits)
+    assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, q, bits, xq.shape[1]))
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
     assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32))
     assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16))
-    sel = np.array([0, 1, 31, 32, 127, 128, 777, 1023, 1024, 1500, 2046, 2047])
-    ref = oracle.linear(inp.x[sel], inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
-    assert np.array_equal(acc.cpu().numpy()[sel], ref.acc)
-    ok, worst = output_within_tolerance(y.cpu().numpy()[sel], ref.y)
+    T = shp.T
+    sel = np.unique(np.array([0, 1, 31, 32, 127, 128, 255, 256, T // 2 - 1, T // 2, T - 2, T - 1]) % T)
+    ref = oracle.linear(inp.x[sel], inp.outlier_idx, bits, inp.w_packed, inp.w_scale, inp.w_out)
+    ok, worst = output_within_tolerance(y[torch.from_numpy(sel).cuda()].cpu().numpy(), ref.y)
     assert ok, worst
+    del y
+    # raw accumulators of the sampled rows (the hook is run on those rows only: the int32
+    # matrix of the largest workload would not be worth its 470 MB)
+    acc = api.quik_int_gemm(xq[torch.from_numpy(sel).cuda()].contiguous(), d["w_q"], shp.K_b, bits)
+    _sync()
+    assert np.array_equal(acc.cpu().numpy(), ref.acc)
