@@ -394,6 +394,219 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         }
 }
 
+// Small-T variant (T <= 32*TM): the layer is bound by streaming the packed weights, not by the
+// matrix cores, so the point is many bytes in flight per CU.  A workgroup owns a (32*TM) x (32*TN)
+// output tile and its four waves split K: every wave streams its own quarter of the weight rows
+// (and of the activations) through a private global->LDS ring, with no workgroup barrier in the main
+// loop (a wave waits only for its own DMA).  The four partial INT32 accumulators are summed exactly
+// through LDS; wave 0 then dequantizes, adds the fp16 outlier product (operands read straight from
+// global memory: they are tiny) and stores.
+template <int BITS, int TM, int TN, int NST, bool RAW>
+__global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
+    constexpr int BKB = 128, CPR = 8, RPI = 8;           // 128-byte stage rows, 8 rows per DMA instr
+    constexpr int BM = 32 * TM, BN = 32 * TN;
+    constexpr int A_INSTR = BM / RPI, B_INSTR = BN / RPI; // per wave (each wave loads its own tiles)
+    constexpr int LPS = A_INSTR + B_INSTR;
+    constexpr int KSUB = BKB / 32;
+    constexpr int SHIFT = (BITS == 4) ? 8 : 0;
+    constexpr int A_BYTES = BM * BKB, B_BYTES = BN * BKB, ST_BYTES = A_BYTES + B_BYTES;
+    constexpr int NF = TM + TN;
+    constexpr int HALVES = (BITS == 4) ? 2 : 1;
+    constexpr int RING = NST * ST_BYTES;                  // per wave
+    constexpr int RED_BYTES = TM * TN * 16 * 64 * 4;      // one wave's accumulators
+    constexpr int LDS_BYTES = (4 * RING > 3 * RED_BYTES) ? 4 * RING : 3 * RED_BYTES;
+    static_assert((NST - 1) * LPS < 64, "vmcnt range");
+
+    __shared__ __align__(1024) uint8_t lds[LDS_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+
+    const int tiles_m = (a.T + BM - 1) / BM;
+    const int t0 = (blockIdx.x % tiles_m) * BM, n0 = (blockIdx.x / tiles_m) * BN;
+
+    const int row_bytes = a.K_b * BITS / 8;
+    const int nk = (row_bytes + BKB - 1) / BKB;
+    // this wave's K range, in stages
+    const int s_begin = (int)((long)nk * wave / 4), s_end = (int)((long)nk * (wave + 1) / 4);
+
+    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * a.ldq, (size_t)(a.T - t0) * a.ldq);
+    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * a.ldw, (size_t)(a.N - n0) * a.ldw);
+
+    uint8_t* ring = lds + wave * RING;
+    const uint32_t ring_addr = lds_addr(ring);
+    const int lrow = lane / CPR, lslot = lane % CPR;
+
+    auto issue = [&](int s) {            // stage s of this wave's range (or beyond: all lanes out of range)
+        const uint32_t sb = (uint32_t)((s - s_begin) % NST) * ST_BYTES;
+        const int koff = s * BKB;
+        const bool live = s < s_end;
+#pragma unroll
+        for (int i = 0; i < A_INSTR; ++i) {
+            int row = i * RPI + lrow;
+            int c = (lslot ^ swz<BKB>(row)) * 16;
+            uint32_t vo = (live && koff + c < a.ldq) ? (uint32_t)(row * a.ldq + koff + c) : kOob;
+            dma16(rA, ring_addr + sb + i * 1024, vo, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_INSTR; ++i) {
+            int row = i * RPI + lrow;
+            int c = (lslot ^ swz<BKB>(row)) * 16;
+            uint32_t vo = (live && koff + c < a.ldw) ? (uint32_t)(row * a.ldw + koff + c) : kOob;
+            dma16(rB, ring_addr + sb + A_BYTES + i * 1024, vo, 0);
+        }
+    };
+
+    uint32_t rd[NF][KSUB];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        int r = (f < TM) ? (f * 32 + l32) : ((f - TM) * 32 + l32);
+        uint32_t base = (f < TM ? 0 : A_BYTES) + r * BKB;
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) rd[f][ks] = base + (((ks * 2 + g) ^ swz<BKB>(r)) << 4);
+    }
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s_begin + s);
+
+    for (int s = s_begin; s < s_end; ++s) {
+        issue(s + NST - 1);
+        wait_vm<(NST - 1) * LPS>();                       // stage s has landed (this wave's own loads)
+        const uint8_t* st = ring + ((s - s_begin) % NST) * ST_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) {
+            v4i ua[TM][HALVES], ub[TN][HALVES];
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                const uint4 w = *reinterpret_cast<const uint4*>(st + rd[f][ks]);
+                v4i* u = (f < TM) ? ua[f] : ub[f - TM];
+                if constexpr (BITS == 4) {
+                    constexpr uint32_t M = 0xF0F0F0F0u;
+                    u[0] = v4i{(int)((w.x << 4) & M), (int)(w.x & M), (int)((w.y << 4) & M), (int)(w.y & M)};
+                    u[1] = v4i{(int)((w.z << 4) & M), (int)(w.z & M), (int)((w.w << 4) & M), (int)(w.w & M)};
+                } else {
+                    u[0] = v4i{(int)w.x, (int)w.y, (int)w.z, (int)w.w};
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < HALVES; ++h)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ua[i][h], ub[j][h], acc[i][j], 0, 0, 0);
+        }
+        // the buffer read here is refilled NST-1 iterations later by this same wave: LDS reads above
+        // have returned (their data fed the MFMAs) before that DMA is issued
+    }
+    wait_vm<0>();
+    __syncthreads();                                      // rings are dead: reuse LDS for the reduction
+
+    // ---- sum the four partial accumulators: waves 1..3 publish, wave 0 adds
+    int* red = reinterpret_cast<int*>(lds);
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    red[(((wave - 1) * TM * TN + i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 0; w < 3; ++w)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc[i][j][r] += red[((w * TM * TN + i * TN + j) * 16 + r) * 64 + lane];
+
+    if constexpr (RAW) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int n = n0 + j * 32 + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int t = t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = acc[i][j][r] >> SHIFT;
+                }
+            }
+        return;
+    } else {
+        // ---- epilogue on wave 0: dequantize, fp16 outlier product from global memory, store
+        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
+        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+        v16f cf[TM][TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            int n = min(n0 + j * 32 + l32, a.N - 1);
+            float sw = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));
+            float wr = a.w_reduced[n];
+            float bv = bias ? __half2float(bias[n]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int t = min(t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3), a.T - 1);
+                    float sa = a.scale[t];
+                    float sh = a.zero[t] + (float)(1 << (BITS - 1)) * sa;
+                    cf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], sa * sw, __builtin_fmaf(sh, wr, bv));
+                }
+        }
+        const __half* __restrict__ xo = static_cast<const __half*>(a.x_out);
+        const __half* __restrict__ wo = static_cast<const __half*>(a.w_out);
+        for (int ko = 0; ko < a.n_out; ko += 16) {
+            const int kk = ko + g * 8;
+            v8h fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                int t = min(t0 + i * 32 + l32, a.T - 1);
+                uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(xo + (size_t)t * a.ldo + kk) : make_uint4(0, 0, 0, 0);
+                fa[i] = __builtin_bit_cast(v8h, w);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int n = min(n0 + j * 32 + l32, a.N - 1);
+                uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(wo + (size_t)n * a.ldwo + kk) : make_uint4(0, 0, 0, 0);
+                fb[j] = __builtin_bit_cast(v8h, w);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], cf[i][j], 0, 0, 0);
+        }
+        __half* __restrict__ y = static_cast<__half*>(a.y);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int n = n0 + j * 32 + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int t = t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (t < a.T && n < a.N) y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+                }
+            }
+    }
+}
+
+
 template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, bool RAW>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
@@ -402,8 +615,20 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <int BITS, int TM, int TN, int NST, bool RAW>
+hipError_t launch_skinny(const GemmArgs& a, hipStream_t stream) {
+    int tiles = ((a.T + 32 * TM - 1) / (32 * TM)) * ((a.N + 32 * TN - 1) / (32 * TN));
+    hipLaunchKernelGGL((gemm_skinny<BITS, TM, TN, NST, RAW>), dim3(tiles), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
 template <int BITS, bool RAW>
 hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
+    // Few tokens: weight streaming dominates.  Up to 32 tokens the K-split kernel; up to 128 tokens
+    // small tiles with a deeper stage ring so that enough workgroups and bytes are in flight.
+    if (a.T <= 32) return launch_skinny<BITS, 1, 1, 2, RAW>(a, stream);
+    if (a.T <= 64) return launch_cfg<BITS, 64, 64, 2, 2, 128, 4, 2, 0, RAW>(a, stream);
+    if (a.T <= 128) return launch_cfg<BITS, 128, 64, 2, 2, 128, 2, 2, 0, RAW>(a, stream);
     // 128-byte stage rows (a full cache line per row per stage), two stage buffers.
     // Large problems: 256 x 128 tiles shared by eight waves (one workgroup per CU) move 25 % fewer
     // operand bytes per MFMA through L1/LDS than two independent 128 x 128 workgroups.  They need

@@ -96,6 +96,10 @@ INT_GEMM_SHAPES = [
     (16, 512, 480, 8), (150, 140, 1000, 8), (257, 129, 4864, 8),
     # enough 256 x 128 tiles to take the eight-wave configuration, ragged in T and N, K tail
     (520, 11000, 480, 4), (770, 5500, 224, 8),
+    # small-T paths: K-split kernel (T <= 32; K shorter than four stages, ragged N), 64 x 64 and
+    # 128 x 64 tile configurations
+    (32, 100, 160, 4), (7, 333, 2432, 4), (20, 95, 4864, 8), (50, 200, 992, 4), (64, 130, 480, 8),
+    (100, 300, 480, 4), (128, 70, 1000, 8),
 ]
 
 
@@ -167,6 +171,11 @@ LINEAR_SHAPES = [
     # eight-wave 256 x 128 tile configuration (>= 256 such tiles), ragged T and N
     synth.LayerShape("big_tiles_ragged", 520, 512, 11000, 32, 4, seed=38),
     synth.LayerShape("big_tiles_w8a8", 770, 256, 5500, 24, 8, seed=39),
+    # small-T paths
+    synth.LayerShape("t32_ragged_n", 32, 1024, 333, 64, 4, seed=40),
+    synth.LayerShape("t5_w8a8", 5, 512, 200, 16, 8, seed=44),
+    synth.LayerShape("t100", 100, 1024, 330, 64, 4, seed=45),
+    synth.LayerShape("t60_w8a8", 60, 768, 190, 40, 8, seed=46),
 ]
 
 
