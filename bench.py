@@ -58,6 +58,43 @@ def cpu_baseline(inp, shp, budget_s=15.0):
                       f"whole layer incl. weight unpack, {dt:.2f} s"}
 
 
+def run_sweep(args, shp, torch, api, synth):
+    """Layer time against token count or outlier count (the paper's appendix sweeps), with the
+    FP16 GEMM of the same shape beside it.  One JSON object; not the headline metric."""
+    import dataclasses
+    dev = "cuda"
+    rows = []
+    if args.sweep == "tokens":
+        points = [dataclasses.replace(shp, T=t) for t in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024,
+                                                          2048, 4096, 8192)]
+    else:
+        points = [dataclasses.replace(shp, n_out=n) for n in (0, 64, 128, 256, 512, 1024)]
+    for p in points:
+        inp = synth.make_inputs(p)
+        x = torch.from_numpy(inp.x).to(dev)
+        idx = torch.from_numpy(inp.outlier_idx).to(dev) if p.n_out else None
+        w_q = torch.from_numpy(inp.w_packed).to(dev)
+        w_scale = torch.from_numpy(inp.w_scale).to(dev)
+        w_out = torch.from_numpy(inp.w_out).to(dev) if p.n_out else None
+        w_red = api.quik_weight_reduce(w_q, w_scale, p.K_b, p.bits)
+        ws = torch.empty(api.quik_workspace_bytes(p.T, p.K, p.N, p.n_out, p.bits), dtype=torch.uint8,
+                         device=dev)
+        y = torch.empty((p.T, p.N), dtype=torch.float16, device=dev)
+        step = lambda: api.quik_linear(x, idx, p.bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
+        for _ in range(args.warmup):
+            step()
+        ms = _event_ms(step, args.steps, torch)
+        wf = (torch.randn((p.N, p.K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
+        for _ in range(5):
+            torch.nn.functional.linear(x, wf)
+        ms16 = _event_ms(lambda: torch.nn.functional.linear(x, wf), args.steps, torch)
+        rows.append({"T": p.T, "n_out": p.n_out, "quik_ms": ms, "fp16_ms": ms16, "speedup": ms16 / ms,
+                     "tops": 2.0 * p.T * p.K * p.N / (ms * 1e-3) / 1e12})
+        del wf, x, w_q, y, ws
+    return {"sweep": args.sweep, "workload": f"{shp.name}: K={shp.K} N={shp.N} bits={shp.bits}",
+            "steps": args.steps, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,6 +103,13 @@ def main():
     ap.add_argument("--workload", default="llama7b_up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay a captured HIP graph holding one step instead of launching every "
+                         "step through the binding (measured: no faster here, direct launches "
+                         "already keep the queue full)")
+    ap.add_argument("--sweep", choices=["tokens", "outliers"], default=None,
+                    help="instead of the headline line, time the layer over a sweep of token counts "
+                         "(1..8192) or outlier counts (0..1024) on the workload's K and N")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (a kernel of known "
                          "traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
@@ -84,6 +128,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     shp = synth.CONFIGS[args.workload]
+    if args.sweep:
+        print(json.dumps(run_sweep(args, shp, torch, api, synth)))
+        return
     inp = synth.make_inputs(shp)
     dev = "cuda"
     x = torch.from_numpy(inp.x).to(dev)
@@ -99,12 +146,27 @@ def main():
     def step():
         api.quik_linear(x, idx, bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
 
+    # --graph: the timed region replays a HIP graph that holds one step (both launches, captured
+    # from the same C-ABI call on the capture stream).
+    graph = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+    run = graph.replay if graph is not None else step
     for _ in range(args.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -124,6 +186,18 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    # fusion ablation (Section 3.4, kernel versions 1-3), same buffers
+    ws_abl = torch.empty(api.quik_ablation_workspace_bytes(T, K, N, n_out, bits), dtype=torch.uint8,
+                         device=dev)
+    ablation = {}
+    for version in (1, 2, 3):
+        fn = lambda v=version: api.quik_linear_ablation(v, x, idx, bits, w_q, w_scale, w_red, w_out,
+                                                        out=y, workspace=ws_abl)
+        for _ in range(5):
+            fn()
+        ablation[f"v{version}"] = _event_ms(fn, it, torch)
+    del ws_abl
 
     ms_fp16 = None
     if not args.no_fp16:
@@ -145,12 +219,15 @@ def main():
         "dtype": f"int{bits} operands on int8 MFMA, int32 accumulate, fp16 outliers",
         "data": "synthetic",
         "config": {"workload": f"{shp.name}: T={T} K={K} N={N} n_out={n_out} bits={bits}",
-                   "launches_per_step": 2},
+                   "launches_per_step": 2, "hip_graph_replay": graph is not None},
         "frac_int8_mfma_peak_layer": tops / PEAK_INT8_TOPS,
         "speedup_vs_fp16_gemm": (ms_fp16 / ms_layer_ev) if ms_fp16 else None,
         "fp16_gemm_ms": ms_fp16,
         "kernels_ms": {"quik_quantize": ms_quant, "quik_gemm_dequant": ms_gemm,
                        "quik_linear_events": ms_layer_ev},
+        "fusion_ablation_ms": {"v1_unfused_quant_unfused_dequant": ablation["v1"],
+                               "v2_fused_quant_unfused_dequant": ablation["v2"],
+                               "v3_fused_quant_fused_dequant": ablation["v3"]},
         "quantize_hbm": {"algorithmic_bytes": quant_bytes,
                          "achieved_GBs": quant_bytes / (ms_quant * 1e-3) / 1e9,
                          "frac": quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS},

@@ -175,6 +175,27 @@ int quik_linear(const void *x, int T, int K, int ldx,
                 void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Fusion ablation of Section 3.4 ("Performance Impact", the kernel versions 1-3): the same layer
+ * with its stages left unfused, for measuring what the fusions buy.
+ *   version 1: unfused quantization (separate passes: move the outlier part, move the base part,
+ *              per-token minimum, per-token maximum, quantize) and unfused dequantization
+ *              (INTmatmul writes INT32 accumulators, FPmatmul writes an fp32 matrix, a last
+ *              elementwise pass dequantizes and adds them);
+ *   version 2: the fused quantization kernel, unfused dequantization;
+ *   version 3: quik_linear itself.
+ * Arguments as for quik_linear; `workspace` must hold quik_ablation_workspace_bytes(...) bytes
+ * (it additionally stages the fp16 base part, the accumulators and the outlier product).
+ * Packed activations, scale and zero are bit-identical to quik_quantize's; the output meets the
+ * same error bar as quik_linear's (summation order differs).
+ */
+size_t quik_ablation_workspace_bytes(int T, int K, int N, int n_out, int bits);
+int quik_linear_ablation(int version, const void *x, int T, int K, int ldx,
+                         const int32_t *outlier_idx, int n_out, int bits,
+                         const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
+                         const void *w_out, int ldwo, const void *bias, int N,
+                         void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Host-side validator for an outlier index list (HOST pointer): returns QUIK_OK
  * if all n_out entries are unique and inside [0, K), QUIK_EINVAL otherwise.
  */

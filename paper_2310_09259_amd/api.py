@@ -52,6 +52,11 @@ def load() -> C.CDLL:
         lib.quik_linear.restype = i
         lib.quik_linear.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
                                     C.c_size_t, vp]
+        lib.quik_ablation_workspace_bytes.restype = C.c_size_t
+        lib.quik_ablation_workspace_bytes.argtypes = [i, i, i, i, i]
+        lib.quik_linear_ablation.restype = i
+        lib.quik_linear_ablation.argtypes = [i, vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
+                                             C.c_size_t, vp]
         lib.quik_check_outlier_idx_host.restype = i
         lib.quik_check_outlier_idx_host.argtypes = [vp, i, i]
         _lib = lib
@@ -186,3 +191,44 @@ def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, bias=
         workspace.numel(), _stream())
     _check(rc, "quik_linear")
     return y
+
+
+def quik_ablation_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int) -> int:
+    return load().quik_ablation_workspace_bytes(T, K, N, n_out, bits)
+
+
+def quik_linear_ablation(version: int, x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out,
+                         bias=None, out=None, workspace=None):
+    """The layer with unfused stages (version 1 or 2; 3 = quik_linear).  Returns (y, workspace)."""
+    x = _dev(x, torch.float16, "x")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, K = x.shape
+    N = w_q.shape[0]
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    need = quik_ablation_workspace_bytes(T, K, N, n_out, bits)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
+    rc = load().quik_linear_ablation(
+        version, _ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits,
+        _ptr(w_q), w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None,
+        w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
+        workspace.numel(), _stream())
+    _check(rc, "quik_linear_ablation")
+    return y, workspace
+
+
+def workspace_views(workspace, T: int, K: int, n_out: int, bits: int):
+    """Views (xq, scale, zero, x_out) into a workspace filled by quik_linear or
+    quik_linear_ablation, following the layout documented for quik_workspace_bytes."""
+    def up256(v):
+        return (v + 255) & ~255
+    ldq = quik_packed_row_bytes(K - n_out, bits)
+    o_scale = up256(T * ldq)
+    o_zero = o_scale + up256(T * 4)
+    o_xout = o_zero + up256(T * 4)
+    xq = workspace[: T * ldq].view(T, ldq)
+    scale = workspace[o_scale: o_scale + T * 4].view(torch.float32)
+    zero = workspace[o_zero: o_zero + T * 4].view(torch.float32)
+    x_out = workspace[o_xout: o_xout + T * n_out * 2].view(torch.float16).view(T, n_out)
+    return xq, scale, zero, x_out

@@ -188,6 +188,91 @@ int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx
                              w_scale, w_reduced, w_out, ldwo, bias, N, y, ldy, stream);
 }
 
+namespace {
+struct AblationLayout {
+    WorkspaceLayout base;
+    size_t x_base, row_min, row_max, acc, result_fp, total;
+    int ldb;
+};
+bool ablation_layout(int T, int K, int N, int n_out, int bits, AblationLayout* w) {
+    if (N <= 0 || !workspace_layout(T, K, n_out, bits, &w->base)) return false;
+    const int K_b = K - n_out;
+    w->ldb = (K_b + 7) & ~7;
+    w->x_base = w->base.total;
+    w->row_min = w->x_base + up256((size_t)T * w->ldb * 2);
+    w->row_max = w->row_min + up256((size_t)T * sizeof(float));
+    w->acc = w->row_max + up256((size_t)T * sizeof(float));
+    w->result_fp = w->acc + up256((size_t)T * N * sizeof(int32_t));
+    w->total = w->result_fp + up256((size_t)T * N * sizeof(float));
+    return true;
+}
+}  // namespace
+
+size_t quik_ablation_workspace_bytes(int T, int K, int N, int n_out, int bits) {
+    AblationLayout w;
+    if (!ablation_layout(T, K, N, n_out, bits, &w)) return 0;
+    return w.total;
+}
+
+int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, const int32_t* outlier_idx,
+                         int n_out, int bits, const void* w_q, int ldw, const void* w_scale,
+                         const float* w_reduced, const void* w_out, int ldwo, const void* bias, int N,
+                         void* y, int ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    if (version == 3)
+        return quik_linear(x, T, K, ldx, outlier_idx, n_out, bits, w_q, ldw, w_scale, w_reduced, w_out,
+                           ldwo, bias, N, y, ldy, workspace, workspace_bytes, stream);
+    if (version != 1 && version != 2) return QUIK_EINVAL;
+    AblationLayout w;
+    if (!ablation_layout(T, K, N, n_out, bits, &w)) return QUIK_EINVAL;
+    if (!workspace) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUIK_EALIGN;
+    if (workspace_bytes < w.total) return QUIK_EWORKSPACE;
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    void* xq = base + w.base.xq;
+    float* scale = reinterpret_cast<float*>(base + w.base.scale);
+    float* zero = reinterpret_cast<float*>(base + w.base.zero);
+    void* x_out = base + w.base.x_out;
+    void* x_base = base + w.x_base;
+    float* row_min = reinterpret_cast<float*>(base + w.row_min);
+    float* row_max = reinterpret_cast<float*>(base + w.row_max);
+    int32_t* acc = reinterpret_cast<int32_t*>(base + w.acc);
+    void* result_fp = base + w.result_fp;
+    const int K_b = K - n_out, ldq = w.base.ldq;
+    int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, n_out);
+    if (rc != QUIK_OK) return rc;
+    rc = check_gemm(xq, ldq, x_out, n_out, T, K_b, n_out, bits, w_q, ldw, w_out, ldwo, N);
+    if (rc != QUIK_OK) return rc;
+    if (ldy < N) return QUIK_EINVAL;
+    if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    quik::QuantizeArgs qa{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, n_out};
+    if (version == 1) {
+        if (quik::launch_unfused_quantize(qa, x_base, w.ldb, row_min, row_max, st) != hipSuccess)
+            return QUIK_ELAUNCH;
+    } else {
+        if (quik::launch_quantize(qa, st) != hipSuccess) return QUIK_ELAUNCH;
+    }
+    quik::GemmArgs g{};
+    g.xq = xq; g.ldq = ldq; g.scale = scale; g.zero = zero; g.x_out = x_out; g.ldo = n_out;
+    g.T = T; g.K_b = K_b; g.n_out = n_out; g.bits = bits;
+    g.w_q = w_q; g.ldw = ldw; g.w_scale = w_scale; g.w_reduced = w_reduced;
+    g.w_out = w_out; g.ldwo = ldwo; g.bias = nullptr; g.N = N;
+    // INTmatmul alone: accumulators go to memory
+    g.y = nullptr; g.acc = acc; g.ldacc = N; g.n_out = 0;
+    if (quik::launch_gemm(g, st) != hipSuccess) return QUIK_ELAUNCH;
+    // FPmatmul alone: fp16 result goes to memory
+    const void* rfp = nullptr;
+    if (n_out > 0) {
+        g.n_out = n_out; g.y = result_fp; g.ldy = N; g.acc = nullptr; g.fp_only = 1;
+        if (quik::launch_gemm(g, st) != hipSuccess) return QUIK_ELAUNCH;
+        rfp = result_fp;
+    }
+    // Dequantization + final add as a separate elementwise pass
+    g.fp_only = 0; g.y = y; g.ldy = ldy; g.bias = bias;
+    return quik::launch_dequant_add(g, acc, N, rfp, N, st) == hipSuccess ? QUIK_OK : QUIK_ELAUNCH;
+}
+
 int quik_check_outlier_idx_host(const int32_t* idx, int n_out, int K) {
     if (n_out < 0 || K <= 0 || n_out >= K) return QUIK_EINVAL;
     if (n_out > 0 && !idx) return QUIK_ENULL;

@@ -144,7 +144,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     const int t0 = tile_m * BM, n0 = tile_n * BN;
 
     const int row_bytes = a.K_b * BITS / 8;
-    const int nk_int = (row_bytes + BKB - 1) / BKB;
+    const int nk_int = a.fp_only ? 0 : (row_bytes + BKB - 1) / BKB;
     const int fp_bytes = a.n_out * 2;
     const int nk_fp = RAW ? 0 : (fp_bytes + BKB - 1) / BKB;
     const int nk = nk_int + nk_fp;
@@ -337,6 +337,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             sw[j] = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));   // exact power-of-two fold of the >> SHIFT
             bv[j] = bias ? __half2float(bias[n]) : 0.0f;
             wr[j] = a.w_reduced[n];
+            if (a.fp_only) { sw[j] = 0.0f; bv[j] = 0.0f; wr[j] = 0.0f; }
         }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -389,7 +390,10 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int t = tw + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                if (t < a.T && n < a.N) y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+                if (t < a.T && n < a.N) {
+                    if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = cf[i][j][r];
+                    else y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+                }
             }
         }
 }
@@ -427,7 +431,7 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
     const int t0 = (blockIdx.x % tiles_m) * BM, n0 = (blockIdx.x / tiles_m) * BN;
 
     const int row_bytes = a.K_b * BITS / 8;
-    const int nk = (row_bytes + BKB - 1) / BKB;
+    const int nk = a.fp_only ? 0 : (row_bytes + BKB - 1) / BKB;
     // this wave's K range, in stages
     const int s_begin = (int)((long)nk * wave / 4), s_end = (int)((long)nk * (wave + 1) / 4);
 
@@ -558,6 +562,7 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
             float sw = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));
             float wr = a.w_reduced[n];
             float bv = bias ? __half2float(bias[n]) : 0.0f;
+            if (a.fp_only) { sw = 0.0f; wr = 0.0f; bv = 0.0f; }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -600,7 +605,10 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int t = t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (t < a.T && n < a.N) y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+                    if (t < a.T && n < a.N) {
+                    if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = cf[i][j][r];
+                    else y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+                }
                 }
             }
     }

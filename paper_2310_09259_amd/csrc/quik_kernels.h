@@ -39,6 +39,7 @@ struct GemmArgs {
     int ldy;
     int32_t* acc;         // int32 [T, ldacc] (raw-accumulator mode, y == null)
     int ldacc;
+    int fp_only;          // 1: skip the integer part; y is then fp32 [T, ldy] = outlier product only
 };
 
 struct WeightReduceArgs {
@@ -52,5 +53,11 @@ struct WeightReduceArgs {
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
+
+// unfused stages (fusion ablation)
+hipError_t launch_unfused_quantize(const QuantizeArgs& a, void* x_base, int ldb, float* row_min,
+                                   float* row_max, hipStream_t stream);
+hipError_t launch_dequant_add(const GemmArgs& a, const int32_t* acc, int ldacc, const void* result_fp,
+                              int ldr, hipStream_t stream);
 
 }  // namespace quik
