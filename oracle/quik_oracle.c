@@ -22,7 +22,11 @@
  *     one correctly rounded reciprocal per token; rounding to integer is
  *     round-half-to-even followed by a clamp to [0, 2^bits - 1].
  *   - wReduced[n] = scaleWeight[n] * sum_k wInt[n,k]   (scale folded in).
- *   - packed INT4: two's-complement nibbles, even k in the low nibble.
+ *   - packed INT4: two's-complement nibbles.  The paper only says "packed format"; the
+ *     nibble order is a free choice per operand.  Weights: element 2p in the low nibble of
+ *     byte p.  Activations: element 2p in the HIGH nibble (so that on the target GPU every
+ *     operand register is produced from a packed word with one AND; the GEMM pairs an
+ *     activation's high nibble with a weight's low nibble of the same k and vice versa).
  *   - base (non-outlier) columns keep ascending original order; outlier column
  *     j of xFP / wFP corresponds to FPindices[j].
  *
@@ -88,10 +92,12 @@ int quik_oracle_base_columns(int K, const int32_t *idx, int n_out, int32_t *base
 
 /*
  * Packed storage of quantized values (Section 3.3, "packed format").
- * bits = 4: byte p holds element 2p in bits 0..3 and element 2p+1 in bits 4..7,
- * two's complement.  bits = 8: one signed byte per element.
+ * bits = 4, two's complement nibbles: byte p holds elements 2p and 2p+1;
+ *   even_high = 0 (weights):     element 2p in bits 0..3, element 2p+1 in bits 4..7;
+ *   even_high = 1 (activations): element 2p in bits 4..7, element 2p+1 in bits 0..3.
+ * bits = 8: one signed byte per element (even_high ignored).
  */
-int quik_oracle_pack(const int8_t *q, int64_t rows, int K_b, int bits, uint8_t *packed)
+int quik_oracle_pack(const int8_t *q, int64_t rows, int K_b, int bits, int even_high, uint8_t *packed)
 {
     if (bits == 8) {
         memcpy(packed, q, (size_t)rows * (size_t)K_b);
@@ -100,13 +106,14 @@ int quik_oracle_pack(const int8_t *q, int64_t rows, int K_b, int bits, uint8_t *
     if (bits != 4 || (K_b & 1)) return QO_EINVAL;
     for (int64_t r = 0; r < rows; ++r)
         for (int p = 0; p < K_b / 2; ++p) {
-            int lo = q[r * K_b + 2 * p], hi = q[r * K_b + 2 * p + 1];
+            int e0 = q[r * K_b + 2 * p], e1 = q[r * K_b + 2 * p + 1];
+            int lo = even_high ? e1 : e0, hi = even_high ? e0 : e1;
             packed[r * (K_b / 2) + p] = (uint8_t)((lo & 0xF) | ((hi & 0xF) << 4));
         }
     return QO_OK;
 }
 
-int quik_oracle_unpack(const uint8_t *packed, int64_t rows, int K_b, int bits, int8_t *q)
+int quik_oracle_unpack(const uint8_t *packed, int64_t rows, int K_b, int bits, int even_high, int8_t *q)
 {
     if (bits == 8) {
         memcpy(q, packed, (size_t)rows * (size_t)K_b);
@@ -117,8 +124,9 @@ int quik_oracle_unpack(const uint8_t *packed, int64_t rows, int K_b, int bits, i
         for (int p = 0; p < K_b / 2; ++p) {
             int b = packed[r * (K_b / 2) + p];
             int lo = b & 0xF, hi = (b >> 4) & 0xF;
-            q[r * K_b + 2 * p] = (int8_t)(lo >= 8 ? lo - 16 : lo);
-            q[r * K_b + 2 * p + 1] = (int8_t)(hi >= 8 ? hi - 16 : hi);
+            int e0 = even_high ? hi : lo, e1 = even_high ? lo : hi;
+            q[r * K_b + 2 * p] = (int8_t)(e0 >= 8 ? e0 - 16 : e0);
+            q[r * K_b + 2 * p + 1] = (int8_t)(e1 >= 8 ? e1 - 16 : e1);
         }
     return QO_OK;
 }
@@ -301,7 +309,7 @@ int quik_oracle_linear(const uint16_t *x, int T, int K, const int32_t *idx, int 
     double *rfp = (double *)malloc(sizeof(double) * (size_t)T * N);
     if (!q || !wq || !scale || !zero || !xo || !acc || !wred || !rfp) goto done;
 
-    if ((rc = quik_oracle_unpack(w_packed, N, K_b, bits, wq))) goto done;
+    if ((rc = quik_oracle_unpack(w_packed, N, K_b, bits, 0, wq))) goto done;
     if ((rc = quik_oracle_weight_reduce(wq, w_scale, N, K_b, wred))) goto done;
     if ((rc = quik_oracle_quantize(x, T, K, idx, n_out, bits, q, scale, zero, xo, NULL))) goto done;
     if ((rc = quik_oracle_fp_matmul(xo, w_out, T, N, n_out, rfp))) goto done;

@@ -82,21 +82,24 @@ def base_columns(K: int, idx: np.ndarray) -> np.ndarray:
     return base[:nb].copy()
 
 
-def pack(q: np.ndarray, bits: int) -> np.ndarray:
+def pack(q: np.ndarray, bits: int, activations: bool = False) -> np.ndarray:
+    """Packed storage.  ``activations`` selects the activation nibble order (element 2p in the
+    high nibble); the default is the weight order (element 2p in the low nibble)."""
     q = np.ascontiguousarray(q, dtype=np.int8)
     rows, K_b = q.shape
     out = np.empty((rows, K_b * bits // 8), np.uint8)
-    _chk(_load().quik_oracle_pack(_p(q), C.c_int64(rows), K_b, bits, _p(out)), "pack")
+    _chk(_load().quik_oracle_pack(_p(q), C.c_int64(rows), K_b, bits, int(activations), _p(out)), "pack")
     return out
 
 
-def unpack(packed: np.ndarray, K_b: int, bits: int) -> np.ndarray:
+def unpack(packed: np.ndarray, K_b: int, bits: int, activations: bool = False) -> np.ndarray:
     packed = np.ascontiguousarray(packed, dtype=np.uint8)
     rows = packed.shape[0]
     if packed.shape[1] != K_b * bits // 8:
         raise ValueError("packed row length does not match K_b and bits")
     out = np.empty((rows, K_b), np.int8)
-    _chk(_load().quik_oracle_unpack(_p(packed), C.c_int64(rows), K_b, bits, _p(out)), "unpack")
+    _chk(_load().quik_oracle_unpack(_p(packed), C.c_int64(rows), K_b, bits, int(activations), _p(out)),
+         "unpack")
     return out
 
 

@@ -61,7 +61,7 @@ def test_hand_worked_example_of_algorithm_1(oracle):
     assert r.scale.tolist() == g["scale"]
     assert r.zero.tolist() == g["zero"]
     assert r.q[0].tolist() == g["q"]
-    assert oracle.pack(r.q, 4)[0].tolist() == g["xq_bytes"]
+    assert oracle.pack(r.q, 4, activations=True)[0].tolist() == g["xq_bytes"]
     assert r.x_out[0].astype(np.float32).tolist() == g["x_out"]
     assert r.w_reduced.tolist() == g["w_reduced"]
     assert r.acc[0].tolist() == g["acc"]
@@ -105,6 +105,11 @@ def test_pack_known_bytes_and_round_trip(oracle):
     assert unp.min() == -8 and unp.max() == 7
     assert unp[0].tolist() == _unpack_nibbles_py(allbytes[0])
     assert np.array_equal(oracle.pack(unp, 4), allbytes)
+    # activation order: element 2p in the high nibble
+    assert oracle.pack(q, 4, activations=True)[0].tolist() == [0x87, 0xFF, 0x12, 0x08]
+    unp_a = oracle.unpack(allbytes, 512, 4, activations=True)
+    assert unp_a[0, 0::2].tolist() == unp[0, 1::2].tolist() and unp_a[0, 1::2].tolist() == unp[0, 0::2].tolist()
+    assert np.array_equal(oracle.pack(unp_a, 4, activations=True), allbytes)
     q8 = np.arange(-128, 128, dtype=np.int8).reshape(2, 128)
     assert np.array_equal(oracle.unpack(oracle.pack(q8, 8), 128, 8), q8)
     assert np.array_equal(oracle.pack(q8, 8).view(np.int8), q8)

@@ -43,7 +43,7 @@ def output_within_tolerance(y_gpu: np.ndarray, y_ref: np.ndarray, rel: float = 5
 
 def expected_xq(oracle, q: np.ndarray, bits: int, ldq: int) -> np.ndarray:
     """Oracle codes -> the packed, zero-padded byte image the library must write."""
-    packed = oracle.pack(q, bits)
+    packed = oracle.pack(q, bits, activations=True)
     out = np.zeros((q.shape[0], ldq), np.uint8)
     out[:, : packed.shape[1]] = packed
     return out
