@@ -76,11 +76,11 @@ def run_sweep(args, shp, torch, api, synth):
         w_q = torch.from_numpy(inp.w_packed).to(dev)
         w_scale = torch.from_numpy(inp.w_scale).to(dev)
         w_out = torch.from_numpy(inp.w_out).to(dev) if p.n_out else None
-        w_red = api.quik_weight_reduce(w_q, w_scale, p.K_b, p.bits)
+        w_red, w_cs = api.quik_weight_reduce(w_q, w_scale, p.K_b, p.bits)
         ws = torch.empty(api.quik_workspace_bytes(p.T, p.K, p.N, p.n_out, p.bits), dtype=torch.uint8,
                          device=dev)
         y = torch.empty((p.T, p.N), dtype=torch.float16, device=dev)
-        step = lambda: api.quik_linear(x, idx, p.bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
+        step = lambda: api.quik_linear(x, idx, p.bits, w_q, w_scale, w_red, w_cs, w_out, out=y, workspace=ws)
         for _ in range(args.warmup):
             step()
         ms = _event_ms(step, args.steps, torch)
@@ -138,13 +138,13 @@ def main():
     w_q = torch.from_numpy(inp.w_packed).to(dev)
     w_scale = torch.from_numpy(inp.w_scale).to(dev)
     w_out = torch.from_numpy(inp.w_out).to(dev) if shp.n_out else None
-    w_red = api.quik_weight_reduce(w_q, w_scale, shp.K_b, shp.bits)
+    w_red, w_cs = api.quik_weight_reduce(w_q, w_scale, shp.K_b, shp.bits)
     T, K, N, K_b, n_out, bits = shp.T, shp.K, shp.N, shp.K_b, shp.n_out, shp.bits
     ws = torch.empty(api.quik_workspace_bytes(T, K, N, n_out, bits), dtype=torch.uint8, device=dev)
     y = torch.empty((T, N), dtype=torch.float16, device=dev)
 
     def step():
-        api.quik_linear(x, idx, bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
+        api.quik_linear(x, idx, bits, w_q, w_scale, w_red, w_cs, w_out, out=y, workspace=ws)
 
     # --graph: the timed region replays a HIP graph that holds one step (both launches, captured
     # from the same C-ABI call on the capture stream).
@@ -171,12 +171,13 @@ def main():
     ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # per-kernel durations (HIP events on the launch stream), same buffers
-    xq, scale, zero, x_out = api.quik_quantize(x, idx, bits)
-    q_out = (xq, scale, zero, x_out)
+    xq, scale, zero, x_out, cs = api.quik_quantize(x, idx, bits)
+    q_out = (xq, scale, zero, x_out, cs)
     it = max(20, args.steps // 2)
     ms_quant = _event_ms(lambda: api.quik_quantize(x, idx, bits, out=q_out), it, torch)
-    ms_gemm = _event_ms(lambda: api.quik_gemm_dequant(xq, scale, zero, x_out if n_out else None, K_b,
-                                                      bits, w_q, w_scale, w_red, w_out, out=y), it, torch)
+    ms_gemm = _event_ms(lambda: api.quik_gemm_dequant(xq, scale, zero, cs, x_out if n_out else None, K_b,
+                                                      bits, w_q, w_scale, w_red, w_cs, w_out, out=y),
+                        it, torch)
     ms_layer_ev = _event_ms(step, it, torch)
 
     if args.calibration_copy:
@@ -192,7 +193,7 @@ def main():
                          device=dev)
     ablation = {}
     for version in (1, 2, 3):
-        fn = lambda v=version: api.quik_linear_ablation(v, x, idx, bits, w_q, w_scale, w_red, w_out,
+        fn = lambda v=version: api.quik_linear_ablation(v, x, idx, bits, w_q, w_scale, w_red, w_cs, w_out,
                                                         out=y, workspace=ws_abl)
         for _ in range(5):
             fn()
@@ -211,7 +212,7 @@ def main():
     ops_int = 2.0 * T * K_b * N
     tops = ops_layer / (ms_step * 1e-3) / 1e12
     gemm_tops = ops_int / (ms_gemm * 1e-3) / 1e12
-    quant_bytes = T * (2 * K + K_b * bits // 8 + 2 * n_out + 8)
+    quant_bytes = T * (2 * K + K_b * bits // 8 + 2 * n_out + 8 + (4 if bits == 4 else 0))
     out = {
         "metric": "QUIK linear TOPS (whole layer: quantize + INT4 GEMM + dequant + fp16 outliers)",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -23,10 +23,21 @@
  *   - Matrices are row-major.  Leading dimensions ("ld...") are row strides, in
  *     ELEMENTS for fp16 / int32 matrices and in BYTES for packed integer
  *     matrices.
- *   - Packed integers: bits = 4 stores two two's-complement nibbles per byte,
- *     element 2p in bits 0..3 and element 2p+1 in bits 4..7 of byte p; bits = 8
- *     stores one signed byte per element.  Quantized activations lie in
+ *   - Packed integers: bits = 4 stores two two's-complement nibbles per byte.
+ *     WEIGHTS keep element 2p in bits 0..3 and element 2p+1 in bits 4..7 of byte
+ *     p.  ACTIVATIONS (xq, produced and consumed only inside this library) keep
+ *     element 2p in bits 4..7 and element 2p+1 in bits 0..3: with opposite
+ *     orders every product pairs a high with a low nibble, which lets the GEMM
+ *     widen each operand register with a single AND.  bits = 8 stores one signed
+ *     byte per element.  Quantized activations lie in
  *     [-2^(bits-1), 2^(bits-1) - 1], weights likewise.
+ *   - Code sums (bits = 4 only; an implementation device, not part of the
+ *     paper's algorithm): code_sum[t] = sum of the signed activation codes at
+ *     EVEN k, w_code_sum[n] = sum of the signed weight codes at ODD k.  The
+ *     widened operands carry an offset of 8 on their low nibbles; these two
+ *     INT32 vectors let the epilogue remove that offset exactly, so the
+ *     accumulator used for dequantization is the exact integer dot product.
+ *     For bits = 8 the pointers are ignored and may be NULL.
  *   - Base columns keep their ascending original order; outlier column j of
  *     x_out and w_out corresponds to input column outlier_idx[j].
  *   - Return value: QUIK_OK (0) or a negative quik_status.  When an error is
@@ -77,7 +88,7 @@ int quik_packed_row_bytes(int K_b, int bits);
 /*
  * Bytes of device workspace quik_linear needs for a [T, K] input with n_out
  * outlier columns: packed activations [T, quik_packed_row_bytes], per-token
- * scale and zero (fp32 each) and the fp16 outlier block [T, n_out], each region
+ * scale and zero (fp32 each), code sums (int32) and the fp16 outlier block [T, n_out], each region
  * aligned to 256 bytes.  Returns 0 on invalid input.  N is accepted for
  * symmetry and does not change the result.
  */
@@ -98,11 +109,13 @@ size_t quik_workspace_bytes(int T, int K, int N, int n_out, int bits);
  *   xq           out  packed [T, ldq bytes], ldq >= K_b*bits/8; bytes of each row
  *                     past the packed data up to ldq are written as zero
  *   scale, zero  out  fp32 [T]
+ *   code_sum     out  int32 [T], sum of q[t, k] over even k (see "Code sums");
+ *                     written for bits = 4 only; NULL = not wanted
  *   x_out        out  fp16 [T, ldo], ldo >= n_out; may be NULL if n_out = 0
  */
 int quik_quantize(const void *x, int T, int K, int ldx,
                   const int32_t *outlier_idx, int n_out, int bits,
-                  void *xq, int ldq, float *scale, float *zero,
+                  void *xq, int ldq, float *scale, float *zero, int32_t *code_sum,
                   void *x_out, int ldo, void *stream);
 
 /*
@@ -111,12 +124,15 @@ int quik_quantize(const void *x, int T, int K, int ldx,
  *   w_reduced[n] = float(w_scale[n]) * float(sum_k w_q[n, k]),  k < K_b.
  * Offline preparation, not part of the timed path.
  *
- *   w_q        in   packed [N, ldw bytes]
- *   w_scale    in   fp16 [N]
- *   w_reduced  out  fp32 [N]
+ *   w_q         in   packed [N, ldw bytes]
+ *   w_scale     in   fp16 [N]
+ *   w_reduced   out  fp32 [N]
+ *   w_code_sum  out  int32 [N], sum of w_q[n, k] over odd k (see "Code sums");
+ *                    written for bits = 4 only; NULL = not wanted
  */
 int quik_weight_reduce(const void *w_q, int ldw, const void *w_scale,
-                       int N, int K_b, int bits, float *w_reduced, void *stream);
+                       int N, int K_b, int bits, float *w_reduced, int32_t *w_code_sum,
+                       void *stream);
 
 /*
  * Integer GEMM + dequantization epilogue + outlier GEMM (Algorithm 1,
@@ -134,26 +150,34 @@ int quik_weight_reduce(const void *w_q, int ldw, const void *w_scale,
  *   xq       in  packed [T, ldq bytes]; bytes of a row between K_b*bits/8 and
  *                ldq MUST be zero (quik_quantize writes them so)
  *   scale, zero  in  fp32 [T]
+ *   code_sum in  int32 [T] as written by quik_quantize (required for bits = 4)
  *   x_out    in  fp16 [T, ldo]        (ignored if n_out = 0, may be NULL)
  *   w_q      in  packed [N, ldw bytes]; pad bytes may hold anything
  *   w_scale  in  fp16 [N];  w_reduced in fp32 [N]
+ *   w_code_sum in int32 [N] as written by quik_weight_reduce (required for bits = 4)
  *   w_out    in  fp16 [N, ldwo]       (ignored if n_out = 0, may be NULL)
  *   bias     in  fp16 [N] or NULL
  *   y        out fp16 [T, ldy], ldy >= N
  * K_b must be below 131072 (INT32 headroom of the 4-bit path).
  */
 int quik_gemm_dequant(const void *xq, int ldq, const float *scale, const float *zero,
-                      const void *x_out, int ldo, int T, int K_b, int n_out, int bits,
+                      const int32_t *code_sum, const void *x_out, int ldo,
+                      int T, int K_b, int n_out, int bits,
                       const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
-                      const void *w_out, int ldwo, const void *bias, int N,
-                      void *y, int ldy, void *stream);
+                      const int32_t *w_code_sum, const void *w_out, int ldwo,
+                      const void *bias, int N, void *y, int ldy, void *stream);
 
 /*
  * Test hook: the same integer K-loop as quik_gemm_dequant, writing the exact
  * INT32 accumulators instead of running the epilogue ("INTmatmul" alone).
+ *   code_sum, w_code_sum  in  both given: the single-AND operand widening of the
+ *                fused kernel plus its exact correction; both NULL: a widening
+ *                that needs no correction (one more shift per register pair).
+ *                Giving exactly one of them is QUIK_ENULL.  Same result either way.
  *   acc  out  int32 [T, ldacc], ldacc >= N
  */
-int quik_int_gemm(const void *xq, int ldq, const void *w_q, int ldw,
+int quik_int_gemm(const void *xq, int ldq, const int32_t *code_sum,
+                  const void *w_q, int ldw, const int32_t *w_code_sum,
                   int T, int N, int K_b, int bits, int32_t *acc, int ldacc, void *stream);
 
 /*
@@ -162,16 +186,16 @@ int quik_int_gemm(const void *xq, int ldq, const void *w_q, int ldw,
  *
  *   x            in   fp16 [T, ldx]
  *   outlier_idx  in   int32 [n_out]
- *   w_q, w_scale, w_reduced, w_out, bias: as in quik_gemm_dequant
+ *   w_q, w_scale, w_reduced, w_code_sum, w_out, bias: as in quik_gemm_dequant
  *   y            out  fp16 [T, ldy]
  *   workspace    device scratch of at least quik_workspace_bytes(...) bytes,
  *                256-byte aligned; contents after the call: packed activations,
- *                scale, zero, x_out (layout private to the library)
+ *                scale, zero, code sums, x_out (layout private to the library)
  */
 int quik_linear(const void *x, int T, int K, int ldx,
                 const int32_t *outlier_idx, int n_out, int bits,
                 const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
-                const void *w_out, int ldwo, const void *bias, int N,
+                const int32_t *w_code_sum, const void *w_out, int ldwo, const void *bias, int N,
                 void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -192,7 +216,8 @@ size_t quik_ablation_workspace_bytes(int T, int K, int N, int n_out, int bits);
 int quik_linear_ablation(int version, const void *x, int T, int K, int ldx,
                          const int32_t *outlier_idx, int n_out, int bits,
                          const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
-                         const void *w_out, int ldwo, const void *bias, int N,
+                         const int32_t *w_code_sum, const void *w_out, int ldwo,
+                         const void *bias, int N,
                          void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*

@@ -41,22 +41,22 @@ def load() -> C.CDLL:
         lib.quik_workspace_bytes.restype = C.c_size_t
         lib.quik_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.quik_quantize.restype = i
-        lib.quik_quantize.argtypes = [vp, i, i, i, vp, i, i, vp, i, f, f, vp, i, vp]
+        lib.quik_quantize.argtypes = [vp, i, i, i, vp, i, i, vp, i, f, f, vp, vp, i, vp]
         lib.quik_weight_reduce.restype = i
-        lib.quik_weight_reduce.argtypes = [vp, i, vp, i, i, i, f, vp]
+        lib.quik_weight_reduce.argtypes = [vp, i, vp, i, i, i, f, vp, vp]
         lib.quik_gemm_dequant.restype = i
-        lib.quik_gemm_dequant.argtypes = [vp, i, f, f, vp, i, i, i, i, i, vp, i, vp, f, vp, i, vp, i,
-                                          vp, i, vp]
+        lib.quik_gemm_dequant.argtypes = [vp, i, f, f, vp, vp, i, i, i, i, i, vp, i, vp, f, vp, vp, i,
+                                          vp, i, vp, i, vp]
         lib.quik_int_gemm.restype = i
-        lib.quik_int_gemm.argtypes = [vp, i, vp, i, i, i, i, i, vp, i, vp]
+        lib.quik_int_gemm.argtypes = [vp, i, vp, vp, i, vp, i, i, i, i, vp, i, vp]
         lib.quik_linear.restype = i
-        lib.quik_linear.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
+        lib.quik_linear.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, vp, i, vp, i, vp, i, vp,
                                     C.c_size_t, vp]
         lib.quik_ablation_workspace_bytes.restype = C.c_size_t
         lib.quik_ablation_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.quik_linear_ablation.restype = i
-        lib.quik_linear_ablation.argtypes = [i, vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
-                                             C.c_size_t, vp]
+        lib.quik_linear_ablation.argtypes = [i, vp, i, i, i, vp, i, i, vp, i, vp, f, vp, vp, i, vp, i, vp, i,
+                                             vp, C.c_size_t, vp]
         lib.quik_check_outlier_idx_host.restype = i
         lib.quik_check_outlier_idx_host.argtypes = [vp, i, i]
         _lib = lib
@@ -109,7 +109,8 @@ def quik_check_outlier_idx_host(idx_host, K: int) -> int:
 
 
 def quik_quantize(x, outlier_idx, bits: int, out=None):
-    """x fp16 [T,K] -> (xq uint8 [T,ldq], scale f32 [T], zero f32 [T], x_out f16 [T,n_out])."""
+    """x fp16 [T,K] -> (xq uint8 [T,ldq], scale f32 [T], zero f32 [T], x_out f16 [T,n_out],
+    code_sum i32 [T]).  code_sum is written for bits = 4 only."""
     x = _dev(x, torch.float16, "x")
     T, K = x.shape
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
@@ -124,56 +125,59 @@ def quik_quantize(x, outlier_idx, bits: int, out=None):
         scale = torch.empty(T, dtype=torch.float32, device=x.device)
         zero = torch.empty(T, dtype=torch.float32, device=x.device)
         x_out = torch.empty((T, n_out), dtype=torch.float16, device=x.device)
+        code_sum = torch.empty(T, dtype=torch.int32, device=x.device)
     else:
-        xq, scale, zero, x_out = out
+        xq, scale, zero, x_out, code_sum = out
     rc = load().quik_quantize(_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out,
-                              bits, _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero),
+                              bits, _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum),
                               _ptr(x_out) if n_out else None, x_out.stride(0) if n_out else 0,
                               _stream())
     _check(rc, "quik_quantize")
-    return xq, scale, zero, x_out
+    return xq, scale, zero, x_out, code_sum
 
 
 def quik_weight_reduce(w_q, w_scale, K_b: int, bits: int):
+    """-> (w_reduced f32 [N], w_code_sum i32 [N]); w_code_sum is written for bits = 4 only."""
     w_q = _dev(w_q, torch.uint8, "w_q")
     w_scale = _dev(w_scale, torch.float16, "w_scale")
     N = w_q.shape[0]
     out = torch.empty(N, dtype=torch.float32, device=w_q.device)
+    w_code_sum = torch.zeros(N, dtype=torch.int32, device=w_q.device)
     rc = load().quik_weight_reduce(_ptr(w_q), w_q.stride(0), _ptr(w_scale), N, K_b, bits, _ptr(out),
-                                   _stream())
+                                   _ptr(w_code_sum), _stream())
     _check(rc, "quik_weight_reduce")
-    return out
+    return out, w_code_sum
 
 
-def quik_gemm_dequant(xq, scale, zero, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced, w_out,
-                      bias=None, out=None):
+def quik_gemm_dequant(xq, scale, zero, code_sum, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced,
+                      w_code_sum, w_out, bias=None, out=None):
     xq = _dev(xq, torch.uint8, "xq")
     w_q = _dev(w_q, torch.uint8, "w_q")
     T, N = xq.shape[0], w_q.shape[0]
     n_out = 0 if x_out is None else int(x_out.shape[1])
     y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=xq.device)
     rc = load().quik_gemm_dequant(
-        _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
+        _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum), _ptr(x_out) if n_out else None,
         x_out.stride(0) if n_out else 0, T, K_b, n_out, bits, _ptr(w_q), w_q.stride(0), _ptr(w_scale),
-        _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias),
-        N, _ptr(y), y.stride(0), _stream())
+        _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
+        w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _stream())
     _check(rc, "quik_gemm_dequant")
     return y
 
 
-def quik_int_gemm(xq, w_q, K_b: int, bits: int):
+def quik_int_gemm(xq, w_q, K_b: int, bits: int, code_sum=None, w_code_sum=None):
     xq = _dev(xq, torch.uint8, "xq")
     w_q = _dev(w_q, torch.uint8, "w_q")
     T, N = xq.shape[0], w_q.shape[0]
     acc = torch.empty((T, N), dtype=torch.int32, device=xq.device)
-    rc = load().quik_int_gemm(_ptr(xq), xq.stride(0), _ptr(w_q), w_q.stride(0), T, N, K_b, bits,
-                              _ptr(acc), acc.stride(0), _stream())
+    rc = load().quik_int_gemm(_ptr(xq), xq.stride(0), _ptr(code_sum), _ptr(w_q), w_q.stride(0),
+                              _ptr(w_code_sum), T, N, K_b, bits, _ptr(acc), acc.stride(0), _stream())
     _check(rc, "quik_int_gemm")
     return acc
 
 
-def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, bias=None, out=None,
-                workspace=None):
+def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum, w_out, bias=None,
+                out=None, workspace=None):
     """Whole layer.  Returns y fp16 [T, N]."""
     x = _dev(x, torch.float16, "x")
     w_q = _dev(w_q, torch.uint8, "w_q")
@@ -186,7 +190,7 @@ def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, bias=
     y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
     rc = load().quik_linear(
         _ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(w_q),
-        w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None,
+        w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
         w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
         workspace.numel(), _stream())
     _check(rc, "quik_linear")
@@ -197,8 +201,8 @@ def quik_ablation_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int)
     return load().quik_ablation_workspace_bytes(T, K, N, n_out, bits)
 
 
-def quik_linear_ablation(version: int, x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out,
-                         bias=None, out=None, workspace=None):
+def quik_linear_ablation(version: int, x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum,
+                         w_out, bias=None, out=None, workspace=None):
     """The layer with unfused stages (version 1 or 2; 3 = quik_linear).  Returns (y, workspace)."""
     x = _dev(x, torch.float16, "x")
     w_q = _dev(w_q, torch.uint8, "w_q")
@@ -211,24 +215,26 @@ def quik_linear_ablation(version: int, x, outlier_idx, bits: int, w_q, w_scale, 
     y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
     rc = load().quik_linear_ablation(
         version, _ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits,
-        _ptr(w_q), w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None,
-        w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
-        workspace.numel(), _stream())
+        _ptr(w_q), w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_code_sum),
+        _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y),
+        y.stride(0), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "quik_linear_ablation")
     return y, workspace
 
 
 def workspace_views(workspace, T: int, K: int, n_out: int, bits: int):
-    """Views (xq, scale, zero, x_out) into a workspace filled by quik_linear or
+    """Views (xq, scale, zero, x_out, code_sum) into a workspace filled by quik_linear or
     quik_linear_ablation, following the layout documented for quik_workspace_bytes."""
     def up256(v):
         return (v + 255) & ~255
     ldq = quik_packed_row_bytes(K - n_out, bits)
     o_scale = up256(T * ldq)
     o_zero = o_scale + up256(T * 4)
-    o_xout = o_zero + up256(T * 4)
+    o_csum = o_zero + up256(T * 4)
+    o_xout = o_csum + up256(T * 4)
     xq = workspace[: T * ldq].view(T, ldq)
     scale = workspace[o_scale: o_scale + T * 4].view(torch.float32)
     zero = workspace[o_zero: o_zero + T * 4].view(torch.float32)
     x_out = workspace[o_xout: o_xout + T * n_out * 2].view(torch.float16).view(T, n_out)
-    return xq, scale, zero, x_out
+    code_sum = workspace[o_csum: o_csum + T * 4].view(torch.int32)
+    return xq, scale, zero, x_out, code_sum

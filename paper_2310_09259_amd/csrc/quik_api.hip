@@ -17,7 +17,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t up256(size_t v) { return (v + 255u) & ~size_t(255); }
 
 struct WorkspaceLayout {
-    size_t xq, scale, zero, x_out, total;
+    size_t xq, scale, zero, code_sum, x_out, total;
     int ldq;
 };
 
@@ -29,7 +29,8 @@ bool workspace_layout(int T, int K, int n_out, int bits, WorkspaceLayout* w) {
     w->xq = 0;
     w->scale = up256((size_t)T * ldq);
     w->zero = w->scale + up256((size_t)T * sizeof(float));
-    w->x_out = w->zero + up256((size_t)T * sizeof(float));
+    w->code_sum = w->zero + up256((size_t)T * sizeof(float));
+    w->x_out = w->code_sum + up256((size_t)T * sizeof(int32_t));
     w->total = w->x_out + up256((size_t)T * (n_out ? n_out : 1) * 2);
     return true;
 }
@@ -105,39 +106,42 @@ size_t quik_workspace_bytes(int T, int K, int N, int n_out, int bits) {
 }
 
 int quik_quantize(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out,
-                  int bits, void* xq, int ldq, float* scale, float* zero, void* x_out, int ldo,
-                  void* stream) {
+                  int bits, void* xq, int ldq, float* scale, float* zero, int32_t* code_sum,
+                  void* x_out, int ldo, void* stream) {
     int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo);
     if (rc != QUIK_OK) return rc;
-    quik::QuantizeArgs a{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo};
+    if (reinterpret_cast<uintptr_t>(code_sum) & 3u) return QUIK_EALIGN;
+    quik::QuantizeArgs a{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo, code_sum};
     return quik::launch_quantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
                                                                                    : QUIK_ELAUNCH;
 }
 
 int quik_weight_reduce(const void* w_q, int ldw, const void* w_scale, int N, int K_b, int bits,
-                       float* w_reduced, void* stream) {
+                       float* w_reduced, int32_t* w_code_sum, void* stream) {
     if (bits != 4 && bits != 8) return QUIK_EINVAL;
     if (N <= 0 || K_b <= 0 || (K_b * bits) % 8 || ldw < K_b * bits / 8) return QUIK_EINVAL;
     if (!w_q || !w_scale || !w_reduced) return QUIK_ENULL;
     if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
-    quik::WeightReduceArgs a{w_q, ldw, w_scale, N, K_b, bits, w_reduced};
+    quik::WeightReduceArgs a{w_q, ldw, w_scale, N, K_b, bits, w_reduced, w_code_sum};
     return quik::launch_weight_reduce(a, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUIK_OK
                : QUIK_ELAUNCH;
 }
 
 int quik_gemm_dequant(const void* xq, int ldq, const float* scale, const float* zero,
-                      const void* x_out, int ldo, int T, int K_b, int n_out, int bits,
-                      const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
-                      const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy,
-                      void* stream) {
+                      const int32_t* code_sum, const void* x_out, int ldo, int T, int K_b, int n_out,
+                      int bits, const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
+                      const int32_t* w_code_sum, const void* w_out, int ldwo, const void* bias, int N,
+                      void* y, int ldy, void* stream) {
     int rc = check_gemm(xq, ldq, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_out, ldwo, N);
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!scale || !zero || !w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (bits == 4 && (!code_sum || !w_code_sum)) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
     quik::GemmArgs a{};
     a.xq = xq; a.ldq = ldq; a.scale = scale; a.zero = zero; a.x_out = x_out; a.ldo = ldo;
+    a.code_sum = code_sum; a.w_code_sum = w_code_sum;
     a.T = T; a.K_b = K_b; a.n_out = n_out; a.bits = bits;
     a.w_q = w_q; a.ldw = ldw; a.w_scale = w_scale; a.w_reduced = w_reduced;
     a.w_out = w_out; a.ldwo = ldwo; a.bias = bias; a.N = N;
@@ -146,13 +150,16 @@ int quik_gemm_dequant(const void* xq, int ldq, const float* scale, const float* 
                                                                                : QUIK_ELAUNCH;
 }
 
-int quik_int_gemm(const void* xq, int ldq, const void* w_q, int ldw, int T, int N, int K_b,
-                  int bits, int32_t* acc, int ldacc, void* stream) {
+int quik_int_gemm(const void* xq, int ldq, const int32_t* code_sum, const void* w_q, int ldw,
+                  const int32_t* w_code_sum, int T, int N, int K_b, int bits, int32_t* acc, int ldacc,
+                  void* stream) {
     int rc = check_gemm(xq, ldq, nullptr, 0, T, K_b, 0, bits, w_q, ldw, nullptr, 0, N);
     if (rc != QUIK_OK) return rc;
     if (ldacc < N) return QUIK_EINVAL;
     if (!acc) return QUIK_ENULL;
+    if ((code_sum == nullptr) != (w_code_sum == nullptr)) return QUIK_ENULL;   // both or neither
     quik::GemmArgs a{};
+    a.code_sum = code_sum; a.w_code_sum = w_code_sum;
     a.xq = xq; a.ldq = ldq; a.T = T; a.K_b = K_b; a.n_out = 0; a.bits = bits;
     a.w_q = w_q; a.ldw = ldw; a.N = N; a.y = nullptr; a.acc = acc; a.ldacc = ldacc;
     return quik::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
@@ -161,8 +168,8 @@ int quik_int_gemm(const void* xq, int ldq, const void* w_q, int ldw, int T, int 
 
 int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out,
                 int bits, const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
-                const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy,
-                void* workspace, size_t workspace_bytes, void* stream) {
+                const int32_t* w_code_sum, const void* w_out, int ldwo, const void* bias, int N, void* y,
+                int ldy, void* workspace, size_t workspace_bytes, void* stream) {
     WorkspaceLayout w;
     if (!workspace_layout(T, K, n_out, bits, &w)) return QUIK_EINVAL;
     if (!workspace) return QUIK_ENULL;
@@ -172,6 +179,7 @@ int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx
     void* xq = base + w.xq;
     float* scale = reinterpret_cast<float*>(base + w.scale);
     float* zero = reinterpret_cast<float*>(base + w.zero);
+    int32_t* code_sum = reinterpret_cast<int32_t*>(base + w.code_sum);
     void* x_out = base + w.x_out;
     const int K_b = K - n_out;
     // validate both stages before anything is enqueued
@@ -181,11 +189,13 @@ int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (bits == 4 && !w_code_sum) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
-    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, w.ldq, scale, zero, x_out, n_out, stream);
+    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, w.ldq, scale, zero, code_sum, x_out,
+                       n_out, stream);
     if (rc != QUIK_OK) return rc;
-    return quik_gemm_dequant(xq, w.ldq, scale, zero, x_out, n_out, T, K_b, n_out, bits, w_q, ldw,
-                             w_scale, w_reduced, w_out, ldwo, bias, N, y, ldy, stream);
+    return quik_gemm_dequant(xq, w.ldq, scale, zero, code_sum, x_out, n_out, T, K_b, n_out, bits, w_q,
+                             ldw, w_scale, w_reduced, w_code_sum, w_out, ldwo, bias, N, y, ldy, stream);
 }
 
 namespace {
@@ -216,11 +226,12 @@ size_t quik_ablation_workspace_bytes(int T, int K, int N, int n_out, int bits) {
 
 int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, const int32_t* outlier_idx,
                          int n_out, int bits, const void* w_q, int ldw, const void* w_scale,
-                         const float* w_reduced, const void* w_out, int ldwo, const void* bias, int N,
-                         void* y, int ldy, void* workspace, size_t workspace_bytes, void* stream) {
+                         const float* w_reduced, const int32_t* w_code_sum, const void* w_out, int ldwo,
+                         const void* bias, int N, void* y, int ldy, void* workspace,
+                         size_t workspace_bytes, void* stream) {
     if (version == 3)
-        return quik_linear(x, T, K, ldx, outlier_idx, n_out, bits, w_q, ldw, w_scale, w_reduced, w_out,
-                           ldwo, bias, N, y, ldy, workspace, workspace_bytes, stream);
+        return quik_linear(x, T, K, ldx, outlier_idx, n_out, bits, w_q, ldw, w_scale, w_reduced,
+                           w_code_sum, w_out, ldwo, bias, N, y, ldy, workspace, workspace_bytes, stream);
     if (version != 1 && version != 2) return QUIK_EINVAL;
     AblationLayout w;
     if (!ablation_layout(T, K, N, n_out, bits, &w)) return QUIK_EINVAL;
@@ -231,6 +242,7 @@ int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, cons
     void* xq = base + w.base.xq;
     float* scale = reinterpret_cast<float*>(base + w.base.scale);
     float* zero = reinterpret_cast<float*>(base + w.base.zero);
+    int32_t* code_sum = reinterpret_cast<int32_t*>(base + w.base.code_sum);
     void* x_out = base + w.base.x_out;
     void* x_base = base + w.x_base;
     float* row_min = reinterpret_cast<float*>(base + w.row_min);
@@ -244,9 +256,10 @@ int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, cons
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (bits == 4 && !w_code_sum) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    quik::QuantizeArgs qa{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, n_out};
+    quik::QuantizeArgs qa{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, n_out, code_sum};
     if (version == 1) {
         if (quik::launch_unfused_quantize(qa, x_base, w.ldb, row_min, row_max, st) != hipSuccess)
             return QUIK_ELAUNCH;
@@ -255,6 +268,7 @@ int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, cons
     }
     quik::GemmArgs g{};
     g.xq = xq; g.ldq = ldq; g.scale = scale; g.zero = zero; g.x_out = x_out; g.ldo = n_out;
+    g.code_sum = code_sum; g.w_code_sum = w_code_sum;
     g.T = T; g.K_b = K_b; g.n_out = n_out; g.bits = bits;
     g.w_q = w_q; g.ldw = ldw; g.w_scale = w_scale; g.w_reduced = w_reduced;
     g.w_out = w_out; g.ldwo = ldwo; g.bias = nullptr; g.N = N;

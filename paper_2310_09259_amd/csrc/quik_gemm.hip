@@ -3,15 +3,24 @@
 // the final add; epilogue fusion as in Section 3.4).
 //
 // Data path.  gfx950 has no 4-bit integer MFMA, so packed nibbles travel
-// HBM -> LDS -> VGPR still packed and are widened in registers: for a 32-bit word
-// w holding eight two's-complement nibbles, (w & 0xF0F0F0F0) and
-// ((w << 4) & 0xF0F0F0F0) are two int8x4 vectors holding 16x the odd and 16x the
-// even nibbles.  Doing the same to both operands makes every product exactly 256x
-// too large; the factor is removed in the epilogue (arithmetic shift for the raw
-// accumulators, an exact power-of-two fold into the scale for the dequantized
-// output).  A dot product does not care in which order k is visited as long as
-// both operands agree, so the odd/even split needs no re-interleaving.  Headroom:
-// K_b * 64 * 256 < 2^31 requires K_b < 131072.
+// HBM -> LDS -> VGPR still packed and are widened to int8 in registers.  A dot
+// product does not care in which order k is visited as long as both operands
+// agree, so the high and the low nibbles of a packed word simply become two
+// different operand registers (no re-interleaving).  Two widenings are used:
+//   symmetric:  (w & 0xF0F0F0F0) and ((w << 4) & 0xF0F0F0F0) hold 16x the signed
+//     nibbles; done to both operands every product is exactly 256x too large
+//     (3 VALU operations per two operand registers).  Used by the raw-accumulator
+//     hook when it is given no correction terms.
+//   asymmetric: one AND per operand register.  (w & 0xF0F0F0F0) is 16x the signed
+//     high nibble; ((w ^ 0x08080808) & 0x0F0F0F0F) is the low nibble plus 8 (an
+//     unsigned value 0..15).  Activations keep element 2p in the high nibble,
+//     weights in the low nibble, so every product pairs a "16x" register with a
+//     "+8" register of the same k: even k gives 16*a*(b+8), odd k gives (a+8)*16*b,
+//     and the accumulator holds 16*sum(a*b) + 128*sum_{even k} a + 128*sum_{odd k} b.
+//     The two sums are per-token / per-channel integers computed once (by the
+//     quantization kernel and by the weight preparation) and subtracted, exactly,
+//     in the epilogue.
+// Headroom: the raw accumulator stays below 2^31 for K_b < 131072.
 //
 // MFMA shape: v_mfma_i32_32x32x32_i8.  First operand = activations (32 token
 // rows), second = weights (32 output channels).  Lane l supplies row/column l%32
@@ -97,9 +106,12 @@ template <int N> __device__ __forceinline__ void wait_vm() {   // s_waitcnt vmcn
 
 // BM x BN output tile per workgroup, WM x WN waves, BKB bytes of every packed row per
 // stage, NST stage buffers, GM = m-tiles per group of the tile order (0: plain column sweep).
-// RAW: write INT32 accumulators instead of running the epilogue.
-template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, bool RAW>
+// MODE 0: fused epilogue (asymmetric widening for 4 bits); MODE 1: write raw INT32 accumulators,
+// symmetric widening; MODE 2: raw accumulators, asymmetric widening plus correction terms.
+template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
 __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
+    constexpr bool RAW = MODE != 0;
+    constexpr bool ASYM = (BITS == 4) && (MODE != 1);
     constexpr int NWAVES = WM * WN, NT = NWAVES * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int CPR = BKB / 16, RPI = 64 / CPR;
@@ -107,7 +119,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     static_assert(A_INSTR >= 1 && B_INSTR >= 1, "tile too small for the wave count");
     constexpr int LPS = A_INSTR + B_INSTR;
     constexpr int KSUB = BKB / 32;
-    constexpr int SHIFT = (BITS == 4) ? 8 : 0;
+    constexpr int SHIFT = (BITS == 4) ? (ASYM ? 4 : 8) : 0;
     constexpr int A_BYTES = BM * BKB, B_BYTES = BN * BKB, ST_BYTES = A_BYTES + B_BYTES;
     constexpr int NF = TM + TN;
     constexpr int HALVES = (BITS == 4) ? 2 : 1;          // MFMAs per output tile per sub-step
@@ -119,6 +131,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES];
     __shared__ __align__(16) float lds_sa[BM];
     __shared__ __align__(16) float lds_sh[BM];
+    __shared__ __align__(16) int lds_ct[BM];             // 8 * (per-token correction sum)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -217,6 +230,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             float z = (t < a.T) ? a.zero[t] : 0.0f;
             lds_sa[r] = s;                                    // scaleAct
             lds_sh[r] = z + (float)(1 << (BITS - 1)) * s;     // zeroAct + halfRange * scaleAct
+            if constexpr (ASYM) lds_ct[r] = (t < a.T && !a.fp_only) ? 8 * a.code_sum[t] : 0;
         }
     }
 
@@ -239,9 +253,19 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         const int f = w >> 2, k = w & 3;
         const uint32_t x = (k == 0) ? R[set][f].x : (k == 1) ? R[set][f].y : (k == 2) ? R[set][f].z : R[set][f].w;
         if constexpr (BITS == 4) {
+            // slot 0 of a word pair holds the even k of the word, slot 1 the odd k
             constexpr uint32_t M = 0xF0F0F0F0u;
-            U[set][f][k >> 1][(k & 1) * 2] = (int)((x << 4) & M);
-            U[set][f][k >> 1][(k & 1) * 2 + 1] = (int)(x & M);
+            const bool act = f < TM;                     // activations: even k in the high nibble
+            uint32_t hi, lo;
+            if constexpr (ASYM) {
+                hi = x & M;                              // 16 * signed high nibble
+                lo = (x ^ 0x08080808u) & 0x0F0F0F0Fu;    // low nibble + 8
+            } else {
+                hi = x & M;
+                lo = (x << 4) & M;                       // 16 * signed, both
+            }
+            U[set][f][k >> 1][(k & 1) * 2] = (int)(act ? hi : lo);
+            U[set][f][k >> 1][(k & 1) * 2 + 1] = (int)(act ? lo : hi);
         } else {
             U[set][f][0][k] = (int)x;
         }
@@ -321,7 +345,11 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int t = tw + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = acc[i][j][r] >> SHIFT;
+                    if (t < a.T && n < a.N) {
+                        int v = acc[i][j][r] >> SHIFT;
+                        if constexpr (ASYM) v -= 8 * (a.code_sum[t] + a.w_code_sum[n]);
+                        a.acc[(size_t)t * a.ldacc + n] = v;
+                    }
                 }
             }
         return;
@@ -331,12 +359,15 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     v16f cf[TM][TN];
     {
         float sw[TN], wr[TN], bv[TN];
+        int cn[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             int n = min(nw + j * 32 + l32, a.N - 1);
-            sw[j] = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));   // exact power-of-two fold of the >> SHIFT
+            sw[j] = __half2float(wsc[n]);
             bv[j] = bias ? __half2float(bias[n]) : 0.0f;
             wr[j] = a.w_reduced[n];
+            cn[j] = 0;
+            if constexpr (ASYM) cn[j] = a.fp_only ? 0 : 8 * a.w_code_sum[n];
             if (a.fp_only) { sw[j] = 0.0f; bv[j] = 0.0f; wr[j] = 0.0f; }
         }
 #pragma unroll
@@ -347,13 +378,19 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
                 const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
                 const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
                 const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
+                int ct_[4] = {0, 0, 0, 0};
+                if constexpr (ASYM) {
+                    const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[lr]);
+                    ct_[0] = ct4.x; ct_[1] = ct4.y; ct_[2] = ct4.z; ct_[3] = ct4.w;
+                }
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) {
                         const int r = rq * 4 + rr;
-                        float v = (float)acc[i][j][r];
-                        cf[i][j][r] = __builtin_fmaf(v, sa_[rr] * sw[j], __builtin_fmaf(sh_[rr], wr[j], bv[j]));
+                        // exact INT32 accumulator of the method
+                        const int ai = (acc[i][j][r] >> SHIFT) - ct_[rr] - cn[j];
+                        cf[i][j][r] = __builtin_fmaf((float)ai, sa_[rr] * sw[j], __builtin_fmaf(sh_[rr], wr[j], bv[j]));
                     }
             }
     }
@@ -405,14 +442,16 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 // loop (a wave waits only for its own DMA).  The four partial INT32 accumulators are summed exactly
 // through LDS; wave 0 then dequantizes, adds the fp16 outlier product (operands read straight from
 // global memory: they are tiny) and stores.
-template <int BITS, int TM, int TN, int NST, bool RAW>
+template <int BITS, int TM, int TN, int NST, int MODE>
 __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
+    constexpr bool RAW = MODE != 0;
+    constexpr bool ASYM = (BITS == 4) && (MODE != 1);
     constexpr int BKB = 128, CPR = 8, RPI = 8;           // 128-byte stage rows, 8 rows per DMA instr
     constexpr int BM = 32 * TM, BN = 32 * TN;
     constexpr int A_INSTR = BM / RPI, B_INSTR = BN / RPI; // per wave (each wave loads its own tiles)
     constexpr int LPS = A_INSTR + B_INSTR;
     constexpr int KSUB = BKB / 32;
-    constexpr int SHIFT = (BITS == 4) ? 8 : 0;
+    constexpr int SHIFT = (BITS == 4) ? (ASYM ? 4 : 8) : 0;
     constexpr int A_BYTES = BM * BKB, B_BYTES = BN * BKB, ST_BYTES = A_BYTES + B_BYTES;
     constexpr int NF = TM + TN;
     constexpr int HALVES = (BITS == 4) ? 2 : 1;
@@ -494,9 +533,19 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
                 const uint4 w = *reinterpret_cast<const uint4*>(st + rd[f][ks]);
                 v4i* u = (f < TM) ? ua[f] : ub[f - TM];
                 if constexpr (BITS == 4) {
+                    // register slots 0/2 hold the even k of a word, slots 1/3 the odd k
                     constexpr uint32_t M = 0xF0F0F0F0u;
-                    u[0] = v4i{(int)((w.x << 4) & M), (int)(w.x & M), (int)((w.y << 4) & M), (int)(w.y & M)};
-                    u[1] = v4i{(int)((w.z << 4) & M), (int)(w.z & M), (int)((w.w << 4) & M), (int)(w.w & M)};
+                    auto hi = [](uint32_t x) { return (int)(x & M); };
+                    auto lo = [](uint32_t x) {
+                        return ASYM ? (int)((x ^ 0x08080808u) & 0x0F0F0F0Fu) : (int)((x << 4) & M);
+                    };
+                    if (f < TM) {                         // activations: even k in the high nibble
+                        u[0] = v4i{hi(w.x), lo(w.x), hi(w.y), lo(w.y)};
+                        u[1] = v4i{hi(w.z), lo(w.z), hi(w.w), lo(w.w)};
+                    } else {                              // weights: even k in the low nibble
+                        u[0] = v4i{lo(w.x), hi(w.x), lo(w.y), hi(w.y)};
+                        u[1] = v4i{lo(w.z), hi(w.z), lo(w.w), hi(w.w)};
+                    }
                 } else {
                     u[0] = v4i{(int)w.x, (int)w.y, (int)w.z, (int)w.w};
                 }
@@ -547,7 +596,11 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int t = t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = acc[i][j][r] >> SHIFT;
+                    if (t < a.T && n < a.N) {
+                        int v = acc[i][j][r] >> SHIFT;
+                        if constexpr (ASYM) v -= 8 * (a.code_sum[t] + a.w_code_sum[n]);
+                        a.acc[(size_t)t * a.ldacc + n] = v;
+                    }
                 }
             }
         return;
@@ -559,9 +612,11 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             int n = min(n0 + j * 32 + l32, a.N - 1);
-            float sw = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));
+            float sw = __half2float(wsc[n]);
             float wr = a.w_reduced[n];
             float bv = bias ? __half2float(bias[n]) : 0.0f;
+            int cn = 0;
+            if constexpr (ASYM) cn = a.fp_only ? 0 : 8 * a.w_code_sum[n];
             if (a.fp_only) { sw = 0.0f; wr = 0.0f; bv = 0.0f; }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -570,7 +625,9 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
                     int t = min(t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3), a.T - 1);
                     float sa = a.scale[t];
                     float sh = a.zero[t] + (float)(1 << (BITS - 1)) * sa;
-                    cf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], sa * sw, __builtin_fmaf(sh, wr, bv));
+                    int ai = acc[i][j][r] >> SHIFT;       // exact INT32 accumulator of the method
+                    if constexpr (ASYM) ai -= cn + (a.fp_only ? 0 : 8 * a.code_sum[t]);
+                    cf[i][j][r] = __builtin_fmaf((float)ai, sa * sw, __builtin_fmaf(sh, wr, bv));
                 }
         }
         const __half* __restrict__ xo = static_cast<const __half*>(a.x_out);
@@ -615,35 +672,35 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 }
 
 
-template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, bool RAW>
+template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_kernel<BITS, BM, BN, WM, WN, BKB, NST, OCC, GM, RAW>), dim3(tiles),
+    hipLaunchKernelGGL((gemm_kernel<BITS, BM, BN, WM, WN, BKB, NST, OCC, GM, MODE>), dim3(tiles),
                        dim3(WM * WN * 64), 0, stream, a);
     return hipGetLastError();
 }
 
-template <int BITS, int TM, int TN, int NST, bool RAW>
+template <int BITS, int TM, int TN, int NST, int MODE>
 hipError_t launch_skinny(const GemmArgs& a, hipStream_t stream) {
     int tiles = ((a.T + 32 * TM - 1) / (32 * TM)) * ((a.N + 32 * TN - 1) / (32 * TN));
-    hipLaunchKernelGGL((gemm_skinny<BITS, TM, TN, NST, RAW>), dim3(tiles), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((gemm_skinny<BITS, TM, TN, NST, MODE>), dim3(tiles), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
-template <int BITS, bool RAW>
+template <int BITS, int MODE>
 hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
     // Few tokens: weight streaming dominates.  Up to 32 tokens the K-split kernel; up to 128 tokens
     // small tiles with a deeper stage ring so that enough workgroups and bytes are in flight.
-    if (a.T <= 32) return launch_skinny<BITS, 1, 1, 2, RAW>(a, stream);
-    if (a.T <= 64) return launch_cfg<BITS, 64, 64, 2, 2, 128, 4, 2, 0, RAW>(a, stream);
-    if (a.T <= 128) return launch_cfg<BITS, 128, 64, 2, 2, 128, 2, 2, 0, RAW>(a, stream);
+    if (a.T <= 32) return launch_skinny<BITS, 1, 1, 2, MODE>(a, stream);
+    if (a.T <= 64) return launch_cfg<BITS, 64, 64, 2, 2, 128, 4, 2, 0, MODE>(a, stream);
+    if (a.T <= 128) return launch_cfg<BITS, 128, 64, 2, 2, 128, 2, 2, 0, MODE>(a, stream);
     // 128-byte stage rows (a full cache line per row per stage), two stage buffers.
     // Large problems: 256 x 128 tiles shared by eight waves (one workgroup per CU) move 25 % fewer
     // operand bytes per MFMA through L1/LDS than two independent 128 x 128 workgroups.  They need
     // at least one tile per CU to pay off; otherwise 128 x 128 tiles with two workgroups per CU.
     const long big_tiles = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
-    if (big_tiles >= 256) return launch_cfg<BITS, 256, 128, 4, 2, 128, 2, 1, 4, RAW>(a, stream);
-    return launch_cfg<BITS, 128, 128, 2, 2, 128, 2, 2, 8, RAW>(a, stream);
+    if (big_tiles >= 256) return launch_cfg<BITS, 256, 128, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
+    return launch_cfg<BITS, 128, 128, 2, 2, 128, 2, 2, 8, MODE>(a, stream);
 }
 
 // one wave per output channel; lanes stride over the packed row
@@ -654,28 +711,37 @@ __global__ __launch_bounds__(kThreads) void weight_reduce_kernel(WeightReduceArg
     if (n >= a.N) return;
     const uint8_t* row = static_cast<const uint8_t*>(a.w_q) + (size_t)n * a.ldw;
     const int row_bytes = a.K_b * BITS / 8;
-    int s = 0;
+    int s = 0, s_odd = 0;                  // all codes; codes at odd positions (high nibbles)
     for (int p = lane; p < row_bytes; p += 64) {
         int b = row[p];
         if constexpr (BITS == 4) {
-            s += ((b & 0xF) ^ 8) - 8;
-            s += ((b >> 4) ^ 8) - 8;
+            int hi = ((b >> 4) ^ 8) - 8;
+            s += ((b & 0xF) ^ 8) - 8 + hi;
+            s_odd += hi;
         } else {
             s += (int)(int8_t)b;
         }
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (lane == 0)
+    for (int o = 32; o > 0; o >>= 1) {
+        s += __shfl_xor(s, o, 64);
+        s_odd += __shfl_xor(s_odd, o, 64);
+    }
+    if (lane == 0) {
         a.w_reduced[n] = __half2float(static_cast<const __half*>(a.w_scale)[n]) * (float)s;
+        if (a.w_code_sum) a.w_code_sum[n] = s_odd;
+    }
 }
 
 }  // namespace
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     const bool raw = a.y == nullptr;
-    if (a.bits == 4) return raw ? dispatch<4, true>(a, stream) : dispatch<4, false>(a, stream);
-    return raw ? dispatch<8, true>(a, stream) : dispatch<8, false>(a, stream);
+    if (a.bits == 4) {
+        if (!raw) return dispatch<4, 0>(a, stream);
+        return (a.code_sum && a.w_code_sum) ? dispatch<4, 2>(a, stream) : dispatch<4, 1>(a, stream);
+    }
+    return raw ? dispatch<8, 1>(a, stream) : dispatch<8, 0>(a, stream);
 }
 
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream) {

@@ -17,6 +17,7 @@ struct QuantizeArgs {
     float* zero;          // [T]
     void* x_out;          // fp16 [T, ldo]
     int ldo;
+    int32_t* code_sum;    // [T] sum of the signed codes at even positions (4-bit; may be null)
 };
 
 struct GemmArgs {
@@ -24,6 +25,7 @@ struct GemmArgs {
     int ldq;
     const float* scale;   // [T]
     const float* zero;    // [T]
+    const int32_t* code_sum;    // [T] sum of the signed activation codes at even k (4-bit; see quik_gemm.hip)
     const void* x_out;    // fp16 [T, ldo]
     int ldo;
     int T, K_b, n_out, bits;
@@ -31,6 +33,7 @@ struct GemmArgs {
     int ldw;
     const void* w_scale;  // fp16 [N]
     const float* w_reduced;
+    const int32_t* w_code_sum;  // [N] sum of the signed weight codes at odd k (4-bit)
     const void* w_out;    // fp16 [N, ldwo]
     int ldwo;
     const void* bias;     // fp16 [N] or null
@@ -48,6 +51,7 @@ struct WeightReduceArgs {
     const void* w_scale;
     int N, K_b, bits;
     float* w_reduced;
+    int32_t* w_code_sum;  // [N], may be null
 };
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);

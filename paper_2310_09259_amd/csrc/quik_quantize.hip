@@ -45,13 +45,12 @@ __device__ __forceinline__ U drop_element(U w, int p) {
 // Quantizes one chunk, squeezes its base elements together and ORs them into the LDS
 // row image at element position base0.  Elements at positions >= K_b are dropped.
 template <int BITS>
-__device__ __forceinline__ void emit_chunk(const Chunk& c, uint32_t m8, int base0, int K_b,
-                                           float mn, float inv, uint32_t* stage) {
+__device__ __forceinline__ int emit_chunk(const Chunk& c, uint32_t m8, int base0, int K_b,
+                                          float mn, float inv, uint32_t* stage) {
     if constexpr (BITS == 4) {
         uint32_t w = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) w |= (code_bits(c.h[i], mn, inv) & 0xFu) << (4 * i);
-        w ^= 0x88888888u;                          // code - halfRange, two's complement nibble
         int cnt = 8;
         while (m8) {                               // rare: squeeze out outlier positions, highest first
             int p = 31 - __clz(m8);
@@ -59,16 +58,22 @@ __device__ __forceinline__ void emit_chunk(const Chunk& c, uint32_t m8, int base
             m8 &= ~(1u << p);
             --cnt;
         }
-        if (base0 >= K_b || cnt == 0) return;
+        if (base0 >= K_b || cnt == 0) return 0;
         int room = K_b - base0;
-        if (cnt < 8) w &= (1u << (4 * cnt)) - 1u;
-        if (room < 8) w &= (1u << (4 * room)) - 1u;
+        if (room < cnt) cnt = room;
+        const uint32_t keep = (cnt < 8) ? ((1u << (4 * cnt)) - 1u) : 0xFFFFFFFFu;
+        w &= keep;                                 // unsigned codes 0..15 of the kept elements
+        // sum of the codes at even positions of the packed row (nibbles base0-parity, +2, ...)
+        const uint32_t sel = (w >> (4 * (base0 & 1))) & 0x0F0F0F0Fu;
+        const int even_sum = (int)__builtin_amdgcn_sad_u8(sel, 0u, 0u);
+        w = (w ^ 0x88888888u) & keep;              // code - halfRange as two's complement nibbles
         uint32_t bit = (uint32_t)base0 * 4u;
         uint32_t wi = bit >> 5, sh = bit & 31u;
         uint32_t lo = w << sh;
         uint32_t hi = sh ? (w >> (32u - sh)) : 0u;
         if (lo) atomicOr(&stage[wi], lo);
         if (hi) atomicOr(&stage[wi + 1], hi);
+        return even_sum;
     } else {
         uint64_t w = 0;
 #pragma unroll
@@ -81,7 +86,7 @@ __device__ __forceinline__ void emit_chunk(const Chunk& c, uint32_t m8, int base
             m8 &= ~(1u << p);
             --cnt;
         }
-        if (base0 >= K_b || cnt == 0) return;
+        if (base0 >= K_b || cnt == 0) return 0;
         int room = K_b - base0;
         if (cnt < 8) w &= (1ull << (8 * cnt)) - 1ull;
         if (room < 8) w &= (1ull << (8 * room)) - 1ull;
@@ -93,6 +98,7 @@ __device__ __forceinline__ void emit_chunk(const Chunk& c, uint32_t m8, int base
         if (p0) atomicOr(&stage[wi], p0);
         if (p1) atomicOr(&stage[wi + 1], p1);
         if (p2) atomicOr(&stage[wi + 2], p2);
+        return 0;
     }
 }
 
@@ -102,7 +108,7 @@ template <int BITS, int TPR, int NCH>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(
     const __half* __restrict__ x, int T, int K, int ldx, const int32_t* __restrict__ idx, int n_out,
     uint8_t* __restrict__ xq, int ldq, float* __restrict__ scale, float* __restrict__ zero,
-    __half* __restrict__ x_out, int ldo) {
+    int32_t* __restrict__ code_sum, __half* __restrict__ x_out, int ldo) {
     constexpr int RPB = kBlock / TPR;             // rows per workgroup iteration
     extern __shared__ __align__(16) uint32_t lds[];
     const int nwords = (K + 31) >> 5;
@@ -110,7 +116,8 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     uint32_t* pre = mask + nwords;
     float* red = reinterpret_cast<float*>(pre + nwords);       // [2 * 4] wave partials
     uint32_t* wave_tot = reinterpret_cast<uint32_t*>(red + 8); // [4]
-    uint32_t* stage_all = wave_tot + 4;                        // RPB rows of ldq bytes
+    int* red_i = reinterpret_cast<int*>(wave_tot + 4);         // [4] wave partials of the code sum
+    uint32_t* stage_all = reinterpret_cast<uint32_t*>(red_i + 4);   // RPB rows of ldq bytes
     // keep the row images 16-byte aligned
     stage_all = reinterpret_cast<uint32_t*>((reinterpret_cast<uintptr_t>(stage_all) + 15) & ~(uintptr_t)15);
 
@@ -188,11 +195,12 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
         if (valid && lt == 0) { scale[t] = s; zero[t] = mn; }
 
         // ---- pass 2: quantize the base elements into the LDS row image
+        int esum = 0;                              // unsigned codes at even positions (4-bit only)
         auto quant_chunk = [&](const Chunk& c, int k0) {
             uint32_t word = mask[k0 >> 5];
             uint32_t below = pre[k0 >> 5] + __popc(word & ((1u << (k0 & 31)) - 1u));
             uint32_t m8 = (word >> (k0 & 31)) & 0xFFu;
-            emit_chunk<BITS>(c, m8, k0 - (int)below, K_b, mn, inv, stage);
+            esum += emit_chunk<BITS>(c, m8, k0 - (int)below, K_b, mn, inv, stage);
         };
         if constexpr (NCH > 0) {
 #pragma unroll
@@ -210,13 +218,34 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
                 }
             }
         }
+        if constexpr (BITS == 4) {
+            // sum over even positions of the signed codes (the GEMM's correction term for the
+            // cheap operand widening); wave partials are combined after the barrier below
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) esum += __shfl_xor(esum, o, 64);
+            if constexpr (TPR > 64) {
+                if ((tid & 63) == 0) red_i[tid >> 6] = esum;
+            }
+        }
         __syncthreads();
+        if constexpr (BITS == 4) {
+            if constexpr (TPR > 64) esum = red_i[0] + red_i[1] + red_i[2] + red_i[3];
+            if (valid && lt == 0 && code_sum) code_sum[t] = esum - 8 * (K_b >> 1);
+        }
 
-        // ---- write the packed row (including its zero padding up to ldq)
+        // ---- write the packed row (including its zero padding up to ldq); 4-bit rows leave with
+        // the two nibbles of every byte swapped: element 2p in the high nibble
         if (valid) {
             uint4* dst = reinterpret_cast<uint4*>(xq + (size_t)t * ldq);
             const uint4* src = reinterpret_cast<const uint4*>(stage);
-            for (int i = lt; i < (ldq >> 4); i += TPR) dst[i] = src[i];
+            for (int i = lt; i < (ldq >> 4); i += TPR) {
+                uint4 v = src[i];
+                if constexpr (BITS == 4) {
+                    auto sw = [](uint32_t w) { return ((w & 0x0F0F0F0Fu) << 4) | ((w >> 4) & 0x0F0F0F0Fu); };
+                    v = make_uint4(sw(v.x), sw(v.y), sw(v.z), sw(v.w));
+                }
+                dst[i] = v;
+            }
             // ---- pass 3: move the outlier columns
             for (int j = lt; j < n_out; j += TPR) {
                 int c = idx[j];
@@ -258,14 +287,14 @@ template <int BITS, int TPR, int NCH>
 hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     constexpr int RPB = kBlock / TPR;
     const int nwords = (a.K + 31) >> 5;
-    size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
+    size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
     int nrowblk = (a.T + RPB - 1) / RPB;
     // a bounded grid: the outlier map is built once per workgroup and the rows of a workgroup
     // are software-pipelined (next row's loads in flight while the current one is processed)
     int grid = nrowblk < 2048 ? nrowblk : 2048;
     hipLaunchKernelGGL((quantize_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
                        (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
-                       a.scale, a.zero, (__half*)a.x_out, a.ldo);
+                       a.scale, a.zero, a.code_sum, (__half*)a.x_out, a.ldo);
     return hipGetLastError();
 }
 

@@ -83,7 +83,9 @@ __global__ __launch_bounds__(kBlock) void quantize_base_kernel(const __half* __r
                                                                int ldb, const float* __restrict__ row_min,
                                                                const float* __restrict__ row_max,
                                                                uint8_t* __restrict__ xq, int ldq,
-                                                               float* __restrict__ scale, float* __restrict__ zero) {
+                                                               float* __restrict__ scale, float* __restrict__ zero,
+                                                               int32_t* __restrict__ code_sum) {
+    __shared__ int red_i[kBlock / 64];
     for (int t = blockIdx.x; t < T; t += gridDim.x) {
         const float mn = row_min[t] + 0.0f;
         const float range = row_max[t] - mn;
@@ -93,16 +95,29 @@ __global__ __launch_bounds__(kBlock) void quantize_base_kernel(const __half* __r
         uint8_t* dst = xq + (size_t)t * ldq;
         const __half* src = x_base + (size_t)t * ldb;
         if constexpr (BITS == 4) {
-            // one byte (two elements) per thread step; K_b is even
+            // one byte (two elements) per thread step; K_b is even.  Activation bytes keep element
+            // 2p in the high nibble; the signed codes at even positions are summed per row.
+            int esum = 0;
             for (int p = threadIdx.x; p < ldq; p += kBlock) {
                 uint32_t b = 0;
                 if (2 * p < K_b) {
-                    uint32_t lo = code_bits(src[2 * p], mn, inv) & 0xFu;
-                    uint32_t hi = code_bits(src[2 * p + 1], mn, inv) & 0xFu;
-                    b = (lo | (hi << 4)) ^ 0x88u;
+                    uint32_t even = code_bits(src[2 * p], mn, inv) & 0xFu;
+                    uint32_t odd = code_bits(src[2 * p + 1], mn, inv) & 0xFu;
+                    b = (odd | (even << 4)) ^ 0x88u;
+                    esum += (int)even - 8;
                 }
                 dst[p] = (uint8_t)b;
             }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) esum += __shfl_xor(esum, o, 64);
+            if ((threadIdx.x & 63) == 0) red_i[threadIdx.x >> 6] = esum;
+            __syncthreads();
+            if (threadIdx.x == 0 && code_sum) {
+                int tot = 0;
+                for (int w = 0; w < kBlock / 64; ++w) tot += red_i[w];
+                code_sum[t] = tot;
+            }
+            __syncthreads();
         } else {
             for (int p = threadIdx.x; p < ldq; p += kBlock)
                 dst[p] = (p < K_b) ? (uint8_t)((code_bits(src[p], mn, inv) & 0xFFu) ^ 0x80u) : (uint8_t)0;
@@ -154,11 +169,11 @@ hipError_t launch_unfused_quantize(const QuantizeArgs& a, void* x_base, int ldb,
     if (a.bits == 4)
         hipLaunchKernelGGL(quantize_base_kernel<4>, dim3(capped(a.T)), dim3(kBlock), 0, stream,
                            (const __half*)x_base, a.T, K_b, ldb, row_min, row_max, (uint8_t*)a.xq, a.ldq,
-                           a.scale, a.zero);
+                           a.scale, a.zero, a.code_sum);
     else
         hipLaunchKernelGGL(quantize_base_kernel<8>, dim3(capped(a.T)), dim3(kBlock), 0, stream,
                            (const __half*)x_base, a.T, K_b, ldb, row_min, row_max, (uint8_t*)a.xq, a.ldq,
-                           a.scale, a.zero);
+                           a.scale, a.zero, a.code_sum);
     return hipGetLastError();
 }
 

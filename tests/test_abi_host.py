@@ -62,31 +62,40 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     u = C.c_void_p(0x1004)          # misaligned
     null = C.c_void_p(0)
     q = lib.quik_quantize
-    # (x, T, K, ldx, idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo, stream)
-    assert q(p, 4, 64, 64, p, 8, 5, p, 32, p, p, p, 8, null) == -1        # bits
-    assert q(p, 0, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -1        # T
-    assert q(p, 4, 64, 64, p, 64, 4, p, 32, p, p, p, 64, null) == -1      # n_out == K
-    assert q(p, 4, 64, 32, p, 8, 4, p, 32, p, p, p, 8, null) == -1        # ldx < K
-    assert q(p, 4, 64, 64, p, 8, 4, p, 16, p, p, p, 8, null) == -1        # ldq too small
-    assert q(null, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -2     # x NULL
-    assert q(p, 4, 64, 64, null, 8, 4, p, 32, p, p, p, 8, null) == -2     # idx NULL with n_out
-    assert q(u, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -3        # x misaligned
-    assert q(p, 4, 64, 64, p, 8, 4, p, 40, p, p, p, 8, null) == -3        # ldq % 16
-    assert q(p, 4, 60, 64, p, 8, 4, p, 32, p, p, p, 8, null) == -4        # K % 8
-    assert q(p, 4, 64, 64, p, 4, 4, p, 32, p, p, p, 8, null) == -4        # n_out % 8
-    assert q(p, 4, 65536, 65536, p, 8, 4, p, 32768, p, p, p, 8, null) == -4   # K too large
+    # (x, T, K, ldx, idx, n_out, bits, xq, ldq, scale, zero, code_sum, x_out, ldo, stream)
+    assert q(p, 4, 64, 64, p, 8, 5, p, 32, p, p, p, p, 8, null) == -1        # bits
+    assert q(p, 0, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -1        # T
+    assert q(p, 4, 64, 64, p, 64, 4, p, 32, p, p, p, p, 64, null) == -1      # n_out == K
+    assert q(p, 4, 64, 32, p, 8, 4, p, 32, p, p, p, p, 8, null) == -1        # ldx < K
+    assert q(p, 4, 64, 64, p, 8, 4, p, 16, p, p, p, p, 8, null) == -1        # ldq too small
+    assert q(null, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -2     # x NULL
+    assert q(p, 4, 64, 64, null, 8, 4, p, 32, p, p, p, p, 8, null) == -2     # idx NULL with n_out
+    assert q(u, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -3        # x misaligned
+    assert q(p, 4, 64, 64, p, 8, 4, p, 40, p, p, p, p, 8, null) == -3        # ldq % 16
+    assert q(p, 4, 60, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -4        # K % 8
+    assert q(p, 4, 64, 64, p, 4, 4, p, 32, p, p, p, p, 8, null) == -4        # n_out % 8
+    assert q(p, 4, 65536, 65536, p, 8, 4, p, 32768, p, p, p, p, 8, null) == -4   # K too large
     g = lib.quik_gemm_dequant
-    # (xq, ldq, scale, zero, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_scale, w_red, w_out, ldwo,
-    #  bias, N, y, ldy, stream)
-    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 16, p, p, p, 8, null, 8, p, 8, null) == -1   # ldw small
-    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, null, 8, null) == -2
-    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, p, 4, null) == -1   # ldy < N
-    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, u, 32, p, p, p, 8, null, 8, p, 8, null) == -3   # w_q align
+    # (xq, ldq, scale, zero, code_sum, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_scale, w_red,
+    #  w_code_sum, w_out, ldwo, bias, N, y, ldy, stream)
+    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 16, p, p, p, p, 8, null, 8, p, 8, null) == -1   # ldw small
+    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, p, 8, null, 8, null, 8, null) == -2
+    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 4, null) == -1   # ldy < N
+    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, u, 32, p, p, p, p, 8, null, 8, p, 8, null) == -3
+    # 4-bit layers need both code-sum vectors; 8-bit layers do not
+    assert g(p, 32, p, p, null, p, 8, 4, 64, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, null) == -2
+    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, null, p, 8, null, 8, p, 8, null) == -2   # w_q align
+    # (xq, ldq, code_sum, w_q, ldw, w_code_sum, T, N, K_b, bits, acc, ldacc, stream): the two
+    # code-sum vectors come together or not at all
+    ig = lib.quik_int_gemm
+    assert ig(p, 32, p, p, 32, null, 4, 8, 64, 4, p, 8, null) == -2
+    assert ig(p, 32, null, p, 32, p, 4, 8, 64, 4, p, 8, null) == -2
+    assert ig(p, 32, null, p, 32, null, 4, 8, 64, 4, null, 8, null) == -2     # acc NULL
     lin = lib.quik_linear
     lin.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
-                    C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+                    C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
                     C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
     need = lib.quik_workspace_bytes(4, 64, 8, 8, 4)
-    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, C.c_void_p(0x1000), need - 1,
+    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, C.c_void_p(0x1000), need - 1,
                null) == -5
-    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, null, need, null) == -2
+    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, null, need, null) == -2

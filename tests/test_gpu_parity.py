@@ -1,7 +1,7 @@
 """GPU-vs-oracle parity through the C ABI (run with -m gpu on an MI355X).
 
-Bars: packed activations, scale, zero, outlier block and INT32 accumulators are
-bit-exact; the fp16 output is within 5e-3 of the oracle's binary32 result
+Bars: packed activations, scale, zero, outlier block, code sums and INT32 accumulators
+are bit-exact; the fp16 output is within 5e-3 of the oracle's binary32 result
 (|y - y_ref| <= 5e-3 * max(|y_ref|, 1e-3 * max|y_ref|) element by element).
 """
 import numpy as np
@@ -32,10 +32,12 @@ def _quantize_case(api, oracle, x, idx, bits):
     T, K = x.shape
     xd = to_dev(x)
     idxd = to_dev(idx) if idx.size else None
-    xq, scale, zero, x_out = api.quik_quantize(xd, idxd, bits)
+    xq, scale, zero, x_out, code_sum = api.quik_quantize(xd, idxd, bits)
     _sync()
     q, s, z, xo = oracle.quantize(x, idx, bits)
     want = expected_xq(oracle, q, bits, xq.shape[1])
+    if bits == 4:                                # sum of the signed codes at even base positions
+        assert np.array_equal(code_sum.cpu().numpy(), q[:, 0::2].astype(np.int32).sum(axis=1)), "code_sum"
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32)), "scale"
     assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32)), "zero"
     got = xq.cpu().numpy()
@@ -103,9 +105,13 @@ INT_GEMM_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("widening", ["plain", "corrected"])
 @pytest.mark.parametrize("T,N,K_b,bits", INT_GEMM_SHAPES)
-def test_int32_accumulators_are_bit_exact(api, oracle, T, N, K_b, bits):
-    import torch
+def test_int32_accumulators_are_bit_exact(api, oracle, T, N, K_b, bits, widening):
+    """Both operand widenings of the 4-bit K loop: the one that needs no correction, and the
+    single-AND one of the fused kernel whose offset is removed with the two code-sum vectors."""
+    if widening == "corrected" and bits != 4:
+        pytest.skip("the 8-bit path has one widening")
     rng = np.random.default_rng(T * 7 + N * 3 + K_b + bits)
     half = 1 << (bits - 1)
     q = rng.integers(-half, half, size=(T, K_b)).astype(np.int8)
@@ -117,7 +123,11 @@ def test_int32_accumulators_are_bit_exact(api, oracle, T, N, K_b, bits):
     # weight pad bytes may hold anything: fill them with 0xFF to prove it
     wp = np.full((N, ld), 0xFF, np.uint8)
     wp[:, : K_b * bits // 8] = oracle.pack(w, bits)
-    acc = api.quik_int_gemm(xq, to_dev(wp), K_b, bits)
+    cs = wcs = None
+    if widening == "corrected":
+        cs = to_dev(q[:, 0::2].astype(np.int32).sum(axis=1).astype(np.int32))
+        wcs = to_dev(w[:, 1::2].astype(np.int32).sum(axis=1).astype(np.int32))
+    acc = api.quik_int_gemm(xq, to_dev(wp), K_b, bits, code_sum=cs, w_code_sum=wcs)
     _sync()
     want = oracle.int_gemm(q, w, bits)
     got = acc.cpu().numpy()
@@ -135,10 +145,13 @@ def test_weight_reduce_is_bit_exact(api, oracle, N, K_b, bits):
     ld = api.quik_packed_row_bytes(K_b, bits)
     buf = np.full((N, ld), 0xFF, np.uint8)
     buf[:, : wp.shape[1]] = wp
-    got = api.quik_weight_reduce(to_dev(buf), to_dev(sw), K_b, bits)
+    got, w_code_sum = api.quik_weight_reduce(to_dev(buf), to_dev(sw), K_b, bits)
     _sync()
-    want = oracle.weight_reduce(oracle.unpack(wp, K_b, bits), sw)
+    wq = oracle.unpack(wp, K_b, bits)
+    want = oracle.weight_reduce(wq, sw)
     assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    if bits == 4:                                # sum of the signed codes at odd positions
+        assert np.array_equal(w_code_sum.cpu().numpy(), wq[:, 1::2].astype(np.int32).sum(axis=1))
 
 
 def _linear_case(api, oracle, shp, bias=False, gain=40.0):
@@ -148,15 +161,15 @@ def _linear_case(api, oracle, shp, bias=False, gain=40.0):
     if bias:
         b = np.random.default_rng(1).standard_normal(shp.N).astype(np.float16)
     ref = oracle.linear(inp.x, inp.outlier_idx, shp.bits, inp.w_packed, inp.w_scale, inp.w_out, bias=b)
-    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
-    y = api.quik_linear(d["x"], d["idx"], shp.bits, d["w_q"], d["w_scale"], w_red, d["w_out"],
+    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
+    y = api.quik_linear(d["x"], d["idx"], shp.bits, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"],
                         bias=to_dev(b) if bias else None)
     _sync()
     assert np.array_equal(w_red.cpu().numpy().view(np.uint32), ref.w_reduced.view(np.uint32))
     ok, worst = output_within_tolerance(y.cpu().numpy(), ref.y)
     assert ok, f"fp16 output outside 5e-3 (worst error / tolerance = {worst:.2f})"
     assert worst > 0                                   # not a trivially equal array
-    return inp, d, ref, w_red
+    return inp, d, ref, w_red, w_cs
 
 
 LINEAR_SHAPES = [
@@ -190,15 +203,17 @@ def test_linear_with_bias(api, oracle):
 
 def test_stages_called_separately_agree_with_the_fused_entry_point(api, oracle):
     shp = synth.LayerShape("stages", 100, 1024, 160, 64, 4, seed=42)
-    inp, d, ref, w_red = _linear_case(api, oracle, shp)
-    xq, scale, zero, x_out = api.quik_quantize(d["x"], d["idx"], 4)
-    y2 = api.quik_gemm_dequant(xq, scale, zero, x_out, shp.K_b, 4, d["w_q"], d["w_scale"], w_red,
-                               d["w_out"])
+    inp, d, ref, w_red, w_cs = _linear_case(api, oracle, shp)
+    xq, scale, zero, x_out, cs = api.quik_quantize(d["x"], d["idx"], 4)
+    y2 = api.quik_gemm_dequant(xq, scale, zero, cs, x_out, shp.K_b, 4, d["w_q"], d["w_scale"], w_red,
+                               w_cs, d["w_out"])
     acc = api.quik_int_gemm(xq, d["w_q"], shp.K_b, 4)
-    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
+    acc2 = api.quik_int_gemm(xq, d["w_q"], shp.K_b, 4, code_sum=cs, w_code_sum=w_cs)
+    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
     _sync()
     assert np.array_equal(y1.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
     assert np.array_equal(acc.cpu().numpy(), ref.acc)
+    assert np.array_equal(acc2.cpu().numpy(), ref.acc)
 
 
 def test_strided_input_and_output(api, oracle):
@@ -211,8 +226,8 @@ def test_strided_input_and_output(api, oracle):
     xbig = torch.full((shp.T, shp.K + 64), 777.0, dtype=torch.float16, device="cuda")
     xbig[:, : shp.K] = d["x"]
     ybig = torch.full((shp.T, shp.N + 24), -5.0, dtype=torch.float16, device="cuda")
-    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
-    api.quik_linear(xbig[:, : shp.K], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"],
+    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    api.quik_linear(xbig[:, : shp.K], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"],
                     out=ybig[:, : shp.N])
     _sync()
     yh = ybig.cpu().numpy()
@@ -235,15 +250,17 @@ def test_full_size_workloads_on_sampled_tokens(api, oracle, name):
     bits = shp.bits
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, bits)
-    xq, scale, zero, x_out = api.quik_quantize(d["x"], d["idx"], bits)
-    y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, d["w_out"])
+    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, bits)
+    xq, scale, zero, x_out, cs = api.quik_quantize(d["x"], d["idx"], bits)
+    y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
     _sync()
     q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, bits)
     assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, q, bits, xq.shape[1]))
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
     assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32))
     assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16))
+    if bits == 4:
+        assert np.array_equal(cs.cpu().numpy(), q[:, 0::2].astype(np.int32).sum(axis=1))
     T = shp.T
     sel = np.unique(np.array([0, 1, 31, 32, 127, 128, 255, 256, T // 2 - 1, T // 2, T - 2, T - 1]) % T)
     ref = oracle.linear(inp.x[sel], inp.outlier_idx, bits, inp.w_packed, inp.w_scale, inp.w_out)
@@ -252,6 +269,12 @@ def test_full_size_workloads_on_sampled_tokens(api, oracle, name):
     del y
     # raw accumulators of the sampled rows (the hook is run on those rows only: the int32
     # matrix of the largest workload would not be worth its 470 MB)
-    acc = api.quik_int_gemm(xq[torch.from_numpy(sel).cuda()].contiguous(), d["w_q"], shp.K_b, bits)
+    rows = torch.from_numpy(sel).cuda()
+    acc = api.quik_int_gemm(xq[rows].contiguous(), d["w_q"], shp.K_b, bits)
     _sync()
     assert np.array_equal(acc.cpu().numpy(), ref.acc)
+    if bits == 4:
+        acc = api.quik_int_gemm(xq[rows].contiguous(), d["w_q"], shp.K_b, bits,
+                                code_sum=cs[rows].contiguous(), w_code_sum=w_cs)
+        _sync()
+        assert np.array_equal(acc.cpu().numpy(), ref.acc)
