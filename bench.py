@@ -98,8 +98,10 @@ def run_sweep(args, shp, torch, api, synth):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=30)
+    # The GPU's clocks take some tens of milliseconds of continuous load to reach their sustained
+    # state (the first ~40 ms run up to 20 % slower), so the untimed warm-up is ~100 ms of steps.
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--workload", default="llama7b_up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true")
@@ -203,7 +205,7 @@ def main():
     ms_fp16 = None
     if not args.no_fp16:
         wf = (torch.randn((N, K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
-        for _ in range(10):
+        for _ in range(max(10, args.warmup // 2)):
             torch.nn.functional.linear(x, wf)
         ms_fp16 = _event_ms(lambda: torch.nn.functional.linear(x, wf), it, torch)
         del wf

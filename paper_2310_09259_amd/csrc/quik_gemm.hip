@@ -219,18 +219,50 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         }
     };
 
+    // ---- epilogue parameters, fetched before the first DMA so that their (in-order) return does
+    // not sit behind the stage loads: per token row (to LDS below) and per output column (registers)
+    constexpr int RPT = (BM + NT - 1) / NT;              // token rows per thread
+    float p_s[RPT], p_z[RPT];
+    int p_c[RPT];
+    float c_sw[TN], c_wr[TN], c_bv[TN];
+    int c_nc[TN];
+    if constexpr (!RAW) {
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int t = t0 + tid + q * NT;
+            const bool ok = (tid + q * NT < BM) && t < a.T;
+            p_s[q] = ok ? a.scale[t] : 0.0f;
+            p_z[q] = ok ? a.zero[t] : 0.0f;
+            p_c[q] = 0;
+            if constexpr (ASYM) p_c[q] = (ok && !a.fp_only) ? a.code_sum[t] : 0;
+        }
+        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
+        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = min(n0 + wn * TN * 32 + j * 32 + l32, a.N - 1);
+            c_sw[j] = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));   // exact power-of-two factor
+            c_bv[j] = bias ? __half2float(bias[n]) : 0.0f;
+            c_wr[j] = a.w_reduced[n];
+            c_nc[j] = 0;
+            if constexpr (ASYM) c_nc[j] = a.fp_only ? 0 : -128 * a.w_code_sum[n];
+            if (a.fp_only) { c_sw[j] = 0.0f; c_bv[j] = 0.0f; c_wr[j] = 0.0f; }
+        }
+    }
+
     // ---- prologue: fill every stage buffer
 #pragma unroll
     for (int s = 0; s < NST; ++s) issue_any(s);
 
     if constexpr (!RAW) {
-        for (int r = tid; r < BM; r += NT) {
-            int t = t0 + r;
-            float s = (t < a.T) ? a.scale[t] : 0.0f;
-            float z = (t < a.T) ? a.zero[t] : 0.0f;
-            lds_sa[r] = s;                                    // scaleAct
-            lds_sh[r] = z + (float)(1 << (BITS - 1)) * s;     // zeroAct + halfRange * scaleAct
-            if constexpr (ASYM) lds_ct[r] = (t < a.T && !a.fp_only) ? 8 * a.code_sum[t] : 0;
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int r = tid + q * NT;
+            if (r < BM) {
+                lds_sa[r] = p_s[q];                                          // scaleAct
+                lds_sh[r] = p_z[q] + (float)(1 << (BITS - 1)) * p_s[q];      // zeroAct + halfRange * scaleAct
+                if constexpr (ASYM) lds_ct[r] = -128 * p_c[q];               // in raw accumulator units
+            }
         }
     }
 
@@ -354,46 +386,35 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             }
         return;
     }
-    const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
-    const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+    // Dequantization.  The raw accumulator is 2^SHIFT times the integer dot product plus, for the
+    // single-AND widening, 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes that,
+    // the conversion to binary32 is exact (at most 24 significant bits), and 2^-SHIFT rides on the
+    // weight scale.
     v16f cf[TM][TN];
-    {
-        float sw[TN], wr[TN], bv[TN];
-        int cn[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int n = min(nw + j * 32 + l32, a.N - 1);
-            sw[j] = __half2float(wsc[n]);
-            bv[j] = bias ? __half2float(bias[n]) : 0.0f;
-            wr[j] = a.w_reduced[n];
-            cn[j] = 0;
-            if constexpr (ASYM) cn[j] = a.fp_only ? 0 : 8 * a.w_code_sum[n];
-            if (a.fp_only) { sw[j] = 0.0f; bv[j] = 0.0f; wr[j] = 0.0f; }
-        }
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const int lr = wm * TM * 32 + i * 32 + 8 * rq + 4 * g;
-                const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
-                const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
-                const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
-                int ct_[4] = {0, 0, 0, 0};
-                if constexpr (ASYM) {
-                    const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[lr]);
-                    ct_[0] = ct4.x; ct_[1] = ct4.y; ct_[2] = ct4.z; ct_[3] = ct4.w;
-                }
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        const int r = rq * 4 + rr;
-                        // exact INT32 accumulator of the method
-                        const int ai = (acc[i][j][r] >> SHIFT) - ct_[rr] - cn[j];
-                        cf[i][j][r] = __builtin_fmaf((float)ai, sa_[rr] * sw[j], __builtin_fmaf(sh_[rr], wr[j], bv[j]));
-                    }
+        for (int rq = 0; rq < 4; ++rq) {
+            const int lr = wm * TM * 32 + i * 32 + 8 * rq + 4 * g;
+            const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
+            const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
+            const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
+            int ct_[4] = {0, 0, 0, 0};
+            if constexpr (ASYM) {
+                const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[lr]);
+                ct_[0] = ct4.x; ct_[1] = ct4.y; ct_[2] = ct4.z; ct_[3] = ct4.w;
             }
-    }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int r = rq * 4 + rr;
+                    int ai = acc[i][j][r];
+                    if constexpr (ASYM) ai = ai + ct_[rr] + c_nc[j];
+                    cf[i][j][r] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j],
+                                                 __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
+                }
+        }
 
     for (; s < nk; ++s) {
 #pragma unroll
@@ -419,6 +440,51 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 
     wait_vm<0>();                          // drain the look-ahead DMA before the wave ends
     __half* __restrict__ y = static_cast<__half*>(a.y);
+#ifndef QUIK_DIRECT_STORE
+    // Output through LDS: a lane owns one column of sixteen rows of every 32 x 32 block, so direct
+    // stores would be 2 bytes per lane.  Each wave instead parks its fp16 tile in its own slice of
+    // the (now dead) stage ring and writes it out as 16-byte pieces, whole 64/128-byte row
+    // segments per instruction.  Needs 16-byte aligned output rows; otherwise the direct path below.
+    constexpr int WROW = TN * 64 + 16;                   // bytes per parked row (padded against bank conflicts)
+    constexpr int WBUF = TM * 32 * WROW;
+    static_assert(NWAVES * WBUF <= NST * ST_BYTES, "stage ring too small to park the output tile");
+    const bool vec_ok = !a.fp_only && ((reinterpret_cast<uintptr_t>(a.y) & 15u) == 0) && (a.ldy % 8 == 0);
+    if (vec_ok) {
+        __syncthreads();                   // every wave is past its last read of the stage ring
+        uint8_t* wbuf = lds + wave_u * WBUF;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    *reinterpret_cast<__half*>(wbuf + row * WROW + (j * 32 + l32) * 2) = __float2half(cf[i][j][r]);
+                }
+        constexpr int CH = TN * 4;                       // 16-byte pieces per row
+        constexpr int RPS = 64 / CH;                     // rows per store instruction
+        const int prow = lane / CH, pch = lane % CH;
+#pragma unroll
+        for (int p = 0; p < TM * 32 / RPS; ++p) {
+            const int row = p * RPS + prow;
+            const uint4 v = *reinterpret_cast<const uint4*>(wbuf + row * WROW + pch * 16);
+            const int t = tw + row, n = nw + pch * 8;
+            if (t < a.T) {
+                __half* dst = y + (size_t)t * a.ldy + n;
+                if (n + 8 <= a.N) {
+                    *reinterpret_cast<uint4*>(dst) = v;
+                } else {
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < a.N)
+                            reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        return;
+    }
+#endif
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
