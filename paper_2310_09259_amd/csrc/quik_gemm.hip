@@ -125,8 +125,13 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     constexpr int HALVES = (BITS == 4) ? 2 : 1;          // MFMAs per output tile per sub-step
     constexpr int SLOTS = TM * TN * HALVES;
     constexpr int WORDS = NF * 4;
-    constexpr int BAR_KS = KSUB - 2;                     // stage barrier sits before this sub-step
-    static_assert(KSUB % 2 == 0 && NST >= 2, "");
+#ifndef QUIK_LA
+#define QUIK_LA 2
+#endif
+    constexpr int LA = (QUIK_LA < KSUB) ? QUIK_LA : KSUB - 1;   // LDS reads run LA sub-steps ahead of their MFMAs
+    constexpr int RD = (KSUB % LA == 0) ? LA : LA + 1;   // raw fragment sets (a divisor of KSUB: static indices)
+    constexpr int BAR_KS = KSUB - LA;                    // stage barrier sits before this sub-step
+    static_assert(KSUB % 2 == 0 && NST >= 2 && LA >= 1 && KSUB % RD == 0, "raw set index must be static");
 
     __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES];
     __shared__ __align__(16) float lds_sa[BM];
@@ -275,15 +280,15 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         for (int ks = 0; ks < KSUB; ++ks) rd[f][ks] = base + (((ks * 2 + g) ^ swz<BKB>(r)) << 4);
     }
 
-    uint4 R[2][NF];
+    uint4 R[RD][NF];
     v4i U[2][NF][HALVES];
 
     auto read_frag = [&](int set, int f, const uint8_t* stage, int ks) {
         R[set][f] = *reinterpret_cast<const uint4*>(stage + rd[f][ks]);
     };
-    auto widen_word = [&](int set, int w) {
+    auto widen_word = [&](int set, int rset, int w) {
         const int f = w >> 2, k = w & 3;
-        const uint32_t x = (k == 0) ? R[set][f].x : (k == 1) ? R[set][f].y : (k == 2) ? R[set][f].z : R[set][f].w;
+        const uint32_t x = (k == 0) ? R[rset][f].x : (k == 1) ? R[rset][f].y : (k == 2) ? R[rset][f].z : R[rset][f].w;
         if constexpr (BITS == 4) {
             // slot 0 of a word pair holds the even k of the word, slot 1 the odd k
             constexpr uint32_t M = 0xF0F0F0F0u;
@@ -325,8 +330,9 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             stage_barrier();
             if (!plain) issue_any(s + NST);
         }
-        const int ts = (ks + 2 < KSUB) ? s : s + 1, tks = (ks + 2) % KSUB;
+        const int ts = (ks + LA < KSUB) ? s : s + 1, tks = (ks + LA) % KSUB;
         const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
+        const int rnext = (ks + 1) % RD, rload = (ks + LA) % RD;   // static: KSUB is a multiple of RD
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < SLOTS; ++m) {
@@ -340,10 +346,10 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             }
 #pragma unroll
             for (int w = 0; w < WORDS; ++w)
-                if (w * SLOTS / WORDS == m) widen_word(par ^ 1, w);
-            if (m < NF) read_frag(par, m, tgt, tks);
+                if (w * SLOTS / WORDS == m) widen_word(par ^ 1, rnext, w);
+            if (m < NF) read_frag(rload, m, tgt, tks);
             if (SLOTS < NF && m == SLOTS - 1)
-                for (int f = SLOTS; f < NF; ++f) read_frag(par, f, tgt, tks);
+                for (int f = SLOTS; f < NF; ++f) read_frag(rload, f, tgt, tks);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -351,9 +357,11 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     wait_vm<(NST - 1) * LPS>();          // stage 0 landed
     __syncthreads();
 #pragma unroll
-    for (int f = 0; f < NF; ++f) { read_frag(0, f, lds, 0); read_frag(1, f, lds, 1); }
+    for (int q = 0; q < LA; ++q)
 #pragma unroll
-    for (int w = 0; w < WORDS; ++w) widen_word(0, w);
+        for (int f = 0; f < NF; ++f) read_frag(q, f, lds, q);
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) widen_word(0, 0, w);
 
     int s = 0;
     for (; s + NST < nk_int - 1; ++s) {
@@ -364,7 +372,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 #pragma unroll
         for (int ks = 0; ks < KSUB; ++ks) substep(s, ks, false);
     }
-    // here: R[0] / R[1] hold raw sub-steps 0 / 1 of stage nk_int (fp16 data)
+    // here: R[0 .. LA-1] hold raw sub-steps 0 .. LA-1 of stage nk_int (fp16 data)
 
     const int tw = t0 + wm * TM * 32, nw = n0 + wn * TN * 32;
     if constexpr (RAW) {
@@ -421,15 +429,15 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         for (int ks = 0; ks < KSUB; ++ks) {
             const int par = ks & 1;
             if (ks == BAR_KS) { stage_barrier(); issue_any(s + NST); }
-            const int ts = (ks + 2 < KSUB) ? s : s + 1, tks = (ks + 2) % KSUB;
+            const int ts = (ks + LA < KSUB) ? s : s + 1, tks = (ks + LA) % KSUB;
             const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
             v8h fa[TM], fb[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = __builtin_bit_cast(v8h, R[par][i]);
+            for (int i = 0; i < TM; ++i) fa[i] = __builtin_bit_cast(v8h, R[ks % RD][i]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = __builtin_bit_cast(v8h, R[par][TM + j]);
+            for (int j = 0; j < TN; ++j) fb[j] = __builtin_bit_cast(v8h, R[ks % RD][TM + j]);
 #pragma unroll
-            for (int f = 0; f < NF; ++f) read_frag(par, f, tgt, tks);
+            for (int f = 0; f < NF; ++f) read_frag((ks + LA) % RD, f, tgt, tks);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -445,7 +453,8 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     // stores would be 2 bytes per lane.  Each wave instead parks its fp16 tile in its own slice of
     // the (now dead) stage ring and writes it out as 16-byte pieces, whole 64/128-byte row
     // segments per instruction.  Needs 16-byte aligned output rows; otherwise the direct path below.
-    constexpr int WROW = TN * 64 + 16;                   // bytes per parked row (padded against bank conflicts)
+    // bytes per parked row: padded against bank conflicts where the ring has the room
+    constexpr int WROW = (NWAVES * TM * 32 * (TN * 64 + 16) <= NST * ST_BYTES) ? TN * 64 + 16 : TN * 64;
     constexpr int WBUF = TM * 32 * WROW;
     static_assert(NWAVES * WBUF <= NST * ST_BYTES, "stage ring too small to park the output tile");
     const bool vec_ok = !a.fp_only && ((reinterpret_cast<uintptr_t>(a.y) & 15u) == 0) && (a.ldy % 8 == 0);

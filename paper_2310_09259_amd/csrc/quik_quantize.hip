@@ -8,19 +8,31 @@
 //
 // Outlier columns are described by a bitmask over the K columns plus an exclusive
 // prefix count per 32-column word, both built once per workgroup in LDS.  A thread
-// that holds columns [k0, k0+8) derives from them which of its elements are base
-// columns and the position of its first base element in the packed output row.
-// Its (at most 8) quantized codes are squeezed into one 32/64-bit value and OR-ed
-// into an LDS image of the packed row at an arbitrary bit offset, so the packed
-// row leaves the CU as full, aligned 128-bit stores.
+// holds the same columns [k0, k0+8) of every row it works on, so everything that
+// follows from the outlier set alone is computed once per workgroup and kept in
+// registers: which of its elements are base columns, where its first base element
+// lands in the packed row, the bit masks that squeeze outlier positions out of a
+// packed chunk.  Per row and element that leaves: one half->float conversion, the
+// subtract, the multiply and the rounding add of the method, and one shift-add that
+// packs the code.
+//   pass 1: outlier halves are overwritten with a quiet NaN, which the packed fp16
+//           minimum/maximum instructions ignore (IEEE minNum/maxNum); fp16 min/max
+//           are exact, so this equals the binary32 min/max of the method;
+//   pass 2: outlier halves are overwritten with the row minimum (code 0) so that
+//           their huge quotients cannot disturb neighbouring codes, then squeezed out.
+// The (at most 8) codes of a chunk are OR-ed into an LDS image of the packed row at
+// an arbitrary bit offset, so the packed row leaves the CU as full, aligned 128-bit
+// stores.  With one wave per row (K <= 4096) nothing in the row loop needs a
+// workgroup barrier: a wave's LDS operations execute in order.
 //
 // Bit exactness: binary32 arithmetic, one IEEE division and one IEEE reciprocal
 // per row, a subtract and a multiply per element (never contracted).  Rounding to
 // the nearest integer, ties to even, is done by adding 1.5 * 2^23: the sum's unit
 // in the last place is 1 there, so the adder's own round-to-nearest-even performs
-// the rounding and the low mantissa bits are the integer.  For finite inputs
+// the rounding, and the sum's bit pattern is 0x4B400000 + code.  For finite inputs
 // (x - min) * (1 / scale) lies in [0, (2^bits - 1) * (1 + 2^-22)], so the clamp of
-// the method can never fire and is replaced by a bit mask.
+// the method can never fire; the codes of a chunk are accumulated with shift-adds of
+// the whole bit patterns and the constant part is subtracted once.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -102,8 +114,331 @@ __device__ __forceinline__ int emit_chunk(const Chunk& c, uint32_t m8, int base0
     }
 }
 
-// NCH > 0: the row is cached in NCH 128-bit registers per thread (K <= TPR*8*NCH).
-// NCH == 0: any K; the second pass re-reads the row (from cache).
+// ---- fast path (row cached in registers) -------------------------------------------------
+
+__device__ __forceinline__ uint32_t pk_min_f16(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+// (m & a) | (~m & b)
+__device__ __forceinline__ uint32_t bit_select(uint32_t m, uint32_t a, uint32_t b) { return (m & a) | (~m & b); }
+
+constexpr uint32_t kNaN2 = 0x7E007E00u;           // two quiet fp16 NaNs
+constexpr uint32_t kMagicBits = 0x4B400000u;      // bit pattern of 1.5 * 2^23
+
+// What a thread knows about one of its chunks from the outlier set alone.
+template <int BITS>
+struct ChunkPlan {
+    uint32_t sel[4];      // per dword: all-ones halves where the element is an outlier (or beyond K)
+    uint32_t low[3];      // 4-bit: masks that drop the three highest outlier positions (all-ones = no-op)
+    uint32_t keep_lo, keep_hi;   // bits of the squeezed chunk that hold codes
+    // bits 0..4: bit offset of the squeezed chunk inside its first word of the row image;
+    // bit 5: the chunk starts at an odd packed position; bits 8..15: outlier positions left for
+    // the generic loop (8-bit: all of them); bits 16..31: index of that first word
+    uint32_t pos;
+    __device__ __forceinline__ uint32_t more() const { return (pos >> 8) & 0xFFu; }
+};
+__device__ __forceinline__ uint32_t pos_shift(uint32_t pos) { return pos & 31u; }
+__device__ __forceinline__ uint32_t pos_even_shift(uint32_t pos) { return (pos >> 3) & 4u; }
+__device__ __forceinline__ uint32_t pos_more(uint32_t pos) { return (pos >> 8) & 0xFFu; }
+__device__ __forceinline__ uint32_t pos_word(uint32_t pos) { return pos >> 16; }
+
+template <int BITS, int TPR>
+__device__ __forceinline__ void plan_chunk(ChunkPlan<BITS>& p, int k0, int K, int K_b,
+                                           const uint32_t* mask, const uint32_t* pre) {
+    uint32_t m8 = 0xFFu;
+    int base0 = 0;
+    if (k0 < K) {
+        const uint32_t word = mask[k0 >> 5];
+        m8 = (word >> (k0 & 31)) & 0xFFu;
+        base0 = k0 - (int)(pre[k0 >> 5] + __popc(word & ((1u << (k0 & 31)) - 1u)));
+    }
+    int cnt = 8 - __popc(m8);
+    if (base0 >= K_b) cnt = 0;                     // only with a malformed index list
+    if (cnt > K_b - base0) cnt = K_b - base0;
+    if (cnt <= 0) { cnt = 0; base0 = 0; }          // nothing to emit: park the (zero) write at word 0
+    const uint32_t squeeze = cnt ? m8 : 0u;        // an empty chunk is masked away whole: no squeeze
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+        p.sel[d] = (((m8 >> (2 * d)) & 1u) ? 0x0000FFFFu : 0u) | (((m8 >> (2 * d + 1)) & 1u) ? 0xFFFF0000u : 0u);
+    uint32_t rest = squeeze;
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            if (rest) {
+                const int pos = 31 - __clz(rest);
+                p.low[j] = pos ? (0xFFFFFFFFu >> (32 - 4 * pos)) : 0u;
+                rest &= ~(1u << pos);
+            } else {
+                p.low[j] = 0xFFFFFFFFu;
+            }
+        }
+    }
+    const int bits = cnt * BITS;                   // 0 .. 64
+    p.keep_lo = bits >= 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
+    p.keep_hi = bits >= 64 ? 0xFFFFFFFFu : (bits > 32 ? ((1u << (bits - 32)) - 1u) : 0u);
+    const uint32_t bit = (uint32_t)base0 * BITS;
+    p.pos = (bit & 31u) | ((base0 & 1) ? 32u : 0u) | (rest << 8) | ((bit >> 5) << 16);
+}
+
+// Codes of the eight elements of a chunk whose outlier halves already read as the row minimum.
+// 4-bit: nibble i of the result; 8-bit: byte i of (lo, hi).
+template <int BITS>
+__device__ __forceinline__ void chunk_codes(const uint32_t (&x)[4], float mn, float inv, uint32_t& lo, uint32_t& hi) {
+    uint32_t b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const __half h = __ushort_as_half((unsigned short)(x[i >> 1] >> (16 * (i & 1))));
+        b[i] = code_bits(h, mn, inv);              // 0x4B400000 + code
+    }
+    if constexpr (BITS == 4) {
+        uint32_t w = b[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) w += b[i] << (4 * i);
+        uint32_t c = 0;                            // the eight shifted copies of the constant part
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c += kMagicBits << (4 * i);
+        lo = w - c;
+        hi = 0;
+    } else {
+        uint32_t w0 = b[0], w1 = b[4];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) { w0 += b[i] << (8 * i); w1 += b[4 + i] << (8 * i); }
+        uint32_t c = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c += kMagicBits << (8 * i);
+        lo = w0 - c;
+        hi = w1 - c;
+    }
+}
+
+// K <= TPR * 8 * NCH: the row lives in NCH 128-bit registers per thread.
+template <int BITS, int TPR, int NCH>
+__global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kernel(
+    const __half* __restrict__ x, int T, int K, int ldx, const int32_t* __restrict__ idx, int n_out,
+    uint8_t* __restrict__ xq, int ldq, float* __restrict__ scale, float* __restrict__ zero,
+    int32_t* __restrict__ code_sum, __half* __restrict__ x_out, int ldo) {
+    constexpr int RPB = kBlock / TPR;             // rows per workgroup iteration
+    constexpr bool WAVE_ROW = TPR == 64;          // a row never leaves its wave: no workgroup barriers
+    extern __shared__ __align__(16) uint32_t lds[];
+    const int nwords = (K + 31) >> 5;
+    uint32_t* mask = lds;
+    uint32_t* pre = mask + nwords;
+    float* red = reinterpret_cast<float*>(pre + nwords);       // [2 * 4] wave partials
+    uint32_t* wave_tot = reinterpret_cast<uint32_t*>(red + 8); // [4]
+    int* red_i = reinterpret_cast<int*>(wave_tot + 4);         // [4] wave partials of the code sum
+    const int img0 = (2 * nwords + 16 + 3) & ~3;               // first row image, 16-byte aligned (in words)
+
+    const int tid = threadIdx.x;
+    const int g = tid / TPR, lt = tid % TPR;
+    const int K_b = K - n_out;
+    const int ldq_words = ldq >> 2;
+    uint32_t* stage = lds + img0 + g * (ldq_words + 4);        // one spare 16 bytes behind every image
+    const int nrowblk = (T + RPB - 1) / RPB;
+
+    auto load_row = [&](uint4 (&cache)[NCH], int rb) {
+        const int t = rb * RPB + g;
+        const __half* row = x + (size_t)(t < T ? t : 0) * ldx;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int k0 = (c * TPR + lt) * 8;
+            if (t < T && k0 < K) cache[c] = *reinterpret_cast<const uint4*>(row + k0);
+            else cache[c] = make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    constexpr bool DOUBLE = NCH <= 4;             // second register set for the next row (register budget)
+    uint4 ca[NCH], cb[DOUBLE ? NCH : 1];
+    int rb = blockIdx.x;
+    if (rb < nrowblk) load_row(ca, rb);            // the first loads do not depend on the outlier map
+    build_outlier_map(idx, n_out, K, nwords, mask, pre, wave_tot);
+
+    ChunkPlan<BITS> plan[NCH];
+    uint32_t any_more = 0;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        plan_chunk<BITS, TPR>(plan[c], (c * TPR + lt) * 8, K, K_b, mask, pre);
+        any_more |= plan[c].more();
+    }
+    // generic squeeze needed by some lane of this wave? (more than three outliers in one 4-bit chunk)
+    const bool wave_more = __builtin_amdgcn_ballot_w64(any_more != 0) != 0;
+
+    auto process_row = [&](const uint4 (&cache)[NCH], int rbk) {
+        const int t = rbk * RPB + g;
+        const bool valid = t < T;
+        const __half* row = x + (size_t)(valid ? t : 0) * ldx;
+
+        // the outlier columns of this row (cache hits: the row has just been read)
+        constexpr int GJ = 4;
+        __half gv[GJ];
+#pragma unroll
+        for (int q = 0; q < GJ; ++q) {
+            const int j = lt + q * TPR;
+            gv[q] = __ushort_as_half((unsigned short)0);
+            if (valid && j < n_out) {
+                const int c = idx[j];
+                if (c >= 0 && c < K) gv[q] = row[c];
+            }
+        }
+
+        for (int i = lt; i < ldq_words; i += TPR) stage[i] = 0u;
+
+        // ---- pass 1: min/max over base columns
+        uint32_t mn2 = kNaN2, mx2 = kNaN2;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const uint32_t xw[4] = {cache[c].x, cache[c].y, cache[c].z, cache[c].w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t v = bit_select(plan[c].sel[d], kNaN2, xw[d]);
+                mn2 = pk_min_f16(mn2, v);
+                mx2 = pk_max_f16(mx2, v);
+            }
+        }
+        float mn = fminf(__half2float(__ushort_as_half((unsigned short)mn2)),
+                         __half2float(__ushort_as_half((unsigned short)(mn2 >> 16))));
+        float mx = fmaxf(__half2float(__ushort_as_half((unsigned short)mx2)),
+                         __half2float(__ushort_as_half((unsigned short)(mx2 >> 16))));
+        mn = wave_min(mn);
+        mx = wave_max(mx);
+        if constexpr (!WAVE_ROW) {
+            const int wv = tid >> 6;
+            if ((tid & 63) == 0) { red[wv] = mn; red[4 + wv] = mx; }
+            __syncthreads();                       // also: row image zeroed by all lanes
+            mn = fminf(fminf(red[0], red[1]), fminf(red[2], red[3]));
+            mx = fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7]));
+        }
+        mn = mn + 0.0f;                            // -0 -> +0
+        const float range = mx - mn;
+        const float s = (range == 0.0f) ? 1.0f : range / (float)((1 << BITS) - 1);
+        const float inv = 1.0f / s;
+        if (valid && lt == 0) { scale[t] = s; zero[t] = mn; }
+        const uint32_t mnh = __half_as_ushort(__float2half(mn));   // exact: the minimum is an fp16 value
+        const uint32_t mnh2 = mnh | (mnh << 16);
+
+        // ---- pass 2: quantize the base elements into the LDS row image
+        uint32_t esum = 0;                         // unsigned codes at even positions (4-bit only)
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const ChunkPlan<BITS>& p = plan[c];
+            const uint32_t xw[4] = {bit_select(p.sel[0], mnh2, cache[c].x), bit_select(p.sel[1], mnh2, cache[c].y),
+                                    bit_select(p.sel[2], mnh2, cache[c].z), bit_select(p.sel[3], mnh2, cache[c].w)};
+            uint32_t lo, hi;
+            chunk_codes<BITS>(xw, mn, inv, lo, hi);
+            // the fields of pos are unpacked per row on purpose (hoisting them out of the row loop
+            // would cost three registers per chunk)
+            uint32_t pos = p.pos;
+            asm volatile("" : "+v"(pos));
+            if constexpr (BITS == 4) {
+#pragma unroll
+                for (int j = 0; j < 3; ++j) lo = bit_select(p.low[j], lo, lo >> 4);
+                if (wave_more) {
+                    uint32_t m = pos_more(pos);
+                    while (m) {
+                        const int hp = 31 - __clz(m);
+                        lo = drop_element<uint32_t, 4>(lo, hp);
+                        m &= ~(1u << hp);
+                    }
+                }
+                lo &= p.keep_lo;
+                esum = __builtin_amdgcn_sad_u8((lo >> pos_even_shift(pos)) & 0x0F0F0F0Fu, 0u, esum);
+                lo = (lo ^ 0x88888888u) & p.keep_lo;          // code - halfRange as two's complement nibbles
+                const uint64_t v = (uint64_t)lo << pos_shift(pos);
+                atomicOr(&stage[pos_word(pos)], (uint32_t)v);
+                atomicOr(&stage[pos_word(pos) + 1], (uint32_t)(v >> 32));
+            } else {
+                uint64_t w = ((uint64_t)hi << 32) | lo;
+                uint32_t m = pos_more(pos);
+                while (m) {
+                    const int hp = 31 - __clz(m);
+                    w = drop_element<uint64_t, 8>(w, hp);
+                    m &= ~(1u << hp);
+                }
+                const uint64_t keep = ((uint64_t)p.keep_hi << 32) | p.keep_lo;
+                w = (w ^ 0x8080808080808080ull) & keep;
+                const uint32_t sh = pos_shift(pos);
+                const uint64_t v = w << sh;
+                const uint32_t top = sh ? (uint32_t)(w >> (64u - sh)) : 0u;
+                atomicOr(&stage[pos_word(pos)], (uint32_t)v);
+                atomicOr(&stage[pos_word(pos) + 1], (uint32_t)(v >> 32));
+                atomicOr(&stage[pos_word(pos) + 2], top);
+            }
+        }
+        if constexpr (BITS == 4) {
+            // sum over even positions of the signed codes (the GEMM's correction term for its
+            // single-AND operand widening)
+            int es = (int)esum;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) es += __shfl_xor(es, o, 64);
+            if constexpr (!WAVE_ROW) {
+                if ((tid & 63) == 0) red_i[tid >> 6] = es;
+                __syncthreads();
+                es = red_i[0] + red_i[1] + red_i[2] + red_i[3];
+            }
+            if (valid && lt == 0 && code_sum) code_sum[t] = es - 8 * (K_b >> 1);
+        } else if constexpr (!WAVE_ROW) {
+            __syncthreads();
+        }
+        if constexpr (WAVE_ROW) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+
+        // ---- write the packed row (including its zero padding up to ldq); 4-bit rows leave with
+        // the two nibbles of every byte swapped: element 2p in the high nibble
+        if (valid) {
+            uint4* dst = reinterpret_cast<uint4*>(xq + (size_t)t * ldq);
+            const uint4* src = reinterpret_cast<const uint4*>(stage);
+            for (int i = lt; i < (ldq >> 4); i += TPR) {
+                uint4 v = src[i];
+                if constexpr (BITS == 4) {
+                    auto sw = [](uint32_t w) { return ((w & 0x0F0F0F0Fu) << 4) | ((w >> 4) & 0x0F0F0F0Fu); };
+                    v = make_uint4(sw(v.x), sw(v.y), sw(v.z), sw(v.w));
+                }
+                dst[i] = v;
+            }
+            // ---- pass 3: move the outlier columns
+#pragma unroll
+            for (int q = 0; q < GJ; ++q) {
+                const int j = lt + q * TPR;
+                if (j < n_out) x_out[(size_t)t * ldo + j] = gv[q];
+            }
+            for (int j = lt + GJ * TPR; j < n_out; j += TPR) {
+                const int c = idx[j];
+                x_out[(size_t)t * ldo + j] = (c >= 0 && c < K) ? row[c] : __ushort_as_half((unsigned short)0);
+            }
+        }
+        if constexpr (WAVE_ROW) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        else __syncthreads();                      // before the next row clears the image
+    };
+
+    if constexpr (DOUBLE) {
+        // The next row is fetched into a second register set while the current one is processed.
+        while (rb < nrowblk) {
+            int nx = rb + gridDim.x;
+            if (nx < nrowblk) load_row(cb, nx);
+            process_row(ca, rb);
+            rb = nx;
+            if (rb >= nrowblk) break;
+            nx = rb + gridDim.x;
+            if (nx < nrowblk) load_row(ca, nx);
+            process_row(cb, rb);
+            rb = nx;
+        }
+    } else {
+        // Long rows: one register set; other waves of the CU cover the load latency.
+        while (rb < nrowblk) {
+            process_row(ca, rb);
+            rb += gridDim.x;
+            if (rb < nrowblk) load_row(ca, rb);
+        }
+    }
+}
+
+// Generic form for any K (used above 16384 columns): the second pass re-reads the row from cache.
 template <int BITS, int TPR, int NCH>
 __global__ __launch_bounds__(kBlock) void quantize_kernel(
     const __half* __restrict__ x, int T, int K, int ldx, const int32_t* __restrict__ idx, int n_out,
@@ -287,14 +622,23 @@ template <int BITS, int TPR, int NCH>
 hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     constexpr int RPB = kBlock / TPR;
     const int nwords = (a.K + 31) >> 5;
-    size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
     int nrowblk = (a.T + RPB - 1) / RPB;
     // a bounded grid: the outlier map is built once per workgroup and the rows of a workgroup
     // are software-pipelined (next row's loads in flight while the current one is processed)
     int grid = nrowblk < 2048 ? nrowblk : 2048;
-    hipLaunchKernelGGL((quantize_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
-                       (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
-                       a.scale, a.zero, a.code_sum, (__half*)a.x_out, a.ldo);
+    if constexpr (NCH > 0) {
+        // map + prefix, reduction scratch, then RPB row images of ldq bytes + 16 spare bytes each
+        const size_t img0 = (size_t)((2 * nwords + 16 + 3) & ~3);
+        const size_t lds = (img0 + (size_t)RPB * ((a.ldq >> 2) + 4)) * 4;
+        hipLaunchKernelGGL((quantize_rows_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
+                           (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
+                           a.scale, a.zero, a.code_sum, (__half*)a.x_out, a.ldo);
+    } else {
+        const size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
+        hipLaunchKernelGGL((quantize_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
+                           (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
+                           a.scale, a.zero, a.code_sum, (__half*)a.x_out, a.ldo);
+    }
     return hipGetLastError();
 }
 
