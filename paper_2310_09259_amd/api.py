@@ -197,6 +197,36 @@ def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum, 
     return y
 
 
+def prepare_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum, w_out, bias=None,
+                   out=None, workspace=None):
+    """quik_linear with the argument marshalling done once: returns (call, y) where call() enqueues
+    one layer on the stream that was current here, on the same buffers every time.  For loops that
+    launch the same layer many times (serving, benchmarking), where building the ctypes arguments
+    would otherwise cost more host time than a small layer takes on the GPU."""
+    x = _dev(x, torch.float16, "x")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, K = x.shape
+    N = w_q.shape[0]
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    need = quik_workspace_bytes(T, K, N, n_out, bits)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
+    keep = (x, outlier_idx, w_q, w_scale, w_reduced, w_code_sum, w_out, bias, y, workspace)
+    args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(w_q),
+            w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
+            w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
+            workspace.numel(), _stream())
+    fn = load().quik_linear
+
+    def call(_keep=keep):
+        rc = fn(*args)
+        if rc != 0:
+            raise QuikError(rc, "quik_linear")
+
+    return call, y
+
+
 def quik_ablation_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int) -> int:
     return load().quik_ablation_workspace_bytes(T, K, N, n_out, bits)
 

@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
         }
     };
 
-    constexpr bool DOUBLE = NCH <= 4;             // second register set for the next row (register budget)
+    constexpr bool DOUBLE = NCH <= 6;             // second register set for the next row (register budget)
     uint4 ca[NCH], cb[DOUBLE ? NCH : 1];
     int rb = blockIdx.x;
     if (rb < nrowblk) load_row(ca, rb);            // the first loads do not depend on the outlier map
@@ -623,9 +623,11 @@ hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     constexpr int RPB = kBlock / TPR;
     const int nwords = (a.K + 31) >> 5;
     int nrowblk = (a.T + RPB - 1) / RPB;
-    // a bounded grid: the outlier map is built once per workgroup and the rows of a workgroup
-    // are software-pipelined (next row's loads in flight while the current one is processed)
-    int grid = nrowblk < 2048 ? nrowblk : 2048;
+    // a bounded grid: the outlier map and the chunk plans are built once per workgroup, so no more
+    // workgroups are launched than the chip keeps resident; each loops over its row blocks (the
+    // next row's loads in flight while the current one is processed where registers allow)
+    constexpr int kResident = 256 * ((NCH >= 4 || NCH == 0) ? 2 : 3);
+    int grid = nrowblk < (NCH > 0 ? kResident : 2048) ? nrowblk : (NCH > 0 ? kResident : 2048);
     if constexpr (NCH > 0) {
         // map + prefix, reduction scratch, then RPB row images of ldq bytes + 16 spare bytes each
         const size_t img0 = (size_t)((2 * nwords + 16 + 3) & ~3);
@@ -649,7 +651,9 @@ hipError_t dispatch(const QuantizeArgs& a, hipStream_t stream) {
     if (K <= 64 * 8 * 2) return launch<BITS, 64, 2>(a, stream);
     if (K <= 64 * 8 * 4) return launch<BITS, 64, 4>(a, stream);
     if (K <= 64 * 8 * 8) return launch<BITS, 64, 8>(a, stream);
+    if (K <= 256 * 8 * 3) return launch<BITS, 256, 3>(a, stream);
     if (K <= 256 * 8 * 4) return launch<BITS, 256, 4>(a, stream);
+    if (K <= 256 * 8 * 6) return launch<BITS, 256, 6>(a, stream);
     if (K <= 256 * 8 * 8) return launch<BITS, 256, 8>(a, stream);
     return launch<BITS, 256, 0>(a, stream);
 }

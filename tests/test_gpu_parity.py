@@ -278,3 +278,17 @@ def test_full_size_workloads_on_sampled_tokens(api, oracle, name):
                                 code_sum=cs[rows].contiguous(), w_code_sum=w_cs)
         _sync()
         assert np.array_equal(acc.cpu().numpy(), ref.acc)
+
+
+def test_prepared_call_matches_direct_call(api, oracle):
+    """The marshal-once form of quik_linear enqueues exactly the same work."""
+    shp = synth.LayerShape("prepared", 90, 1024, 200, 64, 4, seed=47)
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    call, y2 = api.prepare_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    call()
+    call()
+    _sync()
+    assert np.array_equal(y1.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
