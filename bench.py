@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, MI355X data sheet (5.0 POP/s)
 PEAK_HBM_GBS = 8000.0
-# profiles/gemm_kernel_llama7b_up.md: (112406 KiB * 2.0 + 46389 KiB * 1.0) * 1024
-TRAFFIC_BYTES = {"llama7b_up": int((112406 * 2.0 + 46389) * 1024)}
+# profiles/gemm_kernel_llama7b_up.md: (57472 KiB * 2.0 + 44032 KiB * 1.0) * 1024
+TRAFFIC_BYTES = {"llama7b_up": int((57472 * 2.0 + 44032) * 1024)}
 
 
 def _event_ms(fn, iters, torch):
@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--workload", default="llama7b_up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16", action="store_true")
+    ap.add_argument("--no-ablation", action="store_true",
+                    help="skip the fusion-ablation timings (keeps a kernel trace down to the two "
+                         "kernels of the layer and the FP16 comparator)")
     ap.add_argument("--graph", action="store_true",
                     help="replay a captured HIP graph holding one step instead of launching every "
                          "step through the binding (measured: no faster here, direct launches "
@@ -176,10 +179,11 @@ def main():
     xq, scale, zero, x_out, cs = api.quik_quantize(x, idx, bits)
     q_out = (xq, scale, zero, x_out, cs)
     it = max(20, args.steps // 2)
-    ms_quant = _event_ms(lambda: api.quik_quantize(x, idx, bits, out=q_out), it, torch)
-    ms_gemm = _event_ms(lambda: api.quik_gemm_dequant(xq, scale, zero, cs, x_out if n_out else None, K_b,
-                                                      bits, w_q, w_scale, w_red, w_cs, w_out, out=y),
-                        it, torch)
+    quant_call = api.prepare_quantize(x, idx, bits, q_out)
+    gemm_call = api.prepare_gemm_dequant(xq, scale, zero, cs, x_out if n_out else None, K_b, bits, w_q,
+                                         w_scale, w_red, w_cs, w_out, None, y)
+    ms_quant = _event_ms(quant_call, it, torch)
+    ms_gemm = _event_ms(gemm_call, it, torch)
     ms_layer_ev = _event_ms(step, it, torch)
 
     if args.calibration_copy:
@@ -194,7 +198,7 @@ def main():
     ws_abl = torch.empty(api.quik_ablation_workspace_bytes(T, K, N, n_out, bits), dtype=torch.uint8,
                          device=dev)
     ablation = {}
-    for version in (1, 2, 3):
+    for version in (() if args.no_ablation else (1, 2, 3)):
         fn = lambda v=version: api.quik_linear_ablation(v, x, idx, bits, w_q, w_scale, w_red, w_cs, w_out,
                                                         out=y, workspace=ws_abl)
         for _ in range(5):
@@ -228,9 +232,10 @@ def main():
         "fp16_gemm_ms": ms_fp16,
         "kernels_ms": {"quik_quantize": ms_quant, "quik_gemm_dequant": ms_gemm,
                        "quik_linear_events": ms_layer_ev},
-        "fusion_ablation_ms": {"v1_unfused_quant_unfused_dequant": ablation["v1"],
-                               "v2_fused_quant_unfused_dequant": ablation["v2"],
-                               "v3_fused_quant_fused_dequant": ablation["v3"]},
+        "fusion_ablation_ms": None if args.no_ablation else {
+            "v1_unfused_quant_unfused_dequant": ablation["v1"],
+            "v2_fused_quant_unfused_dequant": ablation["v2"],
+            "v3_fused_quant_fused_dequant": ablation["v3"]},
         "quantize_hbm": {"algorithmic_bytes": quant_bytes,
                          "achieved_GBs": quant_bytes / (ms_quant * 1e-3) / 1e9,
                          "frac": quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS},

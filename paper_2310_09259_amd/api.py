@@ -227,6 +227,39 @@ def prepare_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_su
     return call, y
 
 
+def _prepared(fn, name, args, keep):
+    def call(_keep=keep):
+        rc = fn(*args)
+        if rc != 0:
+            raise QuikError(rc, name)
+    return call
+
+
+def prepare_quantize(x, outlier_idx, bits: int, out):
+    """Marshal-once form of quik_quantize writing into out = (xq, scale, zero, x_out, code_sum)."""
+    x = _dev(x, torch.float16, "x")
+    T, K = x.shape
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    xq, scale, zero, x_out, code_sum = out
+    args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(xq),
+            xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum), _ptr(x_out) if n_out else None,
+            x_out.stride(0) if n_out else 0, _stream())
+    return _prepared(load().quik_quantize, "quik_quantize", args, (x, outlier_idx, out))
+
+
+def prepare_gemm_dequant(xq, scale, zero, code_sum, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced,
+                         w_code_sum, w_out, bias, out):
+    """Marshal-once form of quik_gemm_dequant writing into `out`."""
+    T, N = xq.shape[0], w_q.shape[0]
+    n_out = 0 if x_out is None else int(x_out.shape[1])
+    args = (_ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum), _ptr(x_out) if n_out else None,
+            x_out.stride(0) if n_out else 0, T, K_b, n_out, bits, _ptr(w_q), w_q.stride(0), _ptr(w_scale),
+            _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
+            w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(out), out.stride(0), _stream())
+    keep = (xq, scale, zero, code_sum, x_out, w_q, w_scale, w_reduced, w_code_sum, w_out, bias, out)
+    return _prepared(load().quik_gemm_dequant, "quik_gemm_dequant", args, keep)
+
+
 def quik_ablation_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int) -> int:
     return load().quik_ablation_workspace_bytes(T, K, N, n_out, bits)
 
