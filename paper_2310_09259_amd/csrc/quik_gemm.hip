@@ -517,11 +517,11 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 // loop (a wave waits only for its own DMA).  The four partial INT32 accumulators are summed exactly
 // through LDS; wave 0 then dequantizes, adds the fp16 outlier product (operands read straight from
 // global memory: they are tiny) and stores.
-template <int BITS, int TM, int TN, int NST, int MODE>
+template <int BITS, int TM, int TN, int BKB, int NST, int MODE>
 __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
     constexpr bool ASYM = (BITS == 4) && (MODE != 1);
-    constexpr int BKB = 128, CPR = 8, RPI = 8;           // 128-byte stage rows, 8 rows per DMA instr
+    constexpr int CPR = BKB / 16, RPI = 64 / CPR;        // 16-byte pieces per stage row, rows per DMA instr
     constexpr int BM = 32 * TM, BN = 32 * TN;
     constexpr int A_INSTR = BM / RPI, B_INSTR = BN / RPI; // per wave (each wave loads its own tiles)
     constexpr int LPS = A_INSTR + B_INSTR;
@@ -531,7 +531,7 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
     constexpr int NF = TM + TN;
     constexpr int HALVES = (BITS == 4) ? 2 : 1;
     constexpr int RING = NST * ST_BYTES;                  // per wave
-    constexpr int RED_BYTES = TM * TN * 16 * 64 * 4;      // one wave's accumulators
+    constexpr int RED_BYTES = 2 * TM * TN * 16 * 64 * 4;  // one wave's INT32 accumulators + fp32 outlier partials
     constexpr int LDS_BYTES = (4 * RING > 3 * RED_BYTES) ? 4 * RING : 3 * RED_BYTES;
     static_assert((NST - 1) * LPS < 64, "vmcnt range");
 
@@ -593,6 +593,59 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
+    // ---- everything the epilogue needs is requested before the weight stream starts, so none of it
+    // is waited for at the end: per-row parameters (to LDS), per-column parameters and this wave's
+    // share of the fp16 outlier operands (registers).  The outlier product is split over the four
+    // waves like K: wave w takes every fourth 16-column step.
+    constexpr int PF = 4;                                 // prefetched outlier steps per wave (n_out <= 256)
+    __shared__ float prm_sa[BM], prm_sh[BM];
+    __shared__ int prm_ct[BM];
+    float c_sw[TN], c_wr[TN], c_bv[TN];
+    int c_nc[TN];
+    uint4 pfa[PF][TM], pfb[PF][TN];
+    const int fsteps = (a.n_out + 15) >> 4;               // 16-column steps of the outlier product
+    if constexpr (!RAW) {
+        if (tid < BM) {
+            const int t = t0 + tid;
+            const bool ok = t < a.T;
+            const float sc = ok ? a.scale[t] : 0.0f;
+            prm_sa[tid] = sc;
+            prm_sh[tid] = (ok ? a.zero[t] : 0.0f) + (float)(1 << (BITS - 1)) * sc;
+            int cs = 0;
+            if constexpr (ASYM) cs = (ok && !a.fp_only) ? a.code_sum[t] : 0;
+            prm_ct[tid] = -(1 << SHIFT) * 8 * cs;
+        }
+        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
+        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = min(n0 + j * 32 + l32, a.N - 1);
+            c_sw[j] = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));
+            c_wr[j] = a.w_reduced[n];
+            c_bv[j] = bias ? __half2float(bias[n]) : 0.0f;
+            c_nc[j] = 0;
+            if constexpr (ASYM) c_nc[j] = a.fp_only ? 0 : -(1 << SHIFT) * 8 * a.w_code_sum[n];
+            if (a.fp_only) { c_sw[j] = 0.0f; c_wr[j] = 0.0f; c_bv[j] = 0.0f; }
+        }
+        const __half* __restrict__ xo = static_cast<const __half*>(a.x_out);
+        const __half* __restrict__ wo = static_cast<const __half*>(a.w_out);
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int kk = (wave + 4 * q) * 16 + g * 8;   // first of this lane's 8 outlier columns
+            const bool live = (wave + 4 * q) < fsteps && kk < a.n_out;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int t = min(t0 + i * 32 + l32, a.T - 1);
+                pfa[q][i] = live ? *reinterpret_cast<const uint4*>(xo + (size_t)t * a.ldo + kk) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = min(n0 + j * 32 + l32, a.N - 1);
+                pfb[q][j] = live ? *reinterpret_cast<const uint4*>(wo + (size_t)n * a.ldwo + kk) : make_uint4(0, 0, 0, 0);
+            }
+        }
+    }
+
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s_begin + s);
 
@@ -637,18 +690,66 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
         // have returned (their data fed the MFMAs) before that DMA is issued
     }
     wait_vm<0>();
+
+    // ---- this wave's share of the fp16 outlier product, on fresh fp32 accumulators
+    v16f cf[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) cf[i][j][r] = 0.0f;
+    if constexpr (!RAW) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, pfa[q][i]),
+                                                                     __builtin_bit_cast(v8h, pfb[q][j]), cf[i][j], 0, 0, 0);
+        // more than 16 * 4 * PF outlier columns: the rest straight from memory
+        const __half* __restrict__ xo = static_cast<const __half*>(a.x_out);
+        const __half* __restrict__ wo = static_cast<const __half*>(a.w_out);
+        for (int st = wave + 4 * PF; st < fsteps; st += 4) {
+            const int kk = st * 16 + g * 8;
+            v8h fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int t = min(t0 + i * 32 + l32, a.T - 1);
+                const uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(xo + (size_t)t * a.ldo + kk) : make_uint4(0, 0, 0, 0);
+                fa[i] = __builtin_bit_cast(v8h, w);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = min(n0 + j * 32 + l32, a.N - 1);
+                const uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(wo + (size_t)n * a.ldwo + kk) : make_uint4(0, 0, 0, 0);
+                fb[j] = __builtin_bit_cast(v8h, w);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], cf[i][j], 0, 0, 0);
+        }
+    }
     __syncthreads();                                      // rings are dead: reuse LDS for the reduction
 
-    // ---- sum the four partial accumulators: waves 1..3 publish, wave 0 adds
+    // ---- sum the four partial results: waves 1..3 publish, wave 0 adds (INT32 exactly; the fp32
+    // outlier partials in wave order)
     int* red = reinterpret_cast<int*>(lds);
+    float* redf = reinterpret_cast<float*>(lds) + 3 * TM * TN * 16 * 64;
     if (wave > 0) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    red[(((wave - 1) * TM * TN + i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+                for (int r = 0; r < 16; ++r) {
+                    const int slot = (((wave - 1) * TM * TN + i * TN + j) * 16 + r) * 64 + lane;
+                    red[slot] = acc[i][j][r];
+                    if constexpr (!RAW) redf[slot] = cf[i][j][r];
+                }
     }
     __syncthreads();
     if (wave > 0) return;
@@ -659,8 +760,11 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    acc[i][j][r] += red[((w * TM * TN + i * TN + j) * 16 + r) * 64 + lane];
+                for (int r = 0; r < 16; ++r) {
+                    const int slot = ((w * TM * TN + i * TN + j) * 16 + r) * 64 + lane;
+                    acc[i][j][r] += red[slot];
+                    if constexpr (!RAW) cf[i][j][r] += redf[slot];
+                }
 
     if constexpr (RAW) {
 #pragma unroll
@@ -680,67 +784,25 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
             }
         return;
     } else {
-        // ---- epilogue on wave 0: dequantize, fp16 outlier product from global memory, store
-        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
-        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
-        v16f cf[TM][TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            int n = min(n0 + j * 32 + l32, a.N - 1);
-            float sw = __half2float(wsc[n]);
-            float wr = a.w_reduced[n];
-            float bv = bias ? __half2float(bias[n]) : 0.0f;
-            int cn = 0;
-            if constexpr (ASYM) cn = a.fp_only ? 0 : 8 * a.w_code_sum[n];
-            if (a.fp_only) { sw = 0.0f; wr = 0.0f; bv = 0.0f; }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int t = min(t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3), a.T - 1);
-                    float sa = a.scale[t];
-                    float sh = a.zero[t] + (float)(1 << (BITS - 1)) * sa;
-                    int ai = acc[i][j][r] >> SHIFT;       // exact INT32 accumulator of the method
-                    if constexpr (ASYM) ai -= cn + (a.fp_only ? 0 : 8 * a.code_sum[t]);
-                    cf[i][j][r] = __builtin_fmaf((float)ai, sa * sw, __builtin_fmaf(sh, wr, bv));
-                }
-        }
-        const __half* __restrict__ xo = static_cast<const __half*>(a.x_out);
-        const __half* __restrict__ wo = static_cast<const __half*>(a.w_out);
-        for (int ko = 0; ko < a.n_out; ko += 16) {
-            const int kk = ko + g * 8;
-            v8h fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int t = min(t0 + i * 32 + l32, a.T - 1);
-                uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(xo + (size_t)t * a.ldo + kk) : make_uint4(0, 0, 0, 0);
-                fa[i] = __builtin_bit_cast(v8h, w);
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int n = min(n0 + j * 32 + l32, a.N - 1);
-                uint4 w = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(wo + (size_t)n * a.ldwo + kk) : make_uint4(0, 0, 0, 0);
-                fb[j] = __builtin_bit_cast(v8h, w);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], cf[i][j], 0, 0, 0);
-        }
+        // ---- epilogue on wave 0: dequantize (as in gemm_kernel), add the outlier product, store
         __half* __restrict__ y = static_cast<__half*>(a.y);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                int n = n0 + j * 32 + l32;
+                const int n = n0 + j * 32 + l32;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    int t = t0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    const int lr = i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    const int t = t0 + lr;
+                    int ai = acc[i][j][r];
+                    if constexpr (ASYM) ai = ai + prm_ct[lr] + c_nc[j];
+                    const float v = __builtin_fmaf((float)ai, prm_sa[lr] * c_sw[j], __builtin_fmaf(prm_sh[lr], c_wr[j], c_bv[j])) +
+                                    cf[i][j][r];
                     if (t < a.T && n < a.N) {
-                    if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = cf[i][j][r];
-                    else y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
-                }
+                        if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = v;
+                        else y[(size_t)t * a.ldy + n] = __float2half(v);
+                    }
                 }
             }
     }
@@ -755,10 +817,10 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int BITS, int TM, int TN, int NST, int MODE>
+template <int BITS, int TM, int TN, int BKB, int NST, int MODE>
 hipError_t launch_skinny(const GemmArgs& a, hipStream_t stream) {
     int tiles = ((a.T + 32 * TM - 1) / (32 * TM)) * ((a.N + 32 * TN - 1) / (32 * TN));
-    hipLaunchKernelGGL((gemm_skinny<BITS, TM, TN, NST, MODE>), dim3(tiles), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((gemm_skinny<BITS, TM, TN, BKB, NST, MODE>), dim3(tiles), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -766,7 +828,7 @@ template <int BITS, int MODE>
 hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
     // Few tokens: weight streaming dominates.  Up to 32 tokens the K-split kernel; up to 128 tokens
     // small tiles with a deeper stage ring so that enough workgroups and bytes are in flight.
-    if (a.T <= 32) return launch_skinny<BITS, 1, 1, 2, MODE>(a, stream);
+    if (a.T <= 32) return launch_skinny<BITS, 1, 1, 128, 2, MODE>(a, stream);
     if (a.T <= 64) return launch_cfg<BITS, 64, 64, 2, 2, 128, 4, 2, 0, MODE>(a, stream);
     if (a.T <= 128) return launch_cfg<BITS, 128, 64, 2, 2, 128, 2, 2, 0, MODE>(a, stream);
     // 128-byte stage rows (a full cache line per row per stage), two stage buffers.
