@@ -143,14 +143,17 @@ def main():
     w_q = torch.from_numpy(inp.w_packed).to(dev)
     w_scale = torch.from_numpy(inp.w_scale).to(dev)
     w_out = torch.from_numpy(inp.w_out).to(dev) if shp.n_out else None
-    w_red, w_cs = api.quik_weight_reduce(w_q, w_scale, shp.K_b, shp.bits)
+    w_red, w_cs = api.quik_weight_reduce(w_q, w_scale, shp.K_b, shp.weight_bits)
     T, K, N, K_b, n_out, bits = shp.T, shp.K, shp.N, shp.K_b, shp.n_out, shp.bits
+    mixed = shp.weight_bits != bits        # 4-bit weights under 8-bit activations
     ws = torch.empty(api.quik_workspace_bytes(T, K, N, n_out, bits), dtype=torch.uint8, device=dev)
     y = torch.empty((T, N), dtype=torch.float16, device=dev)
 
     # one C-ABI call per step; its arguments are marshalled once (host time per call ~1 us).  A
     # prepared call is bound to the stream it was made on, so graph capture uses the plain call.
-    if args.graph:
+    if mixed:
+        step, _ = api.prepare_linear_w4a8(x, idx, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
+    elif args.graph:
         def step():
             api.quik_linear(x, idx, bits, w_q, w_scale, w_red, w_cs, w_out, out=y, workspace=ws)
     else:
@@ -185,8 +188,13 @@ def main():
     q_out = (xq, scale, zero, x_out, cs)
     it = max(20, args.steps // 2)
     quant_call = api.prepare_quantize(x, idx, bits, q_out)
-    gemm_call = api.prepare_gemm_dequant(xq, scale, zero, cs, x_out if n_out else None, K_b, bits, w_q,
-                                         w_scale, w_red, w_cs, w_out, None, y)
+    if mixed:
+        def gemm_call():
+            api.quik_gemm_dequant_w4a8(xq, scale, zero, x_out if n_out else None, K_b, w_q, w_scale, w_red,
+                                       w_out, out=y)
+    else:
+        gemm_call = api.prepare_gemm_dequant(xq, scale, zero, cs, x_out if n_out else None, K_b, bits, w_q,
+                                             w_scale, w_red, w_cs, w_out, None, y)
     ms_quant = _event_ms(quant_call, it, torch)
     ms_gemm = _event_ms(gemm_call, it, torch)
     ms_layer_ev = _event_ms(step, it, torch)
@@ -203,7 +211,8 @@ def main():
     ws_abl = torch.empty(api.quik_ablation_workspace_bytes(T, K, N, n_out, bits), dtype=torch.uint8,
                          device=dev)
     ablation = {}
-    for version in (() if args.no_ablation else (1, 2, 3)):
+    no_ablation = args.no_ablation or mixed          # the unfused variants exist for equal widths only
+    for version in (() if no_ablation else (1, 2, 3)):
         fn = lambda v=version: api.quik_linear_ablation(v, x, idx, bits, w_q, w_scale, w_red, w_cs, w_out,
                                                         out=y, workspace=ws_abl)
         for _ in range(5):
@@ -228,16 +237,17 @@ def main():
         "metric": "QUIK linear TOPS (whole layer: quantize + INT4 GEMM + dequant + fp16 outliers)",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": f"int{bits} operands on int8 MFMA, int32 accumulate, fp16 outliers",
+        "dtype": (f"int{shp.weight_bits} weights x int{bits} activations" if mixed else f"int{bits} operands") +
+                 " on int8 MFMA, int32 accumulate, fp16 outliers",
         "data": "synthetic",
-        "config": {"workload": f"{shp.name}: T={T} K={K} N={N} n_out={n_out} bits={bits}",
+        "config": {"workload": f"{shp.name}: T={T} K={K} N={N} n_out={n_out} bits={bits}" + (f" w_bits={shp.weight_bits}" if mixed else ""),
                    "launches_per_step": 2, "hip_graph_replay": graph is not None},
         "frac_int8_mfma_peak_layer": tops / PEAK_INT8_TOPS,
         "speedup_vs_fp16_gemm": (ms_fp16 / ms_layer_ev) if ms_fp16 else None,
         "fp16_gemm_ms": ms_fp16,
         "kernels_ms": {"quik_quantize": ms_quant, "quik_gemm_dequant": ms_gemm,
                        "quik_linear_events": ms_layer_ev},
-        "fusion_ablation_ms": None if args.no_ablation else {
+        "fusion_ablation_ms": None if no_ablation else {
             "v1_unfused_quant_unfused_dequant": ablation["v1"],
             "v2_fused_quant_unfused_dequant": ablation["v2"],
             "v3_fused_quant_fused_dequant": ablation["v3"]},

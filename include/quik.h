@@ -221,6 +221,33 @@ int quik_linear_ablation(int version, const void *x, int T, int K, int ldx,
                          void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * 4-bit weights under 8-bit activations ("W4A8", the mixed rows of the paper's
+ * precision ablation for the down-projection, appendix table "LLaMA-2 perplexity
+ * results ... using 256 outliers"): activations are quantized with
+ * quik_quantize(bits = 8); the weights are the packed 4-bit matrix (weight nibble
+ * order, ldw >= K_b/2) with w_reduced from quik_weight_reduce(bits = 4).  The
+ * arithmetic is Algorithm 1 with halfRange = 128 for the activations:
+ *   acc[t,n] = sum_k xq8[t,k] * w_q4[n,k]                               (INT32, exact)
+ *   y[t,n]   = acc * scale[t] * w_scale[n] + (zero[t] + 128 * scale[t]) * w_reduced[n]
+ *            + sum_j x_out[t,j] * w_out[n,j]  (+ bias[n])               -> fp16
+ * Other arguments, limits and error behaviour as for quik_gemm_dequant /
+ * quik_int_gemm / quik_linear with bits = 8 (the workspace is
+ * quik_workspace_bytes(T, K, N, n_out, 8)).  No code-sum vectors are involved.
+ */
+int quik_gemm_dequant_w4a8(const void *xq, int ldq, const float *scale, const float *zero,
+                           const void *x_out, int ldo, int T, int K_b, int n_out,
+                           const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
+                           const void *w_out, int ldwo, const void *bias, int N,
+                           void *y, int ldy, void *stream);
+int quik_int_gemm_w4a8(const void *xq, int ldq, const void *w_q, int ldw,
+                       int T, int N, int K_b, int32_t *acc, int ldacc, void *stream);
+int quik_linear_w4a8(const void *x, int T, int K, int ldx,
+                     const int32_t *outlier_idx, int n_out,
+                     const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
+                     const void *w_out, int ldwo, const void *bias, int N,
+                     void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Host-side validator for an outlier index list (HOST pointer): returns QUIK_OK
  * if all n_out entries are unique and inside [0, K), QUIK_EINVAL otherwise.
  */

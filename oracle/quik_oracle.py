@@ -187,8 +187,21 @@ class OracleResult:
     w_reduced: np.ndarray  # float32 [N]
 
 
-def linear(x, idx, bits, w_packed, w_scale, w_out, bias=None) -> OracleResult:
-    """Whole layer (Algorithm 1, QUIK Matmul)."""
+def linear(x, idx, bits, w_packed, w_scale, w_out, bias=None, w_bits=None) -> OracleResult:
+    """Whole layer (Algorithm 1, QUIK Matmul).  ``w_bits`` (default: ``bits``) is the width of the
+    packed weights when it differs from the activations' (the W4A8 rows of the paper's precision
+    ablation): the same steps of Algorithm 1, called one after the other with each operand's width."""
+    if w_bits is not None and w_bits != bits:
+        x = _h(x)
+        idx = np.ascontiguousarray(idx, dtype=np.int32)
+        K_b = x.shape[1] - int(idx.size)
+        wq = unpack(w_packed, K_b, w_bits)                         # weights: their own width
+        w_reduced = weight_reduce(wq, w_scale)
+        q, scale, zero, x_out = quantize(x, idx, bits)             # activations: theirs
+        result_fp = fp_matmul(x_out, _h(w_out)) if idx.size else None
+        acc = int_gemm(q, wq, max(bits, w_bits))                   # overflow bound of the wider operand
+        y = dequant_add(acc, scale, zero, w_scale, w_reduced, result_fp, bits, bias=bias)   # halfRange of the activations
+        return OracleResult(y, q, scale, zero, x_out, acc, w_reduced)
     x = _h(x)
     T, K = x.shape
     idx = np.ascontiguousarray(idx, dtype=np.int32)

@@ -57,6 +57,13 @@ def load() -> C.CDLL:
         lib.quik_linear_ablation.restype = i
         lib.quik_linear_ablation.argtypes = [i, vp, i, i, i, vp, i, i, vp, i, vp, f, vp, vp, i, vp, i, vp, i,
                                              vp, C.c_size_t, vp]
+        lib.quik_gemm_dequant_w4a8.restype = i
+        lib.quik_gemm_dequant_w4a8.argtypes = [vp, i, f, f, vp, i, i, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp]
+        lib.quik_int_gemm_w4a8.restype = i
+        lib.quik_int_gemm_w4a8.argtypes = [vp, i, vp, i, i, i, i, vp, i, vp]
+        lib.quik_linear_w4a8.restype = i
+        lib.quik_linear_w4a8.argtypes = [vp, i, i, i, vp, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
+                                         C.c_size_t, vp]
         lib.quik_check_outlier_idx_host.restype = i
         lib.quik_check_outlier_idx_host.argtypes = [vp, i, i]
         _lib = lib
@@ -227,12 +234,77 @@ def prepare_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_su
     return call, y
 
 
+def quik_gemm_dequant_w4a8(xq, scale, zero, x_out, K_b: int, w_q, w_scale, w_reduced, w_out, bias=None,
+                           out=None):
+    """8-bit activations (quik_quantize with bits=8) times packed 4-bit weights."""
+    xq = _dev(xq, torch.uint8, "xq")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, N = xq.shape[0], w_q.shape[0]
+    n_out = 0 if x_out is None else int(x_out.shape[1])
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=xq.device)
+    rc = load().quik_gemm_dequant_w4a8(
+        _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
+        x_out.stride(0) if n_out else 0, T, K_b, n_out, _ptr(w_q), w_q.stride(0), _ptr(w_scale),
+        _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias), N,
+        _ptr(y), y.stride(0), _stream())
+    _check(rc, "quik_gemm_dequant_w4a8")
+    return y
+
+
+def quik_int_gemm_w4a8(xq, w_q, K_b: int):
+    xq = _dev(xq, torch.uint8, "xq")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, N = xq.shape[0], w_q.shape[0]
+    acc = torch.empty((T, N), dtype=torch.int32, device=xq.device)
+    rc = load().quik_int_gemm_w4a8(_ptr(xq), xq.stride(0), _ptr(w_q), w_q.stride(0), T, N, K_b, _ptr(acc),
+                                   acc.stride(0), _stream())
+    _check(rc, "quik_int_gemm_w4a8")
+    return acc
+
+
+def quik_linear_w4a8(x, outlier_idx, w_q, w_scale, w_reduced, w_out, bias=None, out=None, workspace=None):
+    """Whole layer with 8-bit activations and packed 4-bit weights.  Returns y fp16 [T, N]."""
+    x = _dev(x, torch.float16, "x")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, K = x.shape
+    N = w_q.shape[0]
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    need = quik_workspace_bytes(T, K, N, n_out, 8)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
+    rc = load().quik_linear_w4a8(
+        _ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(w_q), w_q.stride(0),
+        _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0,
+        _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "quik_linear_w4a8")
+    return y
+
+
 def _prepared(fn, name, args, keep):
     def call(_keep=keep):
         rc = fn(*args)
         if rc != 0:
             raise QuikError(rc, name)
     return call
+
+
+def prepare_linear_w4a8(x, outlier_idx, w_q, w_scale, w_reduced, w_out, bias=None, out=None, workspace=None):
+    """Marshal-once form of quik_linear_w4a8: returns (call, y)."""
+    x = _dev(x, torch.float16, "x")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    T, K = x.shape
+    N = w_q.shape[0]
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    need = quik_workspace_bytes(T, K, N, n_out, 8)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
+    args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(w_q), w_q.stride(0),
+            _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0,
+            _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace), workspace.numel(), _stream())
+    keep = (x, outlier_idx, w_q, w_scale, w_reduced, w_out, bias, y, workspace)
+    return _prepared(load().quik_linear_w4a8, "quik_linear_w4a8", args, keep), y
 
 
 def prepare_quantize(x, outlier_idx, bits: int, out):

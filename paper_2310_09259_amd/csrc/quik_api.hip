@@ -55,12 +55,13 @@ int check_quantize(const void* x, int T, int K, int ldx, const int32_t* idx, int
 }
 
 int check_gemm(const void* xq, int ldq, const void* x_out, int ldo, int T, int K_b, int n_out,
-               int bits, const void* w_q, int ldw, const void* w_out, int ldwo, int N) {
+               int bits, const void* w_q, int ldw, const void* w_out, int ldwo, int N, int w_bits = 0) {
     if (bits != 4 && bits != 8) return QUIK_EINVAL;
+    if (w_bits == 0) w_bits = bits;
+    if (w_bits != bits && !(bits == 8 && w_bits == 4)) return QUIK_EINVAL;
     if (T <= 0 || N <= 0 || K_b <= 0 || n_out < 0) return QUIK_EINVAL;
-    if ((K_b * bits) % 8) return QUIK_EINVAL;
-    const int row_bytes = K_b * bits / 8;
-    if (ldq < row_bytes || ldw < row_bytes) return QUIK_EINVAL;
+    if ((K_b * bits) % 8 || (K_b * w_bits) % 8) return QUIK_EINVAL;
+    if (ldq < K_b * bits / 8 || ldw < K_b * w_bits / 8) return QUIK_EINVAL;
     if (n_out > 0 && (ldo < n_out || ldwo < n_out)) return QUIK_EINVAL;
     if (!xq || !w_q) return QUIK_ENULL;
     if (n_out > 0 && (!x_out || !w_out)) return QUIK_ENULL;
@@ -196,6 +197,69 @@ int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx
     if (rc != QUIK_OK) return rc;
     return quik_gemm_dequant(xq, w.ldq, scale, zero, code_sum, x_out, n_out, T, K_b, n_out, bits, w_q,
                              ldw, w_scale, w_reduced, w_code_sum, w_out, ldwo, bias, N, y, ldy, stream);
+}
+
+// ---- 4-bit weights under 8-bit activations (the W4A8 rows of the paper's precision ablation)
+
+int quik_gemm_dequant_w4a8(const void* xq, int ldq, const float* scale, const float* zero,
+                           const void* x_out, int ldo, int T, int K_b, int n_out, const void* w_q,
+                           int ldw, const void* w_scale, const float* w_reduced, const void* w_out,
+                           int ldwo, const void* bias, int N, void* y, int ldy, void* stream) {
+    int rc = check_gemm(xq, ldq, x_out, ldo, T, K_b, n_out, 8, w_q, ldw, w_out, ldwo, N, 4);
+    if (rc != QUIK_OK) return rc;
+    if (ldy < N) return QUIK_EINVAL;
+    if (!scale || !zero || !w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    quik::GemmArgs a{};
+    a.xq = xq; a.ldq = ldq; a.scale = scale; a.zero = zero; a.x_out = x_out; a.ldo = ldo;
+    a.T = T; a.K_b = K_b; a.n_out = n_out; a.bits = 8; a.w_bits = 4;
+    a.w_q = w_q; a.ldw = ldw; a.w_scale = w_scale; a.w_reduced = w_reduced;
+    a.w_out = w_out; a.ldwo = ldwo; a.bias = bias; a.N = N;
+    a.y = y; a.ldy = ldy; a.acc = nullptr; a.ldacc = 0;
+    return quik::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
+                                                                               : QUIK_ELAUNCH;
+}
+
+int quik_int_gemm_w4a8(const void* xq, int ldq, const void* w_q, int ldw, int T, int N, int K_b,
+                       int32_t* acc, int ldacc, void* stream) {
+    int rc = check_gemm(xq, ldq, nullptr, 0, T, K_b, 0, 8, w_q, ldw, nullptr, 0, N, 4);
+    if (rc != QUIK_OK) return rc;
+    if (ldacc < N) return QUIK_EINVAL;
+    if (!acc) return QUIK_ENULL;
+    quik::GemmArgs a{};
+    a.xq = xq; a.ldq = ldq; a.T = T; a.K_b = K_b; a.n_out = 0; a.bits = 8; a.w_bits = 4;
+    a.w_q = w_q; a.ldw = ldw; a.N = N; a.y = nullptr; a.acc = acc; a.ldacc = ldacc;
+    return quik::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
+                                                                               : QUIK_ELAUNCH;
+}
+
+int quik_linear_w4a8(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out,
+                     const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
+                     const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    WorkspaceLayout w;
+    if (!workspace_layout(T, K, n_out, 8, &w)) return QUIK_EINVAL;
+    if (!workspace) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUIK_EALIGN;
+    if (workspace_bytes < w.total) return QUIK_EWORKSPACE;
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    void* xq = base + w.xq;
+    float* scale = reinterpret_cast<float*>(base + w.scale);
+    float* zero = reinterpret_cast<float*>(base + w.zero);
+    void* x_out = base + w.x_out;
+    const int K_b = K - n_out;
+    int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, 8, xq, w.ldq, scale, zero, x_out, n_out);
+    if (rc != QUIK_OK) return rc;
+    rc = check_gemm(xq, w.ldq, x_out, n_out, T, K_b, n_out, 8, w_q, ldw, w_out, ldwo, N, 4);
+    if (rc != QUIK_OK) return rc;
+    if (ldy < N) return QUIK_EINVAL;
+    if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, 8, xq, w.ldq, scale, zero, nullptr, x_out, n_out,
+                       stream);
+    if (rc != QUIK_OK) return rc;
+    return quik_gemm_dequant_w4a8(xq, w.ldq, scale, zero, x_out, n_out, T, K_b, n_out, w_q, ldw, w_scale,
+                                  w_reduced, w_out, ldwo, bias, N, y, ldy, stream);
 }
 
 namespace {

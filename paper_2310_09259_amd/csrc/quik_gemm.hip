@@ -108,10 +108,17 @@ template <int N> __device__ __forceinline__ void wait_vm() {   // s_waitcnt vmcn
 // stage, NST stage buffers, GM = m-tiles per group of the tile order (0: plain column sweep).
 // MODE 0: fused epilogue (asymmetric widening for 4 bits); MODE 1: write raw INT32 accumulators,
 // symmetric widening; MODE 2: raw accumulators, asymmetric widening plus correction terms.
-template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
+// BITS: activation bits; WBITS: weight bits (equal, or 4-bit weights under 8-bit activations).
+template <int BITS, int WBITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
 __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
     constexpr bool ASYM = (BITS == 4) && (MODE != 1);
+    // Mixed layers: a stage still covers BKB activation bytes = BKB k, which is only BKB/2 packed
+    // weight bytes.  The weight nibbles are widened to 16x int8 (even / odd k of a word in two
+    // registers); the int8 activations are brought into the same k order with two byte permutes
+    // per 8 elements.  Accumulators are exactly 16x the integer dot product.
+    constexpr bool MIXED = (BITS == 8 && WBITS == 4);
+    static_assert(WBITS == BITS || MIXED, "weights: same width as the activations, or 4 under 8");
     constexpr int NWAVES = WM * WN, NT = NWAVES * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int CPR = BKB / 16, RPI = 64 / CPR;
@@ -119,8 +126,14 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     static_assert(A_INSTR >= 1 && B_INSTR >= 1, "tile too small for the wave count");
     constexpr int LPS = A_INSTR + B_INSTR;
     constexpr int KSUB = BKB / 32;
-    constexpr int SHIFT = (BITS == 4) ? (ASYM ? 4 : 8) : 0;
+    constexpr int SHIFT = (BITS == 4) ? (ASYM ? 4 : 8) : (MIXED ? 4 : 0);
     constexpr int A_BYTES = BM * BKB, B_BYTES = BN * BKB, ST_BYTES = A_BYTES + B_BYTES;
+    // mixed int stages: weight rows of BKW bytes, RPW rows per DMA instruction, WI instructions
+    // per wave; the remaining B_INSTR - WI slots of a stage are issued as empty (out-of-range)
+    // loads so that every stage counts the same number of DMA instructions
+    constexpr int BKW = BKB / 2, CPW = BKW / 16, RPW = 64 / CPW;
+    constexpr int WI = MIXED ? BN / RPW / NWAVES : B_INSTR;
+    static_assert(!MIXED || (WI >= 1 && BKB == 128), "mixed layers: tile too small for the wave count");
     constexpr int NF = TM + TN;
     constexpr int HALVES = (BITS == 4) ? 2 : 1;          // MFMAs per output tile per sub-step
     constexpr int SLOTS = TM * TN * HALVES;
@@ -195,13 +208,36 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     }
     const uint32_t m0A = lds_base + wave_u * A_INSTR * 1024;
     const uint32_t m0B = lds_base + A_BYTES + wave_u * B_INSTR * 1024;
+    // mixed int stages: geometry of the half-width weight rows
+    uint32_t voW[WI];
+    int chW[WI];
+    if constexpr (MIXED) {
+#pragma unroll
+        for (int i = 0; i < WI; ++i) {
+            int row = (wave_u * WI + i) * RPW + lane / CPW;
+            int c = ((lane % CPW) ^ swz<BKW>(row)) * 16;
+            chW[i] = c;
+            voW[i] = (uint32_t)(row * a.ldw + c);
+        }
+    }
+    const uint32_t m0W = lds_base + A_BYTES + wave_u * WI * 1024;
+    // where a mixed stage's empty loads land: this wave's 1 KB of the unused half of the B region
+    const uint32_t m0D = lds_base + A_BYTES + BN * BKW + wave_u * 1024;
+    static_assert(!MIXED || NWAVES * 1024 <= BN * BKW, "no room for the empty loads");
 
     // DMA instruction d of a full (unguarded) int stage
     auto issue_one = [&](int s, int d) {
         const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
         const uint32_t so = (uint32_t)s * BKB;
-        if (d < A_INSTR) dma16(rA, m0A + sb + d * 1024, voA[d < A_INSTR ? d : 0], so);
-        else dma16(rB, m0B + sb + (d - A_INSTR) * 1024, voB[d >= A_INSTR ? d - A_INSTR : 0], so);
+        if (d < A_INSTR) {
+            dma16(rA, m0A + sb + d * 1024, voA[d < A_INSTR ? d : 0], so);
+        } else if constexpr (MIXED) {
+            const int j = d - A_INSTR;
+            if (j < WI) dma16(rB, m0W + sb + j * 1024, voW[j < WI ? j : 0], (uint32_t)s * BKW);
+            else dma16(rB, m0D + sb, kOob, 0);
+        } else {
+            dma16(rB, m0B + sb + (d - A_INSTR) * 1024, voB[d >= A_INSTR ? d - A_INSTR : 0], so);
+        }
     };
     // any stage: K tail of the int part, fp16 part, or past the end (all lanes out of range)
     auto issue_any = [&](int s) {
@@ -216,6 +252,16 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         for (int i = 0; i < A_INSTR; ++i) {
             uint32_t vo = (koff + chA[i] < lima) ? (uint32_t)(rwA[i] * lda + koff + chA[i]) : kOob;
             dma16(ra_, m0A + sb + i * 1024, vo, 0);
+        }
+        if (MIXED && !fp) {
+            const int koffw = s * BKW;
+#pragma unroll
+            for (int i = 0; i < B_INSTR; ++i) {
+                uint32_t vo = kOob;
+                if (i < WI && koffw + chW[i < WI ? i : 0] < limb) vo = voW[i < WI ? i : 0] + (uint32_t)koffw;
+                dma16(rb_, (i < WI ? m0W + i * 1024 : m0D) + sb, vo, 0);
+            }
+            return;
         }
 #pragma unroll
         for (int i = 0; i < B_INSTR; ++i) {
@@ -283,8 +329,30 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     uint4 R[RD][NF];
     v4i U[2][NF][HALVES];
 
+    // mixed int stages: 8 bytes (16 nibbles = this lane's k-group) of a half-width weight row
+    uint32_t rdw[MIXED ? TN : 1][KSUB];
+    if constexpr (MIXED) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int r = wn * TN * 32 + j * 32 + l32;
+#pragma unroll
+            for (int ks = 0; ks < KSUB; ++ks) rdw[j][ks] = A_BYTES + r * BKW + ((ks ^ swz<BKW>(r)) << 4) + g * 8;
+        }
+    }
     auto read_frag = [&](int set, int f, const uint8_t* stage, int ks) {
         R[set][f] = *reinterpret_cast<const uint4*>(stage + rd[f][ks]);
+    };
+    // fragment f of sub-step ks of a stage that is an int stage (wide == false) or an fp16 stage
+    auto read_any = [&](int set, int f, const uint8_t* stage, int ks, bool wide) {
+        if constexpr (MIXED) {
+            if (f >= TM && !wide) {
+                const uint2 v = *reinterpret_cast<const uint2*>(stage + rdw[f >= TM ? f - TM : 0][ks]);
+                R[set][f].x = v.x;
+                R[set][f].y = v.y;
+                return;
+            }
+        }
+        read_frag(set, f, stage, ks);
     };
     auto widen_word = [&](int set, int rset, int w) {
         const int f = w >> 2, k = w & 3;
@@ -303,6 +371,17 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             }
             U[set][f][k >> 1][(k & 1) * 2] = (int)(act ? hi : lo);
             U[set][f][k >> 1][(k & 1) * 2 + 1] = (int)(act ? lo : hi);
+        } else if constexpr (MIXED) {
+            if (f < TM) {
+                // int8 activations k0..k15 -> [even k of the low 8 | odd | even of the high 8 | odd]
+                const uint32_t lo = (k < 2) ? R[rset][f].x : R[rset][f].z, hi = (k < 2) ? R[rset][f].y : R[rset][f].w;
+                U[set][f][0][k] = (int)__builtin_amdgcn_perm(hi, lo, (k & 1) ? 0x07050301u : 0x06040200u);
+            } else {
+                // packed weights: word k/2 holds 8 nibbles; even k (low nibbles) / odd k (high), 16x
+                constexpr uint32_t M = 0xF0F0F0F0u;
+                const uint32_t wv = (k < 2) ? R[rset][f].x : R[rset][f].y;
+                U[set][f][0][k] = (int)((k & 1) ? (wv & M) : ((wv << 4) & M));
+            }
         } else {
             U[set][f][0][k] = (int)x;
         }
@@ -333,6 +412,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         const int ts = (ks + LA < KSUB) ? s : s + 1, tks = (ks + LA) % KSUB;
         const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
         const int rnext = (ks + 1) % RD, rload = (ks + LA) % RD;   // static: KSUB is a multiple of RD
+        const bool wide = ts >= nk_int;                             // the look-ahead reaches the fp16 part
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < SLOTS; ++m) {
@@ -347,9 +427,9 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 #pragma unroll
             for (int w = 0; w < WORDS; ++w)
                 if (w * SLOTS / WORDS == m) widen_word(par ^ 1, rnext, w);
-            if (m < NF) read_frag(rload, m, tgt, tks);
+            if (m < NF) read_any(rload, m, tgt, tks, wide);
             if (SLOTS < NF && m == SLOTS - 1)
-                for (int f = SLOTS; f < NF; ++f) read_frag(rload, f, tgt, tks);
+                for (int f = SLOTS; f < NF; ++f) read_any(rload, f, tgt, tks, wide);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -359,7 +439,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 #pragma unroll
     for (int q = 0; q < LA; ++q)
 #pragma unroll
-        for (int f = 0; f < NF; ++f) read_frag(q, f, lds, q);
+        for (int f = 0; f < NF; ++f) read_any(q, f, lds, q, nk_int == 0);
 #pragma unroll
     for (int w = 0; w < WORDS; ++w) widen_word(0, 0, w);
 
@@ -809,10 +889,10 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
 }
 
 
-template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
+template <int BITS, int WBITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_kernel<BITS, BM, BN, WM, WN, BKB, NST, OCC, GM, MODE>), dim3(tiles),
+    hipLaunchKernelGGL((gemm_kernel<BITS, WBITS, BM, BN, WM, WN, BKB, NST, OCC, GM, MODE>), dim3(tiles),
                        dim3(WM * WN * 64), 0, stream, a);
     return hipGetLastError();
 }
@@ -824,20 +904,23 @@ hipError_t launch_skinny(const GemmArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int BITS, int MODE>
+template <int BITS, int WBITS, int MODE>
 hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
-    // Few tokens: weight streaming dominates.  Up to 32 tokens the K-split kernel; up to 128 tokens
-    // small tiles with a deeper stage ring so that enough workgroups and bytes are in flight.
-    if (a.T <= 32) return launch_skinny<BITS, 1, 1, 128, 2, MODE>(a, stream);
-    if (a.T <= 64) return launch_cfg<BITS, 64, 64, 2, 2, 128, 4, 2, 0, MODE>(a, stream);
-    if (a.T <= 128) return launch_cfg<BITS, 128, 64, 2, 2, 128, 2, 2, 0, MODE>(a, stream);
+    // Few tokens: weight streaming dominates.  Up to 32 tokens the K-split kernel (same operand
+    // widths only); up to 128 tokens small tiles with a deeper stage ring so that enough workgroups
+    // and bytes are in flight.
+    if constexpr (BITS == WBITS) {
+        if (a.T <= 32) return launch_skinny<BITS, 1, 1, 128, 2, MODE>(a, stream);
+    }
+    if (a.T <= 64) return launch_cfg<BITS, WBITS, 64, 64, 2, 2, 128, 4, 2, 0, MODE>(a, stream);
+    if (a.T <= 128) return launch_cfg<BITS, WBITS, 128, 64, 2, 2, 128, 2, 2, 0, MODE>(a, stream);
     // 128-byte stage rows (a full cache line per row per stage), two stage buffers.
     // Large problems: 256 x 128 tiles shared by eight waves (one workgroup per CU) move 25 % fewer
     // operand bytes per MFMA through L1/LDS than two independent 128 x 128 workgroups.  They need
     // at least one tile per CU to pay off; otherwise 128 x 128 tiles with two workgroups per CU.
     const long big_tiles = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
-    if (big_tiles >= 256) return launch_cfg<BITS, 256, 128, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
-    return launch_cfg<BITS, 128, 128, 2, 2, 128, 2, 2, 8, MODE>(a, stream);
+    if (big_tiles >= 256) return launch_cfg<BITS, WBITS, 256, 128, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
+    return launch_cfg<BITS, WBITS, 128, 128, 2, 2, 128, 2, 2, 8, MODE>(a, stream);
 }
 
 // one wave per output channel; lanes stride over the packed row
@@ -875,10 +958,11 @@ __global__ __launch_bounds__(kThreads) void weight_reduce_kernel(WeightReduceArg
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     const bool raw = a.y == nullptr;
     if (a.bits == 4) {
-        if (!raw) return dispatch<4, 0>(a, stream);
-        return (a.code_sum && a.w_code_sum) ? dispatch<4, 2>(a, stream) : dispatch<4, 1>(a, stream);
+        if (!raw) return dispatch<4, 4, 0>(a, stream);
+        return (a.code_sum && a.w_code_sum) ? dispatch<4, 4, 2>(a, stream) : dispatch<4, 4, 1>(a, stream);
     }
-    return raw ? dispatch<8, 1>(a, stream) : dispatch<8, 0>(a, stream);
+    if (a.w_bits == 4) return raw ? dispatch<8, 4, 1>(a, stream) : dispatch<8, 4, 0>(a, stream);
+    return raw ? dispatch<8, 8, 1>(a, stream) : dispatch<8, 8, 0>(a, stream);
 }
 
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream) {

@@ -43,6 +43,7 @@ struct GemmArgs {
     int32_t* acc;         // int32 [T, ldacc] (raw-accumulator mode, y == null)
     int ldacc;
     int fp_only;          // 1: skip the integer part; y is then fp32 [T, ldy] = outlier product only
+    int w_bits;           // weight bits if they differ from `bits` (4 under 8-bit activations); 0: same
 };
 
 struct WeightReduceArgs {

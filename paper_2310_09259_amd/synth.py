@@ -30,15 +30,20 @@ class LayerShape:
     n_out: int
     bits: int = 4
     seed: int = BASE_SEED
+    w_bits: int = 0          # weight bits when they differ from the activations' (0: same as bits)
 
     @property
     def K_b(self) -> int:
         return self.K - self.n_out
 
     @property
+    def weight_bits(self) -> int:
+        return self.w_bits or self.bits
+
+    @property
     def row_bytes(self) -> int:
-        """Bytes of one packed row of K_b quantized values."""
-        return self.K_b * self.bits // 8
+        """Bytes of one packed weight row of K_b quantized values."""
+        return self.K_b * self.weight_bits // 8
 
 
 # The five workload families named by the benchmark definition.  Index = config id.
@@ -47,6 +52,8 @@ CONFIGS = {
     "llama7b_up": LayerShape("llama7b_up", 2048, 4096, 11008, 256, 4, BASE_SEED + 1),
     "llama7b_down": LayerShape("llama7b_down", 2048, 11008, 4096, 256, 4, BASE_SEED + 2),
     "llama7b_down_w8a8": LayerShape("llama7b_down_w8a8", 2048, 11008, 4096, 256, 8, BASE_SEED + 2),
+    "llama7b_down_w4a8": LayerShape("llama7b_down_w4a8", 2048, 11008, 4096, 256, 8, BASE_SEED + 2, w_bits=4),
+    "llama7b_down_w8a8_out896": LayerShape("llama7b_down_w8a8_out896", 2048, 11008, 4096, 896, 8, BASE_SEED + 2),
     "llama13b_qkv_t16": LayerShape("llama13b_qkv_t16", 16, 5120, 15360, 256, 4, BASE_SEED + 3),
     "llama13b_qkv_t128": LayerShape("llama13b_qkv_t128", 128, 5120, 15360, 256, 4, BASE_SEED + 3),
     "llama13b_qkv_t1024": LayerShape("llama13b_qkv_t1024", 1024, 5120, 15360, 256, 4, BASE_SEED + 3),
@@ -68,7 +75,7 @@ class LayerInputs:
 
 def make_inputs(shape: LayerShape, outlier_gain: float = 40.0) -> LayerInputs:
     """Draw one layer's inputs.  Deterministic in ``shape.seed`` and the shape."""
-    if (shape.K_b * shape.bits) % 8 != 0:
+    if (shape.K_b * shape.bits) % 8 != 0 or (shape.K_b * shape.weight_bits) % 8 != 0:
         raise ValueError("K_b * bits must be a multiple of 8")
     rng = np.random.Generator(np.random.PCG64(shape.seed))
     T, K, N, n_out = shape.T, shape.K, shape.N, shape.n_out

@@ -292,3 +292,82 @@ def test_prepared_call_matches_direct_call(api, oracle):
     call()
     _sync()
     assert np.array_equal(y1.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
+
+
+# ---- 4-bit weights under 8-bit activations
+
+W4A8_INT_SHAPES = [(16, 512, 480), (200, 300, 992), (129, 257, 3840), (1, 1, 32), (40, 64, 96),
+                   (520, 11000, 480), (100, 300, 1000), (300, 140, 4864)]
+
+
+@pytest.mark.parametrize("T,N,K_b", W4A8_INT_SHAPES)
+def test_w4a8_int32_accumulators_are_bit_exact(api, oracle, T, N, K_b):
+    rng = np.random.default_rng(T * 5 + N * 3 + K_b)
+    q = rng.integers(-128, 128, size=(T, K_b)).astype(np.int8)
+    w = rng.integers(-8, 8, size=(N, K_b)).astype(np.int8)
+    q[0, :] = -128
+    w[0, :] = -8                                 # largest possible accumulator
+    xq = to_dev(expected_xq(oracle, q, 8, api.quik_packed_row_bytes(K_b, 8)))
+    ldw = api.quik_packed_row_bytes(K_b, 4)
+    wp = np.full((N, ldw), 0xFF, np.uint8)       # weight pad bytes may hold anything
+    wp[:, : K_b // 2] = oracle.pack(w, 4)
+    acc = api.quik_int_gemm_w4a8(xq, to_dev(wp), K_b)
+    _sync()
+    want = oracle.int_gemm(q, w, 8)
+    got = acc.cpu().numpy()
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"{len(bad)} accumulators differ, first {bad[:5].tolist()}: "
+                             f"{got[tuple(bad[0])]} vs {want[tuple(bad[0])]}")
+
+
+W4A8_LINEAR_SHAPES = [
+    synth.LayerShape("w4a8_small", 16, 512, 512, 32, 8, seed=61, w_bits=4),
+    synth.LayerShape("w4a8_ragged", 150, 1024, 200, 64, 8, seed=62, w_bits=4),
+    synth.LayerShape("w4a8_multi_tile", 260, 2048, 390, 128, 8, seed=63, w_bits=4),
+    synth.LayerShape("w4a8_no_outliers", 64, 512, 256, 0, 8, seed=64, w_bits=4),
+    synth.LayerShape("w4a8_big_tiles", 520, 512, 11000, 32, 8, seed=65, w_bits=4),
+    synth.LayerShape("w4a8_one_token", 1, 4096, 512, 256, 8, seed=66, w_bits=4),
+]
+
+
+@pytest.mark.parametrize("shp", W4A8_LINEAR_SHAPES, ids=lambda s: s.name)
+def test_w4a8_linear_matches_oracle(api, oracle, shp):
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    ref = oracle.linear(inp.x, inp.outlier_idx, 8, inp.w_packed, inp.w_scale, inp.w_out, w_bits=4)
+    w_red, _ = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    y = api.quik_linear_w4a8(d["x"], d["idx"], d["w_q"], d["w_scale"], w_red, d["w_out"])
+    _sync()
+    assert np.array_equal(w_red.cpu().numpy().view(np.uint32), ref.w_reduced.view(np.uint32))
+    ok, worst = output_within_tolerance(y.cpu().numpy(), ref.y)
+    assert ok, f"fp16 output outside 5e-3 (worst error / tolerance = {worst:.2f})"
+    assert worst > 0
+
+
+def test_w4a8_full_size_on_sampled_tokens(api, oracle):
+    import torch
+    shp = synth.CONFIGS["llama7b_down_w4a8"]
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    w_red, _ = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    xq, scale, zero, x_out, _ = api.quik_quantize(d["x"], d["idx"], 8)
+    y = api.quik_linear_w4a8(d["x"], d["idx"], d["w_q"], d["w_scale"], w_red, d["w_out"])
+    _sync()
+    T = shp.T
+    sel = np.unique(np.array([0, 1, 127, 128, 255, 256, T // 2, T - 2, T - 1]) % T)
+    ref = oracle.linear(inp.x[sel], inp.outlier_idx, 8, inp.w_packed, inp.w_scale, inp.w_out, w_bits=4)
+    rows = torch.from_numpy(sel).cuda()
+    assert np.array_equal(xq[rows].cpu().numpy(), expected_xq(oracle, ref.q, 8, xq.shape[1]))
+    ok, worst = output_within_tolerance(y[rows].cpu().numpy(), ref.y)
+    assert ok, worst
+    acc = api.quik_int_gemm_w4a8(xq[rows].contiguous(), d["w_q"], shp.K_b)
+    _sync()
+    assert np.array_equal(acc.cpu().numpy(), ref.acc)
+
+
+def test_w8a8_with_the_papers_larger_outlier_counts(api, oracle):
+    """8-bit layers keep more outlier columns in the paper (several hundred on the down-projection)."""
+    for n_out, seed in ((688, 71), (896, 72)):
+        shp = synth.LayerShape(f"w8a8_out{n_out}", 70, 2048, 136, n_out, 8, seed=seed)
+        _linear_case(api, oracle, shp)

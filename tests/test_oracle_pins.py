@@ -285,6 +285,27 @@ def test_layer_equals_plain_gemm_of_dequantized_operands(oracle, bits):
     assert np.array_equal(r.acc.astype(np.int64), r.q.astype(np.int64) @ wq.astype(np.int64).T)
 
 
+def test_mixed_width_layer_equals_plain_gemm_of_dequantized_operands(oracle):
+    """4-bit weights under 8-bit activations: the same Eq. (1) identity with halfRange = 128 for the
+    activations and the weights unpacked as nibbles; the quantized activations and their scales
+    are those of the plain 8-bit layer (they do not depend on the weights)."""
+    shp = synth.LayerShape("mixed", 13, 160, 11, 16, 8, seed=23, w_bits=4)
+    inp = synth.make_inputs(shp)
+    assert inp.w_packed.shape == (11, 144 // 2)
+    r = oracle.linear(inp.x, inp.outlier_idx, 8, inp.w_packed, inp.w_scale, inp.w_out, w_bits=4)
+    wq = oracle.unpack(inp.w_packed, shp.K_b, 4).astype(np.float64)
+    assert wq.min() >= -8 and wq.max() <= 7
+    x_hat = (r.q.astype(np.float64) + 128) * r.scale[:, None].astype(np.float64) + r.zero[:, None]
+    w_hat = wq * inp.w_scale.astype(np.float64)[:, None]
+    want = x_hat @ w_hat.T + inp.x[:, inp.outlier_idx].astype(np.float64) @ inp.w_out.astype(np.float64).T
+    mag = np.abs(x_hat) @ np.abs(w_hat).T + 1.0
+    assert np.all(np.abs(r.y - want) <= 2e-7 * mag)
+    assert np.array_equal(r.acc.astype(np.int64), r.q.astype(np.int64) @ wq.astype(np.int64).T)
+    q8, s8, z8, _ = oracle.quantize(inp.x, inp.outlier_idx, 8)
+    assert np.array_equal(q8, r.q) and np.array_equal(s8, r.scale) and np.array_equal(z8, r.zero)
+    assert r.q.min() == -128 and r.q.max() == 127
+
+
 def test_layer_is_within_the_quantization_error_bound_of_the_unquantized_layer(oracle):
     shp, inp, r = _layer(oracle)
     base = oracle.base_columns(shp.K, inp.outlier_idx)
