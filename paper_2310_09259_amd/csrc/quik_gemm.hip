@@ -29,7 +29,9 @@
 // uses v_mfma_f32_32x32x16_f16, whose accumulator has the same layout, so the
 // dequantized tile is simply the C operand of the outlier stages.
 //
-// Pipeline.  A workgroup of four waves owns a BM x BN output tile.  Operand panels
+// Mixed widths (4-bit weights under 8-bit activations): see MIXED in gemm_kernel.
+//
+// Pipeline.  A workgroup of four or eight waves owns a BM x BN output tile.  Operand panels
 // are copied global -> LDS without passing through registers (buffer_load ... lds,
 // 16 bytes per lane, BKB bytes of every row per stage, NST stage buffers).  Rows
 // beyond T / N and bytes beyond the row end are out of range for the buffer
@@ -41,6 +43,12 @@
 // sub-step q+1 are widened and the LDS reads of sub-step q+2 are in flight.
 // One workgroup barrier per stage; right after it the stage buffer it has just
 // freed is refilled, the DMA instructions spread between MFMAs.
+//
+// Epilogue.  Per-row parameters (LDS) and per-column parameters (registers) are
+// fetched before the first DMA.  After the int stages the accumulators are
+// dequantized in place of the C operand of the fp16 outlier stages; the fp16
+// result tile is parked in the dead stage ring and leaves the CU as 16-byte
+// pieces, whole row segments per store instruction.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -138,10 +146,9 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     constexpr int HALVES = (BITS == 4) ? 2 : 1;          // MFMAs per output tile per sub-step
     constexpr int SLOTS = TM * TN * HALVES;
     constexpr int WORDS = NF * 4;
-#ifndef QUIK_LA
-#define QUIK_LA 2
-#endif
-    constexpr int LA = (QUIK_LA < KSUB) ? QUIK_LA : KSUB - 1;   // LDS reads run LA sub-steps ahead of their MFMAs
+    // LDS reads run LA sub-steps ahead of their MFMAs (3 and 4 were measured: no faster, so the cost of
+    // the fragment reads is their throughput, not their latency)
+    constexpr int LA = (2 < KSUB) ? 2 : KSUB - 1;
     constexpr int RD = (KSUB % LA == 0) ? LA : LA + 1;   // raw fragment sets (a divisor of KSUB: static indices)
     constexpr int BAR_KS = KSUB - LA;                    // stage barrier sits before this sub-step
     static_assert(KSUB % 2 == 0 && NST >= 2 && LA >= 1 && KSUB % RD == 0, "raw set index must be static");
@@ -528,7 +535,6 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
 
     wait_vm<0>();                          // drain the look-ahead DMA before the wave ends
     __half* __restrict__ y = static_cast<__half*>(a.y);
-#ifndef QUIK_DIRECT_STORE
     // Output through LDS: a lane owns one column of sixteen rows of every 32 x 32 block, so direct
     // stores would be 2 bytes per lane.  Each wave instead parks its fp16 tile in its own slice of
     // the (now dead) stage ring and writes it out as 16-byte pieces, whole 64/128-byte row
@@ -573,7 +579,6 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         }
         return;
     }
-#endif
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

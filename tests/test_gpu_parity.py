@@ -371,3 +371,21 @@ def test_w8a8_with_the_papers_larger_outlier_counts(api, oracle):
     for n_out, seed in ((688, 71), (896, 72)):
         shp = synth.LayerShape(f"w8a8_out{n_out}", 70, 2048, 136, n_out, 8, seed=seed)
         _linear_case(api, oracle, shp)
+
+
+def test_vector_store_path_with_a_ragged_last_piece(api, oracle):
+    """Output rows 16-byte aligned (ldy % 8 == 0) but N not a multiple of 8: the last 16-byte piece
+    of a row is written element by element and nothing lands beyond column N."""
+    import torch
+    shp = synth.LayerShape("ragged_piece", 300, 512, 333, 32, 4, seed=48)
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    ref = oracle.linear(inp.x, inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
+    ybig = torch.full((shp.T, 344), -7.0, dtype=torch.float16, device="cuda")
+    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"], out=ybig[:, : shp.N])
+    _sync()
+    yh = ybig.cpu().numpy()
+    ok, worst = output_within_tolerance(yh[:, : shp.N], ref.y)
+    assert ok, worst
+    assert np.all(yh[:, shp.N:] == -7.0)
