@@ -557,11 +557,12 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
                     *reinterpret_cast<__half*>(wbuf + row * WROW + (j * 32 + l32) * 2) = __float2half(cf[i][j][r]);
                 }
         constexpr int CH = TN * 4;                       // 16-byte pieces per row
-        constexpr int RPS = 64 / CH;                     // rows per store instruction
+        constexpr int RPS = 64 / CH;                     // rows per store instruction (lanes >= RPS * CH idle)
         const int prow = lane / CH, pch = lane % CH;
 #pragma unroll
-        for (int p = 0; p < TM * 32 / RPS; ++p) {
+        for (int p = 0; p < (TM * 32 + RPS - 1) / RPS; ++p) {
             const int row = p * RPS + prow;
+            if (prow >= RPS || row >= TM * 32) continue;
             const uint4 v = *reinterpret_cast<const uint4*>(wbuf + row * WROW + pch * 16);
             const int t = tw + row, n = nw + pch * 8;
             if (t < a.T) {
@@ -924,8 +925,20 @@ hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
     // operand bytes per MFMA through L1/LDS than two independent 128 x 128 workgroups.  They need
     // at least one tile per CU to pay off; otherwise 128 x 128 tiles with two workgroups per CU.
     const long big_tiles = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
-    if (big_tiles >= 256) return launch_cfg<BITS, WBITS, 256, 128, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
-    return launch_cfg<BITS, WBITS, 128, 128, 2, 2, 128, 2, 2, 8, MODE>(a, stream);
+    if (big_tiles < 256) return launch_cfg<BITS, WBITS, 128, 128, 2, 2, 128, 2, 2, 8, MODE>(a, stream);
+    if constexpr (MODE == 0 && BITS == WBITS) {
+        // One workgroup per CU, so a launch runs in ceil(tiles / 256) rounds.  Tiles of 1.5x the area
+        // (64 x 96 or 96 x 64 per wave: 17 % fewer LDS fragment reads and widening operations per
+        // MFMA, a third fewer per-tile prologues and epilogues) take 1.42x as long per round
+        // (measured); they win whenever they save enough rounds.
+        auto rounds = [&](int bm, int bn) { return (((long)(a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn) + 255) / 256; };
+        const double cost_a = (double)rounds(256, 128);
+        const double cost_b = 1.42 * (double)rounds(256, 192);
+        const double cost_c = 1.42 * (double)rounds(192, 256);
+        if (cost_b < cost_a && cost_b <= cost_c) return launch_cfg<BITS, WBITS, 256, 192, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
+        if (cost_c < cost_a) return launch_cfg<BITS, WBITS, 192, 256, 2, 4, 128, 2, 1, 4, MODE>(a, stream);
+    }
+    return launch_cfg<BITS, WBITS, 256, 128, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
 }
 
 // one wave per output channel; lanes stride over the packed row

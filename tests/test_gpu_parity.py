@@ -184,6 +184,9 @@ LINEAR_SHAPES = [
     # eight-wave 256 x 128 tile configuration (>= 256 such tiles), ragged T and N
     synth.LayerShape("big_tiles_ragged", 520, 512, 11000, 32, 4, seed=38),
     synth.LayerShape("big_tiles_w8a8", 770, 256, 5500, 24, 8, seed=39),
+    # 1.5x-area tiles: 256 x 192 is picked for the two shapes above; 192 x 256 for these
+    synth.LayerShape("tiles_192x256", 576, 256, 16640, 32, 4, seed=49),
+    synth.LayerShape("tiles_192x256_w8a8_ragged", 570, 256, 16630, 24, 8, seed=50),
     # small-T paths
     synth.LayerShape("t32_ragged_n", 32, 1024, 333, 64, 4, seed=40),
     synth.LayerShape("t5_w8a8", 5, 512, 200, 16, 8, seed=44),
