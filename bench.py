@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, MI355X data sheet (5.0 POP/s)
 PEAK_HBM_GBS = 8000.0
-# profiles/gemm_kernel_llama7b_up.md: (57472 KiB * 2.0 + 44032 KiB * 1.0) * 1024
-TRAFFIC_BYTES = {"llama7b_up": int((57472 * 2.0 + 44032) * 1024)}
+# profiles/gemm_kernel_llama7b_up.md: (47796 KiB * 2.0 + 44033 KiB * 1.0) * 1024
+TRAFFIC_BYTES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
 
 
 def _event_ms(fn, iters, torch):
