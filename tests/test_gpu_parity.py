@@ -392,3 +392,54 @@ def test_vector_store_path_with_a_ragged_last_piece(api, oracle):
     ok, worst = output_within_tolerance(yh[:, : shp.N], ref.y)
     assert ok, worst
     assert np.all(yh[:, shp.N:] == -7.0)
+
+
+def _random_shape(seed):
+    """A seeded random layer shape: ragged sizes, every tile configuration reachable."""
+    rng = np.random.default_rng(9000 + seed)
+    kind = seed % 4
+    K = int(rng.integers(1, 160)) * 8 if kind != 3 else int(rng.integers(1, 40)) * 8
+    n_out = int(rng.integers(0, max(1, min(K // 8, 40)))) * 8
+    if n_out >= K:
+        n_out = K - 8
+    if kind == 0:      # few tokens: K-split kernel and small tiles
+        T, N = int(rng.integers(1, 130)), int(rng.integers(1, 700))
+    elif kind == 1:    # 128 x 128 tiles
+        T, N = int(rng.integers(129, 700)), int(rng.integers(1, 900))
+    elif kind == 2:    # mixed
+        T, N = int(rng.integers(1, 400)), int(rng.integers(1, 2000))
+    else:              # at least 256 tiles of 256 x 128: eight-wave configurations, shallow K
+        T, N = int(rng.integers(513, 1100)), int(rng.integers(11000, 17000))
+    mode = ("w4a4", "w8a8", "w4a8")[int(rng.integers(0, 3))]
+    return T, K, N, n_out, mode
+
+
+@pytest.mark.parametrize("seed", range(36))
+def test_random_shapes_match_oracle(api, oracle, seed):
+    T, K, N, n_out, mode = _random_shape(seed)
+    bits = 4 if mode == "w4a4" else 8
+    w_bits = 4 if mode != "w8a8" else 8
+    shp = synth.LayerShape(f"rand{seed}", T, K, N, n_out, bits, seed=9100 + seed, w_bits=0 if w_bits == bits else w_bits)
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    ref = oracle.linear(inp.x, inp.outlier_idx, bits, inp.w_packed, inp.w_scale, inp.w_out,
+                        w_bits=None if w_bits == bits else w_bits)
+    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, w_bits)
+    xq, scale, zero, x_out, cs = api.quik_quantize(d["x"], d["idx"], bits)
+    if mode == "w4a8":
+        y = api.quik_linear_w4a8(d["x"], d["idx"], d["w_q"], d["w_scale"], w_red, d["w_out"])
+        acc = api.quik_int_gemm_w4a8(xq, d["w_q"], shp.K_b)
+    else:
+        y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+        acc = api.quik_int_gemm(xq, d["w_q"], shp.K_b, bits, code_sum=cs if bits == 4 else None,
+                                w_code_sum=w_cs if bits == 4 else None)
+    _sync()
+    what = f"T={T} K={K} N={N} n_out={n_out} {mode}"
+    assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, ref.q, bits, xq.shape[1])), what
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), ref.scale.view(np.uint32)), what
+    assert np.array_equal(zero.cpu().numpy().view(np.uint32), ref.zero.view(np.uint32)), what
+    if n_out:
+        assert np.array_equal(x_out.cpu().numpy().view(np.uint16), ref.x_out.view(np.uint16)), what
+    assert np.array_equal(acc.cpu().numpy(), ref.acc), what
+    ok, worst = output_within_tolerance(y.cpu().numpy(), ref.y)
+    assert ok, f"{what}: output outside 5e-3 ({worst:.2f}x)"
