@@ -242,7 +242,19 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
     uint32_t* stage = lds + img0 + g * (ldq_words + 4);        // one spare 16 bytes behind every image
     const int nrowblk = (T + RPB - 1) / RPB;
 
-    auto load_row = [&](uint4 (&cache)[NCH], int rb) {
+    // the outlier columns this thread moves (the first GJ * TPR of them; -1: none)
+    constexpr int GJ = 4;
+    int cidx[GJ];
+#pragma unroll
+    for (int q = 0; q < GJ; ++q) {
+        const int j = lt + q * TPR;
+        const int c = (j < n_out) ? idx[j] : -1;
+        cidx[q] = (c >= 0 && c < K) ? c : -1;
+    }
+
+    // a row's loads: its chunks and its outlier values, requested together (the outlier values
+    // are needed last, so fetching them with the row keeps their latency off the row's tail)
+    auto load_row = [&](uint4 (&cache)[NCH], unsigned short (&gv)[GJ], int rb) {
         const int t = rb * RPB + g;
         const __half* row = x + (size_t)(t < T ? t : 0) * ldx;
 #pragma unroll
@@ -251,12 +263,16 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
             if (t < T && k0 < K) cache[c] = *reinterpret_cast<const uint4*>(row + k0);
             else cache[c] = make_uint4(0, 0, 0, 0);
         }
+#pragma unroll
+        for (int q = 0; q < GJ; ++q)
+            gv[q] = (t < T && cidx[q] >= 0) ? __half_as_ushort(row[cidx[q]]) : (unsigned short)0;
     };
 
     constexpr bool DOUBLE = NCH <= 6;             // second register set for the next row (register budget)
     uint4 ca[NCH], cb[DOUBLE ? NCH : 1];
+    unsigned short gva[GJ], gvb[GJ];
     int rb = blockIdx.x;
-    if (rb < nrowblk) load_row(ca, rb);            // the first loads do not depend on the outlier map
+    if (rb < nrowblk) load_row(ca, gva, rb);       // the first loads do not depend on the outlier map
     build_outlier_map(idx, n_out, K, nwords, mask, pre, wave_tot);
 
     ChunkPlan<BITS> plan[NCH];
@@ -269,23 +285,10 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
     // generic squeeze needed by some lane of this wave? (more than three outliers in one 4-bit chunk)
     const bool wave_more = __builtin_amdgcn_ballot_w64(any_more != 0) != 0;
 
-    auto process_row = [&](const uint4 (&cache)[NCH], int rbk) {
+    auto process_row = [&](const uint4 (&cache)[NCH], const unsigned short (&gv)[GJ], int rbk) {
         const int t = rbk * RPB + g;
         const bool valid = t < T;
         const __half* row = x + (size_t)(valid ? t : 0) * ldx;
-
-        // the outlier columns of this row (cache hits: the row has just been read)
-        constexpr int GJ = 4;
-        __half gv[GJ];
-#pragma unroll
-        for (int q = 0; q < GJ; ++q) {
-            const int j = lt + q * TPR;
-            gv[q] = __ushort_as_half((unsigned short)0);
-            if (valid && j < n_out) {
-                const int c = idx[j];
-                if (c >= 0 && c < K) gv[q] = row[c];
-            }
-        }
 
         for (int i = lt; i < ldq_words; i += TPR) stage[i] = 0u;
 
@@ -404,7 +407,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
 #pragma unroll
             for (int q = 0; q < GJ; ++q) {
                 const int j = lt + q * TPR;
-                if (j < n_out) x_out[(size_t)t * ldo + j] = gv[q];
+                if (j < n_out) x_out[(size_t)t * ldo + j] = __ushort_as_half(gv[q]);
             }
             for (int j = lt + GJ * TPR; j < n_out; j += TPR) {
                 const int c = idx[j];
@@ -419,21 +422,21 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
         // The next row is fetched into a second register set while the current one is processed.
         while (rb < nrowblk) {
             int nx = rb + gridDim.x;
-            if (nx < nrowblk) load_row(cb, nx);
-            process_row(ca, rb);
+            if (nx < nrowblk) load_row(cb, gvb, nx);
+            process_row(ca, gva, rb);
             rb = nx;
             if (rb >= nrowblk) break;
             nx = rb + gridDim.x;
-            if (nx < nrowblk) load_row(ca, nx);
-            process_row(cb, rb);
+            if (nx < nrowblk) load_row(ca, gva, nx);
+            process_row(cb, gvb, rb);
             rb = nx;
         }
     } else {
         // Long rows: one register set; other waves of the CU cover the load latency.
         while (rb < nrowblk) {
-            process_row(ca, rb);
+            process_row(ca, gva, rb);
             rb += gridDim.x;
-            if (rb < nrowblk) load_row(ca, rb);
+            if (rb < nrowblk) load_row(ca, gva, rb);
         }
     }
 }
@@ -650,7 +653,7 @@ hipError_t dispatch(const QuantizeArgs& a, hipStream_t stream) {
     if (K <= 64 * 8 * 1) return launch<BITS, 64, 1>(a, stream);
     if (K <= 64 * 8 * 2) return launch<BITS, 64, 2>(a, stream);
     if (K <= 64 * 8 * 4) return launch<BITS, 64, 4>(a, stream);
-    if (K <= 64 * 8 * 8) return launch<BITS, 64, 8>(a, stream);
+    if (K <= 256 * 8 * 2) return launch<BITS, 256, 2>(a, stream);
     if (K <= 256 * 8 * 3) return launch<BITS, 256, 3>(a, stream);
     if (K <= 256 * 8 * 4) return launch<BITS, 256, 4>(a, stream);
     if (K <= 256 * 8 * 6) return launch<BITS, 256, 6>(a, stream);
