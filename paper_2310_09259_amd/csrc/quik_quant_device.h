@@ -10,15 +10,32 @@ namespace quant_dev {
 
 constexpr int kBlock = 256;
 
+// Wave-wide reductions whose result every lane receives.  Four DPP steps (two quad permutes, the
+// half-row and the row mirror) leave each row of 16 lanes holding its row's result; the four row
+// results are combined through scalar registers.  No LDS round trips (a butterfly of cross-lane
+// shuffles costs six dependent LDS-routed permutes per reduction).
+template <typename F>
+__device__ __forceinline__ int wave_reduce_bits(int v, F op) {
+    v = op(v, __builtin_amdgcn_mov_dpp(v, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    v = op(v, __builtin_amdgcn_mov_dpp(v, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    v = op(v, __builtin_amdgcn_mov_dpp(v, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    v = op(v, __builtin_amdgcn_mov_dpp(v, 0x140, 0xF, 0xF, true));   // row_mirror
+    const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+    const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+    return op(op(r0, r1), op(r2, r3));
+}
 __device__ __forceinline__ float wave_min(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
-    return v;
+    return __int_as_float(wave_reduce_bits(__float_as_int(v), [](int a, int b) {
+        return __float_as_int(fminf(__int_as_float(a), __int_as_float(b)));
+    }));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    return __int_as_float(wave_reduce_bits(__float_as_int(v), [](int a, int b) {
+        return __float_as_int(fmaxf(__int_as_float(a), __int_as_float(b)));
+    }));
+}
+__device__ __forceinline__ int wave_sum(int v) {
+    return wave_reduce_bits(v, [](int a, int b) { return a + b; });
 }
 
 union Chunk {          // 8 fp16 values = one 128-bit load

@@ -227,6 +227,15 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
     constexpr int RPB = kBlock / TPR;             // rows per workgroup iteration
     constexpr bool WAVE_ROW = TPR == 64;          // a row never leaves its wave: no workgroup barriers
     extern __shared__ __align__(16) uint32_t lds[];
+    // Claim the whole register budget of the launch bounds (512 / waves per SIMD, in units of 8).
+    // Measured on MI355X: when this kernel's allocation ended exactly at its highest live register
+    // (208 and 96 registers, leaving part of the SIMD's file unallocated), that register now and then
+    // read as the work-item id in the second workgroup of a CU; the identical code with a larger
+    // allocation never did.  With the budget claimed, the top of the allocation is live only in the
+    // instantiation that needs all 256 registers (a wave then owns exactly half the file, like the
+    // GEMM kernels, which have shown no such reads).
+    if constexpr (NCH >= 4) asm volatile("" ::: "v255");
+    else asm volatile("" ::: "v167");
     const int nwords = (K + 31) >> 5;
     uint32_t* mask = lds;
     uint32_t* pre = mask + nwords;
@@ -239,7 +248,12 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
     const int g = tid / TPR, lt = tid % TPR;
     const int K_b = K - n_out;
     const int ldq_words = ldq >> 2;
-    uint32_t* stage = lds + img0 + g * (ldq_words + 4);        // one spare 16 bytes behind every image
+    // two images per row group, used by alternate rows: a row may start clearing and filling its
+    // image while slower waves still write the previous row's image out (one spare 16 bytes behind
+    // every image)
+    uint32_t* const stage0 = lds + img0 + g * (ldq_words + 4);
+    const int img_stride = RPB * (ldq_words + 4);
+    int row_parity = 0;
     const int nrowblk = (T + RPB - 1) / RPB;
 
     // the outlier columns this thread moves (the first GJ * TPR of them; -1: none)
@@ -254,7 +268,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
 
     // a row's loads: its chunks and its outlier values, requested together (the outlier values
     // are needed last, so fetching them with the row keeps their latency off the row's tail)
-    auto load_row = [&](uint4 (&cache)[NCH], unsigned short (&gv)[GJ], int rb) {
+    auto load_row = [&](uint4 (&cache)[NCH], uint32_t (&gv)[GJ], int rb) {
         const int t = rb * RPB + g;
         const __half* row = x + (size_t)(t < T ? t : 0) * ldx;
 #pragma unroll
@@ -265,12 +279,12 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
         }
 #pragma unroll
         for (int q = 0; q < GJ; ++q)
-            gv[q] = (t < T && cidx[q] >= 0) ? __half_as_ushort(row[cidx[q]]) : (unsigned short)0;
+            gv[q] = (t < T && cidx[q] >= 0) ? (uint32_t)__half_as_ushort(row[cidx[q]]) : 0u;
     };
 
     constexpr bool DOUBLE = NCH <= 6;             // second register set for the next row (register budget)
     uint4 ca[NCH], cb[DOUBLE ? NCH : 1];
-    unsigned short gva[GJ], gvb[GJ];
+    uint32_t gva[GJ], gvb[GJ];                    // one register each: packing two would stall on the load
     int rb = blockIdx.x;
     if (rb < nrowblk) load_row(ca, gva, rb);       // the first loads do not depend on the outlier map
     build_outlier_map(idx, n_out, K, nwords, mask, pre, wave_tot);
@@ -285,10 +299,12 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
     // generic squeeze needed by some lane of this wave? (more than three outliers in one 4-bit chunk)
     const bool wave_more = __builtin_amdgcn_ballot_w64(any_more != 0) != 0;
 
-    auto process_row = [&](const uint4 (&cache)[NCH], const unsigned short (&gv)[GJ], int rbk) {
+    auto process_row = [&](const uint4 (&cache)[NCH], const uint32_t (&gv)[GJ], int rbk) {
         const int t = rbk * RPB + g;
         const bool valid = t < T;
         const __half* row = x + (size_t)(valid ? t : 0) * ldx;
+        uint32_t* const stage = stage0 + row_parity * img_stride;
+        row_parity ^= 1;
 
         for (int i = lt; i < ldq_words; i += TPR) stage[i] = 0u;
 
@@ -376,9 +392,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
         if constexpr (BITS == 4) {
             // sum over even positions of the signed codes (the GEMM's correction term for its
             // single-AND operand widening)
-            int es = (int)esum;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) es += __shfl_xor(es, o, 64);
+            int es = wave_sum((int)esum);
             if constexpr (!WAVE_ROW) {
                 if ((tid & 63) == 0) red_i[tid >> 6] = es;
                 __syncthreads();
@@ -407,15 +421,16 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
 #pragma unroll
             for (int q = 0; q < GJ; ++q) {
                 const int j = lt + q * TPR;
-                if (j < n_out) x_out[(size_t)t * ldo + j] = __ushort_as_half(gv[q]);
+                if (j < n_out) x_out[(size_t)t * ldo + j] = __ushort_as_half((unsigned short)gv[q]);
             }
             for (int j = lt + GJ * TPR; j < n_out; j += TPR) {
                 const int c = idx[j];
                 x_out[(size_t)t * ldo + j] = (c >= 0 && c < K) ? row[c] : __ushort_as_half((unsigned short)0);
             }
         }
+        // no barrier here: the next row works on the other image, and two barriers of that row lie
+        // between this write-out and the next clearing of this image
         if constexpr (WAVE_ROW) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        else __syncthreads();                      // before the next row clears the image
     };
 
     if constexpr (DOUBLE) {
@@ -632,9 +647,9 @@ hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     constexpr int kResident = 256 * ((NCH >= 4 || NCH == 0) ? 2 : 3);
     int grid = nrowblk < (NCH > 0 ? kResident : 2048) ? nrowblk : (NCH > 0 ? kResident : 2048);
     if constexpr (NCH > 0) {
-        // map + prefix, reduction scratch, then RPB row images of ldq bytes + 16 spare bytes each
+        // map + prefix, reduction scratch, then 2 * RPB row images of ldq bytes + 16 spare bytes each
         const size_t img0 = (size_t)((2 * nwords + 16 + 3) & ~3);
-        const size_t lds = (img0 + (size_t)RPB * ((a.ldq >> 2) + 4)) * 4;
+        const size_t lds = (img0 + 2 * (size_t)RPB * ((a.ldq >> 2) + 4)) * 4;
         hipLaunchKernelGGL((quantize_rows_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
                            (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
                            a.scale, a.zero, a.code_sum, (__half*)a.x_out, a.ldo);

@@ -59,7 +59,7 @@ QUANT_SHAPES = [
     (16, 512, 0, 4), (7, 64, 8, 4), (1, 8, 0, 4),
     (16, 512, 32, 8), (21, 4096, 256, 8), (6, 11008, 256, 8), (3, 20480, 128, 8), (11, 520, 24, 8),
     # more row blocks than workgroups: the software-pipelined row loop runs 2-3 times per workgroup
-    (9001, 512, 32, 4), (5000, 5120, 256, 4), (2500, 8200, 64, 8),
+    (9001, 512, 32, 4), (5000, 5120, 256, 4), (2500, 8200, 64, 8), (3000, 4096, 256, 8),
 ]
 
 
