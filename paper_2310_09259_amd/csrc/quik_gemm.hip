@@ -121,6 +121,11 @@ template <int BITS, int WBITS, int BM, int BN, int WM, int WN, int BKB, int NST,
 __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
     constexpr bool ASYM = (BITS == 4) && (MODE != 1);
+    // The accumulator-only forms are small enough for their register allocation to end anywhere; they
+    // claim the full 256 of their launch bounds so that the top of the allocation is never a live
+    // register (the row-quantization kernel misread such a register on MI355X when its allocation left
+    // part of the SIMD's file free).
+    if constexpr (RAW) asm volatile("" ::: "v255");
     // Mixed layers: a stage still covers BKB activation bytes = BKB k, which is only BKB/2 packed
     // weight bytes.  The weight nibbles are widened to 16x int8 (even / odd k of a word in two
     // registers); the int8 activations are brought into the same k order with two byte permutes
@@ -514,7 +519,6 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     for (; s < nk; ++s) {
 #pragma unroll
         for (int ks = 0; ks < KSUB; ++ks) {
-            const int par = ks & 1;
             if (ks == BAR_KS) { stage_barrier(); issue_any(s + NST); }
             const int ts = (ks + LA < KSUB) ? s : s + 1, tks = (ks + LA) % KSUB;
             const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
