@@ -1,0 +1,61 @@
+// FP6 (E3M2) operand format of the higher-rate 4-bit path.
+// Private to the shared library.
+//
+// The signed 4-bit codes of QUIK-4B (Algorithm 1 of arXiv 2310.09259: values -8 .. 7) are all exactly
+// representable in the 6-bit float format E3M2 (1 sign, 3 exponent bits with bias 3, 2 mantissa bits),
+// their products are integers of magnitude <= 64, and a dot product over K_b < 262144 columns stays
+// below 2^24, so an fp32 accumulator holds the integer result exactly.  gfx950 multiplies FP6 operands
+// at twice its int8 rate (v_mfma_f32_32x32x64_f8f6f4), and the operands need no widening in registers.
+//
+// Row layout ("planes").  The columns of a row are padded with zero codes to S stages of 128 columns.
+// A stage holds four groups of 32 columns, group index q = 2 * ks + g (ks: which of the stage's two
+// 64-column matrix steps, g: which half of the wave's lanes consumes it).  A group is 32 x 6 bits =
+// six dwords d0 .. d5, column j of the group in bits [6j, 6j + 6) of that 192-bit little-endian string:
+// exactly the register image one lane hands to the matrix instruction.  d0 .. d3 of all groups form
+// plane P (16 bytes per group, stage s at byte 64 s, group q at + 16 q); d4, d5 form plane Q, which
+// follows plane P at byte 64 S (stage s at + 32 s, the group (ks, g) at + 16 g + 8 ks), so that a lane
+// fetches its d4, d5 of both steps of a stage with one 16-byte read.  Row pitch >= 96 S bytes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace quik {
+namespace fp6 {
+
+// stages of 128 columns that cover K_b columns
+__host__ __device__ inline int stages(int K_b) { return (K_b + 127) >> 7; }
+// bytes of a row: planes P and Q
+__host__ __device__ inline int row_bytes(int K_b) { return 96 * stages(K_b); }
+// index (in dwords from the row start) of dword d (0 .. 5) of group G of a row with S stages
+__host__ __device__ inline int dword_index(int S, int G, int d) {
+    const int s = G >> 2, q = G & 3, ks = q >> 1, g = q & 1;
+    return d < 4 ? 16 * s + 4 * q + d : 16 * S + 8 * s + 4 * g + 2 * ks + (d - 4);
+}
+
+// E3M2 patterns of u - 8 for the unsigned codes u = 0 .. 7 (values -8 .. -1) and u = 8 .. 15 (0 .. 7)
+constexpr uint32_t kNeg0 = 0x35363738u, kNeg1 = 0x2C303234u;   // -8 -7 -6 -5 | -4 -3 -2 -1
+constexpr uint32_t kPos0 = 0x12100C00u, kPos1 = 0x17161514u;   //  0  1  2  3 |  4  5  6  7
+
+// four unsigned codes, one per byte -> their four E3M2 patterns, one per byte
+__device__ __forceinline__ uint32_t convert4(uint32_t n) {
+    const uint32_t sel = n & 0x07070707u;
+    const uint32_t m = ((n >> 3) & 0x01010101u) * 255u;          // 0xFF where u >= 8
+    const uint32_t neg = __builtin_amdgcn_perm(kNeg1, kNeg0, sel);
+    const uint32_t pos = __builtin_amdgcn_perm(kPos1, kPos0, sel);
+    return (pos & m) | (neg & ~m);
+}
+// bytes b0 .. b3 (6 significant bits each) -> b0 | b1 << 12 | b2 << 24 | b3 << 36
+__device__ __forceinline__ uint64_t spread4(uint32_t c) {
+    const uint32_t lo = (c & 0x3Fu) | ((c & 0x3F00u) << 4) | ((c & 0x3F0000u) << 8);
+    const uint32_t hi = (c >> 24) << 4;
+    return ((uint64_t)hi << 32) | lo;
+}
+// eight unsigned 4-bit codes (element i in nibble i) -> 48 bits, element i in bits [6i, 6i + 6)
+__device__ __forceinline__ uint64_t pack8(uint32_t codes) {
+    const uint32_t even = convert4(codes & 0x0F0F0F0Fu);
+    const uint32_t odd = convert4((codes >> 4) & 0x0F0F0F0Fu);
+    return spread4(even) | (spread4(odd) << 6);
+}
+
+}  // namespace fp6
+}  // namespace quik

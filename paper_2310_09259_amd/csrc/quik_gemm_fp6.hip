@@ -1,0 +1,420 @@
+// QUIK-4B linear layer with the integer product computed on the FP6 matrix pipe of gfx950
+// (Algorithm 1 of arXiv 2310.09259: "INTmatmul", "Dequantization", "FPmatmul", final add; the
+// epilogue fusion of Section 3.4).  The signed 4-bit codes travel as E3M2 patterns (see
+// quik_fp6_device.h: exact, and the fp32 accumulators hold the exact integer dot products), so the
+// K loop is DMA -> LDS -> registers -> v_mfma_f32_32x32x64_f8f6f4 with no widening work at all, at
+// twice the int8 rate of the matrix pipe.
+//
+// A workgroup of WM x WN waves owns a BM x BN output tile.  A stage is 128 columns: per operand row
+// 64 bytes of plane P and 32 bytes of plane Q, copied global -> LDS by 16-byte-per-lane DMA
+// instructions (16 rows of P or 32 rows of Q per instruction), three stage buffers.  Lane (row l%32,
+// half g = l/32) reads 16 bytes of P per 64-column step and 16 bytes of Q per stage; the 16-byte slots
+// are XOR-swizzled so that the rows one read instruction touches fall into distinct banks.  The fp16
+// outlier columns run through the same ring as stages of 32 columns (64 bytes per row: the geometry
+// of plane P), with the dequantized integer part as the C operand of v_mfma_f32_32x32x16_f16, whose
+// accumulator layout is the same.  Rows beyond T / N and columns beyond the row end are out of range
+// for the buffer descriptor or masked by hand and arrive as zeros (the E3M2 pattern of 0).
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "quik_kernels.h"
+#include "quik_gemm_device.h"
+#include "quik_fp6_device.h"
+
+namespace quik {
+
+namespace {
+
+using namespace gemm_dev;
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ int swz_p(int r) { return (r >> 2) & 3; }   // 64-byte rows, four slots
+__device__ __forceinline__ int swz_q(int r) { return (r >> 3) & 1; }   // 32-byte rows, two slots
+
+// MODE 0: fused epilogue, fp16 output; MODE 1: the integer accumulators as INT32.
+template <int BM, int BN, int WM, int WN, int GM, int MODE>
+__global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6_kernel(GemmArgs a) {
+    constexpr bool RAW = MODE != 0;
+    constexpr int NWAVES = WM * WN, NT = NWAVES * 64;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NF = TM + TN;
+    constexpr int NST = 3;
+    constexpr int AP = BM * 64, AQ = BM * 32, BP = BN * 64, BQ = BN * 32;
+    constexpr int OFF_AQ = AP, OFF_BP = AP + AQ, OFF_BQ = AP + AQ + BP, ST_BYTES = AP + AQ + BP + BQ;
+    // DMA instructions of a stage: P planes 16 rows each, Q planes 32 rows each
+    constexpr int N_AP = BM / 16, N_AQ = BM / 32, N_BP = BN / 16, N_BQ = BN / 32;
+    constexpr int N_DMA = N_AP + N_AQ + N_BP + N_BQ;
+    constexpr int LPS = (N_DMA + NWAVES - 1) / NWAVES;    // per wave and stage (missing ones are issued empty)
+    static_assert((NST - 1) * LPS < 64, "vmcnt range");
+    constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
+
+    __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES + 1024];
+    __shared__ __align__(16) float lds_sa[BM];
+    __shared__ __align__(16) float lds_sh[BM];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave_u / WN, wn = wave_u % WN;
+    const int l32 = lane & 31, g = lane >> 5;
+
+    const int tiles_m = (a.T + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    const int id = xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n);
+    int tile_m, tile_n;
+    if constexpr (GM > 0) {
+        const int per_group = GM * tiles_n;
+        const int grp = id / per_group, rem = id % per_group;
+        const int first_m = grp * GM;
+        const int gsz = min(GM, tiles_m - first_m);
+        tile_m = first_m + rem % gsz;
+        tile_n = rem / gsz;
+    } else {
+        tile_m = id % tiles_m;
+        tile_n = id / tiles_m;
+    }
+    const int t0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int S = fp6::stages(a.K_b);
+    const int nk_int = a.fp_only ? 0 : S;
+    const int fp_bytes = a.n_out * 2;
+    const int nk_fp = RAW ? 0 : (fp_bytes + 63) / 64;
+    const int nk = nk_int + nk_fp;
+    const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
+
+    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * a.ldq, (size_t)(a.T - t0) * a.ldq);
+    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * a.ldw, (size_t)(a.N - n0) * a.ldw);
+    const v4i rAf = make_rsrc(a.n_out ? (const uint8_t*)a.x_out + (size_t)t0 * lda_fp : (const uint8_t*)a.xq,
+                              a.n_out ? (size_t)(a.T - t0) * lda_fp : 0);
+    const v4i rBf = make_rsrc(a.n_out ? (const uint8_t*)a.w_out + (size_t)n0 * ldb_fp : (const uint8_t*)a.xq,
+                              a.n_out ? (size_t)(a.N - n0) * ldb_fp : 0);
+    const uint32_t lds_base = lds_addr(lds);
+
+    // DMA instruction d (0 .. N_DMA-1) of a stage: which plane, which rows; this wave issues
+    // d = wave + NWAVES * j.  kind 0: A plane P, 1: A plane Q, 2: B plane P, 3: B plane Q.
+    int d_kind[LPS], d_row[LPS], d_col[LPS];
+    uint32_t d_lds[LPS];
+    v4i r_int[LPS], r_fp[LPS];                            // the descriptor each instruction reads through
+#pragma unroll
+    for (int j = 0; j < LPS; ++j) {
+        const int d = wave_u + NWAVES * j;
+        int kind, i;
+        if (d < N_AP) { kind = 0; i = d; }
+        else if (d < N_AP + N_AQ) { kind = 1; i = d - N_AP; }
+        else if (d < N_AP + N_AQ + N_BP) { kind = 2; i = d - N_AP - N_AQ; }
+        else if (d < N_DMA) { kind = 3; i = d - N_AP - N_AQ - N_BP; }
+        else { kind = 4; i = 0; }
+        const bool isq = kind & 1;
+        const int row = isq ? i * 32 + (lane >> 1) : i * 16 + (lane >> 2);
+        const int slot = isq ? ((lane & 1) ^ swz_q(row)) : ((lane & 3) ^ swz_p(row));
+        d_kind[j] = __builtin_amdgcn_readfirstlane(kind); d_row[j] = row; d_col[j] = slot * 16;
+        const int off = kind == 0 ? 0 : kind == 1 ? OFF_AQ : kind == 2 ? OFF_BP : OFF_BQ;
+        d_lds[j] = (uint32_t)__builtin_amdgcn_readfirstlane(kind == 4 ? DUMMY : off + i * 1024);
+        const bool isb = kind >= 2;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            r_int[j][c] = __builtin_amdgcn_readfirstlane(isb ? rB[c] : rA[c]);
+            r_fp[j][c] = __builtin_amdgcn_readfirstlane(isb ? rBf[c] : rAf[c]);
+        }
+    }
+    // stage s (int part, fp16 part, or past the end: every lane out of range)
+    auto issue = [&](int s) {
+        const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
+        const bool fp = s >= nk_int;
+        const bool live = s < nk;
+        const int sf = s - nk_int;
+#pragma unroll
+        for (int j = 0; j < LPS; ++j) {
+            const int kind = d_kind[j];
+            const bool isq = kind & 1, isb = kind >= 2;
+            uint32_t vo = kOob;
+            if (live && kind < 4) {
+                if (!fp) {
+                    const int col = isq ? 64 * S + 32 * s + d_col[j] : 64 * s + d_col[j];
+                    vo = (uint32_t)(d_row[j] * (isb ? a.ldw : a.ldq) + col);
+                } else if (!isq) {
+                    const int col = 64 * sf + d_col[j];
+                    if (col < fp_bytes) vo = (uint32_t)(d_row[j] * (isb ? ldb_fp : lda_fp) + col);
+                }
+            }
+            dma16(fp ? r_fp[j] : r_int[j], lds_base + (kind == 4 ? 0 : sb) + d_lds[j], vo, 0);
+        }
+    };
+
+    // ---- epilogue parameters, requested before the first DMA
+    constexpr int RPT = (BM + NT - 1) / NT;
+    float p_s[RPT], p_z[RPT];
+    float c_sw[TN], c_wr[TN], c_bv[TN];
+    if constexpr (!RAW) {
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int t = t0 + tid + q * NT;
+            const bool ok = (tid + q * NT < BM) && t < a.T;
+            p_s[q] = ok ? a.scale[t] : 0.0f;
+            p_z[q] = ok ? a.zero[t] : 0.0f;
+        }
+        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
+        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = min(n0 + wn * TN * 32 + j * 32 + l32, a.N - 1);
+            c_sw[j] = __half2float(wsc[n]);
+            c_bv[j] = bias ? __half2float(bias[n]) : 0.0f;
+            c_wr[j] = a.w_reduced[n];
+            if (a.fp_only) { c_sw[j] = 0.0f; c_bv[j] = 0.0f; c_wr[j] = 0.0f; }
+        }
+    }
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s);
+
+    if constexpr (!RAW) {
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int r = tid + q * NT;
+            if (r < BM) {
+                lds_sa[r] = p_s[q];                        // scaleAct
+                lds_sh[r] = p_z[q] + 8.0f * p_s[q];        // zeroAct + halfRange * scaleAct
+            }
+        }
+    }
+
+    // LDS read addresses: plane P slot (2 ks + g), plane Q slot g, of this lane's row of every fragment
+    uint32_t rdp[NF][2], rdq[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int r = (f < TM) ? (wm * TM * 32 + f * 32 + l32) : (wn * TN * 32 + (f - TM) * 32 + l32);
+        const uint32_t bp = (f < TM ? 0 : OFF_BP) + r * 64, bq = (f < TM ? OFF_AQ : OFF_BQ) + r * 32;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) rdp[f][ks] = bp + (((ks * 2 + g) ^ swz_p(r)) << 4);
+        rdq[f] = bq + ((g ^ swz_q(r)) << 4);
+    }
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // iteration s: stage s has landed for everybody and nobody still reads stage s - 1, whose buffer
+    // the DMA of stage s + NST - 1 then refills
+    auto stage_sync = [&](int s) {
+        wait_vm<(NST - 2) * LPS>();
+        __syncthreads();
+        issue(s + NST - 1);
+    };
+
+    int s = 0;
+    for (; s < nk_int; ++s) {
+        stage_sync(s);
+        const uint8_t* st = lds + (s % NST) * ST_BYTES;
+        uint4 P0[NF], P1[NF], Q[NF];
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            P0[f] = *reinterpret_cast<const uint4*>(st + rdp[f][0]);
+            Q[f] = *reinterpret_cast<const uint4*>(st + rdq[f]);
+        }
+#pragma unroll
+        for (int f = 0; f < NF; ++f) P1[f] = *reinterpret_cast<const uint4*>(st + rdp[f][1]);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v8i op[NF];
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                const uint4 p = ks ? P1[f] : P0[f];
+                op[f] = v8i{(int)p.x, (int)p.y, (int)p.z, (int)p.w, (int)(ks ? Q[f].z : Q[f].x),
+                            (int)(ks ? Q[f].w : Q[f].y), 0, 0};
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(op[i], op[TM + j], acc[i][j], 3, 3,
+                                                                                 0, 0, 0, 0);
+        }
+    }
+
+    const int tw = t0 + wm * TM * 32, nw = n0 + wn * TN * 32;
+    if constexpr (RAW) {
+        wait_vm<0>();                      // drain the look-ahead DMA before the wave ends
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = nw + j * 32 + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int t = tw + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = (int)acc[i][j][r];
+                }
+            }
+        return;
+    }
+
+    // Dequantization: the accumulators are exact integers already in binary32.
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            const int lr = wm * TM * 32 + i * 32 + 8 * rq + 4 * g;
+            const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
+            const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
+            const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int r = rq * 4 + rr;
+                    acc[i][j][r] = __builtin_fmaf(acc[i][j][r], sa_[rr] * c_sw[j],
+                                                  __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
+                }
+        }
+
+    // fp16 outlier stages: 32 columns each, two matrix steps of 16
+    for (; s < nk; ++s) {
+        stage_sync(s);
+        const uint8_t* st = lds + (s % NST) * ST_BYTES;
+        uint4 F[2][NF];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int f = 0; f < NF; ++f) F[ks][f] = *reinterpret_cast<const uint4*>(st + rdp[f][ks]);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, F[ks][i]),
+                                                                       __builtin_bit_cast(v8h, F[ks][TM + j]),
+                                                                       acc[i][j], 0, 0, 0);
+    }
+
+    wait_vm<0>();                          // drain the look-ahead DMA before the wave ends
+    __half* __restrict__ y = static_cast<__half*>(a.y);
+    // Output through LDS (each wave parks its fp16 tile in its own slice of the dead stage ring and
+    // writes whole row segments as 16-byte pieces); needs 16-byte aligned output rows.
+    constexpr int WROW = (NWAVES * TM * 32 * (TN * 64 + 16) <= NST * ST_BYTES) ? TN * 64 + 16 : TN * 64;
+    constexpr int WBUF = TM * 32 * WROW;
+    static_assert(NWAVES * WBUF <= NST * ST_BYTES, "stage ring too small to park the output tile");
+    const bool vec_ok = !a.fp_only && ((reinterpret_cast<uintptr_t>(a.y) & 15u) == 0) && (a.ldy % 8 == 0);
+    if (vec_ok) {
+        __syncthreads();                   // every wave is past its last read of the stage ring
+        uint8_t* wbuf = lds + wave_u * WBUF;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    *reinterpret_cast<__half*>(wbuf + row * WROW + (j * 32 + l32) * 2) = __float2half(acc[i][j][r]);
+                }
+        constexpr int CH = TN * 4;                       // 16-byte pieces per row
+        constexpr int RPS = 64 / CH;                     // rows per store instruction
+        const int prow = lane / CH, pch = lane % CH;
+#pragma unroll
+        for (int p = 0; p < (TM * 32 + RPS - 1) / RPS; ++p) {
+            const int row = p * RPS + prow;
+            if (prow >= RPS || row >= TM * 32) continue;
+            const uint4 v = *reinterpret_cast<const uint4*>(wbuf + row * WROW + pch * 16);
+            const int t = tw + row, n = nw + pch * 8;
+            if (t < a.T) {
+                __half* dst = y + (size_t)t * a.ldy + n;
+                if (n + 8 <= a.N) {
+                    *reinterpret_cast<uint4*>(dst) = v;
+                } else {
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < a.N)
+                            reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = nw + j * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = tw + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                if (t < a.T && n < a.N) {
+                    if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = acc[i][j][r];
+                    else y[(size_t)t * a.ldy + n] = __float2half(acc[i][j][r]);
+                }
+            }
+        }
+}
+
+// Signed 4-bit weights (two per byte, column 2p in the low nibble) -> FP6 planes.  One thread per
+// (row, group of 32 columns).  Offline step.
+__global__ __launch_bounds__(256) void weight_pack_fp6_kernel(const uint8_t* __restrict__ w_q, int ldw, int N, int K_b,
+                                                              uint32_t* __restrict__ w6, int ld6_words) {
+    const int S = fp6::stages(K_b);
+    const int groups = 4 * S;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)N * groups) return;
+    const int n = (int)(idx / groups), G = (int)(idx % groups);
+    const uint8_t* src = w_q + (size_t)n * ldw + G * 16;
+    uint32_t cw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int col = G * 32 + i * 8 + b * 2;                 // first column of this byte
+            uint32_t byte = (col < K_b) ? src[i * 4 + b] : 0u;      // columns at or beyond K_b: value 0
+            if (col + 1 >= K_b) byte &= 0x0Fu;
+            v |= byte << (8 * b);
+        }
+        cw[i] = v ^ 0x88888888u;                                    // two's complement -> unsigned code (value + 8)
+    }
+    // 32 columns = four 48-bit strings at bits 0, 48, 96, 144
+    const uint64_t e0 = fp6::pack8(cw[0]), e1 = fp6::pack8(cw[1]), e2 = fp6::pack8(cw[2]), e3 = fp6::pack8(cw[3]);
+    uint32_t d[6];
+    d[0] = (uint32_t)e0;
+    d[1] = (uint32_t)(e0 >> 32) | (uint32_t)(e1 << 16);
+    d[2] = (uint32_t)(e1 >> 16);
+    d[3] = (uint32_t)e2;
+    d[4] = (uint32_t)(e2 >> 32) | (uint32_t)(e3 << 16);
+    d[5] = (uint32_t)(e3 >> 16);
+    uint32_t* row = w6 + (size_t)n * ld6_words;
+#pragma unroll
+    for (int i = 0; i < 6; ++i) row[fp6::dword_index(S, G, i)] = d[i];
+}
+
+template <int BM, int BN, int WM, int WN, int GM, int MODE>
+hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
+    const int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    hipLaunchKernelGGL((gemm_fp6_kernel<BM, BN, WM, WN, GM, MODE>), dim3(tiles), dim3(WM * WN * 64), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t dispatch6(const GemmArgs& a, hipStream_t stream) {
+    const long big = (long)((a.T + 255) / 256) * ((a.N + 191) / 192);
+    if (a.T > 128 && big >= 128) return launch_cfg<256, 192, 4, 2, 4, MODE>(a, stream);
+    return launch_cfg<128, 128, 2, 2, 0, MODE>(a, stream);
+}
+
+}  // namespace
+
+hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream) {
+    if (a.T <= 0 || a.N <= 0) return hipSuccess;
+    return a.y ? dispatch6<0>(a, stream) : dispatch6<1>(a, stream);
+}
+
+hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, int ld6, hipStream_t stream) {
+    if (N <= 0 || K_b <= 0) return hipSuccess;
+    const long total = (long)N * 4 * fp6::stages(K_b);
+    hipLaunchKernelGGL(weight_pack_fp6_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t*>(w_q), ldw, N, K_b, static_cast<uint32_t*>(w6), ld6 / 4);
+    return hipGetLastError();
+}
+
+}  // namespace quik

@@ -39,6 +39,7 @@
 
 #include "quik_kernels.h"
 #include "quik_quant_device.h"
+#include "quik_fp6_device.h"
 
 namespace quik {
 
@@ -218,8 +219,10 @@ __device__ __forceinline__ void chunk_codes(const uint32_t (&x)[4], float mn, fl
     }
 }
 
-// K <= TPR * 8 * NCH: the row lives in NCH 128-bit registers per thread.
-template <int BITS, int TPR, int NCH>
+// K <= TPR * 8 * NCH: the row lives in NCH 128-bit registers per thread.  FP6 (4-bit codes only):
+// the packed row is written as E3M2 patterns in the plane layout of quik_fp6_device.h (ldq is then
+// that layout's row pitch) and no code sum is produced.
+template <int BITS, int TPR, int NCH, bool FP6>
 __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kernel(
     const __half* __restrict__ x, int T, int K, int ldx, const int32_t* __restrict__ idx, int n_out,
     uint8_t* __restrict__ xq, int ldq, float* __restrict__ scale, float* __restrict__ zero,
@@ -248,6 +251,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
     const int g = tid / TPR, lt = tid % TPR;
     const int K_b = K - n_out;
     const int ldq_words = ldq >> 2;
+    const int S6 = fp6::stages(K_b);
     // two images per row group, used by alternate rows: a row may start clearing and filling its
     // image while slower waves still write the previous row's image out (one spare 16 bytes behind
     // every image)
@@ -366,11 +370,28 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                     }
                 }
                 lo &= p.keep_lo;
-                esum = __builtin_amdgcn_sad_u8((lo >> pos_even_shift(pos)) & 0x0F0F0F0Fu, 0u, esum);
-                lo = (lo ^ 0x88888888u) & p.keep_lo;          // code - halfRange as two's complement nibbles
-                const uint64_t v = (uint64_t)lo << pos_shift(pos);
-                atomicOr(&stage[pos_word(pos)], (uint32_t)v);
-                atomicOr(&stage[pos_word(pos) + 1], (uint32_t)(v >> 32));
+                if constexpr (FP6) {
+                    // the kept elements as 6-bit patterns, OR-ed into dwords d, d+1, d+2 of the 192-bit
+                    // string of their group of 32 columns (running on into the next group)
+                    const uint32_t bits6 = 6u * ((uint32_t)__popc(p.keep_lo) >> 2);
+                    const uint64_t v6 = fp6::pack8(lo) & (bits6 >= 48u ? 0xFFFFFFFFFFFFull : ((1ull << bits6) - 1ull));
+                    const uint32_t e0 = (pos_word(pos) * 32u + pos_shift(pos)) >> 2;   // first element's position
+                    const uint32_t G = e0 >> 5, b0 = 6u * (e0 & 31u), d0 = b0 >> 5, sh = b0 & 31u;
+                    const uint64_t vs = v6 << sh;
+                    const uint32_t w3[3] = {(uint32_t)vs, (uint32_t)(vs >> 32), sh ? (uint32_t)(v6 >> (64u - sh)) : 0u};
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+                        uint32_t dd = d0 + i, GG = G;
+                        if (dd >= 6u) { dd -= 6u; ++GG; }
+                        if (w3[i]) atomicOr(&stage[fp6::dword_index(S6, (int)GG, (int)dd)], w3[i]);
+                    }
+                } else {
+                    esum = __builtin_amdgcn_sad_u8((lo >> pos_even_shift(pos)) & 0x0F0F0F0Fu, 0u, esum);
+                    lo = (lo ^ 0x88888888u) & p.keep_lo;      // code - halfRange as two's complement nibbles
+                    const uint64_t v = (uint64_t)lo << pos_shift(pos);
+                    atomicOr(&stage[pos_word(pos)], (uint32_t)v);
+                    atomicOr(&stage[pos_word(pos) + 1], (uint32_t)(v >> 32));
+                }
             } else {
                 uint64_t w = ((uint64_t)hi << 32) | lo;
                 uint32_t m = pos_more(pos);
@@ -389,7 +410,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                 atomicOr(&stage[pos_word(pos) + 2], top);
             }
         }
-        if constexpr (BITS == 4) {
+        if constexpr (BITS == 4 && !FP6) {
             // sum over even positions of the signed codes (the GEMM's correction term for its
             // single-AND operand widening)
             int es = wave_sum((int)esum);
@@ -411,7 +432,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
             const uint4* src = reinterpret_cast<const uint4*>(stage);
             for (int i = lt; i < (ldq >> 4); i += TPR) {
                 uint4 v = src[i];
-                if constexpr (BITS == 4) {
+                if constexpr (BITS == 4 && !FP6) {
                     auto sw = [](uint32_t w) { return ((w & 0x0F0F0F0Fu) << 4) | ((w >> 4) & 0x0F0F0F0Fu); };
                     v = make_uint4(sw(v.x), sw(v.y), sw(v.z), sw(v.w));
                 }
@@ -636,7 +657,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     }
 }
 
-template <int BITS, int TPR, int NCH>
+template <int BITS, int TPR, int NCH, bool FP6>
 hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     constexpr int RPB = kBlock / TPR;
     const int nwords = (a.K + 31) >> 5;
@@ -650,9 +671,11 @@ hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
         // map + prefix, reduction scratch, then 2 * RPB row images of ldq bytes + 16 spare bytes each
         const size_t img0 = (size_t)((2 * nwords + 16 + 3) & ~3);
         const size_t lds = (img0 + 2 * (size_t)RPB * ((a.ldq >> 2) + 4)) * 4;
-        hipLaunchKernelGGL((quantize_rows_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
+        hipLaunchKernelGGL((quantize_rows_kernel<BITS, TPR, NCH, FP6>), dim3(grid), dim3(kBlock), lds, stream,
                            (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
                            a.scale, a.zero, a.code_sum, (__half*)a.x_out, a.ldo);
+    } else if constexpr (FP6) {
+        return hipErrorInvalidValue;               // rows beyond 16384 columns: integer formats only
     } else {
         const size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
         hipLaunchKernelGGL((quantize_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
@@ -662,24 +685,25 @@ hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int BITS>
+template <int BITS, bool FP6>
 hipError_t dispatch(const QuantizeArgs& a, hipStream_t stream) {
     const int K = a.K;
-    if (K <= 64 * 8 * 1) return launch<BITS, 64, 1>(a, stream);
-    if (K <= 64 * 8 * 2) return launch<BITS, 64, 2>(a, stream);
-    if (K <= 64 * 8 * 4) return launch<BITS, 64, 4>(a, stream);
-    if (K <= 256 * 8 * 2) return launch<BITS, 256, 2>(a, stream);
-    if (K <= 256 * 8 * 3) return launch<BITS, 256, 3>(a, stream);
-    if (K <= 256 * 8 * 4) return launch<BITS, 256, 4>(a, stream);
-    if (K <= 256 * 8 * 6) return launch<BITS, 256, 6>(a, stream);
-    if (K <= 256 * 8 * 8) return launch<BITS, 256, 8>(a, stream);
-    return launch<BITS, 256, 0>(a, stream);
+    if (K <= 64 * 8 * 1) return launch<BITS, 64, 1, FP6>(a, stream);
+    if (K <= 64 * 8 * 2) return launch<BITS, 64, 2, FP6>(a, stream);
+    if (K <= 64 * 8 * 4) return launch<BITS, 64, 4, FP6>(a, stream);
+    if (K <= 256 * 8 * 2) return launch<BITS, 256, 2, FP6>(a, stream);
+    if (K <= 256 * 8 * 3) return launch<BITS, 256, 3, FP6>(a, stream);
+    if (K <= 256 * 8 * 4) return launch<BITS, 256, 4, FP6>(a, stream);
+    if (K <= 256 * 8 * 6) return launch<BITS, 256, 6, FP6>(a, stream);
+    if (K <= 256 * 8 * 8) return launch<BITS, 256, 8, FP6>(a, stream);
+    return launch<BITS, 256, 0, FP6>(a, stream);
 }
 
 }  // namespace
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
-    return a.bits == 4 ? dispatch<4>(a, stream) : dispatch<8>(a, stream);
+    if (a.fp6) return a.bits == 4 ? dispatch<4, true>(a, stream) : hipErrorInvalidValue;
+    return a.bits == 4 ? dispatch<4, false>(a, stream) : dispatch<8, false>(a, stream);
 }
 
 }  // namespace quik

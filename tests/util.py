@@ -47,3 +47,43 @@ def expected_xq(oracle, q: np.ndarray, bits: int, ldq: int) -> np.ndarray:
     out = np.zeros((q.shape[0], ldq), np.uint8)
     out[:, : packed.shape[1]] = packed
     return out
+
+
+def e3m2_pattern(v: np.ndarray) -> np.ndarray:
+    """Integers -8 .. 8 -> their bit patterns in the 6-bit float format E3M2 (1 sign bit, 3 exponent
+    bits with bias 3, 2 mantissa bits), written from the format's definition:
+    |v| = (1 + m/4) * 2^(e - 3) for e >= 1; zero is all-zero."""
+    v = np.asarray(v, np.int64)
+    mag = np.abs(v)
+    out = np.zeros(v.shape, np.uint8)
+    nz = mag > 0
+    ex = np.zeros(v.shape, np.int64)
+    ex[nz] = np.floor(np.log2(mag[nz])).astype(np.int64)
+    frac4 = np.zeros(v.shape, np.int64)
+    frac4[nz] = (mag[nz] * 4) // (1 << ex[nz]) - 4           # m: (|v| / 2^ex - 1) * 4
+    assert np.all((mag[nz] * 4) % (1 << ex[nz]) == 0) and np.all(frac4 >= 0) and np.all(frac4 < 4)
+    out[nz] = (((ex[nz] + 3) << 2) | frac4[nz]).astype(np.uint8)
+    out[v < 0] |= 32
+    return out
+
+
+def fp6_rows(q: np.ndarray, ld6: int) -> np.ndarray:
+    """Signed codes int [R, K_b] -> the byte image of "FP6 rows" as include/quik.h defines them:
+    zero-padded to S stages of 128 columns; a group of 32 columns is a 192-bit little-endian string
+    (column j in bits [6j, 6j+6)); bytes 0..15 of stage s, group q = 2*ks + g go to 64 s + 16 q
+    (plane P), bytes 16..23 to 64 S + 32 s + 16 g + 8 ks (plane Q)."""
+    R, K_b = q.shape
+    S = (K_b + 127) // 128
+    codes = np.zeros((R, 128 * S), np.uint8)
+    codes[:, :K_b] = e3m2_pattern(q)
+    bits = ((codes[:, :, None] >> np.arange(6, dtype=np.uint8)) & 1).astype(np.uint8)   # little-endian per code
+    strings = np.packbits(bits.reshape(R, 4 * S, 192), axis=2, bitorder="little")       # [R, 4S, 24] bytes
+    out = np.zeros((R, ld6), np.uint8)
+    for s in range(S):
+        for qq in range(4):
+            ks, g = qq >> 1, qq & 1
+            grp = strings[:, 4 * s + qq, :]
+            out[:, 64 * s + 16 * qq: 64 * s + 16 * qq + 16] = grp[:, :16]
+            o = 64 * S + 32 * s + 16 * g + 8 * ks
+            out[:, o: o + 8] = grp[:, 16:]
+    return out
