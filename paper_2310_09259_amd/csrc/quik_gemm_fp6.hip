@@ -44,8 +44,12 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
     constexpr int OFF_AQ = AP, OFF_BP = AP + AQ, OFF_BQ = AP + AQ + BP, ST_BYTES = AP + AQ + BP + BQ;
     // DMA instructions of a stage: P planes 16 rows each, Q planes 32 rows each
     constexpr int N_AP = BM / 16, N_AQ = BM / 32, N_BP = BN / 16, N_BQ = BN / 32;
-    constexpr int N_DMA = N_AP + N_AQ + N_BP + N_BQ;
-    constexpr int LPS = (N_DMA + NWAVES - 1) / NWAVES;    // per wave and stage (missing ones are issued empty)
+    // DMA slots of a wave per stage, in this order: plane P of A, plane Q of A, plane P of B, plane Q of
+    // B; instruction i = wave + NWAVES * (slot within its plane); a slot whose i does not exist is
+    // issued empty so that every wave counts the same number of DMA instructions
+    constexpr int S_AP = (N_AP + NWAVES - 1) / NWAVES, S_AQ = (N_AQ + NWAVES - 1) / NWAVES;
+    constexpr int S_BP = (N_BP + NWAVES - 1) / NWAVES, S_BQ = (N_BQ + NWAVES - 1) / NWAVES;
+    constexpr int LPS = S_AP + S_AQ + S_BP + S_BQ;
     static_assert((NST - 1) * LPS < 64, "vmcnt range");
     constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
 
@@ -80,6 +84,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
     const int nk_fp = RAW ? 0 : (fp_bytes + 63) / 64;
     const int nk = nk_int + nk_fp;
     const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
+    const int ld_a = a.ldq, ld_b = a.ldw;                 // values, so that nothing takes the address of an argument
 
     const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * a.ldq, (size_t)(a.T - t0) * a.ldq);
     const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * a.ldw, (size_t)(a.N - n0) * a.ldw);
@@ -89,55 +94,43 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
                               a.n_out ? (size_t)(a.N - n0) * ldb_fp : 0);
     const uint32_t lds_base = lds_addr(lds);
 
-    // DMA instruction d (0 .. N_DMA-1) of a stage: which plane, which rows; this wave issues
-    // d = wave + NWAVES * j.  kind 0: A plane P, 1: A plane Q, 2: B plane P, 3: B plane Q.
-    int d_kind[LPS], d_row[LPS], d_col[LPS];
-    uint32_t d_lds[LPS];
-    v4i r_int[LPS], r_fp[LPS];                            // the descriptor each instruction reads through
-#pragma unroll
-    for (int j = 0; j < LPS; ++j) {
-        const int d = wave_u + NWAVES * j;
-        int kind, i;
-        if (d < N_AP) { kind = 0; i = d; }
-        else if (d < N_AP + N_AQ) { kind = 1; i = d - N_AP; }
-        else if (d < N_AP + N_AQ + N_BP) { kind = 2; i = d - N_AP - N_AQ; }
-        else if (d < N_DMA) { kind = 3; i = d - N_AP - N_AQ - N_BP; }
-        else { kind = 4; i = 0; }
-        const bool isq = kind & 1;
-        const int row = isq ? i * 32 + (lane >> 1) : i * 16 + (lane >> 2);
-        const int slot = isq ? ((lane & 1) ^ swz_q(row)) : ((lane & 3) ^ swz_p(row));
-        d_kind[j] = __builtin_amdgcn_readfirstlane(kind); d_row[j] = row; d_col[j] = slot * 16;
+    // Per-lane parts of the DMA source offsets.  A P-plane instruction covers 16 rows (lane / 4) and the
+    // four 16-byte slots of a 64-byte stage row, a Q-plane instruction 32 rows (lane / 2) and two slots;
+    // the swizzle of a row depends only on lane bits 4, 5 because 16 and 32 rows are whole swizzle periods.
+    const int colP = ((lane & 3) ^ ((lane >> 4) & 3)) * 16, colQ = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;
+    const uint32_t vo_ap = (uint32_t)((lane >> 2) * ld_a + colP), vo_aq = (uint32_t)((lane >> 1) * ld_a + 64 * S + colQ);
+    const uint32_t vo_bp = (uint32_t)((lane >> 2) * ld_b + colP), vo_bq = (uint32_t)((lane >> 1) * ld_b + 64 * S + colQ);
+    const uint32_t vo_af = (uint32_t)((lane >> 2) * lda_fp + colP), vo_bf = (uint32_t)((lane >> 2) * ldb_fp + colP);
+    // DMA slot j of stage s (int part, fp16 part, or past the end: every lane out of range)
+    auto issue_one = [&](int s, int j) __attribute__((always_inline)) {
+        const int kind = j < S_AP ? 0 : j < S_AP + S_AQ ? 1 : j < S_AP + S_AQ + S_BP ? 2 : 3;
+        const int seq = kind == 0 ? j : kind == 1 ? j - S_AP : kind == 2 ? j - S_AP - S_AQ : j - S_AP - S_AQ - S_BP;
+        const bool isq = kind & 1, isb = kind >= 2;
+        const int n_kind = kind == 0 ? N_AP : kind == 1 ? N_AQ : kind == 2 ? N_BP : N_BQ;
         const int off = kind == 0 ? 0 : kind == 1 ? OFF_AQ : kind == 2 ? OFF_BP : OFF_BQ;
-        d_lds[j] = (uint32_t)__builtin_amdgcn_readfirstlane(kind == 4 ? DUMMY : off + i * 1024);
-        const bool isb = kind >= 2;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            r_int[j][c] = __builtin_amdgcn_readfirstlane(isb ? rB[c] : rA[c]);
-            r_fp[j][c] = __builtin_amdgcn_readfirstlane(isb ? rBf[c] : rAf[c]);
-        }
-    }
-    // stage s (int part, fp16 part, or past the end: every lane out of range)
-    auto issue = [&](int s) {
+        const int i = wave_u + NWAVES * seq;                    // instruction of this plane (wave-uniform)
+        const bool exists = i < n_kind;
         const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
         const bool fp = s >= nk_int;
-        const bool live = s < nk;
-        const int sf = s - nk_int;
-#pragma unroll
-        for (int j = 0; j < LPS; ++j) {
-            const int kind = d_kind[j];
-            const bool isq = kind & 1, isb = kind >= 2;
-            uint32_t vo = kOob;
-            if (live && kind < 4) {
-                if (!fp) {
-                    const int col = isq ? 64 * S + 32 * s + d_col[j] : 64 * s + d_col[j];
-                    vo = (uint32_t)(d_row[j] * (isb ? a.ldw : a.ldq) + col);
-                } else if (!isq) {
-                    const int col = 64 * sf + d_col[j];
-                    if (col < fp_bytes) vo = (uint32_t)(d_row[j] * (isb ? ldb_fp : lda_fp) + col);
-                }
+        const bool live = s < nk && exists;
+        const int rows = isq ? 32 : 16;
+        uint32_t vo = kOob, so = 0;
+        if (live) {
+            if (!fp) {
+                vo = (isb ? (isq ? vo_bq : vo_bp) : (isq ? vo_aq : vo_ap)) + (uint32_t)(i * rows * (isb ? ld_b : ld_a));
+                so = (uint32_t)((isq ? 32 : 64) * s);
+            } else if (!isq) {
+                const int c0 = 64 * (s - nk_int);
+                vo = (c0 + colP < fp_bytes) ? (isb ? vo_bf : vo_af) + (uint32_t)(i * 16 * (isb ? ldb_fp : lda_fp) + c0) : kOob;
             }
-            dma16(fp ? r_fp[j] : r_int[j], lds_base + (kind == 4 ? 0 : sb) + d_lds[j], vo, 0);
         }
+        const uint32_t dst = lds_base + (exists ? sb + off + i * 1024 : (uint32_t)DUMMY);
+        if (isb) dma16(fp ? rBf : rB, dst, vo, so);
+        else dma16(fp ? rAf : rA, dst, vo, so);
+    };
+    auto issue = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < LPS; ++j) issue_one(s, j);
     };
 
     // ---- epilogue parameters, requested before the first DMA
@@ -165,7 +158,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
     }
 
 #pragma unroll
-    for (int s = 0; s < NST - 1; ++s) issue(s);
+    for (int s = 0; s < NST; ++s) issue(s);
 
     if constexpr (!RAW) {
 #pragma unroll
@@ -178,7 +171,8 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
         }
     }
 
-    // LDS read addresses: plane P slot (2 ks + g), plane Q slot g, of this lane's row of every fragment
+    // LDS read addresses of this lane's row of every fragment: plane P slot 2 ks + g (16 bytes),
+    // plane Q slot g, 8 bytes at + 8 ks
     uint32_t rdp[NF][2], rdq[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
@@ -188,6 +182,16 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
         for (int ks = 0; ks < 2; ++ks) rdp[f][ks] = bp + (((ks * 2 + g) ^ swz_p(r)) << 4);
         rdq[f] = bq + ((g ^ swz_q(r)) << 4);
     }
+    // two fragment sets: the matrix instructions of one 64-column step run on one set while the
+    // LDS reads of the next step fill the other
+    uint4 FP[2][NF];
+    uint2 FQ[2][NF];
+    auto read_p = [&](int set, int f, int s, int ks) __attribute__((always_inline)) {
+        FP[set][f] = *reinterpret_cast<const uint4*>(lds + (s % NST) * ST_BYTES + rdp[f][ks]);
+    };
+    auto read_q = [&](int set, int f, int s, int ks) __attribute__((always_inline)) {
+        FQ[set][f] = *reinterpret_cast<const uint2*>(lds + (s % NST) * ST_BYTES + rdq[f] + 8 * ks);
+    };
 
     v16f acc[TM][TN];
 #pragma unroll
@@ -197,42 +201,69 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // iteration s: stage s has landed for everybody and nobody still reads stage s - 1, whose buffer
-    // the DMA of stage s + NST - 1 then refills
-    auto stage_sync = [&](int s) {
-        wait_vm<(NST - 2) * LPS>();
-        __syncthreads();
-        issue(s + NST - 1);
+    // Step ks of stage s.  Before its second step a stage's successor must have landed for everybody
+    // (its first fragments are read during that step); all reads of stage s itself have completed by
+    // then, so its buffer is refilled with stage s + NST right away, one DMA instruction per matrix
+    // instruction.
+    auto step = [&](int s, int ks, bool wide) __attribute__((always_inline)) {
+        if (ks == 1) {
+            wait_vm<(NST - 2) * LPS>();
+            __syncthreads();
+        }
+        const int ns = ks ? s + 1 : s, nks = ks ^ 1;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < TM * TN; ++m) {
+            const int i = m / TN, j = m % TN;
+            if (!wide) {
+                const v8i oa = v8i{(int)FP[ks][i].x, (int)FP[ks][i].y, (int)FP[ks][i].z, (int)FP[ks][i].w,
+                                   (int)FQ[ks][i].x, (int)FQ[ks][i].y, 0, 0};
+                const v8i ob = v8i{(int)FP[ks][TM + j].x, (int)FP[ks][TM + j].y, (int)FP[ks][TM + j].z,
+                                   (int)FP[ks][TM + j].w, (int)FQ[ks][TM + j].x, (int)FQ[ks][TM + j].y, 0, 0};
+#ifndef QF_NOMFMA
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(oa, ob, acc[i][j], 3, 3, 0, 0, 0, 0);
+#else
+                asm volatile("" :: "v"(oa), "v"(ob));
+#endif
+            } else {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, FP[ks][i]),
+                                                                   __builtin_bit_cast(v8h, FP[ks][TM + j]),
+                                                                   acc[i][j], 0, 0, 0);
+            }
+            if (ks == 1) {
+                constexpr int PER = (TM * TN >= LPS) ? TM * TN / LPS : 1;
+#ifndef QF_NODMA
+                if (m % PER == 0 && m / PER < LPS) issue_one(s + NST, m / PER);
+#endif
+                if constexpr (TM * TN < LPS) {
+                    if (m == TM * TN - 1) {
+#pragma unroll
+                        for (int d = TM * TN; d < LPS; ++d) issue_one(s + NST, d);
+                    }
+                }
+            }
+#ifndef QF_NOREAD
+            if (m < NF) { read_p(nks, m, ns, nks); read_q(nks, m, ns, nks); }
+#endif
+            if constexpr (TM * TN < NF) {
+                if (m == TM * TN - 1) {
+#pragma unroll
+                    for (int f = TM * TN; f < NF; ++f) { read_p(nks, f, ns, nks); read_q(nks, f, ns, nks); }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
+
+    wait_vm<(NST - 1) * LPS>();            // stage 0 landed
+    __syncthreads();
+#pragma unroll
+    for (int f = 0; f < NF; ++f) { read_p(0, f, 0, 0); read_q(0, f, 0, 0); }
 
     int s = 0;
     for (; s < nk_int; ++s) {
-        stage_sync(s);
-        const uint8_t* st = lds + (s % NST) * ST_BYTES;
-        uint4 P0[NF], P1[NF], Q[NF];
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-            P0[f] = *reinterpret_cast<const uint4*>(st + rdp[f][0]);
-            Q[f] = *reinterpret_cast<const uint4*>(st + rdq[f]);
-        }
-#pragma unroll
-        for (int f = 0; f < NF; ++f) P1[f] = *reinterpret_cast<const uint4*>(st + rdp[f][1]);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v8i op[NF];
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                const uint4 p = ks ? P1[f] : P0[f];
-                op[f] = v8i{(int)p.x, (int)p.y, (int)p.z, (int)p.w, (int)(ks ? Q[f].z : Q[f].x),
-                            (int)(ks ? Q[f].w : Q[f].y), 0, 0};
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(op[i], op[TM + j], acc[i][j], 3, 3,
-                                                                                 0, 0, 0, 0);
-        }
+        step(s, 0, false);
+        step(s, 1, false);
     }
 
     const int tw = t0 + wm * TM * 32, nw = n0 + wn * TN * 32;
@@ -271,24 +302,11 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
                 }
         }
 
-    // fp16 outlier stages: 32 columns each, two matrix steps of 16
+    // fp16 outlier stages: 32 columns each, two matrix steps of 16 (plane P geometry; the 8 bytes read
+    // from the plane Q region are ignored)
     for (; s < nk; ++s) {
-        stage_sync(s);
-        const uint8_t* st = lds + (s % NST) * ST_BYTES;
-        uint4 F[2][NF];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int f = 0; f < NF; ++f) F[ks][f] = *reinterpret_cast<const uint4*>(st + rdp[f][ks]);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, F[ks][i]),
-                                                                       __builtin_bit_cast(v8h, F[ks][TM + j]),
-                                                                       acc[i][j], 0, 0, 0);
+        step(s, 0, true);
+        step(s, 1, true);
     }
 
     wait_vm<0>();                          // drain the look-ahead DMA before the wave ends
