@@ -256,40 +256,40 @@ int quik_linear_w4a8(const void *x, int T, int K, int ldx,
  * columns stays below 2^24, so the fp32 accumulators of the matrix instruction hold the
  * integer results exactly (checked against the INT32 reference by quik_int_gemm_fp6).
  *
- * "FP6 rows": the K_b columns of a row are padded with zeros to S = ceil(K_b / 128) stages of
- * 128 columns; a stage holds four groups of 32 columns, group q = 2 * ks + g.  A group is a
- * 192-bit little-endian string (column j of the group in bits [6j, 6j+6)) = dwords d0 .. d5.
- * d0 .. d3 of stage s, group q sit at byte 64 s + 16 q of the row (plane P, 64 S bytes); d4, d5
- * sit at byte 64 S + 32 s + 16 g + 8 ks (plane Q).  quik_fp6_row_bytes(K_b) = 96 S is the row
- * length; the row pitches ld6 / ldw6 must be multiples of 16 bytes and at least that.
+ * "FP6 panels": the K_b columns of a matrix with R rows are padded with zeros to
+ * S = ceil(K_b / 128) stages of 128 columns and stored stage by stage: stage s of row r is the
+ * 96-byte block at byte (s * R + r) * 96 of the buffer (S * R * 96 bytes, 16-byte aligned;
+ * quik_fp6_row_bytes(K_b) = 96 S).  A stage holds four groups of 32 columns, group q = 2 * ks + g.
+ * A group is a 192-bit little-endian string (column j of the group in bits [6j, 6j+6)) = dwords
+ * d0 .. d5; d0 .. d3 of group q sit at byte 16 q of the block, d4, d5 at byte 64 + 16 g + 8 ks.
  *
  *  quik_weight_pack_fp6   offline: packed signed 4-bit weights w_q [N, ldw] (weight nibble
- *                         order of quik.h, ldw >= K_b/2, K_b even) -> FP6 rows w6 [N, ldw6].
+ *                         order of quik.h, ldw >= K_b/2, K_b even) -> FP6 panels w6 (R = N).
  *                         w_scale, w_reduced, w_out stay as for bits = 4 (no code sums).
- *  quik_quantize_fp6      quik_quantize(bits = 4) with the packed output as FP6 rows
- *                         xq6 [T, ld6]; scale, zero, x_out as there; K <= 16384.
- *  quik_gemm_dequant_fp6  quik_gemm_dequant for FP6 rows.
+ *  quik_quantize_fp6      quik_quantize(bits = 4) with the packed output as FP6 panels xq6
+ *                         (R = T); scale, zero, x_out as there; K <= 16384.
+ *  quik_gemm_dequant_fp6  quik_gemm_dequant for FP6 panels.
  *  quik_int_gemm_fp6      acc[t,n] = sum_k q[t,k] * w[n,k] as INT32 (test hook).
  *  quik_linear_fp6        quik_quantize_fp6 + quik_gemm_dequant_fp6 on one stream; workspace of
  *                         quik_workspace_bytes_fp6(T, K, N, n_out) bytes, 256-byte aligned.
  * All pointers are DEVICE pointers (16-byte aligned where the integer forms require it); error
- * behaviour as for the integer forms.
+ * behaviour as for the integer forms; additionally QUIK_EUNSUPPORTED if one stage of all rows
+ * (max(T, N) * 96 S bytes in total) reaches 4 GB.
  */
 int quik_fp6_row_bytes(int K_b);
 size_t quik_workspace_bytes_fp6(int T, int K, int N, int n_out);
-int quik_weight_pack_fp6(const void *w_q, int ldw, int N, int K_b, void *w6, int ldw6, void *stream);
+int quik_weight_pack_fp6(const void *w_q, int ldw, int N, int K_b, void *w6, void *stream);
 int quik_quantize_fp6(const void *x, int T, int K, int ldx, const int32_t *outlier_idx, int n_out,
-                      void *xq6, int ld6, float *scale, float *zero, void *x_out, int ldo,
-                      void *stream);
-int quik_gemm_dequant_fp6(const void *xq6, int ld6, const float *scale, const float *zero,
+                      void *xq6, float *scale, float *zero, void *x_out, int ldo, void *stream);
+int quik_gemm_dequant_fp6(const void *xq6, const float *scale, const float *zero,
                           const void *x_out, int ldo, int T, int K_b, int n_out,
-                          const void *w6, int ldw6, const void *w_scale, const float *w_reduced,
+                          const void *w6, const void *w_scale, const float *w_reduced,
                           const void *w_out, int ldwo, const void *bias, int N,
                           void *y, int ldy, void *stream);
-int quik_int_gemm_fp6(const void *xq6, int ld6, const void *w6, int ldw6,
-                      int T, int N, int K_b, int32_t *acc, int ldacc, void *stream);
+int quik_int_gemm_fp6(const void *xq6, const void *w6, int T, int N, int K_b,
+                      int32_t *acc, int ldacc, void *stream);
 int quik_linear_fp6(const void *x, int T, int K, int ldx, const int32_t *outlier_idx, int n_out,
-                    const void *w6, int ldw6, const void *w_scale, const float *w_reduced,
+                    const void *w6, const void *w_scale, const float *w_reduced,
                     const void *w_out, int ldwo, const void *bias, int N,
                     void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 

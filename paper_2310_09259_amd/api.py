@@ -69,15 +69,15 @@ def load() -> C.CDLL:
         lib.quik_workspace_bytes_fp6.restype = C.c_size_t
         lib.quik_workspace_bytes_fp6.argtypes = [i, i, i, i]
         lib.quik_weight_pack_fp6.restype = i
-        lib.quik_weight_pack_fp6.argtypes = [vp, i, i, i, vp, i, vp]
+        lib.quik_weight_pack_fp6.argtypes = [vp, i, i, i, vp, vp]
         lib.quik_quantize_fp6.restype = i
-        lib.quik_quantize_fp6.argtypes = [vp, i, i, i, vp, i, vp, i, f, f, vp, i, vp]
+        lib.quik_quantize_fp6.argtypes = [vp, i, i, i, vp, i, vp, f, f, vp, i, vp]
         lib.quik_gemm_dequant_fp6.restype = i
-        lib.quik_gemm_dequant_fp6.argtypes = [vp, i, f, f, vp, i, i, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp]
+        lib.quik_gemm_dequant_fp6.argtypes = [vp, f, f, vp, i, i, i, i, vp, vp, f, vp, i, vp, i, vp, i, vp]
         lib.quik_int_gemm_fp6.restype = i
-        lib.quik_int_gemm_fp6.argtypes = [vp, i, vp, i, i, i, i, vp, i, vp]
+        lib.quik_int_gemm_fp6.argtypes = [vp, vp, i, i, i, vp, i, vp]
         lib.quik_linear_fp6.restype = i
-        lib.quik_linear_fp6.argtypes = [vp, i, i, i, vp, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
+        lib.quik_linear_fp6.argtypes = [vp, i, i, i, vp, i, vp, vp, f, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
         lib.quik_check_outlier_idx_host.restype = i
         lib.quik_check_outlier_idx_host.argtypes = [vp, i, i]
         _lib = lib
@@ -357,18 +357,17 @@ def quik_workspace_bytes_fp6(T: int, K: int, N: int, n_out: int) -> int:
 
 
 def quik_weight_pack_fp6(w_q, K_b: int):
-    """packed signed 4-bit weights uint8 [N, ldw] -> FP6 rows uint8 [N, quik_fp6_row_bytes(K_b)]."""
+    """packed signed 4-bit weights uint8 [N, ldw] -> FP6 panels uint8 [stages, N, 96]."""
     w_q = _dev(w_q, torch.uint8, "w_q")
     N = w_q.shape[0]
-    ld6 = quik_fp6_row_bytes(K_b)
-    w6 = torch.empty((N, ld6), dtype=torch.uint8, device=w_q.device)
-    rc = load().quik_weight_pack_fp6(_ptr(w_q), w_q.stride(0), N, K_b, _ptr(w6), w6.stride(0), _stream())
+    w6 = torch.empty((quik_fp6_row_bytes(K_b) // 96, N, 96), dtype=torch.uint8, device=w_q.device)
+    rc = load().quik_weight_pack_fp6(_ptr(w_q), w_q.stride(0), N, K_b, _ptr(w6), _stream())
     _check(rc, "quik_weight_pack_fp6")
     return w6
 
 
 def quik_quantize_fp6(x, outlier_idx, out=None):
-    """x fp16 [T,K] -> (xq6 uint8 [T,ld6], scale f32 [T], zero f32 [T], x_out f16 [T,n_out])."""
+    """x fp16 [T,K] -> (xq6 uint8 [stages,T,96], scale f32 [T], zero f32 [T], x_out f16 [T,n_out])."""
     x = _dev(x, torch.float16, "x")
     T, K = x.shape
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
@@ -378,24 +377,24 @@ def quik_quantize_fp6(x, outlier_idx, out=None):
     if ld6 <= 0:
         raise QuikError(-1, "quik_fp6_row_bytes")
     if out is None:
-        xq6 = torch.empty((T, ld6), dtype=torch.uint8, device=x.device)
+        xq6 = torch.empty((ld6 // 96, T, 96), dtype=torch.uint8, device=x.device)
         scale = torch.empty(T, dtype=torch.float32, device=x.device)
         zero = torch.empty(T, dtype=torch.float32, device=x.device)
         x_out = torch.empty((T, n_out), dtype=torch.float16, device=x.device)
     else:
         xq6, scale, zero, x_out = out
     rc = load().quik_quantize_fp6(_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out,
-                                  _ptr(xq6), xq6.stride(0), _ptr(scale), _ptr(zero),
+                                  _ptr(xq6), _ptr(scale), _ptr(zero),
                                   _ptr(x_out) if n_out else None, x_out.stride(0) if n_out else 0, _stream())
     _check(rc, "quik_quantize_fp6")
     return xq6, scale, zero, x_out
 
 
 def _gemm_dequant_fp6_args(xq6, scale, zero, x_out, K_b, w6, w_scale, w_reduced, w_out, bias, y):
-    T, N = xq6.shape[0], w6.shape[0]
+    T, N = xq6.shape[1], w6.shape[1]
     n_out = 0 if x_out is None else int(x_out.shape[1])
-    return (_ptr(xq6), xq6.stride(0), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
-            x_out.stride(0) if n_out else 0, T, K_b, n_out, _ptr(w6), w6.stride(0), _ptr(w_scale), _ptr(w_reduced),
+    return (_ptr(xq6), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
+            x_out.stride(0) if n_out else 0, T, K_b, n_out, _ptr(w6), _ptr(w_scale), _ptr(w_reduced),
             _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0),
             _stream())
 
@@ -403,7 +402,7 @@ def _gemm_dequant_fp6_args(xq6, scale, zero, x_out, K_b, w6, w_scale, w_reduced,
 def quik_gemm_dequant_fp6(xq6, scale, zero, x_out, K_b: int, w6, w_scale, w_reduced, w_out, bias=None, out=None):
     xq6 = _dev(xq6, torch.uint8, "xq6")
     w6 = _dev(w6, torch.uint8, "w6")
-    y = out if out is not None else torch.empty((xq6.shape[0], w6.shape[0]), dtype=torch.float16, device=xq6.device)
+    y = out if out is not None else torch.empty((xq6.shape[1], w6.shape[1]), dtype=torch.float16, device=xq6.device)
     rc = load().quik_gemm_dequant_fp6(*_gemm_dequant_fp6_args(xq6, scale, zero, x_out, K_b, w6, w_scale, w_reduced,
                                                               w_out, bias, y))
     _check(rc, "quik_gemm_dequant_fp6")
@@ -423,7 +422,7 @@ def prepare_quantize_fp6(x, outlier_idx, out):
     T, K = x.shape
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
     xq6, scale, zero, x_out = out
-    args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(xq6), xq6.stride(0),
+    args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(xq6),
             _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None, x_out.stride(0) if n_out else 0, _stream())
     return _prepared(load().quik_quantize_fp6, "quik_quantize_fp6", args, (x, outlier_idx, out))
 
@@ -431,19 +430,18 @@ def prepare_quantize_fp6(x, outlier_idx, out):
 def quik_int_gemm_fp6(xq6, w6, K_b: int):
     xq6 = _dev(xq6, torch.uint8, "xq6")
     w6 = _dev(w6, torch.uint8, "w6")
-    T, N = xq6.shape[0], w6.shape[0]
+    T, N = xq6.shape[1], w6.shape[1]
     acc = torch.empty((T, N), dtype=torch.int32, device=xq6.device)
-    rc = load().quik_int_gemm_fp6(_ptr(xq6), xq6.stride(0), _ptr(w6), w6.stride(0), T, N, K_b, _ptr(acc),
-                                  acc.stride(0), _stream())
+    rc = load().quik_int_gemm_fp6(_ptr(xq6), _ptr(w6), T, N, K_b, _ptr(acc), acc.stride(0), _stream())
     _check(rc, "quik_int_gemm_fp6")
     return acc
 
 
 def _linear_fp6_args(x, outlier_idx, w6, w_scale, w_reduced, w_out, bias, y, workspace):
     T, K = x.shape
-    N = w6.shape[0]
+    N = w6.shape[1]
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
-    return (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(w6), w6.stride(0),
+    return (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(w6),
             _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0,
             _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace), workspace.numel(), _stream())
 
@@ -452,7 +450,7 @@ def _linear_fp6_buffers(x, outlier_idx, w6, out, workspace):
     x = _dev(x, torch.float16, "x")
     w6 = _dev(w6, torch.uint8, "w6")
     T, K = x.shape
-    N = w6.shape[0]
+    N = w6.shape[1]
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
     need = quik_workspace_bytes_fp6(T, K, N, n_out)
     if workspace is None:

@@ -361,46 +361,43 @@ int quik_fp6_row_bytes(int K_b) {
 size_t quik_workspace_bytes_fp6(int T, int K, int N, int n_out) {
     (void)N;
     if (T <= 0 || K <= 0 || n_out < 0 || n_out >= K) return 0;
-    const int ld6 = quik_fp6_row_bytes(K - n_out);
-    if (ld6 <= 0) return 0;
-    return up256((size_t)T * ld6) + 2 * up256((size_t)T * sizeof(float)) + up256((size_t)T * (n_out ? n_out : 1) * 2);
+    const int rb = quik_fp6_row_bytes(K - n_out);
+    if (rb <= 0) return 0;
+    return up256((size_t)T * rb) + 2 * up256((size_t)T * sizeof(float)) + up256((size_t)T * (n_out ? n_out : 1) * 2);
 }
 
-int quik_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, int ld6, void* stream) {
+int quik_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, void* stream) {
     if (N <= 0 || K_b <= 0 || K_b % 2 || ldw < K_b / 2) return QUIK_EINVAL;
     if (!w_q || !w6) return QUIK_ENULL;
     if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
-    if (ld6 < quik_fp6_row_bytes(K_b)) return QUIK_EINVAL;
-    if (ld6 % 16 || !aligned16(w6)) return QUIK_EALIGN;
-    return quik::launch_weight_pack_fp6(w_q, ldw, N, K_b, w6, ld6, static_cast<hipStream_t>(stream)) == hipSuccess
+    if (!aligned16(w6)) return QUIK_EALIGN;
+    return quik::launch_weight_pack_fp6(w_q, ldw, N, K_b, w6, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUIK_OK
                : QUIK_ELAUNCH;
 }
 
 int quik_quantize_fp6(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out, void* xq6,
-                      int ld6, float* scale, float* zero, void* x_out, int ldo, void* stream) {
-    // same argument rules as the 4-bit integer form, except for the row pitch of the packed output
+                      float* scale, float* zero, void* x_out, int ldo, void* stream) {
+    // same argument rules as the 4-bit integer form, except for the layout of the packed output
     int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, 4, xq6, 16 * ((K + 15) / 16), scale, zero, x_out, ldo);
     if (rc != QUIK_OK) return rc;
     if (K > 16384) return QUIK_EUNSUPPORTED;
-    if (ld6 < quik_fp6_row_bytes(K - n_out)) return QUIK_EINVAL;
-    if (ld6 % 16) return QUIK_EALIGN;
-    quik::QuantizeArgs a{x, T, K, ldx, outlier_idx, n_out, 4, xq6, ld6, scale, zero, x_out, ldo, nullptr, 1};
+    quik::QuantizeArgs a{x, T, K, ldx, outlier_idx, n_out, 4, xq6, quik_fp6_row_bytes(K - n_out), scale, zero,
+                         x_out, ldo, nullptr, 1};
     return quik::launch_quantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK : QUIK_ELAUNCH;
 }
 
 namespace {
-int check_gemm_fp6(const void* xq6, int ld6, const void* x_out, int ldo, int T, int K_b, int n_out,
-                   const void* w6, int ldw6, const void* w_out, int ldwo, int N) {
+int check_gemm_fp6(const void* xq6, const void* x_out, int ldo, int T, int K_b, int n_out, const void* w6,
+                   const void* w_out, int ldwo, int N) {
     if (T <= 0 || N <= 0 || K_b <= 0 || n_out < 0) return QUIK_EINVAL;
     if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
-    const int need = quik_fp6_row_bytes(K_b);
-    if (ld6 < need || ldw6 < need) return QUIK_EINVAL;
+    // a stage of all rows must stay below 4 GB (32-bit offsets inside the copy descriptors)
+    if ((uint64_t)quik_fp6_row_bytes(K_b) * (uint64_t)(T > N ? T : N) >= (1ull << 32)) return QUIK_EUNSUPPORTED;
     if (n_out > 0 && (ldo < n_out || ldwo < n_out)) return QUIK_EINVAL;
     if (!xq6 || !w6) return QUIK_ENULL;
     if (n_out > 0 && (!x_out || !w_out)) return QUIK_ENULL;
     if (n_out % 8) return QUIK_EUNSUPPORTED;
-    if (ld6 % 16 || ldw6 % 16) return QUIK_EALIGN;
     if (n_out > 0 && (ldo % 8 || ldwo % 8)) return QUIK_EALIGN;
     if (!aligned16(xq6) || !aligned16(w6)) return QUIK_EALIGN;
     if (n_out > 0 && (!aligned16(x_out) || !aligned16(w_out))) return QUIK_EALIGN;
@@ -408,64 +405,62 @@ int check_gemm_fp6(const void* xq6, int ld6, const void* x_out, int ldo, int T, 
 }
 }  // namespace
 
-int quik_gemm_dequant_fp6(const void* xq6, int ld6, const float* scale, const float* zero, const void* x_out,
-                          int ldo, int T, int K_b, int n_out, const void* w6, int ldw6, const void* w_scale,
-                          const float* w_reduced, const void* w_out, int ldwo, const void* bias, int N, void* y,
-                          int ldy, void* stream) {
-    int rc = check_gemm_fp6(xq6, ld6, x_out, ldo, T, K_b, n_out, w6, ldw6, w_out, ldwo, N);
+int quik_gemm_dequant_fp6(const void* xq6, const float* scale, const float* zero, const void* x_out, int ldo, int T,
+                          int K_b, int n_out, const void* w6, const void* w_scale, const float* w_reduced,
+                          const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy, void* stream) {
+    int rc = check_gemm_fp6(xq6, x_out, ldo, T, K_b, n_out, w6, w_out, ldwo, N);
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!scale || !zero || !w_scale || !w_reduced || !y) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
     quik::GemmArgs a{};
-    a.xq = xq6; a.ldq = ld6; a.scale = scale; a.zero = zero; a.x_out = x_out; a.ldo = ldo;
+    a.xq = xq6; a.scale = scale; a.zero = zero; a.x_out = x_out; a.ldo = ldo;
     a.T = T; a.K_b = K_b; a.n_out = n_out; a.bits = 4;
-    a.w_q = w6; a.ldw = ldw6; a.w_scale = w_scale; a.w_reduced = w_reduced;
+    a.w_q = w6; a.w_scale = w_scale; a.w_reduced = w_reduced;
     a.w_out = w_out; a.ldwo = ldwo; a.bias = bias; a.N = N;
     a.y = y; a.ldy = ldy; a.acc = nullptr; a.ldacc = 0;
     return quik::launch_gemm_fp6(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK : QUIK_ELAUNCH;
 }
 
-int quik_int_gemm_fp6(const void* xq6, int ld6, const void* w6, int ldw6, int T, int N, int K_b, int32_t* acc,
-                      int ldacc, void* stream) {
-    int rc = check_gemm_fp6(xq6, ld6, nullptr, 0, T, K_b, 0, w6, ldw6, nullptr, 0, N);
+int quik_int_gemm_fp6(const void* xq6, const void* w6, int T, int N, int K_b, int32_t* acc, int ldacc,
+                      void* stream) {
+    int rc = check_gemm_fp6(xq6, nullptr, 0, T, K_b, 0, w6, nullptr, 0, N);
     if (rc != QUIK_OK) return rc;
     if (ldacc < N) return QUIK_EINVAL;
     if (!acc) return QUIK_ENULL;
     quik::GemmArgs a{};
-    a.xq = xq6; a.ldq = ld6; a.T = T; a.K_b = K_b; a.n_out = 0; a.bits = 4;
-    a.w_q = w6; a.ldw = ldw6; a.N = N; a.y = nullptr; a.acc = acc; a.ldacc = ldacc;
+    a.xq = xq6; a.T = T; a.K_b = K_b; a.n_out = 0; a.bits = 4;
+    a.w_q = w6; a.N = N; a.y = nullptr; a.acc = acc; a.ldacc = ldacc;
     return quik::launch_gemm_fp6(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK : QUIK_ELAUNCH;
 }
 
 int quik_linear_fp6(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out, const void* w6,
-                    int ldw6, const void* w_scale, const float* w_reduced, const void* w_out, int ldwo,
-                    const void* bias, int N, void* y, int ldy, void* workspace, size_t workspace_bytes,
-                    void* stream) {
+                    const void* w_scale, const float* w_reduced, const void* w_out, int ldwo, const void* bias,
+                    int N, void* y, int ldy, void* workspace, size_t workspace_bytes, void* stream) {
     const size_t need = quik_workspace_bytes_fp6(T, K, N, n_out);
     if (need == 0) return QUIK_EINVAL;
     if (!workspace) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUIK_EALIGN;
     if (workspace_bytes < need) return QUIK_EWORKSPACE;
-    const int K_b = K - n_out, ld6 = quik_fp6_row_bytes(K_b);
+    const int K_b = K - n_out, rb = quik_fp6_row_bytes(K_b);
     uint8_t* base = static_cast<uint8_t*>(workspace);
     void* xq6 = base;
-    float* scale = reinterpret_cast<float*>(base + up256((size_t)T * ld6));
+    float* scale = reinterpret_cast<float*>(base + up256((size_t)T * rb));
     float* zero = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(scale) + up256((size_t)T * sizeof(float)));
     void* x_out = reinterpret_cast<uint8_t*>(zero) + up256((size_t)T * sizeof(float));
     // validate both stages before anything is enqueued
     int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, 4, xq6, 16 * ((K + 15) / 16), scale, zero, x_out, n_out);
     if (rc != QUIK_OK) return rc;
     if (K > 16384) return QUIK_EUNSUPPORTED;
-    rc = check_gemm_fp6(xq6, ld6, x_out, n_out, T, K_b, n_out, w6, ldw6, w_out, ldwo, N);
+    rc = check_gemm_fp6(xq6, x_out, n_out, T, K_b, n_out, w6, w_out, ldwo, N);
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
-    rc = quik_quantize_fp6(x, T, K, ldx, outlier_idx, n_out, xq6, ld6, scale, zero, x_out, n_out, stream);
+    rc = quik_quantize_fp6(x, T, K, ldx, outlier_idx, n_out, xq6, scale, zero, x_out, n_out, stream);
     if (rc != QUIK_OK) return rc;
-    return quik_gemm_dequant_fp6(xq6, ld6, scale, zero, x_out, n_out, T, K_b, n_out, w6, ldw6, w_scale, w_reduced,
-                                 w_out, ldwo, bias, N, y, ldy, stream);
+    return quik_gemm_dequant_fp6(xq6, scale, zero, x_out, n_out, T, K_b, n_out, w6, w_scale, w_reduced, w_out, ldwo,
+                                 bias, N, y, ldy, stream);
 }
 
 int quik_check_outlier_idx_host(const int32_t* idx, int n_out, int K) {

@@ -7,14 +7,15 @@
 // below 2^24, so an fp32 accumulator holds the integer result exactly.  gfx950 multiplies FP6 operands
 // at twice its int8 rate (v_mfma_f32_32x32x64_f8f6f4), and the operands need no widening in registers.
 //
-// Row layout ("planes").  The columns of a row are padded with zero codes to S stages of 128 columns.
-// A stage holds four groups of 32 columns, group index q = 2 * ks + g (ks: which of the stage's two
-// 64-column matrix steps, g: which half of the wave's lanes consumes it).  A group is 32 x 6 bits =
-// six dwords d0 .. d5, column j of the group in bits [6j, 6j + 6) of that 192-bit little-endian string:
-// exactly the register image one lane hands to the matrix instruction.  d0 .. d3 of all groups form
-// plane P (16 bytes per group, stage s at byte 64 s, group q at + 16 q); d4, d5 form plane Q, which
-// follows plane P at byte 64 S (stage s at + 32 s, the group (ks, g) at + 16 g + 8 ks), so that a lane
-// fetches its d4, d5 of both steps of a stage with one 16-byte read.  Row pitch >= 96 S bytes.
+// Operand layout ("panels").  The columns of a matrix with R rows are padded with zero codes to S
+// stages of 128 columns, and the matrix is stored stage by stage: stage s of row r is the 96-byte block
+// at byte (s * R + r) * 96, so the rows of an output tile are one contiguous run per stage (whole cache
+// lines for the copy engine).  A stage holds four groups of 32 columns, group index q = 2 * ks + g
+// (ks: which of the stage's two 64-column matrix steps, g: which half of the wave's lanes consumes it).
+// A group is 32 x 6 bits = six dwords d0 .. d5, column j of the group in bits [6j, 6j + 6) of that
+// 192-bit little-endian string: exactly the register image one lane hands to the matrix instruction.
+// d0 .. d3 of group q sit at byte 16 q of the block; d4, d5 of group (ks, g) at byte 64 + 16 g + 8 ks, so
+// that a lane's d4, d5 of both steps are adjacent.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -24,12 +25,12 @@ namespace fp6 {
 
 // stages of 128 columns that cover K_b columns
 __host__ __device__ inline int stages(int K_b) { return (K_b + 127) >> 7; }
-// bytes of a row: planes P and Q
+// bytes of one row summed over its stages (a matrix of R rows takes R times this)
 __host__ __device__ inline int row_bytes(int K_b) { return 96 * stages(K_b); }
-// index (in dwords from the row start) of dword d (0 .. 5) of group G of a row with S stages
-__host__ __device__ inline int dword_index(int S, int G, int d) {
-    const int s = G >> 2, q = G & 3, ks = q >> 1, g = q & 1;
-    return d < 4 ? 16 * s + 4 * q + d : 16 * S + 8 * s + 4 * g + 2 * ks + (d - 4);
+// index (in dwords, inside the 96-byte block of its stage) of dword d (0 .. 5) of group q (0 .. 3)
+__host__ __device__ inline int block_dword(int q, int d) {
+    const int ks = q >> 1, g = q & 1;
+    return d < 4 ? 4 * q + d : 16 + 4 * g + 2 * ks + (d - 4);
 }
 
 // E3M2 patterns of u - 8 for the unsigned codes u = 0 .. 7 (values -8 .. -1) and u = 8 .. 15 (0 .. 7)

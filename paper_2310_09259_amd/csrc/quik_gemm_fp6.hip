@@ -5,15 +5,17 @@
 // K loop is DMA -> LDS -> registers -> v_mfma_f32_32x32x64_f8f6f4 with no widening work at all, at
 // twice the int8 rate of the matrix pipe.
 //
-// A workgroup of WM x WN waves owns a BM x BN output tile.  A stage is 128 columns: per operand row
-// 64 bytes of plane P and 32 bytes of plane Q, copied global -> LDS by 16-byte-per-lane DMA
-// instructions (16 rows of P or 32 rows of Q per instruction), three stage buffers.  Lane (row l%32,
-// half g = l/32) reads 16 bytes of P per 64-column step and 16 bytes of Q per stage; the 16-byte slots
-// are XOR-swizzled so that the rows one read instruction touches fall into distinct banks.  The fp16
-// outlier columns run through the same ring as stages of 32 columns (64 bytes per row: the geometry
-// of plane P), with the dequantized integer part as the C operand of v_mfma_f32_32x32x16_f16, whose
-// accumulator layout is the same.  Rows beyond T / N and columns beyond the row end are out of range
-// for the buffer descriptor or masked by hand and arrive as zeros (the E3M2 pattern of 0).
+// A workgroup of WM x WN waves owns a BM x BN output tile.  A stage is 128 columns = one 96-byte block per
+// operand row; the operands are stored stage by stage (quik_fp6_device.h), so the tile's rows of a stage
+// are one contiguous run of BM * 96 (BN * 96) bytes that 16-byte-per-lane DMA instructions copy global ->
+// LDS as it is, whole cache lines per instruction; three stage buffers.  Lane (row l%32, half g = l/32)
+// reads, per 64-column step, 16 bytes (dwords 0..3 of its group) and 8 bytes (dwords 4, 5); the 16-byte
+// pieces of a block are exchanged pairwise in every second group of eight rows (by the DMA's choice of
+// source piece) so that the rows one read instruction touches fall into distinct banks.  The fp16
+// outlier columns run through the same ring as stages of 32 columns (64-byte rows, 16 rows per DMA
+// instruction), with the dequantized integer part as the C operand of v_mfma_f32_32x32x16_f16, whose
+// accumulator layout is the same.  Rows beyond T / N are out of range for the per-stage buffer
+// descriptors and arrive as zeros (the E3M2 pattern of 0); columns beyond K_b are zero padding.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -30,26 +32,36 @@ using namespace gemm_dev;
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ int swz_p(int r) { return (r >> 2) & 3; }   // 64-byte rows, four slots
-__device__ __forceinline__ int swz_q(int r) { return (r >> 3) & 1; }   // 32-byte rows, two slots
+__device__ __forceinline__ int swz_f(int r) { return (r >> 2) & 3; }   // fp16 stages: 64-byte rows, four pieces
+__device__ __forceinline__ int swz_6(int r) { return (r >> 3) & 1; }   // FP6 stages: 96-byte rows, pieces paired
+
+// descriptor r moved forward by `bytes`
+__device__ __forceinline__ v4i advance(v4i r, uint32_t bytes) {
+    const uint64_t base = (((uint64_t)(uint32_t)r[1]) << 32 | (uint32_t)r[0]) + bytes;
+    r[0] = (int)(uint32_t)base;
+    r[1] = (int)(uint32_t)(base >> 32);
+    return r;
+}
 
 // MODE 0: fused epilogue, fp16 output; MODE 1: the integer accumulators as INT32.
 template <int BM, int BN, int WM, int WN, int GM, int MODE>
 __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
+    // claim the whole register budget of the launch bounds, so that the highest allocated register is
+    // never a live one (see the note in the row-quantization kernel)
+    asm volatile("" ::: "v255");
     constexpr int NWAVES = WM * WN, NT = NWAVES * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NF = TM + TN;
     constexpr int NST = 3;
-    constexpr int AP = BM * 64, AQ = BM * 32, BP = BN * 64, BQ = BN * 32;
-    constexpr int OFF_AQ = AP, OFF_BP = AP + AQ, OFF_BQ = AP + AQ + BP, ST_BYTES = AP + AQ + BP + BQ;
-    // DMA instructions of a stage: P planes 16 rows each, Q planes 32 rows each
-    constexpr int N_AP = BM / 16, N_AQ = BM / 32, N_BP = BN / 16, N_BQ = BN / 32;
-    // DMA slots of a wave per stage, in this order: plane P of A, plane Q of A, plane P of B, plane Q of
-    // B; instruction i = wave + NWAVES * (slot within its plane); a slot whose i does not exist is
-    // issued empty so that every wave counts the same number of DMA instructions
-    constexpr int S_AP = (N_AP + NWAVES - 1) / NWAVES, S_AQ = (N_AQ + NWAVES - 1) / NWAVES;
-    constexpr int S_BP = (N_BP + NWAVES - 1) / NWAVES, S_BQ = (N_BQ + NWAVES - 1) / NWAVES;
-    constexpr int LPS = S_AP + S_AQ + S_BP + S_BQ;
+    constexpr int A_BYTES = BM * 96, B_BYTES = BN * 96, ST_BYTES = A_BYTES + B_BYTES;
+    // DMA instructions of a stage (1 KB each): FP6 stages BM * 96 / 1024 and BN * 96 / 1024, fp16 stages
+    // BM / 16 and BN / 16.  Slots of a wave per stage: S_A for A, then S_B for B; instruction
+    // i = wave + NWAVES * (slot within its operand); a slot whose i does not exist is issued empty so
+    // that every wave counts the same number of DMA instructions.
+    constexpr int N_A = BM * 96 / 1024, N_B = BN * 96 / 1024, N_AF = BM / 16, N_BF = BN / 16;
+    constexpr int S_A = (N_A + NWAVES - 1) / NWAVES, S_B = (N_B + NWAVES - 1) / NWAVES;
+    constexpr int LPS = S_A + S_B;
+    static_assert(BM % 32 == 0 && BN % 32 == 0 && N_AF <= S_A * NWAVES && N_BF <= S_B * NWAVES, "slot count");
     static_assert((NST - 1) * LPS < 64, "vmcnt range");
     constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
 
@@ -84,49 +96,58 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
     const int nk_fp = RAW ? 0 : (fp_bytes + 63) / 64;
     const int nk = nk_int + nk_fp;
     const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
-    const int ld_a = a.ldq, ld_b = a.ldw;                 // values, so that nothing takes the address of an argument
+    const int T_ = a.T, N_ = a.N;                         // values, so that nothing takes the address of an argument
 
-    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * a.ldq, (size_t)(a.T - t0) * a.ldq);
-    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * a.ldw, (size_t)(a.N - n0) * a.ldw);
+    // stage 0 of the tile's rows; stage s lies s * T * 96 (s * N * 96) bytes further on
+    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * 96, (size_t)(a.T - t0) * 96);
+    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * 96, (size_t)(a.N - n0) * 96);
     const v4i rAf = make_rsrc(a.n_out ? (const uint8_t*)a.x_out + (size_t)t0 * lda_fp : (const uint8_t*)a.xq,
                               a.n_out ? (size_t)(a.T - t0) * lda_fp : 0);
     const v4i rBf = make_rsrc(a.n_out ? (const uint8_t*)a.w_out + (size_t)n0 * ldb_fp : (const uint8_t*)a.xq,
                               a.n_out ? (size_t)(a.N - n0) * ldb_fp : 0);
     const uint32_t lds_base = lds_addr(lds);
 
-    // Per-lane parts of the DMA source offsets.  A P-plane instruction covers 16 rows (lane / 4) and the
-    // four 16-byte slots of a 64-byte stage row, a Q-plane instruction 32 rows (lane / 2) and two slots;
-    // the swizzle of a row depends only on lane bits 4, 5 because 16 and 32 rows are whole swizzle periods.
-    const int colP = ((lane & 3) ^ ((lane >> 4) & 3)) * 16, colQ = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;
-    const uint32_t vo_ap = (uint32_t)((lane >> 2) * ld_a + colP), vo_aq = (uint32_t)((lane >> 1) * ld_a + 64 * S + colQ);
-    const uint32_t vo_bp = (uint32_t)((lane >> 2) * ld_b + colP), vo_bq = (uint32_t)((lane >> 1) * ld_b + 64 * S + colQ);
-    const uint32_t vo_af = (uint32_t)((lane >> 2) * lda_fp + colP), vo_bf = (uint32_t)((lane >> 2) * ldb_fp + colP);
+    // Per-lane DMA source offsets.  FP6 stage, slot q: lane handles the 16-byte piece p = 64 i + lane of the
+    // tile's run, i.e. piece p % 6 of row p / 6, and fetches the piece the swizzle assigns to that place.
+    uint32_t vo_a[S_A], vo_b[S_B];
+#pragma unroll
+    for (int q = 0; q < S_A; ++q) {
+        const int pc = 64 * (wave_u + NWAVES * q) + lane, row = pc / 6, c = pc - 6 * row;
+        vo_a[q] = (uint32_t)(row * 96 + ((c ^ swz_6(row)) << 4));
+    }
+#pragma unroll
+    for (int q = 0; q < S_B; ++q) {
+        const int pc = 64 * (wave_u + NWAVES * q) + lane, row = pc / 6, c = pc - 6 * row;
+        vo_b[q] = (uint32_t)(row * 96 + ((c ^ swz_6(row)) << 4));
+    }
+    // fp16 stage: 16 rows (lane / 4) x four pieces of a 64-byte stage row per instruction
+    const int colF = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
+    const uint32_t vo_af = (uint32_t)((lane >> 2) * lda_fp + colF), vo_bf = (uint32_t)((lane >> 2) * ldb_fp + colF);
     // DMA slot j of stage s (int part, fp16 part, or past the end: every lane out of range)
     auto issue_one = [&](int s, int j) __attribute__((always_inline)) {
-        const int kind = j < S_AP ? 0 : j < S_AP + S_AQ ? 1 : j < S_AP + S_AQ + S_BP ? 2 : 3;
-        const int seq = kind == 0 ? j : kind == 1 ? j - S_AP : kind == 2 ? j - S_AP - S_AQ : j - S_AP - S_AQ - S_BP;
-        const bool isq = kind & 1, isb = kind >= 2;
-        const int n_kind = kind == 0 ? N_AP : kind == 1 ? N_AQ : kind == 2 ? N_BP : N_BQ;
-        const int off = kind == 0 ? 0 : kind == 1 ? OFF_AQ : kind == 2 ? OFF_BP : OFF_BQ;
-        const int i = wave_u + NWAVES * seq;                    // instruction of this plane (wave-uniform)
-        const bool exists = i < n_kind;
+        const bool isb = j >= S_A;
+        const int seq = isb ? j - S_A : j;
+        const int i = wave_u + NWAVES * seq;                    // instruction of this operand (wave-uniform)
         const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
         const bool fp = s >= nk_int;
-        const bool live = s < nk && exists;
-        const int rows = isq ? 32 : 16;
-        uint32_t vo = kOob, so = 0;
-        if (live) {
-            if (!fp) {
-                vo = (isb ? (isq ? vo_bq : vo_bp) : (isq ? vo_aq : vo_ap)) + (uint32_t)(i * rows * (isb ? ld_b : ld_a));
-                so = (uint32_t)((isq ? 32 : 64) * s);
-            } else if (!isq) {
-                const int c0 = 64 * (s - nk_int);
-                vo = (c0 + colP < fp_bytes) ? (isb ? vo_bf : vo_af) + (uint32_t)(i * 16 * (isb ? ldb_fp : lda_fp) + c0) : kOob;
-            }
+        uint32_t vo = kOob;
+        bool exists;
+        uint32_t dst;
+        if (!fp) {
+            exists = i < (isb ? N_B : N_A);
+            if (s < nk && exists) vo = isb ? vo_b[isb ? seq : 0] : vo_a[isb ? 0 : seq];
+            dst = sb + (isb ? A_BYTES : 0) + i * 1024;
+        } else {
+            exists = i < (isb ? N_BF : N_AF);
+            const int c0 = 64 * (s - nk_int);
+            if (s < nk && exists && c0 + colF < fp_bytes)
+                vo = (isb ? vo_bf : vo_af) + (uint32_t)(i * 16 * (isb ? ldb_fp : lda_fp) + c0);
+            dst = sb + (isb ? BM * 64 : 0) + i * 1024;
         }
-        const uint32_t dst = lds_base + (exists ? sb + off + i * 1024 : (uint32_t)DUMMY);
-        if (isb) dma16(fp ? rBf : rB, dst, vo, so);
-        else dma16(fp ? rAf : rA, dst, vo, so);
+        dst = lds_base + (exists ? dst : (uint32_t)DUMMY);
+        if (fp) dma16(isb ? rBf : rAf, dst, vo, 0);
+        else if (isb) dma16(advance(rB, (uint32_t)s * (uint32_t)N_ * 96u), dst, vo, 0);
+        else dma16(advance(rA, (uint32_t)s * (uint32_t)T_ * 96u), dst, vo, 0);
     };
     auto issue = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
@@ -171,23 +192,27 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
         }
     }
 
-    // LDS read addresses of this lane's row of every fragment: plane P slot 2 ks + g (16 bytes),
-    // plane Q slot g, 8 bytes at + 8 ks
-    uint32_t rdp[NF][2], rdq[NF];
+    // LDS read addresses of this lane's row of every fragment.  FP6 stage: piece 2 ks + g of the row's
+    // 96-byte block (16 bytes) and 8 bytes at 64 + 16 g + 8 ks; fp16 stage: piece 2 ks + g of a 64-byte row.
+    uint32_t rdp[NF][2], rdq[NF], rdf[NF][2];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
         const int r = (f < TM) ? (wm * TM * 32 + f * 32 + l32) : (wn * TN * 32 + (f - TM) * 32 + l32);
-        const uint32_t bp = (f < TM ? 0 : OFF_BP) + r * 64, bq = (f < TM ? OFF_AQ : OFF_BQ) + r * 32;
+        const uint32_t b6 = (f < TM ? 0 : A_BYTES) + r * 96, bf = (f < TM ? 0 : BM * 64) + r * 64;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) rdp[f][ks] = bp + (((ks * 2 + g) ^ swz_p(r)) << 4);
-        rdq[f] = bq + ((g ^ swz_q(r)) << 4);
+        for (int ks = 0; ks < 2; ++ks) {
+            rdp[f][ks] = b6 + (((ks * 2 + g) ^ swz_6(r)) << 4);
+            rdf[f][ks] = bf + (((ks * 2 + g) ^ swz_f(r)) << 4);
+        }
+        rdq[f] = b6 + 64 + ((g ^ swz_6(r)) << 4);
     }
     // two fragment sets: the matrix instructions of one 64-column step run on one set while the
     // LDS reads of the next step fill the other
     uint4 FP[2][NF];
     uint2 FQ[2][NF];
     auto read_p = [&](int set, int f, int s, int ks) __attribute__((always_inline)) {
-        FP[set][f] = *reinterpret_cast<const uint4*>(lds + (s % NST) * ST_BYTES + rdp[f][ks]);
+        const uint32_t ad = (s >= nk_int) ? rdf[f][ks] : rdp[f][ks];
+        FP[set][f] = *reinterpret_cast<const uint4*>(lds + (s % NST) * ST_BYTES + ad);
     };
     auto read_q = [&](int set, int f, int s, int ks) __attribute__((always_inline)) {
         FQ[set][f] = *reinterpret_cast<const uint2*>(lds + (s % NST) * ST_BYTES + rdq[f] + 8 * ks);
@@ -369,10 +394,10 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
         }
 }
 
-// Signed 4-bit weights (two per byte, column 2p in the low nibble) -> FP6 planes.  One thread per
+// Signed 4-bit weights (two per byte, column 2p in the low nibble) -> FP6 panels.  One thread per
 // (row, group of 32 columns).  Offline step.
 __global__ __launch_bounds__(256) void weight_pack_fp6_kernel(const uint8_t* __restrict__ w_q, int ldw, int N, int K_b,
-                                                              uint32_t* __restrict__ w6, int ld6_words) {
+                                                              uint32_t* __restrict__ w6) {
     const int S = fp6::stages(K_b);
     const int groups = 4 * S;
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -401,9 +426,9 @@ __global__ __launch_bounds__(256) void weight_pack_fp6_kernel(const uint8_t* __r
     d[3] = (uint32_t)e2;
     d[4] = (uint32_t)(e2 >> 32) | (uint32_t)(e3 << 16);
     d[5] = (uint32_t)(e3 >> 16);
-    uint32_t* row = w6 + (size_t)n * ld6_words;
+    uint32_t* blk = w6 + ((size_t)(G >> 2) * N + n) * 24;         // the row's 96-byte block of this stage
 #pragma unroll
-    for (int i = 0; i < 6; ++i) row[fp6::dword_index(S, G, i)] = d[i];
+    for (int i = 0; i < 6; ++i) blk[fp6::block_dword(G & 3, i)] = d[i];
 }
 
 template <int BM, int BN, int WM, int WN, int GM, int MODE>
@@ -427,11 +452,11 @@ hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream) {
     return a.y ? dispatch6<0>(a, stream) : dispatch6<1>(a, stream);
 }
 
-hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, int ld6, hipStream_t stream) {
+hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, hipStream_t stream) {
     if (N <= 0 || K_b <= 0) return hipSuccess;
     const long total = (long)N * 4 * fp6::stages(K_b);
     hipLaunchKernelGGL(weight_pack_fp6_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                       static_cast<const uint8_t*>(w_q), ldw, N, K_b, static_cast<uint32_t*>(w6), ld6 / 4);
+                       static_cast<const uint8_t*>(w_q), ldw, N, K_b, static_cast<uint32_t*>(w6));
     return hipGetLastError();
 }
 

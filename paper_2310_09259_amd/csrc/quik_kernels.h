@@ -18,7 +18,8 @@ struct QuantizeArgs {
     void* x_out;          // fp16 [T, ldo]
     int ldo;
     int32_t* code_sum;    // [T] sum of the signed codes at even positions (4-bit; may be null)
-    int fp6;              // 1: 4-bit codes written as E3M2 patterns in the plane layout (quik_fp6_device.h)
+    int fp6;              // 1: 4-bit codes written as E3M2 patterns in the panel layout (quik_fp6_device.h);
+                          //    xq is then the [stage][T][96-byte] buffer and ldq = 96 * stages
 };
 
 struct GemmArgs {
@@ -59,9 +60,9 @@ struct WeightReduceArgs {
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
-// FP6 path (quik_gemm_fp6.hip): xq / w_q of GemmArgs are rows in the plane layout, ldq / ldw their pitch
+// FP6 path (quik_gemm_fp6.hip): xq / w_q of GemmArgs are panel buffers [stage][row][96 bytes]; ldq / ldw unused
 hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream);
-hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, int ld6, hipStream_t stream);
+hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, hipStream_t stream);
 
 // unfused stages (fusion ablation)
 hipError_t launch_unfused_quantize(const QuantizeArgs& a, void* x_base, int ldb, float* row_min,

@@ -220,8 +220,9 @@ __device__ __forceinline__ void chunk_codes(const uint32_t (&x)[4], float mn, fl
 }
 
 // K <= TPR * 8 * NCH: the row lives in NCH 128-bit registers per thread.  FP6 (4-bit codes only):
-// the packed row is written as E3M2 patterns in the plane layout of quik_fp6_device.h (ldq is then
-// that layout's row pitch) and no code sum is produced.
+// the packed row is written as E3M2 patterns in the panel layout of quik_fp6_device.h (xq is then the
+// whole [stage][row][96-byte] buffer, ldq the 96 * stages bytes of one row's LDS image) and no code sum
+// is produced.
 template <int BITS, int TPR, int NCH, bool FP6>
 __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kernel(
     const __half* __restrict__ x, int T, int K, int ldx, const int32_t* __restrict__ idx, int n_out,
@@ -251,7 +252,6 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
     const int g = tid / TPR, lt = tid % TPR;
     const int K_b = K - n_out;
     const int ldq_words = ldq >> 2;
-    const int S6 = fp6::stages(K_b);
     // two images per row group, used by alternate rows: a row may start clearing and filling its
     // image while slower waves still write the previous row's image out (one spare 16 bytes behind
     // every image)
@@ -286,7 +286,8 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
             gv[q] = (t < T && cidx[q] >= 0) ? (uint32_t)__half_as_ushort(row[cidx[q]]) : 0u;
     };
 
-    constexpr bool DOUBLE = NCH <= 6;             // second register set for the next row (register budget)
+    // second register set for the next row, where the register budget has room for it
+    constexpr bool DOUBLE = FP6 ? NCH <= 4 : NCH <= 6;
     uint4 ca[NCH], cb[DOUBLE ? NCH : 1];
     uint32_t gva[GJ], gvb[GJ];                    // one register each: packing two would stall on the load
     int rb = blockIdx.x;
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                     for (int i = 0; i < 3; ++i) {
                         uint32_t dd = d0 + i, GG = G;
                         if (dd >= 6u) { dd -= 6u; ++GG; }
-                        if (w3[i]) atomicOr(&stage[fp6::dword_index(S6, (int)GG, (int)dd)], w3[i]);
+                        if (w3[i]) atomicOr(&stage[24u * (GG >> 2) + (uint32_t)fp6::block_dword((int)(GG & 3u), (int)dd)], w3[i]);
                     }
                 } else {
                     esum = __builtin_amdgcn_sad_u8((lo >> pos_even_shift(pos)) & 0x0F0F0F0Fu, 0u, esum);
@@ -428,10 +429,15 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
         // ---- write the packed row (including its zero padding up to ldq); 4-bit rows leave with
         // the two nibbles of every byte swapped: element 2p in the high nibble
         if (valid) {
-            uint4* dst = reinterpret_cast<uint4*>(xq + (size_t)t * ldq);
+            uint4* dst = reinterpret_cast<uint4*>(xq + (FP6 ? (size_t)0 : (size_t)t * ldq));
             const uint4* src = reinterpret_cast<const uint4*>(stage);
             for (int i = lt; i < (ldq >> 4); i += TPR) {
                 uint4 v = src[i];
+                if constexpr (FP6) {                   // piece i of the image = piece i % 6 of stage i / 6
+                    const int st = i / 6, c = i - 6 * st;
+                    dst[((size_t)st * T + t) * 6 + c] = v;
+                    continue;
+                }
                 if constexpr (BITS == 4 && !FP6) {
                     auto sw = [](uint32_t w) { return ((w & 0x0F0F0F0Fu) << 4) | ((w >> 4) & 0x0F0F0F0Fu); };
                     v = make_uint4(sw(v.x), sw(v.y), sw(v.z), sw(v.w));

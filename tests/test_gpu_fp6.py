@@ -1,14 +1,14 @@
 """GPU-vs-oracle parity of the FP6 (E3M2) form of the 4-bit layer, through the C ABI.
 
-Bars as for the integer path: FP6 rows of activations and weights (the oracle's integer codes,
-mapped through the format's definition and the row layout of include/quik.h), scale, zero, outlier
+Bars as for the integer path: FP6 panels of activations and weights (the oracle's integer codes,
+mapped through the format's definition and the panel layout of include/quik.h), scale, zero, outlier
 block and the INT32 accumulators are bit-exact; the fp16 output is within 5e-3 of the oracle's
 binary32 result."""
 import numpy as np
 import pytest
 
 from paper_2310_09259_amd import synth
-from tests.util import fp6_rows, output_within_tolerance, to_dev, upload
+from tests.util import fp6_panels, output_within_tolerance, to_dev, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -54,10 +54,10 @@ def test_quantize_fp6_is_bit_exact(api, oracle, T, K, n_out):
     q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, 4)
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32)), "scale"
     assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32)), "zero"
-    got, want = xq6.cpu().numpy(), fp6_rows(q, xq6.shape[1])
+    got, want = xq6.cpu().numpy(), fp6_panels(q)
     if not np.array_equal(got, want):
         bad = np.argwhere(got != want)
-        raise AssertionError(f"FP6 rows differ at {len(bad)} bytes, first {bad[:5].tolist()}")
+        raise AssertionError(f"FP6 panels differ at {len(bad)} bytes, first {bad[:5].tolist()}")
     if n_out:
         assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16)), "x_out"
 
@@ -72,7 +72,7 @@ def test_weight_pack_fp6_is_bit_exact(api, oracle, N, K_b):
     buf[:, :wp.shape[1]] = wp
     w6 = api.quik_weight_pack_fp6(to_dev(buf), K_b)
     _sync()
-    assert np.array_equal(w6.cpu().numpy(), fp6_rows(wq, w6.shape[1]))
+    assert np.array_equal(w6.cpu().numpy(), fp6_panels(wq))
 
 
 def _linear_case(api, oracle, shp, bias=False):
@@ -138,8 +138,7 @@ def test_fp6_worst_case_magnitudes_stay_exact(api, oracle):
     q[1::2, ::3] = 7
     w = np.full((N, K_b), -8, np.int8)
     w[::3, 1::2] = 7
-    ld6 = api.quik_fp6_row_bytes(K_b)
-    acc = api.quik_int_gemm_fp6(to_dev(fp6_rows(q, ld6)), to_dev(fp6_rows(w, ld6)), K_b)
+    acc = api.quik_int_gemm_fp6(to_dev(fp6_panels(q)), to_dev(fp6_panels(w)), K_b)
     _sync()
     want = q.astype(np.int64) @ w.astype(np.int64).T
     assert want.max() == 64 * K_b

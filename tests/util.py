@@ -67,23 +67,23 @@ def e3m2_pattern(v: np.ndarray) -> np.ndarray:
     return out
 
 
-def fp6_rows(q: np.ndarray, ld6: int) -> np.ndarray:
-    """Signed codes int [R, K_b] -> the byte image of "FP6 rows" as include/quik.h defines them:
-    zero-padded to S stages of 128 columns; a group of 32 columns is a 192-bit little-endian string
-    (column j in bits [6j, 6j+6)); bytes 0..15 of stage s, group q = 2*ks + g go to 64 s + 16 q
-    (plane P), bytes 16..23 to 64 S + 32 s + 16 g + 8 ks (plane Q)."""
+def fp6_panels(q: np.ndarray) -> np.ndarray:
+    """Signed codes int [R, K_b] -> the byte image of "FP6 panels" as include/quik.h defines them,
+    shaped [S, R, 96]: zero-padded to S stages of 128 columns; stage s of row r is block [s, r];
+    a group of 32 columns is a 192-bit little-endian string (column j in bits [6j, 6j+6)); bytes
+    0..15 of group q = 2*ks + g go to byte 16 q of the block, bytes 16..23 to 64 + 16 g + 8 ks."""
     R, K_b = q.shape
     S = (K_b + 127) // 128
     codes = np.zeros((R, 128 * S), np.uint8)
     codes[:, :K_b] = e3m2_pattern(q)
     bits = ((codes[:, :, None] >> np.arange(6, dtype=np.uint8)) & 1).astype(np.uint8)   # little-endian per code
     strings = np.packbits(bits.reshape(R, 4 * S, 192), axis=2, bitorder="little")       # [R, 4S, 24] bytes
-    out = np.zeros((R, ld6), np.uint8)
+    out = np.zeros((S, R, 96), np.uint8)
     for s in range(S):
         for qq in range(4):
             ks, g = qq >> 1, qq & 1
             grp = strings[:, 4 * s + qq, :]
-            out[:, 64 * s + 16 * qq: 64 * s + 16 * qq + 16] = grp[:, :16]
-            o = 64 * S + 32 * s + 16 * g + 8 * ks
-            out[:, o: o + 8] = grp[:, 16:]
+            out[s, :, 16 * qq: 16 * qq + 16] = grp[:, :16]
+            o = 64 + 16 * g + 8 * ks
+            out[s, :, o: o + 8] = grp[:, 16:]
     return out
