@@ -257,11 +257,11 @@ int quik_linear_w4a8(const void *x, int T, int K, int ldx,
  * integer results exactly (checked against the INT32 reference by quik_int_gemm_fp6).
  *
  * "FP6 panels": the K_b columns of a matrix with R rows are padded with zeros to
- * S = ceil(K_b / 128) stages of 128 columns and stored stage by stage: stage s of row r is the
- * 96-byte block at byte (s * R + r) * 96 of the buffer (S * R * 96 bytes, 16-byte aligned;
- * quik_fp6_row_bytes(K_b) = 96 S).  A stage holds four groups of 32 columns, group q = 2 * ks + g.
- * A group is a 192-bit little-endian string (column j of the group in bits [6j, 6j+6)) = dwords
- * d0 .. d5; d0 .. d3 of group q sit at byte 16 q of the block, d4, d5 at byte 64 + 16 g + 8 ks.
+ * S = ceil(K_b / 64) stages of 64 columns and stored stage by stage: stage s of row r is the
+ * 48-byte block at byte (s * R + r) * 48 of the buffer (S * R * 48 bytes, 16-byte aligned;
+ * quik_fp6_row_bytes(K_b) = 48 S).  A stage holds two groups of 32 columns, g = 0, 1.  A group
+ * is a 192-bit little-endian string (column j of the group in bits [6j, 6j+6)) = dwords
+ * d0 .. d5; d0 .. d3 of group g sit at byte 16 g of the block, d4, d5 at byte 32 + 8 g.
  *
  *  quik_weight_pack_fp6   offline: packed signed 4-bit weights w_q [N, ldw] (weight nibble
  *                         order of quik.h, ldw >= K_b/2, K_b even) -> FP6 panels w6 (R = N).
@@ -274,7 +274,7 @@ int quik_linear_w4a8(const void *x, int T, int K, int ldx,
  *                         quik_workspace_bytes_fp6(T, K, N, n_out) bytes, 256-byte aligned.
  * All pointers are DEVICE pointers (16-byte aligned where the integer forms require it); error
  * behaviour as for the integer forms; additionally QUIK_EUNSUPPORTED if one stage of all rows
- * (max(T, N) * 96 S bytes in total) reaches 4 GB.
+ * (max(T, N) * 48 bytes) reaches 4 GB.
  */
 int quik_fp6_row_bytes(int K_b);
 size_t quik_workspace_bytes_fp6(int T, int K, int N, int n_out);

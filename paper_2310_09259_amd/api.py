@@ -357,17 +357,17 @@ def quik_workspace_bytes_fp6(T: int, K: int, N: int, n_out: int) -> int:
 
 
 def quik_weight_pack_fp6(w_q, K_b: int):
-    """packed signed 4-bit weights uint8 [N, ldw] -> FP6 panels uint8 [stages, N, 96]."""
+    """packed signed 4-bit weights uint8 [N, ldw] -> FP6 panels uint8 [stages, N, 48]."""
     w_q = _dev(w_q, torch.uint8, "w_q")
     N = w_q.shape[0]
-    w6 = torch.empty((quik_fp6_row_bytes(K_b) // 96, N, 96), dtype=torch.uint8, device=w_q.device)
+    w6 = torch.empty((quik_fp6_row_bytes(K_b) // 48, N, 48), dtype=torch.uint8, device=w_q.device)
     rc = load().quik_weight_pack_fp6(_ptr(w_q), w_q.stride(0), N, K_b, _ptr(w6), _stream())
     _check(rc, "quik_weight_pack_fp6")
     return w6
 
 
 def quik_quantize_fp6(x, outlier_idx, out=None):
-    """x fp16 [T,K] -> (xq6 uint8 [stages,T,96], scale f32 [T], zero f32 [T], x_out f16 [T,n_out])."""
+    """x fp16 [T,K] -> (xq6 uint8 [stages,T,48], scale f32 [T], zero f32 [T], x_out f16 [T,n_out])."""
     x = _dev(x, torch.float16, "x")
     T, K = x.shape
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
@@ -377,7 +377,7 @@ def quik_quantize_fp6(x, outlier_idx, out=None):
     if ld6 <= 0:
         raise QuikError(-1, "quik_fp6_row_bytes")
     if out is None:
-        xq6 = torch.empty((ld6 // 96, T, 96), dtype=torch.uint8, device=x.device)
+        xq6 = torch.empty((ld6 // 48, T, 48), dtype=torch.uint8, device=x.device)
         scale = torch.empty(T, dtype=torch.float32, device=x.device)
         zero = torch.empty(T, dtype=torch.float32, device=x.device)
         x_out = torch.empty((T, n_out), dtype=torch.float16, device=x.device)

@@ -355,7 +355,7 @@ int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, cons
 
 int quik_fp6_row_bytes(int K_b) {
     if (K_b <= 0 || K_b >= kMaxKb) return 0;
-    return 96 * ((K_b + 127) / 128);
+    return 48 * ((K_b + 63) / 64);
 }
 
 size_t quik_workspace_bytes_fp6(int T, int K, int N, int n_out) {

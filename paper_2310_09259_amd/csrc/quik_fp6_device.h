@@ -8,14 +8,13 @@
 // at twice its int8 rate (v_mfma_f32_32x32x64_f8f6f4), and the operands need no widening in registers.
 //
 // Operand layout ("panels").  The columns of a matrix with R rows are padded with zero codes to S
-// stages of 128 columns, and the matrix is stored stage by stage: stage s of row r is the 96-byte block
-// at byte (s * R + r) * 96, so the rows of an output tile are one contiguous run per stage (whole cache
-// lines for the copy engine).  A stage holds four groups of 32 columns, group index q = 2 * ks + g
-// (ks: which of the stage's two 64-column matrix steps, g: which half of the wave's lanes consumes it).
-// A group is 32 x 6 bits = six dwords d0 .. d5, column j of the group in bits [6j, 6j + 6) of that
-// 192-bit little-endian string: exactly the register image one lane hands to the matrix instruction.
-// d0 .. d3 of group q sit at byte 16 q of the block; d4, d5 of group (ks, g) at byte 64 + 16 g + 8 ks, so
-// that a lane's d4, d5 of both steps are adjacent.
+// stages of 64 columns (one step of the matrix instruction), and the matrix is stored stage by stage:
+// stage s of row r is the 48-byte block at byte (s * R + r) * 48, so the rows of an output tile are one
+// contiguous run per stage (whole cache lines for the copy engine, and nothing to rearrange on the way
+// into LDS).  A stage holds two groups of 32 columns, g = 0, 1: the half of the wave's lanes that
+// consumes it.  A group is 32 x 6 bits = six dwords d0 .. d5, column j of the group in bits
+// [6j, 6j + 6) of that 192-bit little-endian string: exactly the register image one lane hands to the
+// matrix instruction.  d0 .. d3 of group g sit at byte 16 g of the block, d4, d5 at byte 32 + 8 g.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -23,15 +22,12 @@
 namespace quik {
 namespace fp6 {
 
-// stages of 128 columns that cover K_b columns
-__host__ __device__ inline int stages(int K_b) { return (K_b + 127) >> 7; }
+// stages of 64 columns that cover K_b columns
+__host__ __device__ inline int stages(int K_b) { return (K_b + 63) >> 6; }
 // bytes of one row summed over its stages (a matrix of R rows takes R times this)
-__host__ __device__ inline int row_bytes(int K_b) { return 96 * stages(K_b); }
-// index (in dwords, inside the 96-byte block of its stage) of dword d (0 .. 5) of group q (0 .. 3)
-__host__ __device__ inline int block_dword(int q, int d) {
-    const int ks = q >> 1, g = q & 1;
-    return d < 4 ? 4 * q + d : 16 + 4 * g + 2 * ks + (d - 4);
-}
+__host__ __device__ inline int row_bytes(int K_b) { return 48 * stages(K_b); }
+// index (in dwords, inside the 48-byte block of its stage) of dword d (0 .. 5) of group g (0, 1)
+__host__ __device__ inline int block_dword(int g, int d) { return d < 4 ? 4 * g + d : 8 + 2 * g + (d - 4); }
 
 // E3M2 patterns of u - 8 for the unsigned codes u = 0 .. 7 (values -8 .. -1) and u = 8 .. 15 (0 .. 7)
 constexpr uint32_t kNeg0 = 0x35363738u, kNeg1 = 0x2C303234u;   // -8 -7 -6 -5 | -4 -3 -2 -1

@@ -5,17 +5,21 @@
 // K loop is DMA -> LDS -> registers -> v_mfma_f32_32x32x64_f8f6f4 with no widening work at all, at
 // twice the int8 rate of the matrix pipe.
 //
-// A workgroup of WM x WN waves owns a BM x BN output tile.  A stage is 128 columns = one 96-byte block per
-// operand row; the operands are stored stage by stage (quik_fp6_device.h), so the tile's rows of a stage
-// are one contiguous run of BM * 96 (BN * 96) bytes that 16-byte-per-lane DMA instructions copy global ->
-// LDS as it is, whole cache lines per instruction; three stage buffers.  Lane (row l%32, half g = l/32)
-// reads, per 64-column step, 16 bytes (dwords 0..3 of its group) and 8 bytes (dwords 4, 5); the 16-byte
-// pieces of a block are exchanged pairwise in every second group of eight rows (by the DMA's choice of
-// source piece) so that the rows one read instruction touches fall into distinct banks.  The fp16
-// outlier columns run through the same ring as stages of 32 columns (64-byte rows, 16 rows per DMA
-// instruction), with the dequantized integer part as the C operand of v_mfma_f32_32x32x16_f16, whose
-// accumulator layout is the same.  Rows beyond T / N are out of range for the per-stage buffer
-// descriptors and arrive as zeros (the E3M2 pattern of 0); columns beyond K_b are zero padding.
+// A workgroup of WM x WN waves owns a BM x BN output tile.  A stage is 64 columns = one matrix step = one
+// 48-byte block per operand row; the operands are stored stage by stage (quik_fp6_device.h), so the
+// tile's rows of a stage are one contiguous run of BM * 48 (BN * 48) bytes that 16-byte-per-lane DMA
+// instructions copy global -> LDS as it is.  The K loop is bound by how many bytes a CU keeps in flight
+// (completion is in order, so every request waits like the slowest before it): the stage ring takes
+// nearly all of the LDS, seven stages for the 256 x 192 tile.  Lane (row l%32, half g = l/32) reads,
+// per stage, 16 bytes (dwords 0..3 of its group) and 8 bytes (dwords 4, 5); 48-byte rows need no
+// swizzle (twelve dwords per row walk all 64 banks in sixteen rows).  One workgroup barrier per stage;
+// right after it the buffer that was read during the previous stage is refilled, the DMA
+// instructions spread between the matrix instructions.  The fp16 outlier columns run through the same
+// ring as stages of 16 columns (32-byte rows, 32 rows per DMA instruction, pieces exchanged in every
+// second group of eight rows), with the dequantized integer part as the C operand of
+// v_mfma_f32_32x32x16_f16, whose accumulator layout is the same.  Rows beyond T / N are out of range
+// for the per-stage buffer descriptors and arrive as zeros (the E3M2 pattern of 0); columns beyond K_b
+// are zero padding.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -32,8 +36,7 @@ using namespace gemm_dev;
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ int swz_f(int r) { return (r >> 2) & 3; }   // fp16 stages: 64-byte rows, four pieces
-__device__ __forceinline__ int swz_6(int r) { return (r >> 3) & 1; }   // FP6 stages: 96-byte rows, pieces paired
+__device__ __forceinline__ int swz_f(int r) { return (r >> 3) & 1; }   // fp16 stages: 32-byte rows, two pieces
 
 // descriptor r moved forward by `bytes`
 __device__ __forceinline__ v4i advance(v4i r, uint32_t bytes) {
@@ -44,7 +47,7 @@ __device__ __forceinline__ v4i advance(v4i r, uint32_t bytes) {
 }
 
 // MODE 0: fused epilogue, fp16 output; MODE 1: the integer accumulators as INT32.
-template <int BM, int BN, int WM, int WN, int GM, int MODE>
+template <int BM, int BN, int WM, int WN, int NST, int GM, int MODE>
 __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
     // claim the whole register budget of the launch bounds, so that the highest allocated register is
@@ -52,17 +55,14 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
     asm volatile("" ::: "v255");
     constexpr int NWAVES = WM * WN, NT = NWAVES * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NF = TM + TN;
-    constexpr int NST = 3;
-    constexpr int A_BYTES = BM * 96, B_BYTES = BN * 96, ST_BYTES = A_BYTES + B_BYTES;
-    // DMA instructions of a stage (1 KB each): FP6 stages BM * 96 / 1024 and BN * 96 / 1024, fp16 stages
-    // BM / 16 and BN / 16.  Slots of a wave per stage: S_A for A, then S_B for B; instruction
-    // i = wave + NWAVES * (slot within its operand); a slot whose i does not exist is issued empty so
-    // that every wave counts the same number of DMA instructions.
-    constexpr int N_A = BM * 96 / 1024, N_B = BN * 96 / 1024, N_AF = BM / 16, N_BF = BN / 16;
-    constexpr int S_A = (N_A + NWAVES - 1) / NWAVES, S_B = (N_B + NWAVES - 1) / NWAVES;
-    constexpr int LPS = S_A + S_B;
-    static_assert(BM % 32 == 0 && BN % 32 == 0 && N_AF <= S_A * NWAVES && N_BF <= S_B * NWAVES, "slot count");
-    static_assert((NST - 1) * LPS < 64, "vmcnt range");
+    constexpr int A_BYTES = BM * 48, B_BYTES = BN * 48, ST_BYTES = A_BYTES + B_BYTES;
+    // DMA instructions of a stage (1 KB each): FP6 stages N_A + N_B over the tile's two runs, fp16 stages
+    // BM / 32 and BN / 32.  A wave issues LPS of them per stage: instruction i = wave + NWAVES * slot; one
+    // that does not exist is issued empty so that every wave counts the same number.
+    constexpr int N_A = BM * 48 / 1024, N_B = BN * 48 / 1024, N_AF = BM / 32, N_BF = BN / 32;
+    constexpr int LPS = (N_A + N_B + NWAVES - 1) / NWAVES;
+    static_assert(BM % 64 == 0 && BN % 64 == 0 && N_AF + N_BF <= LPS * NWAVES && (BM + BN) * 32 <= ST_BYTES, "geometry");
+    static_assert(NST * LPS < 64, "vmcnt range");
     constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
 
     __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES + 1024];
@@ -93,61 +93,67 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
     const int S = fp6::stages(a.K_b);
     const int nk_int = a.fp_only ? 0 : S;
     const int fp_bytes = a.n_out * 2;
-    const int nk_fp = RAW ? 0 : (fp_bytes + 63) / 64;
+    const int nk_fp = RAW ? 0 : (fp_bytes + 31) / 32;
     const int nk = nk_int + nk_fp;
     const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
     const int T_ = a.T, N_ = a.N;                         // values, so that nothing takes the address of an argument
 
-    // stage 0 of the tile's rows; stage s lies s * T * 96 (s * N * 96) bytes further on
-    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * 96, (size_t)(a.T - t0) * 96);
-    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * 96, (size_t)(a.N - n0) * 96);
+    // stage 0 of the tile's rows; stage s lies s * T * 48 (s * N * 48) bytes further on
+    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * 48, (size_t)(a.T - t0) * 48);
+    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * 48, (size_t)(a.N - n0) * 48);
     const v4i rAf = make_rsrc(a.n_out ? (const uint8_t*)a.x_out + (size_t)t0 * lda_fp : (const uint8_t*)a.xq,
                               a.n_out ? (size_t)(a.T - t0) * lda_fp : 0);
     const v4i rBf = make_rsrc(a.n_out ? (const uint8_t*)a.w_out + (size_t)n0 * ldb_fp : (const uint8_t*)a.xq,
                               a.n_out ? (size_t)(a.N - n0) * ldb_fp : 0);
     const uint32_t lds_base = lds_addr(lds);
 
-    // Per-lane DMA source offsets.  FP6 stage, slot q: lane handles the 16-byte piece p = 64 i + lane of the
-    // tile's run, i.e. piece p % 6 of row p / 6, and fetches the piece the swizzle assigns to that place.
-    uint32_t vo_a[S_A], vo_b[S_B];
-#pragma unroll
-    for (int q = 0; q < S_A; ++q) {
-        const int pc = 64 * (wave_u + NWAVES * q) + lane, row = pc / 6, c = pc - 6 * row;
-        vo_a[q] = (uint32_t)(row * 96 + ((c ^ swz_6(row)) << 4));
-    }
-#pragma unroll
-    for (int q = 0; q < S_B; ++q) {
-        const int pc = 64 * (wave_u + NWAVES * q) + lane, row = pc / 6, c = pc - 6 * row;
-        vo_b[q] = (uint32_t)(row * 96 + ((c ^ swz_6(row)) << 4));
-    }
-    // fp16 stage: 16 rows (lane / 4) x four pieces of a 64-byte stage row per instruction
-    const int colF = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
-    const uint32_t vo_af = (uint32_t)((lane >> 2) * lda_fp + colF), vo_bf = (uint32_t)((lane >> 2) * ldb_fp + colF);
+    // fp16 stage: 32 rows (lane / 2) x two 16-byte pieces of a 32-byte stage row per instruction
+    const int colF = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;
+    const uint32_t vo_af = (uint32_t)((lane >> 1) * lda_fp + colF), vo_bf = (uint32_t)((lane >> 1) * ldb_fp + colF);
     // DMA slot j of stage s (int part, fp16 part, or past the end: every lane out of range)
     auto issue_one = [&](int s, int j) __attribute__((always_inline)) {
-        const bool isb = j >= S_A;
-        const int seq = isb ? j - S_A : j;
-        const int i = wave_u + NWAVES * seq;                    // instruction of this operand (wave-uniform)
+        const int i = wave_u + NWAVES * j;                      // instruction of the stage (wave-uniform)
         const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
         const bool fp = s >= nk_int;
-        uint32_t vo = kOob;
-        bool exists;
-        uint32_t dst;
+        uint32_t vo = kOob, dst = (uint32_t)DUMMY;
+        v4i r;
         if (!fp) {
-            exists = i < (isb ? N_B : N_A);
-            if (s < nk && exists) vo = isb ? vo_b[isb ? seq : 0] : vo_a[isb ? 0 : seq];
-            dst = sb + (isb ? A_BYTES : 0) + i * 1024;
+            // instructions 0 .. N_A-1 copy A's run, N_A .. N_A+N_B-1 B's: piece 64 i' + lane of the run
+            const bool isb = i >= N_A;
+            const int ii = isb ? i - N_A : i;
+            if (i < N_A + N_B) {
+                dst = sb + (isb ? A_BYTES : 0) + ii * 1024;
+                if (s < nk) vo = (uint32_t)(ii * 1024 + lane * 16);
+            }
+            r = isb ? advance(rB, (uint32_t)s * (uint32_t)N_ * 48u) : advance(rA, (uint32_t)s * (uint32_t)T_ * 48u);
         } else {
-            exists = i < (isb ? N_BF : N_AF);
-            const int c0 = 64 * (s - nk_int);
-            if (s < nk && exists && c0 + colF < fp_bytes)
-                vo = (isb ? vo_bf : vo_af) + (uint32_t)(i * 16 * (isb ? ldb_fp : lda_fp) + c0);
-            dst = sb + (isb ? BM * 64 : 0) + i * 1024;
+            const bool isb = i >= N_AF;
+            const int ii = isb ? i - N_AF : i;
+            const int c0 = 32 * (s - nk_int);
+            if (i < N_AF + N_BF) {
+                dst = sb + (isb ? BM * 32 : 0) + ii * 1024;
+                if (s < nk && c0 + colF < fp_bytes)
+                    vo = (isb ? vo_bf : vo_af) + (uint32_t)(ii * 32 * (isb ? ldb_fp : lda_fp) + c0);
+            }
+            r = isb ? rBf : rAf;
         }
-        dst = lds_base + (exists ? dst : (uint32_t)DUMMY);
-        if (fp) dma16(isb ? rBf : rAf, dst, vo, 0);
-        else if (isb) dma16(advance(rB, (uint32_t)s * (uint32_t)N_ * 96u), dst, vo, 0);
-        else dma16(advance(rA, (uint32_t)s * (uint32_t)T_ * 96u), dst, vo, 0);
+        // wave-uniform by construction; say so, the DMA takes them in scalar registers
+        r = v4i{__builtin_amdgcn_readfirstlane(r[0]), __builtin_amdgcn_readfirstlane(r[1]),
+                __builtin_amdgcn_readfirstlane(r[2]), __builtin_amdgcn_readfirstlane(r[3])};
+        dma16(r, (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + dst)), vo, 0);
+    };
+    // DMA slot j of an FP6 stage that exists (the hot loop's form)
+    auto issue_int = [&](int s, int j) __attribute__((always_inline)) {
+        const int i = wave_u + NWAVES * j;
+        const bool isb = i >= N_A;
+        const int ii = isb ? i - N_A : i;
+        const bool exists = i < N_A + N_B;
+        const uint32_t dst = exists ? (uint32_t)(s % NST) * ST_BYTES + (isb ? A_BYTES : 0) + ii * 1024 : (uint32_t)DUMMY;
+        const uint32_t vo = exists ? (uint32_t)(ii * 1024 + lane * 16) : kOob;
+        v4i r = isb ? advance(rB, (uint32_t)s * (uint32_t)N_ * 48u) : advance(rA, (uint32_t)s * (uint32_t)T_ * 48u);
+        r = v4i{__builtin_amdgcn_readfirstlane(r[0]), __builtin_amdgcn_readfirstlane(r[1]),
+                __builtin_amdgcn_readfirstlane(r[2]), __builtin_amdgcn_readfirstlane(r[3])};
+        dma16(r, (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + dst)), vo, 0);
     };
     auto issue = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
@@ -192,30 +198,23 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
         }
     }
 
-    // LDS read addresses of this lane's row of every fragment.  FP6 stage: piece 2 ks + g of the row's
-    // 96-byte block (16 bytes) and 8 bytes at 64 + 16 g + 8 ks; fp16 stage: piece 2 ks + g of a 64-byte row.
-    uint32_t rdp[NF][2], rdq[NF], rdf[NF][2];
+    // LDS read addresses of this lane's row of every fragment.  FP6 stage: piece g of the row's 48-byte
+    // block (16 bytes) and 8 bytes at 32 + 8 g; fp16 stage: piece g of a 32-byte row.
+    uint32_t rdp[NF], rdf[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
         const int r = (f < TM) ? (wm * TM * 32 + f * 32 + l32) : (wn * TN * 32 + (f - TM) * 32 + l32);
-        const uint32_t b6 = (f < TM ? 0 : A_BYTES) + r * 96, bf = (f < TM ? 0 : BM * 64) + r * 64;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            rdp[f][ks] = b6 + (((ks * 2 + g) ^ swz_6(r)) << 4);
-            rdf[f][ks] = bf + (((ks * 2 + g) ^ swz_f(r)) << 4);
-        }
-        rdq[f] = b6 + 64 + ((g ^ swz_6(r)) << 4);
+        rdp[f] = (f < TM ? 0 : A_BYTES) + r * 48 + 16 * g;
+        rdf[f] = (f < TM ? 0 : BM * 32) + r * 32 + ((g ^ swz_f(r)) << 4);
     }
-    // two fragment sets: the matrix instructions of one 64-column step run on one set while the
-    // LDS reads of the next step fill the other
+    // two fragment sets: the matrix instructions of one stage run on one set while the LDS reads of the
+    // next stage fill the other
     uint4 FP[2][NF];
     uint2 FQ[2][NF];
-    auto read_p = [&](int set, int f, int s, int ks) __attribute__((always_inline)) {
-        const uint32_t ad = (s >= nk_int) ? rdf[f][ks] : rdp[f][ks];
-        FP[set][f] = *reinterpret_cast<const uint4*>(lds + (s % NST) * ST_BYTES + ad);
-    };
-    auto read_q = [&](int set, int f, int s, int ks) __attribute__((always_inline)) {
-        FQ[set][f] = *reinterpret_cast<const uint2*>(lds + (s % NST) * ST_BYTES + rdq[f] + 8 * ks);
+    auto read_frag = [&](int set, int f, int s) __attribute__((always_inline)) {
+        const uint8_t* st = lds + (s % NST) * ST_BYTES;
+        FP[set][f] = *reinterpret_cast<const uint4*>(st + rdp[f]);
+        FQ[set][f] = *reinterpret_cast<const uint2*>(st + rdp[f] + 32 - 8 * g);     // 32 + 8 g of the block
     };
 
     v16f acc[TM][TN];
@@ -226,69 +225,52 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // Step ks of stage s.  Before its second step a stage's successor must have landed for everybody
-    // (its first fragments are read during that step); all reads of stage s itself have completed by
-    // then, so its buffer is refilled with stage s + NST right away, one DMA instruction per matrix
-    // instruction.
-    auto step = [&](int s, int ks, bool wide) __attribute__((always_inline)) {
-        if (ks == 1) {
-            wait_vm<(NST - 2) * LPS>();
-            __syncthreads();
-        }
-        const int ns = ks ? s + 1 : s, nks = ks ^ 1;
+    // FP6 stage s.  Its successor must have landed for everybody (its fragments are read during this
+    // stage); all reads of stage s itself completed before the barrier, so its buffer is refilled with
+    // stage s + NST right away, one DMA instruction per matrix instruction.  PLAIN: stage s + NST is an
+    // FP6 stage; AHEAD: stage s + 1 is one.
+    auto step = [&](int s, int set, bool plain, bool ahead) __attribute__((always_inline)) {
+        wait_vm<(NST - 2) * LPS>();
+        __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < TM * TN; ++m) {
             const int i = m / TN, j = m % TN;
-            if (!wide) {
-                const v8i oa = v8i{(int)FP[ks][i].x, (int)FP[ks][i].y, (int)FP[ks][i].z, (int)FP[ks][i].w,
-                                   (int)FQ[ks][i].x, (int)FQ[ks][i].y, 0, 0};
-                const v8i ob = v8i{(int)FP[ks][TM + j].x, (int)FP[ks][TM + j].y, (int)FP[ks][TM + j].z,
-                                   (int)FP[ks][TM + j].w, (int)FQ[ks][TM + j].x, (int)FQ[ks][TM + j].y, 0, 0};
-#ifndef QF_NOMFMA
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(oa, ob, acc[i][j], 3, 3, 0, 0, 0, 0);
-#else
-                asm volatile("" :: "v"(oa), "v"(ob));
-#endif
-            } else {
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, FP[ks][i]),
-                                                                   __builtin_bit_cast(v8h, FP[ks][TM + j]),
-                                                                   acc[i][j], 0, 0, 0);
-            }
-            if (ks == 1) {
-                constexpr int PER = (TM * TN >= LPS) ? TM * TN / LPS : 1;
-#ifndef QF_NODMA
-                if (m % PER == 0 && m / PER < LPS) issue_one(s + NST, m / PER);
-#endif
-                if constexpr (TM * TN < LPS) {
-                    if (m == TM * TN - 1) {
-#pragma unroll
-                        for (int d = TM * TN; d < LPS; ++d) issue_one(s + NST, d);
-                    }
-                }
-            }
-#ifndef QF_NOREAD
-            if (m < NF) { read_p(nks, m, ns, nks); read_q(nks, m, ns, nks); }
-#endif
-            if constexpr (TM * TN < NF) {
-                if (m == TM * TN - 1) {
-#pragma unroll
-                    for (int f = TM * TN; f < NF; ++f) { read_p(nks, f, ns, nks); read_q(nks, f, ns, nks); }
-                }
-            }
+            const v8i oa = v8i{(int)FP[set][i].x, (int)FP[set][i].y, (int)FP[set][i].z, (int)FP[set][i].w,
+                               (int)FQ[set][i].x, (int)FQ[set][i].y, 0, 0};
+            const v8i ob = v8i{(int)FP[set][TM + j].x, (int)FP[set][TM + j].y, (int)FP[set][TM + j].z,
+                               (int)FP[set][TM + j].w, (int)FQ[set][TM + j].x, (int)FQ[set][TM + j].y, 0, 0};
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(oa, ob, acc[i][j], 3, 3, 0, 0, 0, 0);
+            if (m < LPS) { if (plain) issue_int(s + NST, m); else issue_one(s + NST, m); }
+            if (ahead && m < NF) read_frag(set ^ 1, m, s + 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    static_assert(TM * TN >= NF && TM * TN >= LPS, "a stage has fewer matrix instructions than reads or copies to place");
 
     wait_vm<(NST - 1) * LPS>();            // stage 0 landed
     __syncthreads();
+    if (nk_int > 0) {
 #pragma unroll
-    for (int f = 0; f < NF; ++f) { read_p(0, f, 0, 0); read_q(0, f, 0, 0); }
+        for (int f = 0; f < NF; ++f) read_frag(0, f, 0);
+    }
 
     int s = 0;
-    for (; s < nk_int; ++s) {
-        step(s, 0, false);
-        step(s, 1, false);
+    for (; s + 1 + NST < nk_int; s += 2) {
+        step(s, 0, true, true);
+        step(s + 1, 1, true, true);
+    }
+    for (; s + 2 < nk_int; s += 2) {
+        step(s, 0, false, true);
+        step(s + 1, 1, false, true);
+    }
+    if (s + 2 == nk_int) {
+        step(s, 0, false, true);
+        step(s + 1, 1, false, false);
+        s += 2;
+    } else if (s + 1 == nk_int) {
+        step(s, 0, false, false);
+        s += 1;
     }
 
     const int tw = t0 + wm * TM * 32, nw = n0 + wn * TN * 32;
@@ -327,11 +309,34 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
                 }
         }
 
-    // fp16 outlier stages: 32 columns each, two matrix steps of 16 (plane P geometry; the 8 bytes read
-    // from the plane Q region are ignored)
-    for (; s < nk; ++s) {
-        step(s, 0, true);
-        step(s, 1, true);
+    // fp16 outlier stages: 16 columns each, one matrix step, same protocol as the FP6 stages (fragments
+    // of stage s + 1 are read while the matrix instructions of stage s run; one barrier per stage)
+    auto wide_step = [&](int s, int set) __attribute__((always_inline)) {
+        wait_vm<(NST - 2) * LPS>();
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        const uint8_t* nxt = lds + ((s + 1) % NST) * ST_BYTES;
+#pragma unroll
+        for (int m = 0; m < TM * TN; ++m) {
+            const int i = m / TN, j = m % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, FP[set][i]),
+                                                               __builtin_bit_cast(v8h, FP[set][TM + j]), acc[i][j], 0, 0, 0);
+            if (m < LPS) issue_one(s + NST, m);
+            if (m < NF) FP[set ^ 1][m] = *reinterpret_cast<const uint4*>(nxt + rdf[m]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    if (s < nk) {
+        wait_vm<(NST - 1) * LPS>();        // first fp16 stage landed
+        __syncthreads();
+        const uint8_t* st = lds + (s % NST) * ST_BYTES;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) FP[0][f] = *reinterpret_cast<const uint4*>(st + rdf[f]);
+        for (; s + 1 < nk; s += 2) {
+            wide_step(s, 0);
+            wide_step(s + 1, 1);
+        }
+        if (s < nk) { wide_step(s, 0); ++s; }
     }
 
     wait_vm<0>();                          // drain the look-ahead DMA before the wave ends
@@ -399,7 +404,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_fp6
 __global__ __launch_bounds__(256) void weight_pack_fp6_kernel(const uint8_t* __restrict__ w_q, int ldw, int N, int K_b,
                                                               uint32_t* __restrict__ w6) {
     const int S = fp6::stages(K_b);
-    const int groups = 4 * S;
+    const int groups = 2 * S;
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long)N * groups) return;
     const int n = (int)(idx / groups), G = (int)(idx % groups);
@@ -426,23 +431,23 @@ __global__ __launch_bounds__(256) void weight_pack_fp6_kernel(const uint8_t* __r
     d[3] = (uint32_t)e2;
     d[4] = (uint32_t)(e2 >> 32) | (uint32_t)(e3 << 16);
     d[5] = (uint32_t)(e3 >> 16);
-    uint32_t* blk = w6 + ((size_t)(G >> 2) * N + n) * 24;         // the row's 96-byte block of this stage
+    uint32_t* blk = w6 + ((size_t)(G >> 1) * N + n) * 12;         // the row's 48-byte block of this stage
 #pragma unroll
-    for (int i = 0; i < 6; ++i) blk[fp6::block_dword(G & 3, i)] = d[i];
+    for (int i = 0; i < 6; ++i) blk[fp6::block_dword(G & 1, i)] = d[i];
 }
 
-template <int BM, int BN, int WM, int WN, int GM, int MODE>
+template <int BM, int BN, int WM, int WN, int NST, int GM, int MODE>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     const int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_fp6_kernel<BM, BN, WM, WN, GM, MODE>), dim3(tiles), dim3(WM * WN * 64), 0, stream, a);
+    hipLaunchKernelGGL((gemm_fp6_kernel<BM, BN, WM, WN, NST, GM, MODE>), dim3(tiles), dim3(WM * WN * 64), 0, stream, a);
     return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t dispatch6(const GemmArgs& a, hipStream_t stream) {
     const long big = (long)((a.T + 255) / 256) * ((a.N + 191) / 192);
-    if (a.T > 128 && big >= 128) return launch_cfg<256, 192, 4, 2, 4, MODE>(a, stream);
-    return launch_cfg<128, 128, 2, 2, 0, MODE>(a, stream);
+    if (a.T > 128 && big >= 128) return launch_cfg<256, 192, 4, 2, 7, 4, MODE>(a, stream);
+    return launch_cfg<128, 128, 2, 2, 6, 0, MODE>(a, stream);
 }
 
 }  // namespace
@@ -454,7 +459,7 @@ hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream) {
 
 hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, hipStream_t stream) {
     if (N <= 0 || K_b <= 0) return hipSuccess;
-    const long total = (long)N * 4 * fp6::stages(K_b);
+    const long total = (long)N * 2 * fp6::stages(K_b);
     hipLaunchKernelGGL(weight_pack_fp6_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        static_cast<const uint8_t*>(w_q), ldw, N, K_b, static_cast<uint32_t*>(w6));
     return hipGetLastError();

@@ -19,7 +19,7 @@ struct QuantizeArgs {
     int ldo;
     int32_t* code_sum;    // [T] sum of the signed codes at even positions (4-bit; may be null)
     int fp6;              // 1: 4-bit codes written as E3M2 patterns in the panel layout (quik_fp6_device.h);
-                          //    xq is then the [stage][T][96-byte] buffer and ldq = 96 * stages
+                          //    xq is then the [stage][T][48-byte] buffer and ldq = 48 * stages
 };
 
 struct GemmArgs {
@@ -60,7 +60,7 @@ struct WeightReduceArgs {
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
-// FP6 path (quik_gemm_fp6.hip): xq / w_q of GemmArgs are panel buffers [stage][row][96 bytes]; ldq / ldw unused
+// FP6 path (quik_gemm_fp6.hip): xq / w_q of GemmArgs are panel buffers [stage][row][48 bytes]; ldq / ldw unused
 hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, hipStream_t stream);
 

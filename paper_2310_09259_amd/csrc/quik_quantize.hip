@@ -221,7 +221,7 @@ __device__ __forceinline__ void chunk_codes(const uint32_t (&x)[4], float mn, fl
 
 // K <= TPR * 8 * NCH: the row lives in NCH 128-bit registers per thread.  FP6 (4-bit codes only):
 // the packed row is written as E3M2 patterns in the panel layout of quik_fp6_device.h (xq is then the
-// whole [stage][row][96-byte] buffer, ldq the 96 * stages bytes of one row's LDS image) and no code sum
+// whole [stage][row][48-byte] buffer, ldq the 48 * stages bytes of one row's LDS image) and no code sum
 // is produced.
 template <int BITS, int TPR, int NCH, bool FP6>
 __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kernel(
@@ -384,7 +384,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                     for (int i = 0; i < 3; ++i) {
                         uint32_t dd = d0 + i, GG = G;
                         if (dd >= 6u) { dd -= 6u; ++GG; }
-                        if (w3[i]) atomicOr(&stage[24u * (GG >> 2) + (uint32_t)fp6::block_dword((int)(GG & 3u), (int)dd)], w3[i]);
+                        if (w3[i]) atomicOr(&stage[12u * (GG >> 1) + (uint32_t)fp6::block_dword((int)(GG & 1u), (int)dd)], w3[i]);
                     }
                 } else {
                     esum = __builtin_amdgcn_sad_u8((lo >> pos_even_shift(pos)) & 0x0F0F0F0Fu, 0u, esum);
@@ -433,9 +433,9 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
             const uint4* src = reinterpret_cast<const uint4*>(stage);
             for (int i = lt; i < (ldq >> 4); i += TPR) {
                 uint4 v = src[i];
-                if constexpr (FP6) {                   // piece i of the image = piece i % 6 of stage i / 6
-                    const int st = i / 6, c = i - 6 * st;
-                    dst[((size_t)st * T + t) * 6 + c] = v;
+                if constexpr (FP6) {                   // piece i of the image = piece i % 3 of stage i / 3
+                    const int st = i / 3, c = i - 3 * st;
+                    dst[((size_t)st * T + t) * 3 + c] = v;
                     continue;
                 }
                 if constexpr (BITS == 4 && !FP6) {

@@ -99,3 +99,62 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, C.c_void_p(0x1000), need - 1,
                null) == -5
     assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, null, need, null) == -2
+
+
+def test_fp6_sizes_and_bad_arguments(lib):
+    vp, i = C.c_void_p, C.c_int
+    lib.quik_workspace_bytes_fp6.restype = C.c_size_t
+    assert lib.quik_fp6_row_bytes(64) == 48
+    assert lib.quik_fp6_row_bytes(65) == 96                  # padded to whole stages of 64 columns
+    assert lib.quik_fp6_row_bytes(3840) == 2880
+    assert lib.quik_fp6_row_bytes(0) == 0
+    ws = lib.quik_workspace_bytes_fp6(2048, 4096, 11008, 256)
+    assert ws >= 2048 * 2880 + 2 * 2048 * 4 + 2048 * 256 * 2 and ws % 256 == 0
+    assert lib.quik_workspace_bytes_fp6(16, 64, 1, 64) == 0
+    p, u, null = vp(0x1000), vp(0x1004), vp(0)
+    pk = lib.quik_weight_pack_fp6
+    pk.argtypes = [vp, i, i, i, vp, vp]
+    assert pk(p, 32, 8, 64, null, null) == -2
+    assert pk(p, 16, 8, 64, p, null) == -1                   # ldw < K_b / 2
+    assert pk(p, 32, 8, 63, p, null) == -1                   # odd K_b
+    assert pk(p, 32, 8, 64, u, null) == -3
+    q6 = lib.quik_quantize_fp6
+    q6.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, vp, i, vp]
+    assert q6(p, 4, 64, 64, null, 8, p, p, p, p, 8, null) == -2           # idx NULL with n_out
+    assert q6(p, 4, 60, 64, p, 8, p, p, p, p, 8, null) == -4              # K % 8
+    assert q6(p, 4, 32768, 32768, p, 8, p, p, p, p, 8, null) == -4        # K beyond the FP6 form's limit
+    g6 = lib.quik_gemm_dequant_fp6
+    g6.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, i, vp, i, vp, i, vp]
+    # (xq6, scale, zero, x_out, ldo, T, K_b, n_out, w6, w_scale, w_reduced, w_out, ldwo, bias, N, y, ldy, stream)
+    assert g6(p, p, p, p, 8, 4, 64, 8, p, p, p, p, 8, null, 8, null, 8, null) == -2
+    assert g6(p, p, p, p, 8, 4, 64, 8, p, p, p, p, 8, null, 8, p, 4, null) == -1      # ldy < N
+    assert g6(u, p, p, p, 8, 4, 64, 8, p, p, p, p, 8, null, 8, p, 8, null) == -3
+    assert g6(p, p, p, p, 4, 4, 64, 8, p, p, p, p, 8, null, 8, p, 8, null) == -1      # ldo < n_out
+    ig = lib.quik_int_gemm_fp6
+    ig.argtypes = [vp, vp, i, i, i, vp, i, vp]
+    assert ig(p, p, 4, 8, 64, null, 8, null) == -2
+    assert ig(p, p, 4, 8, 64, p, 4, null) == -1
+    lin = lib.quik_linear_fp6
+    lin.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
+    need = lib.quik_workspace_bytes_fp6(4, 64, 8, 8)
+    assert lin(p, 4, 64, 64, p, 8, p, p, p, p, 8, null, 8, p, 8, vp(0x1000), need - 1, null) == -5
+    assert lin(p, 4, 64, 64, p, 8, p, p, p, p, 8, null, 8, p, 8, null, need, null) == -2
+
+
+def test_e3m2_patterns_decode_to_the_integers():
+    """The test-side FP6 encoder (tests/util.py) against the format's value formula: 1 sign bit,
+    3 exponent bits with bias 3, 2 mantissa bits; e = 0 is subnormal."""
+    from tests.util import e3m2_pattern, fp6_panels
+    v = np.arange(-8, 9)
+    p = e3m2_pattern(v).astype(np.int64)
+    s, e, m = p >> 5, (p >> 2) & 7, p & 3
+    val = np.where(e == 0, m / 4.0 * 2.0 ** (1 - 3), (1 + m / 4.0) * 2.0 ** (e - 3.0)) * np.where(s == 1, -1.0, 1.0)
+    assert np.array_equal(val, v.astype(np.float64))
+    # layout: one row, columns 0..63 -> one 48-byte block; column 0 in the low six bits of byte 0,
+    # column 32 in the low six bits of byte 16, columns 21 / 53 straddle into bytes 32.. / 40..
+    q = np.zeros((1, 64), np.int64)
+    q[0, 0], q[0, 32], q[0, 31], q[0, 63] = 1, 2, -8, 7
+    blk = fp6_panels(q)[0, 0]
+    assert blk.shape == (48,)
+    assert blk[0] & 63 == 12 and blk[16] & 63 == 16
+    assert blk[39] >> 2 == 56 and blk[47] >> 2 == 23          # last column of each group: top six bits of its 24 bytes

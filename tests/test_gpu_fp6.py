@@ -27,16 +27,6 @@ def _sync():
     torch.cuda.synchronize()
 
 
-def test_e3m2_patterns_decode_to_the_integers():
-    """The test-side encoder against the format's value formula."""
-    from tests.util import e3m2_pattern
-    v = np.arange(-8, 9)
-    p = e3m2_pattern(v).astype(np.int64)
-    s, e, m = p >> 5, (p >> 2) & 7, p & 3
-    val = np.where(e == 0, m / 4.0 * 2.0 ** (1 - 3), (1 + m / 4.0) * 2.0 ** (e - 3.0)) * np.where(s == 1, -1.0, 1.0)
-    assert np.array_equal(val, v.astype(np.float64))
-
-
 # T, K, n_out: every row-caching variant of the quantization kernel up to 16384 columns, ragged
 # group / stage ends (K_b not a multiple of 32 or 128), no outliers, several rows per workgroup
 QUANT_SHAPES = [(16, 512, 32), (37, 520, 24), (5, 1024, 64), (33, 2048, 128), (64, 4096, 256), (19, 5120, 256),
@@ -60,6 +50,22 @@ def test_quantize_fp6_is_bit_exact(api, oracle, T, K, n_out):
         raise AssertionError(f"FP6 panels differ at {len(bad)} bytes, first {bad[:5].tolist()}")
     if n_out:
         assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16)), "x_out"
+
+
+@pytest.mark.parametrize("K", [4096, 6144, 8192, 11008, 16384])
+def test_quantize_fp6_many_rows_per_workgroup_repeated(api, oracle, K):
+    """As the integer form's test of the same name (tests/test_gpu_parity.py)."""
+    T = 1500
+    shp = synth.LayerShape("q6", T, K, 8, 256, 4, seed=77 + K)
+    inp = synth.make_inputs(shp)
+    q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, 4)
+    want = fp6_panels(q)
+    xd, idxd = to_dev(inp.x), to_dev(inp.outlier_idx)
+    for rep in range(3):
+        xq6, scale, zero, x_out = api.quik_quantize_fp6(xd, idxd)
+        _sync()
+        got = xq6.cpu().numpy()
+        assert np.array_equal(got, want), f"call {rep}: {int((got != want).sum())} bytes differ"
 
 
 @pytest.mark.parametrize("N,K_b", [(8, 32), (33, 480), (100, 3840), (7, 130), (64, 10752)])

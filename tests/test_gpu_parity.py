@@ -70,6 +70,27 @@ def test_quantize_is_bit_exact(api, oracle, T, K, n_out, bits):
     _quantize_case(api, oracle, inp.x, inp.outlier_idx, bits)
 
 
+@pytest.mark.parametrize("K", [4096, 6144, 8192, 11008, 16384])
+@pytest.mark.parametrize("bits", [4, 8])
+def test_quantize_many_rows_per_workgroup_repeated(api, oracle, K, bits):
+    """Every workgroup-per-row variant with several rows per workgroup and two or three workgroups per
+    CU, three calls in a row: a misread register in the second workgroup of a CU once produced wrong
+    packed bytes in some rows of some calls."""
+    T = 1500
+    shp = synth.LayerShape("q", T, K, 8, 256, bits, seed=77 + K)
+    inp = synth.make_inputs(shp)
+    q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, bits)
+    xd, idxd = to_dev(inp.x), to_dev(inp.outlier_idx)
+    want = None
+    for rep in range(3):
+        xq, scale, zero, x_out, cs = api.quik_quantize(xd, idxd, bits)
+        _sync()
+        if want is None:
+            want = expected_xq(oracle, q, bits, xq.shape[1])
+        got = xq.cpu().numpy()
+        assert np.array_equal(got, want), f"call {rep}: {int((got != want).sum())} packed bytes differ"
+
+
 def test_quantize_unsorted_indices_and_degenerate_rows(api, oracle):
     rng = np.random.default_rng(5)
     T, K = 12, 1024

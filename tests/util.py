@@ -69,21 +69,18 @@ def e3m2_pattern(v: np.ndarray) -> np.ndarray:
 
 def fp6_panels(q: np.ndarray) -> np.ndarray:
     """Signed codes int [R, K_b] -> the byte image of "FP6 panels" as include/quik.h defines them,
-    shaped [S, R, 96]: zero-padded to S stages of 128 columns; stage s of row r is block [s, r];
+    shaped [S, R, 48]: zero-padded to S stages of 64 columns; stage s of row r is block [s, r];
     a group of 32 columns is a 192-bit little-endian string (column j in bits [6j, 6j+6)); bytes
-    0..15 of group q = 2*ks + g go to byte 16 q of the block, bytes 16..23 to 64 + 16 g + 8 ks."""
+    0..15 of group g go to byte 16 g of the block, bytes 16..23 to byte 32 + 8 g."""
     R, K_b = q.shape
-    S = (K_b + 127) // 128
-    codes = np.zeros((R, 128 * S), np.uint8)
+    S = (K_b + 63) // 64
+    codes = np.zeros((R, 64 * S), np.uint8)
     codes[:, :K_b] = e3m2_pattern(q)
     bits = ((codes[:, :, None] >> np.arange(6, dtype=np.uint8)) & 1).astype(np.uint8)   # little-endian per code
-    strings = np.packbits(bits.reshape(R, 4 * S, 192), axis=2, bitorder="little")       # [R, 4S, 24] bytes
-    out = np.zeros((S, R, 96), np.uint8)
-    for s in range(S):
-        for qq in range(4):
-            ks, g = qq >> 1, qq & 1
-            grp = strings[:, 4 * s + qq, :]
-            out[s, :, 16 * qq: 16 * qq + 16] = grp[:, :16]
-            o = 64 + 16 * g + 8 * ks
-            out[s, :, o: o + 8] = grp[:, 16:]
+    strings = np.packbits(bits.reshape(R, 2 * S, 192), axis=2, bitorder="little")       # [R, 2S, 24] bytes
+    out = np.zeros((S, R, 48), np.uint8)
+    for g in range(2):
+        grp = strings[:, g::2, :]                      # [R, S, 24]: group g of every stage
+        out[:, :, 16 * g: 16 * g + 16] = grp[:, :, :16].transpose(1, 0, 2)
+        out[:, :, 32 + 8 * g: 40 + 8 * g] = grp[:, :, 16:].transpose(1, 0, 2)
     return out
