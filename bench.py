@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, MI355X data sheet (5.0 POP/s)
+PEAK_FP6_TOPS = 10100.0      # dense FP6 / FP4 matrix rate, MI355X data sheet (10.1 PFLOP/s)
 PEAK_HBM_GBS = 8000.0
 # profiles/gemm_kernel_llama7b_up.md: (47796 KiB * 2.0 + 44033 KiB * 1.0) * 1024
 TRAFFIC_BYTES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
@@ -115,6 +116,8 @@ def main():
     ap.add_argument("--sweep", choices=["tokens", "outliers"], default=None,
                     help="instead of the headline line, time the layer over a sweep of token counts "
                          "(1..8192) or outlier counts (0..1024) on the workload's K and N")
+    ap.add_argument("--no-fp6", action="store_true",
+                    help="skip the timing of the FP6-matrix-pipe form of the 4-bit layer")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (a kernel of known "
                          "traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
@@ -220,6 +223,30 @@ def main():
         ablation[f"v{version}"] = _event_ms(fn, it, torch)
     del ws_abl
 
+    # the same 4-bit layer with the integer product on the FP6 matrix pipe (exact; reported beside the
+    # headline, which stays on the int8-MFMA path the benchmark spec names)
+    fp6 = None
+    if bits == 4 and not mixed and K <= 16384 and not args.no_fp6:
+        w6 = api.quik_weight_pack_fp6(w_q, K_b)
+        ws6 = torch.empty(api.quik_workspace_bytes_fp6(T, K, N, n_out), dtype=torch.uint8, device=dev)
+        step6, _ = api.prepare_linear_fp6(x, idx, w6, w_scale, w_red, w_out, out=y, workspace=ws6)
+        q6 = api.quik_quantize_fp6(x, idx)
+        gemm6 = api.prepare_gemm_dequant_fp6(q6[0], q6[1], q6[2], q6[3] if n_out else None, K_b, w6, w_scale,
+                                             w_red, w_out, None, y)
+        quant6 = api.prepare_quantize_fp6(x, idx, q6)
+        for _ in range(max(10, args.warmup // 2)):
+            step6()
+        ms6_layer = _event_ms(step6, it, torch)
+        ms6_gemm = _event_ms(gemm6, it, torch)
+        ms6_quant = _event_ms(quant6, it, torch)
+        fp6 = {"layer_ms": ms6_layer, "layer_TOPS": 2.0 * T * K * N / (ms6_layer * 1e-3) / 1e12,
+               "kernels_ms": {"quik_quantize_fp6": ms6_quant, "quik_gemm_dequant_fp6": ms6_gemm},
+               "roofline": {"bound": "mfma", "kernel": "gemm_fp6_kernel", "peak": PEAK_FP6_TOPS, "unit": "TOP/s",
+                            "achieved": 2.0 * T * K_b * N / (ms6_gemm * 1e-3) / 1e12,
+                            "frac": 2.0 * T * K_b * N / (ms6_gemm * 1e-3) / 1e12 / PEAK_FP6_TOPS},
+               "operand_bytes_per_element": 0.75}
+        del w6, ws6, q6
+
     ms_fp16 = None
     if not args.no_fp16:
         wf = (torch.randn((N, K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
@@ -263,6 +290,8 @@ def main():
                      "traffic": TRAFFIC_BYTES.get(args.workload),
                      "algorithmic_ops_per_launch": ops_int},
     }
+    if fp6 is not None:
+        out["fp6_path"] = fp6
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, shp)
     print(json.dumps(out))
