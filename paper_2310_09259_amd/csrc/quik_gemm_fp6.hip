@@ -445,9 +445,14 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
 
 template <int MODE>
 hipError_t dispatch6(const GemmArgs& a, hipStream_t stream) {
-    const long big = (long)((a.T + 255) / 256) * ((a.N + 191) / 192);
-    if (a.T > 128 && big >= 128) return launch_cfg<256, 192, 4, 2, 7, 4, MODE>(a, stream);
-    return launch_cfg<128, 128, 2, 2, 6, 0, MODE>(a, stream);
+    // One workgroup of eight waves per CU, so a launch runs in ceil(tiles / 256) rounds; a 256 x 192 tile
+    // takes about 1.4x as long as a 256 x 128 one.  Few tokens or few tiles: 128 x 128 tiles, two
+    // workgroups per CU.
+    auto rounds = [&](int bm, int bn) { return (((long)(a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn) + 255) / 256; };
+    const long tiles_128 = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
+    if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 6, 0, MODE>(a, stream);
+    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 7, 4, MODE>(a, stream);
+    return launch_cfg<256, 128, 4, 2, 8, 4, MODE>(a, stream);
 }
 
 }  // namespace

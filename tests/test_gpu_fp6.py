@@ -106,6 +106,8 @@ LINEAR_SHAPES = [
     # eight-wave 256 x 192 tiles (>= 128 of them), ragged T and N, K_b not a multiple of 128
     synth.LayerShape("big_tiles_ragged", 520, 512, 11000, 32, 4, seed=38),
     synth.LayerShape("big_tiles_k", 700, 1320, 5000, 40, 4, seed=51),
+    # 256 x 128 tiles (the 1.5x-area tile would not save a round here), ragged T and N
+    synth.LayerShape("tiles_256x128", 1030, 256, 15300, 24, 4, seed=53),
 ]
 
 
