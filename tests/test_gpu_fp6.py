@@ -151,3 +151,42 @@ def test_fp6_worst_case_magnitudes_stay_exact(api, oracle):
     want = q.astype(np.int64) @ w.astype(np.int64).T
     assert want.max() == 64 * K_b
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), want)
+
+
+FULL_SIZE = ["llama7b_up", "llama7b_down", "llama13b_qkv_t128", "llama13b_qkv_t1024", "llama13b_qkv_t4096",
+             "llama70b_up"]
+
+
+@pytest.mark.parametrize("name", FULL_SIZE)
+def test_full_size_workloads_on_sampled_tokens_fp6(api, oracle, name):
+    """The 4-bit benchmark workloads at full size on the FP6 path, in the launch configuration
+    bench.py times: quantization checked in full (panels, scale, zero, outlier block), the output on
+    sampled token rows, and the whole output against the int8-MFMA path's (bit-identical where that
+    path runs its large-tile kernel, i.e. above 32 tokens)."""
+    import torch
+    shp = synth.CONFIGS[name]
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w6 = api.quik_weight_pack_fp6(d["w_q"], shp.K_b)
+    xq6, scale, zero, x_out = api.quik_quantize_fp6(d["x"], d["idx"])
+    y = api.quik_linear_fp6(d["x"], d["idx"], w6, d["w_scale"], w_red, d["w_out"])
+    _sync()
+    q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, 4)
+    assert np.array_equal(xq6.cpu().numpy(), fp6_panels(q))
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
+    assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32))
+    assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16))
+    T = shp.T
+    sel = np.unique(np.array([0, 1, 31, 32, 127, 128, 255, 256, T // 2 - 1, T // 2, T - 2, T - 1]) % T)
+    ref = oracle.linear(inp.x[sel], inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
+    ok, worst = output_within_tolerance(y[torch.from_numpy(sel).cuda()].cpu().numpy(), ref.y)
+    assert ok, worst
+    y_int = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    _sync()
+    assert torch.equal(y.view(torch.int16), y_int.view(torch.int16))
+    del y, y_int
+    # exact accumulators of the sampled rows (their panels are built by the test-side packer)
+    acc = api.quik_int_gemm_fp6(to_dev(fp6_panels(ref.q)), w6, shp.K_b)
+    _sync()
+    assert np.array_equal(acc.cpu().numpy(), ref.acc)
