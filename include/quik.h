@@ -294,6 +294,64 @@ int quik_linear_fp6(const void *x, int T, int K, int ldx, const int32_t *outlier
                     void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * QUIK-4B for 2:4-sparse weights (the joint INT4 + 2:4 format of Section 4.3.2, "Sparsity"; the
+ * arithmetic is Algorithm 1 unchanged, with a weight matrix in which at most two of every four
+ * consecutive base columns 4i .. 4i+3 are nonzero).  The integer product runs on the sparse int8
+ * matrix instruction of gfx950 (twice the dense int8 rate, exact INT32 accumulation); results are
+ * those of the bits = 4 entry points for the same matrices.
+ *
+ * Both operands are stored stage by stage: the K_b columns are padded with zeros to
+ * S = ceil(K_b / 64) stages of 64 columns, and the rows of a stage follow each other.
+ *   activations xq24: stage s of token t is the 32-byte block at byte (s * T + t) * 32
+ *     (S * T * 32 bytes; quik_sp24_act_row_bytes(K_b) = 32 S).  Byte 4 m + p of a block holds the
+ *     signed codes (two's complement nibbles) of columns 8 m + p (high nibble) and 8 m + 4 + p
+ *     (low nibble) of the stage.
+ *   weights w24: stage s of channel n is the 24-byte block at byte (s * R + n) * 24 with
+ *     R = N rounded up to even (quik_sp24_weight_bytes(N, K_b) = S * R * 24 bytes).  A block is two
+ *     8-byte value fields (halves h = 0, 1), then two 4-byte index words (h = 0, 1).  The group
+ *     of four columns kappa (0 .. 15) of the stage belongs to half h = (kappa / 4) % 2, pair
+ *     q = 4 (kappa / 8) + kappa % 4; its two kept values are values c = 2 q and 2 q + 1 of the
+ *     half: value c is a two's complement nibble in dword c / 8 of the field, byte c % 4, low
+ *     nibble if (c / 4) % 2 == 0, else high; bits [2 c, 2 c + 2) of the half's index word give its
+ *     position 0 .. 3 in the group.  Kept positions: the nonzero ones, filled up to two with the
+ *     lowest unused positions, ascending.
+ *
+ *  quik_weight_pack_sp24   offline: packed signed 4-bit weights w_q [N, ldw] (weight nibble order
+ *                          of quik.h, ldw >= K_b/2, K_b even) -> w24.  `violations` (DEVICE int32,
+ *                          may be NULL) is incremented by the number of groups with more than two
+ *                          nonzero values (such a group keeps only its first two: clear the counter
+ *                          before the call, read it after the stream has finished, and reject the
+ *                          matrix unless it is 0).  w_scale, w_reduced, w_out stay as for bits = 4
+ *                          (no code sums).
+ *  quik_quantize_sp24      quik_quantize(bits = 4) with the packed output as xq24; scale, zero,
+ *                          x_out as there; K <= 16384.
+ *  quik_gemm_dequant_sp24  quik_gemm_dequant for these operands.
+ *  quik_int_gemm_sp24      acc[t,n] = sum_k q[t,k] * w[n,k] as INT32 (test hook).
+ *  quik_linear_sp24        quik_quantize_sp24 + quik_gemm_dequant_sp24 on one stream; workspace of
+ *                          quik_workspace_bytes_sp24(T, K, N, n_out) bytes, 256-byte aligned.
+ * All pointers are DEVICE pointers (16-byte aligned where the integer forms require it); error
+ * behaviour as for the integer forms; additionally QUIK_EUNSUPPORTED if xq24 or w24 reaches 4 GB.
+ */
+int quik_sp24_act_row_bytes(int K_b);
+size_t quik_sp24_weight_bytes(int N, int K_b);
+size_t quik_workspace_bytes_sp24(int T, int K, int N, int n_out);
+int quik_weight_pack_sp24(const void *w_q, int ldw, int N, int K_b, void *w24,
+                          int32_t *violations, void *stream);
+int quik_quantize_sp24(const void *x, int T, int K, int ldx, const int32_t *outlier_idx, int n_out,
+                       void *xq24, float *scale, float *zero, void *x_out, int ldo, void *stream);
+int quik_gemm_dequant_sp24(const void *xq24, const float *scale, const float *zero,
+                           const void *x_out, int ldo, int T, int K_b, int n_out,
+                           const void *w24, const void *w_scale, const float *w_reduced,
+                           const void *w_out, int ldwo, const void *bias, int N,
+                           void *y, int ldy, void *stream);
+int quik_int_gemm_sp24(const void *xq24, const void *w24, int T, int N, int K_b,
+                       int32_t *acc, int ldacc, void *stream);
+int quik_linear_sp24(const void *x, int T, int K, int ldx, const int32_t *outlier_idx, int n_out,
+                     const void *w24, const void *w_scale, const float *w_reduced,
+                     const void *w_out, int ldwo, const void *bias, int N,
+                     void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Host-side validator for an outlier index list (HOST pointer): returns QUIK_OK
  * if all n_out entries are unique and inside [0, K), QUIK_EINVAL otherwise.
  */

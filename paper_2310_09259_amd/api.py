@@ -76,6 +76,22 @@ def load() -> C.CDLL:
         lib.quik_gemm_dequant_fp6.argtypes = [vp, f, f, vp, i, i, i, i, vp, vp, f, vp, i, vp, i, vp, i, vp]
         lib.quik_int_gemm_fp6.restype = i
         lib.quik_int_gemm_fp6.argtypes = [vp, vp, i, i, i, vp, i, vp]
+        lib.quik_sp24_act_row_bytes.restype = i
+        lib.quik_sp24_act_row_bytes.argtypes = [i]
+        lib.quik_sp24_weight_bytes.restype = C.c_size_t
+        lib.quik_sp24_weight_bytes.argtypes = [i, i]
+        lib.quik_workspace_bytes_sp24.restype = C.c_size_t
+        lib.quik_workspace_bytes_sp24.argtypes = [i, i, i, i]
+        lib.quik_weight_pack_sp24.restype = i
+        lib.quik_weight_pack_sp24.argtypes = [vp, i, i, i, vp, vp, vp]
+        lib.quik_quantize_sp24.restype = i
+        lib.quik_quantize_sp24.argtypes = [vp, i, i, i, vp, i, vp, f, f, vp, i, vp]
+        lib.quik_gemm_dequant_sp24.restype = i
+        lib.quik_gemm_dequant_sp24.argtypes = [vp, f, f, vp, i, i, i, i, vp, vp, f, vp, i, vp, i, vp, i, vp]
+        lib.quik_int_gemm_sp24.restype = i
+        lib.quik_int_gemm_sp24.argtypes = [vp, vp, i, i, i, vp, i, vp]
+        lib.quik_linear_sp24.restype = i
+        lib.quik_linear_sp24.argtypes = [vp, i, i, i, vp, i, vp, vp, f, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
         lib.quik_linear_fp6.restype = i
         lib.quik_linear_fp6.argtypes = [vp, i, i, i, vp, i, vp, vp, f, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
         lib.quik_check_outlier_idx_host.restype = i
@@ -473,6 +489,152 @@ def prepare_linear_fp6(x, outlier_idx, w6, w_scale, w_reduced, w_out, bias=None,
     args = _linear_fp6_args(x, outlier_idx, w6, w_scale, w_reduced, w_out, bias, y, workspace)
     keep = (x, outlier_idx, w6, w_scale, w_reduced, w_out, bias, y, workspace)
     return _prepared(load().quik_linear_fp6, "quik_linear_fp6", args, keep), y
+
+
+# ---- 2:4-sparse weights on the sparse int8 matrix instruction ------------------------------------
+
+def quik_sp24_act_row_bytes(K_b: int) -> int:
+    return load().quik_sp24_act_row_bytes(K_b)
+
+
+def quik_sp24_weight_bytes(N: int, K_b: int) -> int:
+    return load().quik_sp24_weight_bytes(N, K_b)
+
+
+def quik_workspace_bytes_sp24(T: int, K: int, N: int, n_out: int) -> int:
+    return load().quik_workspace_bytes_sp24(T, K, N, n_out)
+
+
+def quik_weight_pack_sp24(w_q, K_b: int, check: bool = True):
+    """packed signed 4-bit weights uint8 [N, ldw] -> uint8 [stages, N rounded up to even, 24].
+
+    With check (the default) the call waits for the result and raises unless every group of four
+    columns has at most two nonzero values."""
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    N = w_q.shape[0]
+    nbytes = quik_sp24_weight_bytes(N, K_b)
+    if nbytes <= 0:
+        raise QuikError(-1, "quik_sp24_weight_bytes")
+    stages = quik_sp24_act_row_bytes(K_b) // 32
+    w24 = torch.empty((stages, nbytes // (24 * stages), 24), dtype=torch.uint8, device=w_q.device)
+    violations = torch.zeros(1, dtype=torch.int32, device=w_q.device) if check else None
+    rc = load().quik_weight_pack_sp24(_ptr(w_q), w_q.stride(0), N, K_b, _ptr(w24), _ptr(violations), _stream())
+    _check(rc, "quik_weight_pack_sp24")
+    if check and int(violations.item()) != 0:
+        raise QuikError(-1, "quik_weight_pack_sp24: %d groups of four with more than two nonzero weights"
+                        % int(violations.item()))
+    return w24
+
+
+def quik_quantize_sp24(x, outlier_idx, out=None):
+    """x fp16 [T,K] -> (xq24 uint8 [stages,T,32], scale f32 [T], zero f32 [T], x_out f16 [T,n_out])."""
+    x = _dev(x, torch.float16, "x")
+    T, K = x.shape
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    if n_out:
+        _dev(outlier_idx, torch.int32, "outlier_idx")
+    ld = quik_sp24_act_row_bytes(K - n_out)
+    if ld <= 0:
+        raise QuikError(-1, "quik_sp24_act_row_bytes")
+    if out is None:
+        xq24 = torch.empty((ld // 32, T, 32), dtype=torch.uint8, device=x.device)
+        scale = torch.empty(T, dtype=torch.float32, device=x.device)
+        zero = torch.empty(T, dtype=torch.float32, device=x.device)
+        x_out = torch.empty((T, n_out), dtype=torch.float16, device=x.device)
+    else:
+        xq24, scale, zero, x_out = out
+    rc = load().quik_quantize_sp24(_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out,
+                                   _ptr(xq24), _ptr(scale), _ptr(zero),
+                                   _ptr(x_out) if n_out else None, x_out.stride(0) if n_out else 0, _stream())
+    _check(rc, "quik_quantize_sp24")
+    return xq24, scale, zero, x_out
+
+
+def _gemm_dequant_sp24_args(xq24, scale, zero, x_out, K_b, w24, w_scale, w_reduced, w_out, bias, y):
+    T, N = xq24.shape[1], int(w_scale.numel())
+    n_out = 0 if x_out is None else int(x_out.shape[1])
+    return (_ptr(xq24), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
+            x_out.stride(0) if n_out else 0, T, K_b, n_out, _ptr(w24), _ptr(w_scale), _ptr(w_reduced),
+            _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0),
+            _stream())
+
+
+def quik_gemm_dequant_sp24(xq24, scale, zero, x_out, K_b: int, w24, w_scale, w_reduced, w_out, bias=None, out=None):
+    xq24 = _dev(xq24, torch.uint8, "xq24")
+    w24 = _dev(w24, torch.uint8, "w24")
+    y = out if out is not None else torch.empty((xq24.shape[1], int(w_scale.numel())), dtype=torch.float16,
+                                                device=xq24.device)
+    rc = load().quik_gemm_dequant_sp24(*_gemm_dequant_sp24_args(xq24, scale, zero, x_out, K_b, w24, w_scale,
+                                                                w_reduced, w_out, bias, y))
+    _check(rc, "quik_gemm_dequant_sp24")
+    return y
+
+
+def prepare_gemm_dequant_sp24(xq24, scale, zero, x_out, K_b: int, w24, w_scale, w_reduced, w_out, bias, out):
+    """Marshal-once form of quik_gemm_dequant_sp24 writing into `out`."""
+    args = _gemm_dequant_sp24_args(xq24, scale, zero, x_out, K_b, w24, w_scale, w_reduced, w_out, bias, out)
+    keep = (xq24, scale, zero, x_out, w24, w_scale, w_reduced, w_out, bias, out)
+    return _prepared(load().quik_gemm_dequant_sp24, "quik_gemm_dequant_sp24", args, keep)
+
+
+def prepare_quantize_sp24(x, outlier_idx, out):
+    """Marshal-once form of quik_quantize_sp24 writing into out = (xq24, scale, zero, x_out)."""
+    x = _dev(x, torch.float16, "x")
+    T, K = x.shape
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    xq24, scale, zero, x_out = out
+    args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(xq24),
+            _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None, x_out.stride(0) if n_out else 0, _stream())
+    return _prepared(load().quik_quantize_sp24, "quik_quantize_sp24", args, (x, outlier_idx, out))
+
+
+def quik_int_gemm_sp24(xq24, w24, N: int, K_b: int):
+    xq24 = _dev(xq24, torch.uint8, "xq24")
+    w24 = _dev(w24, torch.uint8, "w24")
+    T = xq24.shape[1]
+    acc = torch.empty((T, N), dtype=torch.int32, device=xq24.device)
+    rc = load().quik_int_gemm_sp24(_ptr(xq24), _ptr(w24), T, N, K_b, _ptr(acc), acc.stride(0), _stream())
+    _check(rc, "quik_int_gemm_sp24")
+    return acc
+
+
+def _linear_sp24_args(x, outlier_idx, w24, w_scale, w_reduced, w_out, bias, y, workspace):
+    T, K = x.shape
+    N = int(w_scale.numel())
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    return (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, _ptr(w24),
+            _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0,
+            _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace), workspace.numel(), _stream())
+
+
+def _linear_sp24_buffers(x, outlier_idx, w24, w_scale, out, workspace):
+    x = _dev(x, torch.float16, "x")
+    w24 = _dev(w24, torch.uint8, "w24")
+    T, K = x.shape
+    N = int(w_scale.numel())
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    need = quik_workspace_bytes_sp24(T, K, N, n_out)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
+    return y, workspace
+
+
+def quik_linear_sp24(x, outlier_idx, w24, w_scale, w_reduced, w_out, bias=None, out=None, workspace=None):
+    """Whole 4-bit layer with 2:4-sparse weights.  Returns y fp16 [T, N]."""
+    y, workspace = _linear_sp24_buffers(x, outlier_idx, w24, w_scale, out, workspace)
+    rc = load().quik_linear_sp24(*_linear_sp24_args(x, outlier_idx, w24, w_scale, w_reduced, w_out, bias, y,
+                                                    workspace))
+    _check(rc, "quik_linear_sp24")
+    return y
+
+
+def prepare_linear_sp24(x, outlier_idx, w24, w_scale, w_reduced, w_out, bias=None, out=None, workspace=None):
+    """Marshal-once form of quik_linear_sp24: returns (call, y)."""
+    y, workspace = _linear_sp24_buffers(x, outlier_idx, w24, w_scale, out, workspace)
+    args = _linear_sp24_args(x, outlier_idx, w24, w_scale, w_reduced, w_out, bias, y, workspace)
+    keep = (x, outlier_idx, w24, w_scale, w_reduced, w_out, bias, y, workspace)
+    return _prepared(load().quik_linear_sp24, "quik_linear_sp24", args, keep), y
 
 
 def quik_ablation_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int) -> int:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquik.so")
-SOURCES = ["quik_api.hip", "quik_quantize.hip", "quik_gemm.hip", "quik_gemm_fp6.hip", "quik_unfused.hip"]
+SOURCES = ["quik_api.hip", "quik_quantize.hip", "quik_gemm.hip", "quik_gemm_fp6.hip", "quik_gemm_sp24.hip", "quik_unfused.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

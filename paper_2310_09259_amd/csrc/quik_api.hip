@@ -463,6 +463,126 @@ int quik_linear_fp6(const void* x, int T, int K, int ldx, const int32_t* outlier
                                  bias, N, y, ldy, stream);
 }
 
+// ---- 2:4-sparse weights on the sparse int8 matrix instruction -----------------------------------
+
+int quik_sp24_act_row_bytes(int K_b) {
+    if (K_b <= 0 || K_b >= kMaxKb) return 0;
+    return 32 * ((K_b + 63) / 64);
+}
+
+size_t quik_sp24_weight_bytes(int N, int K_b) {
+    if (N <= 0 || K_b <= 0 || K_b >= kMaxKb) return 0;
+    return (size_t)((K_b + 63) / 64) * (size_t)quik::sp24_weight_rows(N) * 24u;
+}
+
+size_t quik_workspace_bytes_sp24(int T, int K, int N, int n_out) {
+    (void)N;
+    if (T <= 0 || K <= 0 || n_out < 0 || n_out >= K) return 0;
+    const int rb = quik_sp24_act_row_bytes(K - n_out);
+    if (rb <= 0) return 0;
+    return up256((size_t)T * rb) + 2 * up256((size_t)T * sizeof(float)) + up256((size_t)T * (n_out ? n_out : 1) * 2);
+}
+
+int quik_weight_pack_sp24(const void* w_q, int ldw, int N, int K_b, void* w24, int32_t* violations, void* stream) {
+    if (N <= 0 || K_b <= 0 || K_b % 2 || ldw < K_b / 2) return QUIK_EINVAL;
+    if (!w_q || !w24) return QUIK_ENULL;
+    if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
+    if (!aligned16(w24)) return QUIK_EALIGN;
+    if (violations && (reinterpret_cast<uintptr_t>(violations) & 3u)) return QUIK_EALIGN;
+    return quik::launch_weight_pack_sp24(w_q, ldw, N, K_b, w24, violations, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess
+               ? QUIK_OK
+               : QUIK_ELAUNCH;
+}
+
+int quik_quantize_sp24(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out, void* xq24,
+                       float* scale, float* zero, void* x_out, int ldo, void* stream) {
+    // same argument rules as the 4-bit integer form, except for the layout of the packed output
+    int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, 4, xq24, 16 * ((K + 15) / 16), scale, zero, x_out, ldo);
+    if (rc != QUIK_OK) return rc;
+    if (K > 16384) return QUIK_EUNSUPPORTED;
+    quik::QuantizeArgs a{x, T, K, ldx, outlier_idx, n_out, 4, xq24, quik_sp24_act_row_bytes(K - n_out), scale, zero,
+                         x_out, ldo, nullptr, 2};
+    return quik::launch_quantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK : QUIK_ELAUNCH;
+}
+
+namespace {
+int check_gemm_sp24(const void* xq24, const void* x_out, int ldo, int T, int K_b, int n_out, const void* w24,
+                    const void* w_out, int ldwo, int N) {
+    if (T <= 0 || N <= 0 || K_b <= 0 || n_out < 0) return QUIK_EINVAL;
+    if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
+    // both buffers must stay below 4 GB (32-bit stage offsets inside the copy descriptors)
+    if ((uint64_t)quik_sp24_act_row_bytes(K_b) * (uint64_t)T >= (1ull << 32)) return QUIK_EUNSUPPORTED;
+    if ((uint64_t)quik_sp24_weight_bytes(N, K_b) >= (1ull << 32)) return QUIK_EUNSUPPORTED;
+    if (n_out > 0 && (ldo < n_out || ldwo < n_out)) return QUIK_EINVAL;
+    if (!xq24 || !w24) return QUIK_ENULL;
+    if (n_out > 0 && (!x_out || !w_out)) return QUIK_ENULL;
+    if (n_out % 8) return QUIK_EUNSUPPORTED;
+    if (n_out > 0 && (ldo % 8 || ldwo % 8)) return QUIK_EALIGN;
+    if (!aligned16(xq24) || !aligned16(w24)) return QUIK_EALIGN;
+    if (n_out > 0 && (!aligned16(x_out) || !aligned16(w_out))) return QUIK_EALIGN;
+    return QUIK_OK;
+}
+}  // namespace
+
+int quik_gemm_dequant_sp24(const void* xq24, const float* scale, const float* zero, const void* x_out, int ldo, int T,
+                           int K_b, int n_out, const void* w24, const void* w_scale, const float* w_reduced,
+                           const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy, void* stream) {
+    int rc = check_gemm_sp24(xq24, x_out, ldo, T, K_b, n_out, w24, w_out, ldwo, N);
+    if (rc != QUIK_OK) return rc;
+    if (ldy < N) return QUIK_EINVAL;
+    if (!scale || !zero || !w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    quik::GemmArgs a{};
+    a.xq = xq24; a.scale = scale; a.zero = zero; a.x_out = x_out; a.ldo = ldo;
+    a.T = T; a.K_b = K_b; a.n_out = n_out; a.bits = 4;
+    a.w_q = w24; a.w_scale = w_scale; a.w_reduced = w_reduced;
+    a.w_out = w_out; a.ldwo = ldwo; a.bias = bias; a.N = N;
+    a.y = y; a.ldy = ldy; a.acc = nullptr; a.ldacc = 0;
+    return quik::launch_gemm_sp24(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK : QUIK_ELAUNCH;
+}
+
+int quik_int_gemm_sp24(const void* xq24, const void* w24, int T, int N, int K_b, int32_t* acc, int ldacc,
+                       void* stream) {
+    int rc = check_gemm_sp24(xq24, nullptr, 0, T, K_b, 0, w24, nullptr, 0, N);
+    if (rc != QUIK_OK) return rc;
+    if (ldacc < N) return QUIK_EINVAL;
+    if (!acc) return QUIK_ENULL;
+    quik::GemmArgs a{};
+    a.xq = xq24; a.T = T; a.K_b = K_b; a.n_out = 0; a.bits = 4;
+    a.w_q = w24; a.N = N; a.y = nullptr; a.acc = acc; a.ldacc = ldacc;
+    return quik::launch_gemm_sp24(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK : QUIK_ELAUNCH;
+}
+
+int quik_linear_sp24(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out, const void* w24,
+                     const void* w_scale, const float* w_reduced, const void* w_out, int ldwo, const void* bias,
+                     int N, void* y, int ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    const size_t need = quik_workspace_bytes_sp24(T, K, N, n_out);
+    if (need == 0) return QUIK_EINVAL;
+    if (!workspace) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUIK_EALIGN;
+    if (workspace_bytes < need) return QUIK_EWORKSPACE;
+    const int K_b = K - n_out, rb = quik_sp24_act_row_bytes(K_b);
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    void* xq24 = base;
+    float* scale = reinterpret_cast<float*>(base + up256((size_t)T * rb));
+    float* zero = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(scale) + up256((size_t)T * sizeof(float)));
+    void* x_out = reinterpret_cast<uint8_t*>(zero) + up256((size_t)T * sizeof(float));
+    // validate both stages before anything is enqueued
+    int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, 4, xq24, 16 * ((K + 15) / 16), scale, zero, x_out, n_out);
+    if (rc != QUIK_OK) return rc;
+    if (K > 16384) return QUIK_EUNSUPPORTED;
+    rc = check_gemm_sp24(xq24, x_out, n_out, T, K_b, n_out, w24, w_out, ldwo, N);
+    if (rc != QUIK_OK) return rc;
+    if (ldy < N) return QUIK_EINVAL;
+    if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
+    if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    rc = quik_quantize_sp24(x, T, K, ldx, outlier_idx, n_out, xq24, scale, zero, x_out, n_out, stream);
+    if (rc != QUIK_OK) return rc;
+    return quik_gemm_dequant_sp24(xq24, scale, zero, x_out, n_out, T, K_b, n_out, w24, w_scale, w_reduced, w_out,
+                                  ldwo, bias, N, y, ldy, stream);
+}
+
 int quik_check_outlier_idx_host(const int32_t* idx, int n_out, int K) {
     if (n_out < 0 || K <= 0 || n_out >= K) return QUIK_EINVAL;
     if (n_out > 0 && !idx) return QUIK_ENULL;

@@ -1,0 +1,557 @@
+// QUIK-4B linear layer for 2:4-sparse weights, the integer product computed by the sparse int8 matrix
+// instruction of gfx950 (Algorithm 1 of arXiv 2310.09259: "INTmatmul", "Dequantization", "FPmatmul",
+// final add, with the epilogue fusion of Section 3.4; the weight format is the joint INT4 + 2:4 one of
+// Section 4.3.2).  v_smfmac_i32_32x32x64_i8 runs at twice the dense int8 rate and accumulates exactly in
+// INT32.  Operand formats and the measured register layout of the instruction: quik_sp24_device.h.
+//
+// The sparse operand is the instruction's first one, so it carries the weights: an accumulator register
+// belongs to an output channel and a lane to a token, the transpose of the dense kernels' arrangement.
+// Per-token parameters therefore live in registers, per-channel ones in LDS, and a lane converts four
+// neighbouring channels of its token at a time.
+//
+// A workgroup of WM x WN waves owns a BM (tokens) x BN (channels) output tile.  A stage is 64 columns = one
+// matrix step: 32 bytes per token row and 24 per weight row, stored stage by stage, so the tile's rows of
+// a stage are two contiguous runs that 16-byte-per-lane DMA instructions copy global -> LDS.  As in the
+// FP6 kernel the K loop is bound by the bytes a CU keeps in flight, so the stage ring takes most of the
+// LDS.  One workgroup barrier per stage; right after it the buffer read during the previous stage is
+// refilled, and while the matrix instructions of stage s issue, the packed words of stage s + 1 are
+// read from LDS and widened to int8 (two or three VALU operations per two operand registers).  The 32-byte
+// activation rows exchange their two pieces in every second group of eight rows (bank conflicts); the
+// 24-byte weight rows need no swizzle.  The fp16 outlier columns run through the same ring as stages of 16
+// columns, with the dequantized integer part as the C operand of v_mfma_f32_32x32x16_f16 (weights first,
+// so the accumulator layout is the same).  Rows beyond T / N are out of range for the per-stage buffer
+// descriptors and arrive as zeros.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "quik_kernels.h"
+#include "quik_gemm_device.h"
+#include "quik_sp24_device.h"
+
+namespace quik {
+
+namespace {
+
+using namespace gemm_dev;
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ int swz_f(int r) { return (r >> 3) & 1; }   // 32-byte rows, two pieces
+
+// descriptor r moved forward by `bytes`
+__device__ __forceinline__ v4i advance(v4i r, uint32_t bytes) {
+    const uint64_t base = (((uint64_t)(uint32_t)r[1]) << 32 | (uint32_t)r[0]) + bytes;
+    r[0] = (int)(uint32_t)base;
+    r[1] = (int)(uint32_t)(base >> 32);
+    return r;
+}
+
+// rows of a weight stage in memory: N rounded up to even, so that every stage starts 16-byte aligned
+__host__ __device__ inline int weight_rows(int N) { return (N + 1) & ~1; }
+
+// MODE 0: fused epilogue, fp16 output; MODE 1: the integer accumulators as INT32.
+template <int BM, int BN, int WM, int WN, int NST, int GM, int MODE>
+__global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp24_kernel(GemmArgs a) {
+    constexpr bool RAW = MODE != 0;
+    // claim the whole register budget of the launch bounds, so that the highest allocated register is
+    // never a live one (see the note in the row-quantization kernel)
+    asm volatile("" ::: "v255");
+    constexpr int NWAVES = WM * WN, NT = NWAVES * 64;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NF = TM + TN, SL = TM * TN;
+    constexpr int A_BYTES = BM * sp24::kActBytes;
+    // DMA instructions of a stage (1 KB each): N_A + N_B over the tile's two runs (the last one of the
+    // weights may be partly empty); fp16 stages BM / 32 and BN / 32.  A wave issues LPS per stage:
+    // instruction i = wave + NWAVES * slot; one that does not exist is issued empty so that every wave
+    // counts the same number.
+    constexpr int N_A = A_BYTES / 1024, N_B = (BN * sp24::kWgtBytes + 1023) / 1024, N_AF = BM / 32, N_BF = BN / 32;
+    constexpr int B_BYTES = N_B * 1024;
+    constexpr int ST_BYTES = (A_BYTES + B_BYTES > (BM + BN) * 32) ? A_BYTES + B_BYTES : (BM + BN) * 32;
+    constexpr int N_MAX = (N_A + N_B > N_AF + N_BF) ? N_A + N_B : N_AF + N_BF;
+    constexpr int LPS = (N_MAX + NWAVES - 1) / NWAVES;
+    static_assert(BM % 64 == 0 && BN % 64 == 0 && BN <= NT, "geometry");
+    static_assert(NST * LPS < 64, "vmcnt range");
+    static_assert(SL >= 4 && SL >= LPS, "a stage has too few matrix instructions to place its reads and copies");
+    constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
+
+    __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES + 1024];
+    __shared__ __align__(16) float lds_sw[BN];            // scaleWeight / 256
+    __shared__ __align__(16) float lds_wr[BN];            // wReduced
+    __shared__ __align__(16) float lds_bv[BN];            // bias
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave_u / WN, wn = wave_u % WN;
+    const int l32 = lane & 31, g = lane >> 5;
+
+    const int tiles_m = (a.T + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    const int id = xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n);
+    int tile_m, tile_n;
+    if constexpr (GM > 0) {
+        const int per_group = GM * tiles_n;
+        const int grp = id / per_group, rem = id % per_group;
+        const int first_m = grp * GM;
+        const int gsz = min(GM, tiles_m - first_m);
+        tile_m = first_m + rem % gsz;
+        tile_n = rem / gsz;
+    } else {
+        tile_m = id % tiles_m;
+        tile_n = id / tiles_m;
+    }
+    const int t0 = tile_m * BM, n0 = tile_n * BN;
+
+    const int S = sp24::stages(a.K_b);
+    const int nk_int = a.fp_only ? 0 : S;
+    const int fp_bytes = a.n_out * 2;
+    const int nk_fp = RAW ? 0 : (fp_bytes + 31) / 32;
+    const int nk = nk_int + nk_fp;
+    const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
+    const uint32_t strideA = (uint32_t)a.T * sp24::kActBytes;                  // bytes from stage to stage
+    const uint32_t strideB = (uint32_t)weight_rows(a.N) * sp24::kWgtBytes;
+
+    // stage 0 of the tile's rows
+    const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * sp24::kActBytes, (size_t)(a.T - t0) * sp24::kActBytes);
+    // (range rounded up to whole 16-byte pieces: for an odd N it ends inside the zero padding row)
+    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * sp24::kWgtBytes,
+                             ((size_t)(a.N - n0) * sp24::kWgtBytes + 15) & ~(size_t)15);
+    const v4i rAf = make_rsrc(a.n_out ? (const uint8_t*)a.x_out + (size_t)t0 * lda_fp : (const uint8_t*)a.xq,
+                              a.n_out ? (size_t)(a.T - t0) * lda_fp : 0);
+    const v4i rBf = make_rsrc(a.n_out ? (const uint8_t*)a.w_out + (size_t)n0 * ldb_fp : (const uint8_t*)a.xq,
+                              a.n_out ? (size_t)(a.N - n0) * ldb_fp : 0);
+    const uint32_t lds_base = lds_addr(lds);
+
+    // 32-byte rows (activation stages and both operands of fp16 stages): an instruction copies 32 rows
+    // (lane / 2), two 16-byte pieces each, exchanged in every second group of eight rows
+    const int colF = ((lane & 1) ^ ((lane >> 4) & 1)) * 16;
+    const uint32_t vo_a = (uint32_t)((lane >> 1) * 32 + colF);
+    const uint32_t vo_af = (uint32_t)((lane >> 1) * lda_fp + colF), vo_bf = (uint32_t)((lane >> 1) * ldb_fp + colF);
+    // DMA slot j of stage s (int part, fp16 part, or past the end: every lane out of range)
+    auto issue_one = [&](int s, int j) __attribute__((always_inline)) {
+        const int i = wave_u + NWAVES * j;                      // instruction of the stage (wave-uniform)
+        const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
+        const bool fp = s >= nk_int;
+        uint32_t vo = kOob, dst = (uint32_t)DUMMY;
+        v4i r;
+        if (!fp) {
+            const bool isb = i >= N_A;
+            const int ii = isb ? i - N_A : i;
+            if (i < N_A + N_B) {
+                dst = sb + (isb ? A_BYTES : 0) + ii * 1024;
+                if (s < nk) {
+                    if (!isb) vo = (uint32_t)(ii * 1024) + vo_a;
+                    else if (ii * 1024 + lane * 16 < BN * sp24::kWgtBytes) vo = (uint32_t)(ii * 1024 + lane * 16);
+                }
+            }
+            r = isb ? advance(rB, (uint32_t)s * strideB) : advance(rA, (uint32_t)s * strideA);
+        } else {
+            const bool isb = i >= N_AF;
+            const int ii = isb ? i - N_AF : i;
+            const int c0 = 32 * (s - nk_int);
+            if (i < N_AF + N_BF) {
+                dst = sb + (isb ? BM * 32 : 0) + ii * 1024;
+                if (s < nk && c0 + colF < fp_bytes)
+                    vo = (isb ? vo_bf : vo_af) + (uint32_t)(ii * 32 * (isb ? ldb_fp : lda_fp) + c0);
+            }
+            r = isb ? rBf : rAf;
+        }
+        // wave-uniform by construction; say so, the DMA takes them in scalar registers
+        r = v4i{__builtin_amdgcn_readfirstlane(r[0]), __builtin_amdgcn_readfirstlane(r[1]),
+                __builtin_amdgcn_readfirstlane(r[2]), __builtin_amdgcn_readfirstlane(r[3])};
+        dma16(r, (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + dst)), vo, 0);
+    };
+    // DMA slot j of an integer stage that exists (the hot loop's form)
+    auto issue_int = [&](int s, int j) __attribute__((always_inline)) {
+        const int i = wave_u + NWAVES * j;
+        const bool isb = i >= N_A;
+        const int ii = isb ? i - N_A : i;
+        const bool exists = i < N_A + N_B;
+        const uint32_t dst = exists ? (uint32_t)(s % NST) * ST_BYTES + (isb ? A_BYTES : 0) + ii * 1024 : (uint32_t)DUMMY;
+        uint32_t vo = kOob;
+        if (exists) {
+            if (!isb) vo = (uint32_t)(ii * 1024) + vo_a;
+            else if (ii * 1024 + lane * 16 < BN * sp24::kWgtBytes) vo = (uint32_t)(ii * 1024 + lane * 16);
+        }
+        v4i r = isb ? advance(rB, (uint32_t)s * strideB) : advance(rA, (uint32_t)s * strideA);
+        r = v4i{__builtin_amdgcn_readfirstlane(r[0]), __builtin_amdgcn_readfirstlane(r[1]),
+                __builtin_amdgcn_readfirstlane(r[2]), __builtin_amdgcn_readfirstlane(r[3])};
+        dma16(r, (uint32_t)__builtin_amdgcn_readfirstlane((int)(lds_base + dst)), vo, 0);
+    };
+    auto issue = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < LPS; ++j) issue_one(s, j);
+    };
+
+    // ---- epilogue parameters, requested before the first DMA: per token in registers (a lane owns
+    // one token of every token fragment), per channel through LDS
+    float t_s[TM], t_h[TM];
+    float p_sw = 0.0f, p_wr = 0.0f, p_bv = 0.0f;
+    if constexpr (!RAW) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int t = t0 + wm * TM * 32 + i * 32 + l32;
+            const float sc = t < a.T ? a.scale[t] : 0.0f, zr = t < a.T ? a.zero[t] : 0.0f;
+            t_s[i] = sc;                                   // scaleAct
+            t_h[i] = zr + 8.0f * sc;                       // zeroAct + halfRange * scaleAct
+        }
+        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
+        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+        if (tid < BN && !a.fp_only) {
+            const int n = min(n0 + tid, a.N - 1);
+            p_sw = __half2float(wsc[n]) * (1.0f / 256.0f);   // exact power-of-two factor
+            p_bv = bias ? __half2float(bias[n]) : 0.0f;
+            p_wr = a.w_reduced[n];
+        }
+    }
+
+#pragma unroll
+    for (int s = 0; s < NST; ++s) issue(s);
+
+    if constexpr (!RAW) {
+        if (tid < BN) { lds_sw[tid] = p_sw; lds_wr[tid] = p_wr; lds_bv[tid] = p_bv; }
+    }
+
+    // LDS read addresses of this lane's row of every fragment (token fragments first).  32-byte rows:
+    // piece g, exchanged as above; weight rows of an integer stage: 8 bytes of values at 8 g, index word at
+    // 16 + 4 g.
+    uint32_t rdf[NF], rdw[TN];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int r = (f < TM) ? (wm * TM * 32 + f * 32 + l32) : (wn * TN * 32 + (f - TM) * 32 + l32);
+        rdf[f] = (f < TM ? 0 : BM * 32) + r * 32 + ((g ^ swz_f(r)) << 4);
+        if (f >= TM) rdw[f - TM] = A_BYTES + r * sp24::kWgtBytes + 8 * g;
+    }
+    // packed fragments of the next stage (one set) and two sets of widened operands: the matrix
+    // instructions of a stage run on one set while the next stage's words are widened into the other
+    uint4 RA[TM];
+    uint2 RW[TN];
+    v8i UA[2][TM];
+    v4i UW[2][TN];
+    int UI[2][TN];
+    uint4 FP[2][NF];                                       // fp16 stages
+
+    auto read_frag = [&](int set, int f, int s) __attribute__((always_inline)) {
+        const uint8_t* st = lds + (s % NST) * ST_BYTES;
+        if (f < TM) {
+            RA[f] = *reinterpret_cast<const uint4*>(st + rdf[f]);
+        } else {
+            RW[f - TM] = *reinterpret_cast<const uint2*>(st + rdw[f - TM]);
+            UI[set][f - TM] = *reinterpret_cast<const int*>(st + rdw[f - TM] + 16 - 4 * g);   // 16 + 4 g of the row
+        }
+    };
+    auto widen = [&](int set, int f) __attribute__((always_inline)) {
+        constexpr uint32_t M = 0xF0F0F0F0u;
+        if (f < TM) {
+            const uint32_t w[4] = {RA[f].x, RA[f].y, RA[f].z, RA[f].w};
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                UA[set][f][2 * m] = (int)(w[m] & M);               // columns 8 m .. 8 m + 3, sixteen-fold
+                UA[set][f][2 * m + 1] = (int)((w[m] << 4) & M);    // columns 8 m + 4 .. 8 m + 7
+            }
+        } else {
+            const int j = f - TM;
+            UW[set][j] = v4i{(int)((RW[j].x << 4) & M), (int)(RW[j].x & M), (int)((RW[j].y << 4) & M), (int)(RW[j].y & M)};
+        }
+    };
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // Integer stage s.  Its successor must have landed for everybody (its fragments are read during this
+    // stage); all reads of stage s itself completed before the barrier, so its buffer is refilled with
+    // stage s + NST right away.  PLAIN: stage s + NST is an integer stage; AHEAD: stage s + 1 is one.
+    // The next stage's fragments are requested in the first two slots and widened in the others.
+    auto step = [&](int s, int set, bool plain, bool ahead) __attribute__((always_inline)) {
+        wait_vm<(NST - 2) * LPS>();
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < SL; ++m) {
+            const int i = m / TN, j = m % TN;
+            acc[i][j] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(UW[set][j], UA[set][i], acc[i][j], UI[set][j], 0, 0);
+            if (m < LPS) { if (plain) issue_int(s + NST, m); else issue_one(s + NST, m); }
+            if (ahead) {
+                if (m == 0) {
+#pragma unroll
+                    for (int f = 0; f < TM; ++f) read_frag(set ^ 1, f, s + 1);
+                }
+                if (m == 1) {
+#pragma unroll
+                    for (int f = TM; f < NF; ++f) read_frag(set ^ 1, f, s + 1);
+                }
+                if (m >= 2) {
+#pragma unroll
+                    for (int f = 0; f < NF; ++f)
+                        if (2 + f * (SL - 2) / NF == m) widen(set ^ 1, f);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    wait_vm<(NST - 1) * LPS>();            // stage 0 landed
+    __syncthreads();
+    if (nk_int > 0) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) read_frag(0, f, 0);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) widen(0, f);
+    }
+
+    int s = 0;
+    for (; s + 1 + NST < nk_int; s += 2) {
+        step(s, 0, true, true);
+        step(s + 1, 1, true, true);
+    }
+    for (; s + 2 < nk_int; s += 2) {
+        step(s, 0, false, true);
+        step(s + 1, 1, false, true);
+    }
+    if (s + 2 == nk_int) {
+        step(s, 0, false, true);
+        step(s + 1, 1, false, false);
+        s += 2;
+    } else if (s + 1 == nk_int) {
+        step(s, 0, false, false);
+        s += 1;
+    }
+
+    // lane: token tw + 32 i + l32; register r of fragment j: channel nw + 32 j + 8 (r / 4) + 4 g + r % 4
+    const int tw = t0 + wm * TM * 32, nw = n0 + wn * TN * 32;
+    if constexpr (RAW) {
+        wait_vm<0>();                      // drain the look-ahead DMA before the wave ends
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int t = tw + i * 32 + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int n = nw + j * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = acc[i][j][r] >> 8;   // exact: a multiple of 256
+                }
+            }
+        return;
+    }
+
+    // Dequantization: the accumulators are 256 times the integer dot products (the factor rides on the
+    // weight scale); the conversion to binary32 is exact (at most 24 significant bits).
+    v16f cf[TM][TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            const int lc = wn * TN * 32 + j * 32 + 8 * rq + 4 * g;
+            const float4 sw4 = *reinterpret_cast<const float4*>(&lds_sw[lc]);
+            const float4 wr4 = *reinterpret_cast<const float4*>(&lds_wr[lc]);
+            const float4 bv4 = *reinterpret_cast<const float4*>(&lds_bv[lc]);
+            const float sw_[4] = {sw4.x, sw4.y, sw4.z, sw4.w}, wr_[4] = {wr4.x, wr4.y, wr4.z, wr4.w};
+            const float bv_[4] = {bv4.x, bv4.y, bv4.z, bv4.w};
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int r = rq * 4 + rr;
+                    cf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], t_s[i] * sw_[rr],
+                                                 __builtin_fmaf(t_h[i], wr_[rr], bv_[rr]));
+                }
+        }
+
+    // fp16 outlier stages: 16 columns each, one matrix step, same protocol as the integer stages
+    auto wide_step = [&](int s, int set) __attribute__((always_inline)) {
+        wait_vm<(NST - 2) * LPS>();
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        const uint8_t* nxt = lds + ((s + 1) % NST) * ST_BYTES;
+#pragma unroll
+        for (int m = 0; m < SL; ++m) {
+            const int i = m / TN, j = m % TN;
+            cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, FP[set][TM + j]),
+                                                              __builtin_bit_cast(v8h, FP[set][i]), cf[i][j], 0, 0, 0);
+            if (m < LPS) issue_one(s + NST, m);
+            if (m < NF) FP[set ^ 1][m] = *reinterpret_cast<const uint4*>(nxt + rdf[m]);
+            if (SL < NF && m == SL - 1) {
+#pragma unroll
+                for (int f = SL; f < NF; ++f) FP[set ^ 1][f] = *reinterpret_cast<const uint4*>(nxt + rdf[f]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    if (s < nk) {
+        wait_vm<(NST - 1) * LPS>();        // first fp16 stage landed
+        __syncthreads();
+        const uint8_t* st = lds + (s % NST) * ST_BYTES;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) FP[0][f] = *reinterpret_cast<const uint4*>(st + rdf[f]);
+        for (; s + 1 < nk; s += 2) {
+            wide_step(s, 0);
+            wide_step(s + 1, 1);
+        }
+        if (s < nk) { wide_step(s, 0); ++s; }
+    }
+
+    wait_vm<0>();                          // drain the look-ahead DMA before the wave ends
+    __half* __restrict__ y = static_cast<__half*>(a.y);
+    // Output through LDS: each wave parks its fp16 tile (token rows) in its own slice of the dead stage
+    // ring, four channels = 8 bytes per lane and write, and stores whole row segments as 16-byte pieces;
+    // needs 16-byte aligned output rows.
+    constexpr int WROW = (NWAVES * TM * 32 * (TN * 64 + 16) <= NST * ST_BYTES) ? TN * 64 + 16 : TN * 64;
+    constexpr int WBUF = TM * 32 * WROW;
+    static_assert(NWAVES * WBUF <= NST * ST_BYTES, "stage ring too small to park the output tile");
+    const bool vec_ok = !a.fp_only && ((reinterpret_cast<uintptr_t>(a.y) & 15u) == 0) && (a.ldy % 8 == 0);
+    if (vec_ok) {
+        __syncthreads();                   // every wave is past its last read of the stage ring
+        uint8_t* wbuf = lds + wave_u * WBUF;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const __half2 h0 = __floats2half2_rn(cf[i][j][4 * rq], cf[i][j][4 * rq + 1]);
+                    const __half2 h1 = __floats2half2_rn(cf[i][j][4 * rq + 2], cf[i][j][4 * rq + 3]);
+                    uint2 v;
+                    v.x = __builtin_bit_cast(uint32_t, h0);
+                    v.y = __builtin_bit_cast(uint32_t, h1);
+                    *reinterpret_cast<uint2*>(wbuf + (i * 32 + l32) * WROW + (j * 32 + 8 * rq + 4 * g) * 2) = v;
+                }
+        constexpr int CH = TN * 4;                       // 16-byte pieces per row
+        constexpr int RPS = 64 / CH;                     // rows per store instruction
+        const int prow = lane / CH, pch = lane % CH;
+#pragma unroll
+        for (int p = 0; p < (TM * 32 + RPS - 1) / RPS; ++p) {
+            const int row = p * RPS + prow;
+            if (prow >= RPS || row >= TM * 32) continue;
+            const uint4 v = *reinterpret_cast<const uint4*>(wbuf + row * WROW + pch * 16);
+            const int t = tw + row, n = nw + pch * 8;
+            if (t < a.T) {
+                __half* dst = y + (size_t)t * a.ldy + n;
+                if (n + 8 <= a.N) {
+                    *reinterpret_cast<uint4*>(dst) = v;
+                } else {
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < a.N)
+                            reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+                }
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int t = tw + i * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int n = nw + j * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                if (t < a.T && n < a.N) {
+                    if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = cf[i][j][r];
+                    else y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+                }
+            }
+        }
+}
+
+// Signed 4-bit weights (two per byte, column 2p in the low nibble) -> the weight format of
+// quik_sp24_device.h.  One thread per (row, stage).  A group of four with more than two nonzero values
+// is counted in *violations (if not null) and keeps its first two.  Offline step.
+__global__ __launch_bounds__(256) void weight_pack_sp24_kernel(const uint8_t* __restrict__ w_q, int ldw, int N, int K_b,
+                                                               uint32_t* __restrict__ w24, int* __restrict__ violations) {
+    const int S = sp24::stages(K_b);
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)N * S) return;
+    const int n = (int)(idx / S), s = (int)(idx % S);
+    const uint8_t* src = w_q + (size_t)n * ldw + s * 32;
+    uint64_t vals[2] = {0, 0};
+    uint32_t ind[2] = {0, 0};
+    int bad = 0;
+    for (int kappa = 0; kappa < 16; ++kappa) {
+        int v[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int col = s * 64 + kappa * 4 + p;
+            int nib = 0;
+            if (col < K_b) {
+                const uint32_t byte = src[(kappa * 4 + p) >> 1];
+                nib = (int)((p & 1) ? (byte >> 4) : (byte & 0xFu));
+            }
+            v[p] = nib;                                   // two's complement nibble; 0 = value 0
+        }
+        // kept positions: the nonzero ones (at most two count), then the lowest unused ones, ascending
+        int keep[2], nk = 0, nz = 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            if (v[p] != 0) { if (nk < 2) keep[nk++] = p; ++nz; }
+        if (nz > 2) ++bad;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            if (nk < 2 && v[p] == 0) keep[nk++] = p;
+        if (keep[0] > keep[1]) { const int tmp = keep[0]; keep[0] = keep[1]; keep[1] = tmp; }
+        const int hg = sp24::half_of_group(kappa), q = sp24::pair_of_group(kappa);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int c = 2 * q + e;
+            const int bit = 32 * (c >> 3) + 8 * (c & 3) + 4 * ((c >> 2) & 1);
+            vals[hg] |= (uint64_t)(uint32_t)v[keep[e]] << bit;
+            ind[hg] |= (uint32_t)keep[e] << (2 * c);
+        }
+    }
+    uint32_t* blk = w24 + ((size_t)s * weight_rows(N) + n) * 6;
+    blk[0] = (uint32_t)vals[0];
+    blk[1] = (uint32_t)(vals[0] >> 32);
+    blk[2] = (uint32_t)vals[1];
+    blk[3] = (uint32_t)(vals[1] >> 32);
+    blk[4] = ind[0];
+    blk[5] = ind[1];
+    if ((N & 1) && n == N - 1) {                          // the padding row of an odd N: zeros
+#pragma unroll
+        for (int i = 0; i < 6; ++i) blk[6 + i] = 0u;
+    }
+    if (bad && violations) atomicAdd(violations, bad);
+}
+
+template <int BM, int BN, int WM, int WN, int NST, int GM, int MODE>
+hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
+    const int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    hipLaunchKernelGGL((gemm_sp24_kernel<BM, BN, WM, WN, NST, GM, MODE>), dim3(tiles), dim3(WM * WN * 64), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t dispatch24(const GemmArgs& a, hipStream_t stream) {
+    // One workgroup of eight waves per CU, so a launch runs in ceil(tiles / 256) rounds; a 256 x 192 tile
+    // takes about 1.4x as long as a 256 x 128 one.  Few tokens or few tiles: 128 x 128 tiles, two
+    // workgroups per CU.
+    auto rounds = [&](int bm, int bn) { return (((long)(a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn) + 255) / 256; };
+    const long tiles_128 = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
+    if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 9, 0, MODE>(a, stream);
+    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 10, 4, MODE>(a, stream);
+    return launch_cfg<256, 128, 4, 2, 12, 4, MODE>(a, stream);
+}
+
+}  // namespace
+
+int sp24_weight_rows(int N) { return weight_rows(N); }
+
+hipError_t launch_gemm_sp24(const GemmArgs& a, hipStream_t stream) {
+    if (a.T <= 0 || a.N <= 0) return hipSuccess;
+    return a.y ? dispatch24<0>(a, stream) : dispatch24<1>(a, stream);
+}
+
+hipError_t launch_weight_pack_sp24(const void* w_q, int ldw, int N, int K_b, void* w24, int* violations,
+                                   hipStream_t stream) {
+    if (N <= 0 || K_b <= 0) return hipSuccess;
+    const long total = (long)N * sp24::stages(K_b);
+    hipLaunchKernelGGL(weight_pack_sp24_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t*>(w_q), ldw, N, K_b, static_cast<uint32_t*>(w24), violations);
+    return hipGetLastError();
+}
+
+}  // namespace quik

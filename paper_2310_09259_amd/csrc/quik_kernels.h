@@ -18,8 +18,10 @@ struct QuantizeArgs {
     void* x_out;          // fp16 [T, ldo]
     int ldo;
     int32_t* code_sum;    // [T] sum of the signed codes at even positions (4-bit; may be null)
-    int fp6;              // 1: 4-bit codes written as E3M2 patterns in the panel layout (quik_fp6_device.h);
-                          //    xq is then the [stage][T][48-byte] buffer and ldq = 48 * stages
+    int format;           // 0: row-major packed rows.  1: 4-bit codes written as E3M2 patterns in the panel
+                          //    layout (quik_fp6_device.h); xq is then the [stage][T][48-byte] buffer and
+                          //    ldq = 48 * stages.  2: 4-bit codes in the activation format of the 2:4-sparse
+                          //    path (quik_sp24_device.h); xq is the [stage][T][32-byte] buffer, ldq = 32 * stages
 };
 
 struct GemmArgs {
@@ -63,6 +65,12 @@ hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
 // FP6 path (quik_gemm_fp6.hip): xq / w_q of GemmArgs are panel buffers [stage][row][48 bytes]; ldq / ldw unused
 hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, hipStream_t stream);
+// 2:4-sparse path (quik_gemm_sp24.hip): xq = activations [stage][T][32 bytes], w_q = weights
+// [stage][sp24_weight_rows(N)][24 bytes] (quik_sp24_device.h); ldq / ldw unused
+hipError_t launch_gemm_sp24(const GemmArgs& a, hipStream_t stream);
+hipError_t launch_weight_pack_sp24(const void* w_q, int ldw, int N, int K_b, void* w24, int* violations,
+                                   hipStream_t stream);
+int sp24_weight_rows(int N);
 
 // unfused stages (fusion ablation)
 hipError_t launch_unfused_quantize(const QuantizeArgs& a, void* x_base, int ldb, float* row_min,

@@ -40,6 +40,7 @@
 #include "quik_kernels.h"
 #include "quik_quant_device.h"
 #include "quik_fp6_device.h"
+#include "quik_sp24_device.h"
 
 namespace quik {
 
@@ -219,17 +220,19 @@ __device__ __forceinline__ void chunk_codes(const uint32_t (&x)[4], float mn, fl
     }
 }
 
-// K <= TPR * 8 * NCH: the row lives in NCH 128-bit registers per thread.  FP6 (4-bit codes only):
+// K <= TPR * 8 * NCH: the row lives in NCH 128-bit registers per thread.  FMT 1 (4-bit codes only):
 // the packed row is written as E3M2 patterns in the panel layout of quik_fp6_device.h (xq is then the
 // whole [stage][row][48-byte] buffer, ldq the 48 * stages bytes of one row's LDS image) and no code sum
-// is produced.
-template <int BITS, int TPR, int NCH, bool FP6>
+// is produced.  FMT 2 (4-bit codes only): the packed row leaves in the activation format of the 2:4-sparse
+// path (quik_sp24_device.h: [stage][row][32-byte] buffer, ldq = 32 * stages), again without a code sum.
+template <int BITS, int TPR, int NCH, int FMT>
 __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kernel(
     const __half* __restrict__ x, int T, int K, int ldx, const int32_t* __restrict__ idx, int n_out,
     uint8_t* __restrict__ xq, int ldq, float* __restrict__ scale, float* __restrict__ zero,
     int32_t* __restrict__ code_sum, __half* __restrict__ x_out, int ldo) {
     constexpr int RPB = kBlock / TPR;             // rows per workgroup iteration
     constexpr bool WAVE_ROW = TPR == 64;          // a row never leaves its wave: no workgroup barriers
+    constexpr bool FP6 = FMT == 1, SP24 = FMT == 2;
     extern __shared__ __align__(16) uint32_t lds[];
     // Claim the whole register budget of the launch bounds (512 / waves per SIMD, in units of 8).
     // Measured on MI355X: when this kernel's allocation ended exactly at its highest live register
@@ -387,7 +390,8 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                         if (w3[i]) atomicOr(&stage[12u * (GG >> 1) + (uint32_t)fp6::block_dword((int)(GG & 1u), (int)dd)], w3[i]);
                     }
                 } else {
-                    esum = __builtin_amdgcn_sad_u8((lo >> pos_even_shift(pos)) & 0x0F0F0F0Fu, 0u, esum);
+                    if constexpr (!SP24)
+                        esum = __builtin_amdgcn_sad_u8((lo >> pos_even_shift(pos)) & 0x0F0F0F0Fu, 0u, esum);
                     lo = (lo ^ 0x88888888u) & p.keep_lo;      // code - halfRange as two's complement nibbles
                     const uint64_t v = (uint64_t)lo << pos_shift(pos);
                     atomicOr(&stage[pos_word(pos)], (uint32_t)v);
@@ -411,7 +415,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                 atomicOr(&stage[pos_word(pos) + 2], top);
             }
         }
-        if constexpr (BITS == 4 && !FP6) {
+        if constexpr (BITS == 4 && FMT == 0) {
             // sum over even positions of the signed codes (the GEMM's correction term for its
             // single-AND operand widening)
             int es = wave_sum((int)esum);
@@ -429,7 +433,7 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
         // ---- write the packed row (including its zero padding up to ldq); 4-bit rows leave with
         // the two nibbles of every byte swapped: element 2p in the high nibble
         if (valid) {
-            uint4* dst = reinterpret_cast<uint4*>(xq + (FP6 ? (size_t)0 : (size_t)t * ldq));
+            uint4* dst = reinterpret_cast<uint4*>(xq + (FMT != 0 ? (size_t)0 : (size_t)t * ldq));
             const uint4* src = reinterpret_cast<const uint4*>(stage);
             for (int i = lt; i < (ldq >> 4); i += TPR) {
                 uint4 v = src[i];
@@ -438,7 +442,12 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                     dst[((size_t)st * T + t) * 3 + c] = v;
                     continue;
                 }
-                if constexpr (BITS == 4 && !FP6) {
+                if constexpr (SP24) {                  // piece i of the image = piece i % 2 of stage i / 2
+                    v = make_uint4(sp24::act_word(v.x), sp24::act_word(v.y), sp24::act_word(v.z), sp24::act_word(v.w));
+                    dst[((size_t)(i >> 1) * T + t) * 2 + (i & 1)] = v;
+                    continue;
+                }
+                if constexpr (BITS == 4 && FMT == 0) {
                     auto sw = [](uint32_t w) { return ((w & 0x0F0F0F0Fu) << 4) | ((w >> 4) & 0x0F0F0F0Fu); };
                     v = make_uint4(sw(v.x), sw(v.y), sw(v.z), sw(v.w));
                 }
@@ -663,7 +672,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
     }
 }
 
-template <int BITS, int TPR, int NCH, bool FP6>
+template <int BITS, int TPR, int NCH, int FMT>
 hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     constexpr int RPB = kBlock / TPR;
     const int nwords = (a.K + 31) >> 5;
@@ -677,11 +686,11 @@ hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
         // map + prefix, reduction scratch, then 2 * RPB row images of ldq bytes + 16 spare bytes each
         const size_t img0 = (size_t)((2 * nwords + 16 + 3) & ~3);
         const size_t lds = (img0 + 2 * (size_t)RPB * ((a.ldq >> 2) + 4)) * 4;
-        hipLaunchKernelGGL((quantize_rows_kernel<BITS, TPR, NCH, FP6>), dim3(grid), dim3(kBlock), lds, stream,
+        hipLaunchKernelGGL((quantize_rows_kernel<BITS, TPR, NCH, FMT>), dim3(grid), dim3(kBlock), lds, stream,
                            (const __half*)a.x, a.T, a.K, a.ldx, a.idx, a.n_out, (uint8_t*)a.xq, a.ldq,
                            a.scale, a.zero, a.code_sum, (__half*)a.x_out, a.ldo);
-    } else if constexpr (FP6) {
-        return hipErrorInvalidValue;               // rows beyond 16384 columns: integer formats only
+    } else if constexpr (FMT != 0) {
+        return hipErrorInvalidValue;               // rows beyond 16384 columns: row-major integer formats only
     } else {
         const size_t lds = (size_t)nwords * 8 + 8 * 4 + 4 * 4 + 4 * 4 + 16 + (size_t)RPB * a.ldq;
         hipLaunchKernelGGL((quantize_kernel<BITS, TPR, NCH>), dim3(grid), dim3(kBlock), lds, stream,
@@ -691,25 +700,27 @@ hipError_t launch(const QuantizeArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int BITS, bool FP6>
+template <int BITS, int FMT>
 hipError_t dispatch(const QuantizeArgs& a, hipStream_t stream) {
     const int K = a.K;
-    if (K <= 64 * 8 * 1) return launch<BITS, 64, 1, FP6>(a, stream);
-    if (K <= 64 * 8 * 2) return launch<BITS, 64, 2, FP6>(a, stream);
-    if (K <= 64 * 8 * 4) return launch<BITS, 64, 4, FP6>(a, stream);
-    if (K <= 256 * 8 * 2) return launch<BITS, 256, 2, FP6>(a, stream);
-    if (K <= 256 * 8 * 3) return launch<BITS, 256, 3, FP6>(a, stream);
-    if (K <= 256 * 8 * 4) return launch<BITS, 256, 4, FP6>(a, stream);
-    if (K <= 256 * 8 * 6) return launch<BITS, 256, 6, FP6>(a, stream);
-    if (K <= 256 * 8 * 8) return launch<BITS, 256, 8, FP6>(a, stream);
-    return launch<BITS, 256, 0, FP6>(a, stream);
+    if (K <= 64 * 8 * 1) return launch<BITS, 64, 1, FMT>(a, stream);
+    if (K <= 64 * 8 * 2) return launch<BITS, 64, 2, FMT>(a, stream);
+    if (K <= 64 * 8 * 4) return launch<BITS, 64, 4, FMT>(a, stream);
+    if (K <= 256 * 8 * 2) return launch<BITS, 256, 2, FMT>(a, stream);
+    if (K <= 256 * 8 * 3) return launch<BITS, 256, 3, FMT>(a, stream);
+    if (K <= 256 * 8 * 4) return launch<BITS, 256, 4, FMT>(a, stream);
+    if (K <= 256 * 8 * 6) return launch<BITS, 256, 6, FMT>(a, stream);
+    if (K <= 256 * 8 * 8) return launch<BITS, 256, 8, FMT>(a, stream);
+    return launch<BITS, 256, 0, FMT>(a, stream);
 }
 
 }  // namespace
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream) {
-    if (a.fp6) return a.bits == 4 ? dispatch<4, true>(a, stream) : hipErrorInvalidValue;
-    return a.bits == 4 ? dispatch<4, false>(a, stream) : dispatch<8, false>(a, stream);
+    if (a.format == 1) return a.bits == 4 ? dispatch<4, 1>(a, stream) : hipErrorInvalidValue;
+    if (a.format == 2) return a.bits == 4 ? dispatch<4, 2>(a, stream) : hipErrorInvalidValue;
+    if (a.format != 0) return hipErrorInvalidValue;
+    return a.bits == 4 ? dispatch<4, 0>(a, stream) : dispatch<8, 0>(a, stream);
 }
 
 }  // namespace quik

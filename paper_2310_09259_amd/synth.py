@@ -31,6 +31,7 @@ class LayerShape:
     bits: int = 4
     seed: int = BASE_SEED
     w_bits: int = 0          # weight bits when they differ from the activations' (0: same as bits)
+    sparse24: bool = False   # 4-bit weights with two of every four consecutive base columns set to zero
 
     @property
     def K_b(self) -> int:
@@ -87,4 +88,13 @@ def make_inputs(shape: LayerShape, outlier_gain: float = 40.0) -> LayerInputs:
     w_packed = rng.integers(0, 256, size=(N, shape.row_bytes), dtype=np.uint8)
     w_scale = rng.uniform(0.005, 0.02, size=N).astype(np.float16)
     w_out = (rng.standard_normal((N, n_out), dtype=np.float32) * np.float32(0.02)).astype(np.float16)
+    if shape.sparse24:
+        # 2:4 structure (Section 4.3.2 of the paper prunes with SparseGPT; here the two survivors of every
+        # group of four nibbles = two bytes are drawn at random): AND with one of the six 16-bit masks
+        # that keep two nibbles
+        if shape.weight_bits != 4 or shape.K_b % 4:
+            raise ValueError("sparse24 needs 4-bit weights and K_b a multiple of 4")
+        keep = np.array([0x00FF, 0x0F0F, 0xF00F, 0x0FF0, 0xF0F0, 0xFF00], np.uint16)
+        mask = keep[rng.integers(0, 6, size=(N, shape.row_bytes // 2))]
+        w_packed = (w_packed.view(np.uint16) & mask).view(np.uint8)
     return LayerInputs(shape, x, idx, w_packed, w_scale, w_out)

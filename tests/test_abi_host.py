@@ -141,6 +141,116 @@ def test_fp6_sizes_and_bad_arguments(lib):
     assert lin(p, 4, 64, 64, p, 8, p, p, p, p, 8, null, 8, p, 8, null, need, null) == -2
 
 
+def test_sp24_sizes_and_bad_arguments(lib):
+    vp, i = C.c_void_p, C.c_int
+    lib.quik_workspace_bytes_sp24.restype = C.c_size_t
+    lib.quik_sp24_weight_bytes.restype = C.c_size_t
+    assert lib.quik_sp24_act_row_bytes(64) == 32
+    assert lib.quik_sp24_act_row_bytes(65) == 64             # padded to whole stages of 64 columns
+    assert lib.quik_sp24_act_row_bytes(3840) == 1920
+    assert lib.quik_sp24_act_row_bytes(0) == 0
+    assert lib.quik_sp24_weight_bytes(8, 64) == 8 * 24
+    assert lib.quik_sp24_weight_bytes(7, 130) == 3 * 8 * 24  # rows rounded up to even, three stages
+    assert lib.quik_sp24_weight_bytes(0, 64) == 0
+    ws = lib.quik_workspace_bytes_sp24(2048, 4096, 11008, 256)
+    assert ws >= 2048 * 1920 + 2 * 2048 * 4 + 2048 * 256 * 2 and ws % 256 == 0
+    assert lib.quik_workspace_bytes_sp24(16, 64, 1, 64) == 0
+    p, u, null = vp(0x1000), vp(0x1004), vp(0)
+    pk = lib.quik_weight_pack_sp24
+    pk.argtypes = [vp, i, i, i, vp, vp, vp]
+    assert pk(p, 32, 8, 64, null, null, null) == -2
+    assert pk(p, 16, 8, 64, p, null, null) == -1             # ldw < K_b / 2
+    assert pk(p, 32, 8, 63, p, null, null) == -1             # odd K_b
+    assert pk(p, 32, 8, 64, u, null, null) == -3
+    assert pk(p, 32, 8, 64, p, vp(0x1002), null) == -3       # misaligned counter
+    q = lib.quik_quantize_sp24
+    q.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, vp, i, vp]
+    assert q(p, 4, 64, 64, null, 8, p, p, p, p, 8, null) == -2            # idx NULL with n_out
+    assert q(p, 4, 60, 64, p, 8, p, p, p, p, 8, null) == -4               # K % 8
+    assert q(p, 4, 32768, 32768, p, 8, p, p, p, p, 8, null) == -4         # K beyond this form's limit
+    g = lib.quik_gemm_dequant_sp24
+    g.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, i, vp, i, vp, i, vp]
+    # (xq24, scale, zero, x_out, ldo, T, K_b, n_out, w24, w_scale, w_reduced, w_out, ldwo, bias, N, y, ldy, stream)
+    assert g(p, p, p, p, 8, 4, 64, 8, p, p, p, p, 8, null, 8, null, 8, null) == -2
+    assert g(p, p, p, p, 8, 4, 64, 8, p, p, p, p, 8, null, 8, p, 4, null) == -1       # ldy < N
+    assert g(u, p, p, p, 8, 4, 64, 8, p, p, p, p, 8, null, 8, p, 8, null) == -3
+    assert g(p, p, p, p, 4, 4, 64, 8, p, p, p, p, 8, null, 8, p, 8, null) == -1       # ldo < n_out
+    ig = lib.quik_int_gemm_sp24
+    ig.argtypes = [vp, vp, i, i, i, vp, i, vp]
+    assert ig(p, p, 4, 8, 64, null, 8, null) == -2
+    assert ig(p, p, 4, 8, 64, p, 4, null) == -1
+    lin = lib.quik_linear_sp24
+    lin.argtypes = [vp, i, i, i, vp, i, vp, vp, vp, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
+    need = lib.quik_workspace_bytes_sp24(4, 64, 8, 8)
+    assert lin(p, 4, 64, 64, p, 8, p, p, p, p, 8, null, 8, p, 8, vp(0x1000), need - 1, null) == -5
+    assert lin(p, 4, 64, 64, p, 8, p, p, p, p, 8, null, 8, p, 8, null, need, null) == -2
+
+
+def _decode_sp24_weights(panels, N, K_b):
+    """include/quik.h's description of the sparse weight buffer read backwards, value by value."""
+    S = panels.shape[0]
+    dec = np.zeros((N, 64 * S), np.int64)
+    for s in range(S):
+        for n in range(N):
+            blk = [int(v) for v in panels[s, n]]
+            for kappa in range(16):
+                h, qq = (kappa // 4) % 2, 4 * (kappa // 8) + kappa % 4
+                word = blk[16 + 4 * h] | blk[17 + 4 * h] << 8 | blk[18 + 4 * h] << 16 | blk[19 + 4 * h] << 24
+                for e in range(2):
+                    c = 2 * qq + e
+                    byte = blk[8 * h + 4 * (c // 8) + c % 4]
+                    nib = (byte >> 4) if (c // 4) % 2 else (byte & 0xF)
+                    pos = (word >> (2 * c)) & 3
+                    dec[n, 64 * s + 4 * kappa + pos] += nib - 16 if nib >= 8 else nib
+    return dec
+
+
+def test_sp24_test_side_packers_round_trip_and_generator_is_2of4():
+    """The packers the GPU tests compare against, checked on the CPU: decoding their output value by
+    value gives back the matrix (and zeros in the padding); the synthetic 2:4 weights have at most two
+    nonzero values in every group of four and are otherwise the dense draw."""
+    import dataclasses
+    import oracle
+    from paper_2310_09259_amd import synth
+    from tests.util import is_2of4, sp24_act_panels, sp24_weight_panels
+    rng = np.random.default_rng(3)
+    N, K_b = 5, 136
+    w = rng.integers(-8, 8, size=(N, K_b // 4, 4))
+    for n in range(N):
+        for gidx in range(K_b // 4):
+            w[n, gidx, rng.choice(4, 2 + (gidx % 3 == 0), replace=False)] = 0
+    w = w.reshape(N, K_b)
+    panels = sp24_weight_panels(w)
+    assert panels.shape == (3, 6, 24) and not panels[:, 5].any()
+    dec = _decode_sp24_weights(panels, N, K_b)
+    assert np.array_equal(dec[:, :K_b], w) and not dec[:, K_b:].any()
+    # index positions ascend inside every pair
+    for s in range(3):
+        for n in range(N):
+            for h in range(2):
+                word = int.from_bytes(bytes(panels[s, n, 16 + 4 * h:20 + 4 * h]), "little")
+                for qq in range(8):
+                    assert (word >> (4 * qq)) & 3 < (word >> (4 * qq + 2)) & 3
+    q = rng.integers(-8, 8, size=(4, 70))
+    act = sp24_act_panels(q)
+    assert act.shape == (2, 4, 32)
+    back = np.zeros((4, 128), np.int64)
+    for s in range(2):
+        for b in range(32):
+            m, pp = b // 4, b % 4
+            hi, lo = act[s, :, b].astype(np.int64) >> 4, act[s, :, b].astype(np.int64) & 15
+            back[:, 64 * s + 8 * m + pp] = np.where(hi >= 8, hi - 16, hi)
+            back[:, 64 * s + 8 * m + 4 + pp] = np.where(lo >= 8, lo - 16, lo)
+    assert np.array_equal(back[:, :70], q) and not back[:, 70:].any()
+    shp = synth.LayerShape("s", 4, 264, 9, 8, 4, seed=9)
+    dense = synth.make_inputs(shp)
+    sparse = synth.make_inputs(dataclasses.replace(shp, sparse24=True))
+    wd, wsp = oracle.unpack(dense.w_packed, shp.K_b, 4), oracle.unpack(sparse.w_packed, shp.K_b, 4)
+    assert is_2of4(wsp).all() and not is_2of4(wd).all()
+    assert np.all((wsp == wd) | (wsp == 0))
+    assert np.array_equal(dense.x, sparse.x) and np.array_equal(dense.w_out, sparse.w_out)
+
+
 def test_e3m2_patterns_decode_to_the_integers():
     """The test-side FP6 encoder (tests/util.py) against the format's value formula: 1 sign bit,
     3 exponent bits with bias 3, 2 mantissa bits; e = 0 is subnormal."""

@@ -84,3 +84,54 @@ def fp6_panels(q: np.ndarray) -> np.ndarray:
         out[:, :, 16 * g: 16 * g + 16] = grp[:, :, :16].transpose(1, 0, 2)
         out[:, :, 32 + 8 * g: 40 + 8 * g] = grp[:, :, 16:].transpose(1, 0, 2)
     return out
+
+
+def is_2of4(wq: np.ndarray) -> np.ndarray:
+    """Per group of four consecutive columns: at most two nonzero values?  wq int [N, K_b], K_b % 4 == 0."""
+    N, K_b = wq.shape
+    return (wq.reshape(N, K_b // 4, 4) != 0).sum(axis=2) <= 2
+
+
+def sp24_act_panels(q: np.ndarray) -> np.ndarray:
+    """Signed codes int [T, K_b] -> the activation buffer of the 2:4-sparse path as include/quik.h
+    defines it, shaped [S, T, 32]: zero-padded to S stages of 64 columns; byte 4 m + p of a stage's
+    block holds column 8 m + p in the high nibble and column 8 m + 4 + p in the low nibble (two's
+    complement)."""
+    T, K_b = q.shape
+    S = (K_b + 63) // 64
+    nib = np.zeros((T, 64 * S), np.uint8)
+    nib[:, :K_b] = q.astype(np.int64) & 0xF
+    blk = nib.reshape(T, S, 8, 8)                       # [t, s, m, i]
+    by = (blk[..., :4] << 4) | blk[..., 4:]             # [t, s, m, p]
+    return np.ascontiguousarray(by.reshape(T, S, 32).transpose(1, 0, 2))
+
+
+def sp24_weight_panels(wq: np.ndarray) -> np.ndarray:
+    """Signed 4-bit weights int [N, K_b] -> the weight buffer of the 2:4-sparse path as include/quik.h
+    defines it, shaped [S, R, 24] with R = N rounded up to even (the padding row is zero).  Groups
+    with more than two nonzero values keep their first two."""
+    N, K_b = wq.shape
+    S = (K_b + 63) // 64
+    R = (N + 1) // 2 * 2
+    w = np.zeros((N, 64 * S), np.int64)
+    w[:, :K_b] = wq
+    grp = w.reshape(N, S, 16, 4)                        # [n, s, kappa, p]
+    # kept positions: nonzero ones first, then the lowest unused, two in all, ascending
+    key = np.where(grp != 0, 0, 4) + np.arange(4)
+    keep = np.sort(np.argsort(key, axis=3, kind="stable")[..., :2], axis=3)      # [n, s, kappa, e]
+    val = np.take_along_axis(grp, keep, axis=3) & 0xF
+    out = np.zeros((S, R, 24), np.uint8)
+    index = np.zeros((N, S, 2), np.uint64)
+    for kappa in range(16):
+        h, qq = (kappa // 4) % 2, 4 * (kappa // 8) + kappa % 4
+        for e in range(2):
+            c = 2 * qq + e
+            byte = 8 * h + 4 * (c // 8) + c % 4
+            shift = 0 if (c // 4) % 2 == 0 else 4
+            out[:, :N, byte] |= (val[:, :, kappa, e].T << shift).astype(np.uint8)
+            index[:, :, h] |= keep[:, :, kappa, e].astype(np.uint64) << np.uint64(2 * c)
+    for h in range(2):
+        word = index[:, :, h].T.astype(np.uint32)       # [s, n]
+        for b in range(4):
+            out[:, :N, 16 + 4 * h + b] = ((word >> (8 * b)) & 0xFF).astype(np.uint8)
+    return out
