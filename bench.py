@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA, MI355X data sheet (5.0 POP/s)
 PEAK_FP6_TOPS = 10100.0      # dense FP6 / FP4 matrix rate, MI355X data sheet (10.1 PFLOP/s)
+PEAK_SP24_TOPS = 10000.0     # 2:4-sparse int8 matrix rate counted in dense-equivalent operations: twice the
+                             # dense int8 figure (the sparse instruction does a 64-column step in the time
+                             # of a dense 32-column one)
 PEAK_HBM_GBS = 8000.0
 # profiles/gemm_kernel_llama7b_up.md: (47796 KiB * 2.0 + 44033 KiB * 1.0) * 1024
 TRAFFIC_BYTES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
@@ -118,6 +121,8 @@ def main():
                          "(1..8192) or outlier counts (0..1024) on the workload's K and N")
     ap.add_argument("--no-fp6", action="store_true",
                     help="skip the timing of the FP6-matrix-pipe form of the 4-bit layer")
+    ap.add_argument("--no-sp24", action="store_true",
+                    help="skip the timing of the 2:4-sparse form of the 4-bit layer")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (a kernel of known "
                          "traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
@@ -247,6 +252,36 @@ def main():
                "operand_bytes_per_element": 0.75}
         del w6, ws6, q6
 
+    # the 4-bit layer with 2:4-sparse weights on the sparse int8 matrix instruction: same shape, same
+    # activations, the synthetic weights with two of every four base columns cleared (reported beside
+    # the headline; rates count the dense-equivalent operations 2 T K N)
+    sp24 = None
+    if bits == 4 and not mixed and K <= 16384 and K_b % 4 == 0 and not args.no_sp24:
+        import dataclasses
+        inp_s = synth.make_inputs(dataclasses.replace(shp, sparse24=True))
+        w_qs = torch.from_numpy(inp_s.w_packed).to(dev)
+        w_red_s, _ = api.quik_weight_reduce(w_qs, w_scale, K_b, 4)
+        w24 = api.quik_weight_pack_sp24(w_qs, K_b)
+        ws24 = torch.empty(api.quik_workspace_bytes_sp24(T, K, N, n_out), dtype=torch.uint8, device=dev)
+        step24, _ = api.prepare_linear_sp24(x, idx, w24, w_scale, w_red_s, w_out, out=y, workspace=ws24)
+        q24 = api.quik_quantize_sp24(x, idx)
+        gemm24 = api.prepare_gemm_dequant_sp24(q24[0], q24[1], q24[2], q24[3] if n_out else None, K_b, w24,
+                                               w_scale, w_red_s, w_out, None, y)
+        quant24 = api.prepare_quantize_sp24(x, idx, q24)
+        for _ in range(max(10, args.warmup // 2)):
+            step24()
+        ms24_layer = _event_ms(step24, it, torch)
+        ms24_gemm = _event_ms(gemm24, it, torch)
+        ms24_quant = _event_ms(quant24, it, torch)
+        sp24 = {"layer_ms": ms24_layer, "layer_TOPS_dense_equivalent": 2.0 * T * K * N / (ms24_layer * 1e-3) / 1e12,
+                "kernels_ms": {"quik_quantize_sp24": ms24_quant, "quik_gemm_dequant_sp24": ms24_gemm},
+                "roofline": {"bound": "mfma", "kernel": "gemm_sp24_kernel", "peak": PEAK_SP24_TOPS,
+                             "unit": "TOP/s (dense-equivalent)",
+                             "achieved": 2.0 * T * K_b * N / (ms24_gemm * 1e-3) / 1e12,
+                             "frac": 2.0 * T * K_b * N / (ms24_gemm * 1e-3) / 1e12 / PEAK_SP24_TOPS},
+                "weight_bytes_per_element": 0.375, "activation_bytes_per_element": 0.5}
+        del w24, ws24, q24, w_qs, inp_s
+
     ms_fp16 = None
     if not args.no_fp16:
         wf = (torch.randn((N, K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
@@ -292,6 +327,8 @@ def main():
     }
     if fp6 is not None:
         out["fp6_path"] = fp6
+    if sp24 is not None:
+        out["sp24_path"] = sp24
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, shp)
     print(json.dumps(out))

@@ -51,7 +51,8 @@ __device__ __forceinline__ v4i advance(v4i r, uint32_t bytes) {
 __host__ __device__ inline int weight_rows(int N) { return (N + 1) & ~1; }
 
 // MODE 0: fused epilogue, fp16 output; MODE 1: the integer accumulators as INT32.
-template <int BM, int BN, int WM, int WN, int NST, int GM, int MODE>
+// NST: stage buffers of the ring; KS: stages per workgroup barrier (NST a multiple of KS).
+template <int BM, int BN, int WM, int WN, int NST, int KS, int GM, int MODE>
 __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp24_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
     // claim the whole register budget of the launch bounds, so that the highest allocated register is
@@ -71,6 +72,15 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
     constexpr int LPS = (N_MAX + NWAVES - 1) / NWAVES;
     static_assert(BM % 64 == 0 && BN % 64 == 0 && BN <= NT, "geometry");
     static_assert(NST * LPS < 64, "vmcnt range");
+    static_assert(NST >= KS + 3, "ring too short");
+    // Ring protocol.  The packed words of integer stage s + 2 are read from LDS while the matrix
+    // instructions of stage s issue (and widened during stage s + 1), and the workgroup meets at a barrier
+    // before every KS-th stage s (s % KS == 0).  At that barrier stages up to s + KS + 1 must have landed
+    // (they are read before the next barrier), and stages up to s + 1 are in registers everywhere, so
+    // during stage s' of the group its own buffer is refilled with stage s' + NST.  The prologue requests
+    // stages 0 .. NST - 1.  (fp16 stages: read one stage ahead, a barrier before every stage.)
+    constexpr int AHEAD = NST;
+    constexpr int WAIT_BAR = (NST - KS - 2) * LPS;        // requests that may still be in flight at a barrier
     static_assert(SL >= 4 && SL >= LPS, "a stage has too few matrix instructions to place its reads and copies");
     constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
 
@@ -181,34 +191,32 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
         for (int j = 0; j < LPS; ++j) issue_one(s, j);
     };
 
-    // ---- epilogue parameters, requested before the first DMA: per token in registers (a lane owns
-    // one token of every token fragment), per channel through LDS
-    float t_s[TM], t_h[TM];
-    float p_sw = 0.0f, p_wr = 0.0f, p_bv = 0.0f;
+    // ---- epilogue parameters: per token in registers (a lane owns one token of every token fragment),
+    // per channel through LDS.  They are requested before the first DMA, so that their (in-order) return
+    // does not sit behind the stage loads, and first touched after the integer stages: an earlier use
+    // would make the compiler wait for them and, with them, for every stage load requested since.
+    float t_s[TM], t_z[TM];
+    float p_wr = 0.0f;
+    uint32_t p_sw = 0, p_bv = 0;                           // binary16 patterns
     if constexpr (!RAW) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int t = t0 + wm * TM * 32 + i * 32 + l32;
-            const float sc = t < a.T ? a.scale[t] : 0.0f, zr = t < a.T ? a.zero[t] : 0.0f;
-            t_s[i] = sc;                                   // scaleAct
-            t_h[i] = zr + 8.0f * sc;                       // zeroAct + halfRange * scaleAct
+            t_s[i] = t < a.T ? a.scale[t] : 0.0f;
+            t_z[i] = t < a.T ? a.zero[t] : 0.0f;
         }
-        const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
-        const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
+        const uint16_t* __restrict__ wsc = static_cast<const uint16_t*>(a.w_scale);
+        const uint16_t* __restrict__ bias = static_cast<const uint16_t*>(a.bias);
         if (tid < BN && !a.fp_only) {
             const int n = min(n0 + tid, a.N - 1);
-            p_sw = __half2float(wsc[n]) * (1.0f / 256.0f);   // exact power-of-two factor
-            p_bv = bias ? __half2float(bias[n]) : 0.0f;
+            p_sw = wsc[n];
+            p_bv = (bias ? bias : wsc)[n];                 // no branch here: a join would wait for the loads
             p_wr = a.w_reduced[n];
         }
     }
 
 #pragma unroll
-    for (int s = 0; s < NST; ++s) issue(s);
-
-    if constexpr (!RAW) {
-        if (tid < BN) { lds_sw[tid] = p_sw; lds_wr[tid] = p_wr; lds_bv[tid] = p_bv; }
-    }
+    for (int s = 0; s < AHEAD; ++s) issue(s);
 
     // LDS read addresses of this lane's row of every fragment (token fragments first).  32-byte rows:
     // piece g, exchanged as above; weight rows of an integer stage: 8 bytes of values at 8 g, index word at
@@ -220,10 +228,11 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
         rdf[f] = (f < TM ? 0 : BM * 32) + r * 32 + ((g ^ swz_f(r)) << 4);
         if (f >= TM) rdw[f - TM] = A_BYTES + r * sp24::kWgtBytes + 8 * g;
     }
-    // packed fragments of the next stage (one set) and two sets of widened operands: the matrix
-    // instructions of a stage run on one set while the next stage's words are widened into the other
-    uint4 RA[TM];
-    uint2 RW[TN];
+    // two sets of packed fragments and two sets of widened operands, by stage parity: the matrix
+    // instructions of stage s run on one set of operands while the words of stage s + 1 are widened into
+    // the other and those of stage s + 2 arrive from LDS
+    uint4 RA[2][TM];
+    uint2 RW[2][TN];
     v8i UA[2][TM];
     v4i UW[2][TN];
     int UI[2][TN];
@@ -231,17 +240,19 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
 
     auto read_frag = [&](int set, int f, int s) __attribute__((always_inline)) {
         const uint8_t* st = lds + (s % NST) * ST_BYTES;
-        if (f < TM) {
-            RA[f] = *reinterpret_cast<const uint4*>(st + rdf[f]);
-        } else {
-            RW[f - TM] = *reinterpret_cast<const uint2*>(st + rdw[f - TM]);
-            UI[set][f - TM] = *reinterpret_cast<const int*>(st + rdw[f - TM] + 16 - 4 * g);   // 16 + 4 g of the row
-        }
+        if (f < TM) RA[set][f] = *reinterpret_cast<const uint4*>(st + rdf[f]);
+        else RW[set][f - TM] = *reinterpret_cast<const uint2*>(st + rdw[f - TM]);
+    };
+    // index word of weight fragment j: goes straight into the operand register (so it is requested only
+    // after the last matrix instruction of the stage that still uses the old one)
+    auto read_index = [&](int set, int j, int s) __attribute__((always_inline)) {
+        const uint8_t* st = lds + (s % NST) * ST_BYTES;
+        UI[set][j] = *reinterpret_cast<const int*>(st + rdw[j] + 16 - 4 * g);      // 16 + 4 g of the row
     };
     auto widen = [&](int set, int f) __attribute__((always_inline)) {
         constexpr uint32_t M = 0xF0F0F0F0u;
         if (f < TM) {
-            const uint32_t w[4] = {RA[f].x, RA[f].y, RA[f].z, RA[f].w};
+            const uint32_t w[4] = {RA[set][f].x, RA[set][f].y, RA[set][f].z, RA[set][f].w};
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 UA[set][f][2 * m] = (int)(w[m] & M);               // columns 8 m .. 8 m + 3, sixteen-fold
@@ -249,7 +260,8 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
             }
         } else {
             const int j = f - TM;
-            UW[set][j] = v4i{(int)((RW[j].x << 4) & M), (int)(RW[j].x & M), (int)((RW[j].y << 4) & M), (int)(RW[j].y & M)};
+            UW[set][j] = v4i{(int)((RW[set][j].x << 4) & M), (int)(RW[set][j].x & M), (int)((RW[set][j].y << 4) & M),
+                             (int)(RW[set][j].y & M)};
         }
     };
 
@@ -261,62 +273,73 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // Integer stage s.  Its successor must have landed for everybody (its fragments are read during this
-    // stage); all reads of stage s itself completed before the barrier, so its buffer is refilled with
-    // stage s + NST right away.  PLAIN: stage s + NST is an integer stage; AHEAD: stage s + 1 is one.
-    // The next stage's fragments are requested in the first two slots and widened in the others.
-    auto step = [&](int s, int set, bool plain, bool ahead) __attribute__((always_inline)) {
-        wait_vm<(NST - 2) * LPS>();
-        __syncthreads();
+    // Integer stage s, set = s % 2 (BAR: s % KS == 0, the group's barrier comes first).  PLAIN: stage
+    // s + NST is an integer stage; NEXT1 / NEXT2: stages s + 1 / s + 2 are.  Stage s + 1's words (they
+    // arrived during the previous stage) are widened between the matrix instructions, stage s + 2's are
+    // requested in the first two slots.
+    auto step = [&](int s, int set, bool bar, bool plain, bool next1, bool next2) __attribute__((always_inline)) {
+        if (bar) {
+            wait_vm<WAIT_BAR>();
+            __syncthreads();
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int m = 0; m < SL; ++m) {
             const int i = m / TN, j = m % TN;
             acc[i][j] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(UW[set][j], UA[set][i], acc[i][j], UI[set][j], 0, 0);
-            if (m < LPS) { if (plain) issue_int(s + NST, m); else issue_one(s + NST, m); }
-            if (ahead) {
+            if (m < LPS) { if (plain) issue_int(s + AHEAD, m); else issue_one(s + AHEAD, m); }
+            if (next2) {
                 if (m == 0) {
 #pragma unroll
-                    for (int f = 0; f < TM; ++f) read_frag(set ^ 1, f, s + 1);
+                    for (int f = 0; f < TM; ++f) read_frag(set, f, s + 2);
                 }
                 if (m == 1) {
 #pragma unroll
-                    for (int f = TM; f < NF; ++f) read_frag(set ^ 1, f, s + 1);
+                    for (int f = TM; f < NF; ++f) read_frag(set, f, s + 2);
                 }
-                if (m >= 2) {
+                if (i == TM - 1) read_index(set, j, s + 2);
+            }
+            if (next1) {
 #pragma unroll
-                    for (int f = 0; f < NF; ++f)
-                        if (2 + f * (SL - 2) / NF == m) widen(set ^ 1, f);
-                }
+                for (int f = 0; f < NF; ++f)
+                    if (f * SL / NF == m) widen(set ^ 1, f);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    wait_vm<(NST - 1) * LPS>();            // stage 0 landed
+    wait_vm<(NST - 2) * LPS>();            // stages 0 and 1 landed
     __syncthreads();
     if (nk_int > 0) {
 #pragma unroll
         for (int f = 0; f < NF; ++f) read_frag(0, f, 0);
 #pragma unroll
+        for (int j = 0; j < TN; ++j) read_index(0, j, 0);
+    }
+    if (nk_int > 1) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) read_frag(1, f, 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) read_index(1, j, 1);
+    }
+    if (nk_int > 0) {
+#pragma unroll
         for (int f = 0; f < NF; ++f) widen(0, f);
     }
 
+    static_assert(KS == 1 || KS == 2, "the loops below step two stages at a time");
+    constexpr bool BAR1 = KS == 1;         // the odd stage of a pair opens a group only if groups are single stages
     int s = 0;
-    for (; s + 1 + NST < nk_int; s += 2) {
-        step(s, 0, true, true);
-        step(s + 1, 1, true, true);
+    for (; s + 1 + AHEAD < nk_int; s += 2) {
+        step(s, 0, true, true, true, true);
+        step(s + 1, 1, BAR1, true, true, true);
     }
-    for (; s + 2 < nk_int; s += 2) {
-        step(s, 0, false, true);
-        step(s + 1, 1, false, true);
+    for (; s + 1 < nk_int; s += 2) {
+        step(s, 0, true, false, true, s + 2 < nk_int);
+        step(s + 1, 1, BAR1, false, s + 2 < nk_int, s + 3 < nk_int);
     }
-    if (s + 2 == nk_int) {
-        step(s, 0, false, true);
-        step(s + 1, 1, false, false);
-        s += 2;
-    } else if (s + 1 == nk_int) {
-        step(s, 0, false, false);
+    if (s < nk_int) {
+        step(s, 0, true, false, false, false);
         s += 1;
     }
 
@@ -340,6 +363,15 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
 
     // Dequantization: the accumulators are 256 times the integer dot products (the factor rides on the
     // weight scale); the conversion to binary32 is exact (at most 24 significant bits).
+    if (tid < BN) {
+        lds_sw[tid] = __half2float(__ushort_as_half((unsigned short)p_sw)) * (1.0f / 256.0f);   // exact power-of-two factor
+        lds_wr[tid] = p_wr;
+        lds_bv[tid] = a.bias ? __half2float(__ushort_as_half((unsigned short)p_bv)) : 0.0f;
+    }
+    float t_h[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) t_h[i] = t_z[i] + 8.0f * t_s[i];     // zeroAct + halfRange * scaleAct
+    __syncthreads();
     v16f cf[TM][TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -361,9 +393,11 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
                 }
         }
 
-    // fp16 outlier stages: 16 columns each, one matrix step, same protocol as the integer stages
+    // fp16 outlier stages: 16 columns each, one matrix step; stage s + 1 is read while the matrix
+    // instructions of stage s issue, and stage s's buffer (read during stage s - 1, before this barrier)
+    // is refilled
     auto wide_step = [&](int s, int set) __attribute__((always_inline)) {
-        wait_vm<(NST - 2) * LPS>();
+        wait_vm<WAIT_BAR>();
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
         const uint8_t* nxt = lds + ((s + 1) % NST) * ST_BYTES;
@@ -372,7 +406,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
             const int i = m / TN, j = m % TN;
             cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, FP[set][TM + j]),
                                                               __builtin_bit_cast(v8h, FP[set][i]), cf[i][j], 0, 0, 0);
-            if (m < LPS) issue_one(s + NST, m);
+            if (m < LPS) issue_one(s + AHEAD, m);
             if (m < NF) FP[set ^ 1][m] = *reinterpret_cast<const uint4*>(nxt + rdf[m]);
             if (SL < NF && m == SL - 1) {
 #pragma unroll
@@ -382,7 +416,9 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
         }
     };
     if (s < nk) {
-        wait_vm<(NST - 1) * LPS>();        // first fp16 stage landed
+        // the first fp16 stage has landed (at most KS + 1 stages behind the last barrier's stage); the wait
+        // and barrier matter only if there was no integer stage
+        wait_vm<WAIT_BAR>();
         __syncthreads();
         const uint8_t* st = lds + (s % NST) * ST_BYTES;
 #pragma unroll
@@ -517,10 +553,10 @@ __global__ __launch_bounds__(256) void weight_pack_sp24_kernel(const uint8_t* __
     if (bad && violations) atomicAdd(violations, bad);
 }
 
-template <int BM, int BN, int WM, int WN, int NST, int GM, int MODE>
+template <int BM, int BN, int WM, int WN, int NST, int KS, int GM, int MODE>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     const int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_sp24_kernel<BM, BN, WM, WN, NST, GM, MODE>), dim3(tiles), dim3(WM * WN * 64), 0, stream, a);
+    hipLaunchKernelGGL((gemm_sp24_kernel<BM, BN, WM, WN, NST, KS, GM, MODE>), dim3(tiles), dim3(WM * WN * 64), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -531,9 +567,9 @@ hipError_t dispatch24(const GemmArgs& a, hipStream_t stream) {
     // workgroups per CU.
     auto rounds = [&](int bm, int bn) { return (((long)(a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn) + 255) / 256; };
     const long tiles_128 = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
-    if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 9, 0, MODE>(a, stream);
-    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 10, 4, MODE>(a, stream);
-    return launch_cfg<256, 128, 4, 2, 12, 4, MODE>(a, stream);
+    if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 9, 2, 0, MODE>(a, stream);
+    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 10, 2, 4, MODE>(a, stream);
+    return launch_cfg<256, 128, 4, 2, 12, 2, 4, MODE>(a, stream);
 }
 
 }  // namespace
