@@ -279,7 +279,7 @@ def main():
                              "unit": "TOP/s (dense-equivalent)",
                              "achieved": 2.0 * T * K_b * N / (ms24_gemm * 1e-3) / 1e12,
                              "frac": 2.0 * T * K_b * N / (ms24_gemm * 1e-3) / 1e12 / PEAK_SP24_TOPS},
-                "weight_bytes_per_element": 0.375, "activation_bytes_per_element": 0.5}
+                "weight_bytes_per_element": 0.5, "activation_bytes_per_element": 0.5}
         del w24, ws24, q24, w_qs, inp_s
 
     ms_fp16 = None

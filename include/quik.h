@@ -306,9 +306,9 @@ int quik_linear_fp6(const void *x, int T, int K, int ldx, const int32_t *outlier
  *     (S * T * 32 bytes; quik_sp24_act_row_bytes(K_b) = 32 S).  Byte 4 m + p of a block holds the
  *     signed codes (two's complement nibbles) of columns 8 m + p (high nibble) and 8 m + 4 + p
  *     (low nibble) of the stage.
- *   weights w24: stage s of channel n is the 24-byte block at byte (s * R + n) * 24 with
- *     R = N rounded up to even (quik_sp24_weight_bytes(N, K_b) = S * R * 24 bytes).  A block is two
- *     8-byte value fields (halves h = 0, 1), then two 4-byte index words (h = 0, 1).  The group
+ *   weights w24: stage s of channel n is the 32-byte block at byte (s * N + n) * 32
+ *     (quik_sp24_weight_bytes(N, K_b) = S * N * 32 bytes).  A block is two 16-byte records
+ *     (halves h = 0, 1): an 8-byte value field, a 4-byte index word, 4 zero bytes.  The group
  *     of four columns kappa (0 .. 15) of the stage belongs to half h = (kappa / 4) % 2, pair
  *     q = 4 (kappa / 8) + kappa % 4; its two kept values are values c = 2 q and 2 q + 1 of the
  *     half: value c is a two's complement nibble in dword c / 8 of the field, byte c % 4, low

@@ -506,7 +506,7 @@ def quik_workspace_bytes_sp24(T: int, K: int, N: int, n_out: int) -> int:
 
 
 def quik_weight_pack_sp24(w_q, K_b: int, check: bool = True):
-    """packed signed 4-bit weights uint8 [N, ldw] -> uint8 [stages, N rounded up to even, 24].
+    """packed signed 4-bit weights uint8 [N, ldw] -> uint8 [stages, N, 32].
 
     With check (the default) the call waits for the result and raises unless every group of four
     columns has at most two nonzero values."""
@@ -516,7 +516,7 @@ def quik_weight_pack_sp24(w_q, K_b: int, check: bool = True):
     if nbytes <= 0:
         raise QuikError(-1, "quik_sp24_weight_bytes")
     stages = quik_sp24_act_row_bytes(K_b) // 32
-    w24 = torch.empty((stages, nbytes // (24 * stages), 24), dtype=torch.uint8, device=w_q.device)
+    w24 = torch.empty((stages, nbytes // (32 * stages), 32), dtype=torch.uint8, device=w_q.device)
     violations = torch.zeros(1, dtype=torch.int32, device=w_q.device) if check else None
     rc = load().quik_weight_pack_sp24(_ptr(w_q), w_q.stride(0), N, K_b, _ptr(w24), _ptr(violations), _stream())
     _check(rc, "quik_weight_pack_sp24")

@@ -472,7 +472,7 @@ int quik_sp24_act_row_bytes(int K_b) {
 
 size_t quik_sp24_weight_bytes(int N, int K_b) {
     if (N <= 0 || K_b <= 0 || K_b >= kMaxKb) return 0;
-    return (size_t)((K_b + 63) / 64) * (size_t)quik::sp24_weight_rows(N) * 24u;
+    return (size_t)((K_b + 63) / 64) * (size_t)N * 32u;
 }
 
 size_t quik_workspace_bytes_sp24(int T, int K, int N, int n_out) {

@@ -10,17 +10,19 @@
 // neighbouring channels of its token at a time.
 //
 // A workgroup of WM x WN waves owns a BM (tokens) x BN (channels) output tile.  A stage is 64 columns = one
-// matrix step: 32 bytes per token row and 24 per weight row, stored stage by stage, so the tile's rows of
-// a stage are two contiguous runs that 16-byte-per-lane DMA instructions copy global -> LDS.  As in the
-// FP6 kernel the K loop is bound by the bytes a CU keeps in flight, so the stage ring takes most of the
-// LDS.  One workgroup barrier per stage; right after it the buffer read during the previous stage is
-// refilled, and while the matrix instructions of stage s issue, the packed words of stage s + 1 are
-// read from LDS and widened to int8 (two or three VALU operations per two operand registers).  The 32-byte
-// activation rows exchange their two pieces in every second group of eight rows (bank conflicts); the
-// 24-byte weight rows need no swizzle.  The fp16 outlier columns run through the same ring as stages of 16
-// columns, with the dequantized integer part as the C operand of v_mfma_f32_32x32x16_f16 (weights first,
-// so the accumulator layout is the same).  Rows beyond T / N are out of range for the per-stage buffer
-// descriptors and arrive as zeros.
+// matrix step: 32 bytes per token row and 32 per weight row, stored stage by stage, so the tile's rows of
+// a stage are two contiguous runs that 16-byte-per-lane DMA instructions copy global -> LDS (32 rows per
+// instruction, the two 16-byte pieces of a row exchanged in every second group of eight rows, which keeps
+// the 16-byte LDS reads free of bank conflicts).  The stage ring takes most of the LDS.  The packed words
+// of stage s + 2 are read from LDS (one 16-byte read per fragment) and those of stage s + 1 widened to
+// int8 (two or three VALU operations per two operand registers) while the matrix instructions of stage s
+// issue; one workgroup barrier per two stages, after which the buffers just read are refilled.  Measured
+// on MI355X: LDS read instructions of a wave do not hide behind its matrix instructions (their cost adds
+// to the loop time whatever their latency slack), VALU work in these amounts does.  The fp16 outlier
+// columns run through the same ring as stages of 16 columns of the same shape, with the dequantized
+// integer part as the C operand of v_mfma_f32_32x32x16_f16 (weights first, so the accumulator layout is
+// the same).  Rows beyond T / N are out of range for the per-stage buffer descriptors and arrive as
+// zeros.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -47,9 +49,6 @@ __device__ __forceinline__ v4i advance(v4i r, uint32_t bytes) {
     return r;
 }
 
-// rows of a weight stage in memory: N rounded up to even, so that every stage starts 16-byte aligned
-__host__ __device__ inline int weight_rows(int N) { return (N + 1) & ~1; }
-
 // MODE 0: fused epilogue, fp16 output; MODE 1: the integer accumulators as INT32.
 // NST: stage buffers of the ring; KS: stages per workgroup barrier (NST a multiple of KS).
 template <int BM, int BN, int WM, int WN, int NST, int KS, int GM, int MODE>
@@ -60,16 +59,14 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
     asm volatile("" ::: "v255");
     constexpr int NWAVES = WM * WN, NT = NWAVES * 64;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NF = TM + TN, SL = TM * TN;
-    constexpr int A_BYTES = BM * sp24::kActBytes;
-    // DMA instructions of a stage (1 KB each): N_A + N_B over the tile's two runs (the last one of the
-    // weights may be partly empty); fp16 stages BM / 32 and BN / 32.  A wave issues LPS per stage:
+    static_assert(sp24::kActBytes == 32 && sp24::kWgtBytes == 32, "every stage row is 32 bytes");
+    // Integer and fp16 stages have the same shape in LDS: BM token rows, then BN channel rows, 32 bytes
+    // each.  DMA instructions of a stage (1 KB = 32 rows each): N_A + N_B.  A wave issues LPS per stage:
     // instruction i = wave + NWAVES * slot; one that does not exist is issued empty so that every wave
     // counts the same number.
-    constexpr int N_A = A_BYTES / 1024, N_B = (BN * sp24::kWgtBytes + 1023) / 1024, N_AF = BM / 32, N_BF = BN / 32;
-    constexpr int B_BYTES = N_B * 1024;
-    constexpr int ST_BYTES = (A_BYTES + B_BYTES > (BM + BN) * 32) ? A_BYTES + B_BYTES : (BM + BN) * 32;
-    constexpr int N_MAX = (N_A + N_B > N_AF + N_BF) ? N_A + N_B : N_AF + N_BF;
-    constexpr int LPS = (N_MAX + NWAVES - 1) / NWAVES;
+    constexpr int A_BYTES = BM * 32, B_BYTES = BN * 32, ST_BYTES = A_BYTES + B_BYTES;
+    constexpr int N_A = BM / 32, N_B = BN / 32;
+    constexpr int LPS = (N_A + N_B + NWAVES - 1) / NWAVES;
     static_assert(BM % 64 == 0 && BN % 64 == 0 && BN <= NT, "geometry");
     static_assert(NST * LPS < 64, "vmcnt range");
     static_assert(NST >= KS + 3, "ring too short");
@@ -81,7 +78,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
     // stages 0 .. NST - 1.  (fp16 stages: read one stage ahead, a barrier before every stage.)
     constexpr int AHEAD = NST;
     constexpr int WAIT_BAR = (NST - KS - 2) * LPS;        // requests that may still be in flight at a barrier
-    static_assert(SL >= 4 && SL >= LPS, "a stage has too few matrix instructions to place its reads and copies");
+    static_assert(SL >= 4 && SL >= LPS && TM <= (TM - 1) * TN, "a stage has too few matrix instructions to place its reads and copies");
     constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
 
     __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES + 1024];
@@ -117,13 +114,11 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
     const int nk = nk_int + nk_fp;
     const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
     const uint32_t strideA = (uint32_t)a.T * sp24::kActBytes;                  // bytes from stage to stage
-    const uint32_t strideB = (uint32_t)weight_rows(a.N) * sp24::kWgtBytes;
+    const uint32_t strideB = (uint32_t)a.N * sp24::kWgtBytes;
 
     // stage 0 of the tile's rows
     const v4i rA = make_rsrc((const uint8_t*)a.xq + (size_t)t0 * sp24::kActBytes, (size_t)(a.T - t0) * sp24::kActBytes);
-    // (range rounded up to whole 16-byte pieces: for an odd N it ends inside the zero padding row)
-    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * sp24::kWgtBytes,
-                             ((size_t)(a.N - n0) * sp24::kWgtBytes + 15) & ~(size_t)15);
+    const v4i rB = make_rsrc((const uint8_t*)a.w_q + (size_t)n0 * sp24::kWgtBytes, (size_t)(a.N - n0) * sp24::kWgtBytes);
     const v4i rAf = make_rsrc(a.n_out ? (const uint8_t*)a.x_out + (size_t)t0 * lda_fp : (const uint8_t*)a.xq,
                               a.n_out ? (size_t)(a.T - t0) * lda_fp : 0);
     const v4i rBf = make_rsrc(a.n_out ? (const uint8_t*)a.w_out + (size_t)n0 * ldb_fp : (const uint8_t*)a.xq,
@@ -147,17 +142,14 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
             const int ii = isb ? i - N_A : i;
             if (i < N_A + N_B) {
                 dst = sb + (isb ? A_BYTES : 0) + ii * 1024;
-                if (s < nk) {
-                    if (!isb) vo = (uint32_t)(ii * 1024) + vo_a;
-                    else if (ii * 1024 + lane * 16 < BN * sp24::kWgtBytes) vo = (uint32_t)(ii * 1024 + lane * 16);
-                }
+                if (s < nk) vo = (uint32_t)(ii * 1024) + vo_a;
             }
             r = isb ? advance(rB, (uint32_t)s * strideB) : advance(rA, (uint32_t)s * strideA);
         } else {
-            const bool isb = i >= N_AF;
-            const int ii = isb ? i - N_AF : i;
+            const bool isb = i >= N_A;
+            const int ii = isb ? i - N_A : i;
             const int c0 = 32 * (s - nk_int);
-            if (i < N_AF + N_BF) {
+            if (i < N_A + N_B) {
                 dst = sb + (isb ? BM * 32 : 0) + ii * 1024;
                 if (s < nk && c0 + colF < fp_bytes)
                     vo = (isb ? vo_bf : vo_af) + (uint32_t)(ii * 32 * (isb ? ldb_fp : lda_fp) + c0);
@@ -176,11 +168,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
         const int ii = isb ? i - N_A : i;
         const bool exists = i < N_A + N_B;
         const uint32_t dst = exists ? (uint32_t)(s % NST) * ST_BYTES + (isb ? A_BYTES : 0) + ii * 1024 : (uint32_t)DUMMY;
-        uint32_t vo = kOob;
-        if (exists) {
-            if (!isb) vo = (uint32_t)(ii * 1024) + vo_a;
-            else if (ii * 1024 + lane * 16 < BN * sp24::kWgtBytes) vo = (uint32_t)(ii * 1024 + lane * 16);
-        }
+        const uint32_t vo = exists ? (uint32_t)(ii * 1024) + vo_a : kOob;
         v4i r = isb ? advance(rB, (uint32_t)s * strideB) : advance(rA, (uint32_t)s * strideA);
         r = v4i{__builtin_amdgcn_readfirstlane(r[0]), __builtin_amdgcn_readfirstlane(r[1]),
                 __builtin_amdgcn_readfirstlane(r[2]), __builtin_amdgcn_readfirstlane(r[3])};
@@ -218,36 +206,29 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
 #pragma unroll
     for (int s = 0; s < AHEAD; ++s) issue(s);
 
-    // LDS read addresses of this lane's row of every fragment (token fragments first).  32-byte rows:
-    // piece g, exchanged as above; weight rows of an integer stage: 8 bytes of values at 8 g, index word at
-    // 16 + 4 g.
-    uint32_t rdf[NF], rdw[TN];
+    // LDS read addresses of this lane's row of every fragment (token fragments first): piece g of the
+    // 32-byte row, exchanged as above
+    uint32_t rdf[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
         const int r = (f < TM) ? (wm * TM * 32 + f * 32 + l32) : (wn * TN * 32 + (f - TM) * 32 + l32);
         rdf[f] = (f < TM ? 0 : BM * 32) + r * 32 + ((g ^ swz_f(r)) << 4);
-        if (f >= TM) rdw[f - TM] = A_BYTES + r * sp24::kWgtBytes + 8 * g;
     }
     // two sets of packed fragments and two sets of widened operands, by stage parity: the matrix
     // instructions of stage s run on one set of operands while the words of stage s + 1 are widened into
     // the other and those of stage s + 2 arrive from LDS
+    // (a weight fragment's packed words hold its index word too, which the matrix instruction takes as it
+    // is: such a fragment is requested only after the last matrix instruction that uses the old index)
     uint4 RA[2][TM];
-    uint2 RW[2][TN];
+    uint4 RW[2][TN];                                       // x, y: values; z: index word
     v8i UA[2][TM];
     v4i UW[2][TN];
-    int UI[2][TN];
     uint4 FP[2][NF];                                       // fp16 stages
 
     auto read_frag = [&](int set, int f, int s) __attribute__((always_inline)) {
         const uint8_t* st = lds + (s % NST) * ST_BYTES;
         if (f < TM) RA[set][f] = *reinterpret_cast<const uint4*>(st + rdf[f]);
-        else RW[set][f - TM] = *reinterpret_cast<const uint2*>(st + rdw[f - TM]);
-    };
-    // index word of weight fragment j: goes straight into the operand register (so it is requested only
-    // after the last matrix instruction of the stage that still uses the old one)
-    auto read_index = [&](int set, int j, int s) __attribute__((always_inline)) {
-        const uint8_t* st = lds + (s % NST) * ST_BYTES;
-        UI[set][j] = *reinterpret_cast<const int*>(st + rdw[j] + 16 - 4 * g);      // 16 + 4 g of the row
+        else RW[set][f - TM] = *reinterpret_cast<const uint4*>(st + rdf[f]);
     };
     auto widen = [&](int set, int f) __attribute__((always_inline)) {
         constexpr uint32_t M = 0xF0F0F0F0u;
@@ -276,7 +257,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
     // Integer stage s, set = s % 2 (BAR: s % KS == 0, the group's barrier comes first).  PLAIN: stage
     // s + NST is an integer stage; NEXT1 / NEXT2: stages s + 1 / s + 2 are.  Stage s + 1's words (they
     // arrived during the previous stage) are widened between the matrix instructions, stage s + 2's are
-    // requested in the first two slots.
+    // requested one fragment per slot.
     auto step = [&](int s, int set, bool bar, bool plain, bool next1, bool next2) __attribute__((always_inline)) {
         if (bar) {
             wait_vm<WAIT_BAR>();
@@ -286,18 +267,11 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
 #pragma unroll
         for (int m = 0; m < SL; ++m) {
             const int i = m / TN, j = m % TN;
-            acc[i][j] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(UW[set][j], UA[set][i], acc[i][j], UI[set][j], 0, 0);
+            acc[i][j] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(UW[set][j], UA[set][i], acc[i][j], (int)RW[set][j].z, 0, 0);
             if (m < LPS) { if (plain) issue_int(s + AHEAD, m); else issue_one(s + AHEAD, m); }
             if (next2) {
-                if (m == 0) {
-#pragma unroll
-                    for (int f = 0; f < TM; ++f) read_frag(set, f, s + 2);
-                }
-                if (m == 1) {
-#pragma unroll
-                    for (int f = TM; f < NF; ++f) read_frag(set, f, s + 2);
-                }
-                if (i == TM - 1) read_index(set, j, s + 2);
+                if (m < TM) read_frag(set, m, s + 2);
+                if (i == TM - 1) read_frag(set, TM + j, s + 2);
             }
             if (next1) {
 #pragma unroll
@@ -313,14 +287,10 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
     if (nk_int > 0) {
 #pragma unroll
         for (int f = 0; f < NF; ++f) read_frag(0, f, 0);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) read_index(0, j, 0);
     }
     if (nk_int > 1) {
 #pragma unroll
         for (int f = 0; f < NF; ++f) read_frag(1, f, 1);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) read_index(1, j, 1);
     }
     if (nk_int > 0) {
 #pragma unroll
@@ -539,17 +509,9 @@ __global__ __launch_bounds__(256) void weight_pack_sp24_kernel(const uint8_t* __
             ind[hg] |= (uint32_t)keep[e] << (2 * c);
         }
     }
-    uint32_t* blk = w24 + ((size_t)s * weight_rows(N) + n) * 6;
-    blk[0] = (uint32_t)vals[0];
-    blk[1] = (uint32_t)(vals[0] >> 32);
-    blk[2] = (uint32_t)vals[1];
-    blk[3] = (uint32_t)(vals[1] >> 32);
-    blk[4] = ind[0];
-    blk[5] = ind[1];
-    if ((N & 1) && n == N - 1) {                          // the padding row of an odd N: zeros
-#pragma unroll
-        for (int i = 0; i < 6; ++i) blk[6 + i] = 0u;
-    }
+    uint4* blk = reinterpret_cast<uint4*>(w24) + ((size_t)s * N + n) * 2;
+    blk[0] = make_uint4((uint32_t)vals[0], (uint32_t)(vals[0] >> 32), ind[0], 0u);
+    blk[1] = make_uint4((uint32_t)vals[1], (uint32_t)(vals[1] >> 32), ind[1], 0u);
     if (bad && violations) atomicAdd(violations, bad);
 }
 
@@ -573,8 +535,6 @@ hipError_t dispatch24(const GemmArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
-
-int sp24_weight_rows(int N) { return weight_rows(N); }
 
 hipError_t launch_gemm_sp24(const GemmArgs& a, hipStream_t stream) {
     if (a.T <= 0 || a.N <= 0) return hipSuccess;

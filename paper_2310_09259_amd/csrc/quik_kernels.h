@@ -66,11 +66,10 @@ hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
 hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, hipStream_t stream);
 // 2:4-sparse path (quik_gemm_sp24.hip): xq = activations [stage][T][32 bytes], w_q = weights
-// [stage][sp24_weight_rows(N)][24 bytes] (quik_sp24_device.h); ldq / ldw unused
+// [stage][N][32 bytes] (quik_sp24_device.h); ldq / ldw unused
 hipError_t launch_gemm_sp24(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_pack_sp24(const void* w_q, int ldw, int N, int K_b, void* w24, int* violations,
                                    hipStream_t stream);
-int sp24_weight_rows(int N);
 
 // unfused stages (fusion ablation)
 hipError_t launch_unfused_quantize(const QuantizeArgs& a, void* x_base, int ldb, float* row_min,

@@ -24,10 +24,12 @@
 // (word & 0xF0F0F0F0) and ((word << 4) & 0xF0F0F0F0) are then sixteen times the int8 values of two
 // whole groups of four, byte p = position p, which is what the dense operand wants.
 //
-// Weights (R = N rows): 24 bytes per row and stage: 8 bytes of values for half 0, 8 for half 1, then the
-// 4-byte index words of half 0 and half 1.  Value c (0 .. 15) of a half sits in dword c / 8 of its 8 bytes,
-// byte c % 4, low nibble if (c / 4) % 2 == 0, else high: (dword << 4) & 0xF0F0F0F0 and dword & 0xF0F0F0F0
-// of the two dwords are the four registers of the sparse operand, sixteen times the int8 values.
+// Weights (R = N rows): 32 bytes per row and stage, one 16-byte record per half: 8 bytes of values, the
+// 4-byte index word, 4 bytes of zero padding (so that one 16-byte LDS read fetches all a lane needs; read
+// instructions, not bytes, are what the K loop pays for).  Value c (0 .. 15) of a half sits in dword c / 8
+// of its 8 bytes, byte c % 4, low nibble if (c / 4) % 2 == 0, else high: (dword << 4) & 0xF0F0F0F0 and
+// dword & 0xF0F0F0F0 of the two dwords are the four registers of the sparse operand, sixteen times the
+// int8 values.
 // Kept positions of a group: its nonzero positions, filled up to two with the lowest unused positions
 // (whose values are zero), in ascending order.
 // Accumulators are exactly 256 times the integer dot products; |256 * 64 * K_b / 2| < 2^31 for
@@ -41,7 +43,7 @@ namespace sp24 {
 
 __host__ __device__ inline int stages(int K_b) { return (K_b + 63) >> 6; }
 constexpr int kActBytes = 32;      // per row and stage
-constexpr int kWgtBytes = 24;
+constexpr int kWgtBytes = 32;
 
 // group kappa of a stage -> (half g, pair q) of the sparse operand
 __host__ __device__ inline int half_of_group(int kappa) { return (kappa >> 2) & 1; }

@@ -149,8 +149,8 @@ def test_sp24_sizes_and_bad_arguments(lib):
     assert lib.quik_sp24_act_row_bytes(65) == 64             # padded to whole stages of 64 columns
     assert lib.quik_sp24_act_row_bytes(3840) == 1920
     assert lib.quik_sp24_act_row_bytes(0) == 0
-    assert lib.quik_sp24_weight_bytes(8, 64) == 8 * 24
-    assert lib.quik_sp24_weight_bytes(7, 130) == 3 * 8 * 24  # rows rounded up to even, three stages
+    assert lib.quik_sp24_weight_bytes(8, 64) == 8 * 32
+    assert lib.quik_sp24_weight_bytes(7, 130) == 3 * 7 * 32  # three stages
     assert lib.quik_sp24_weight_bytes(0, 64) == 0
     ws = lib.quik_workspace_bytes_sp24(2048, 4096, 11008, 256)
     assert ws >= 2048 * 1920 + 2 * 2048 * 4 + 2048 * 256 * 2 and ws % 256 == 0
@@ -195,10 +195,10 @@ def _decode_sp24_weights(panels, N, K_b):
             blk = [int(v) for v in panels[s, n]]
             for kappa in range(16):
                 h, qq = (kappa // 4) % 2, 4 * (kappa // 8) + kappa % 4
-                word = blk[16 + 4 * h] | blk[17 + 4 * h] << 8 | blk[18 + 4 * h] << 16 | blk[19 + 4 * h] << 24
+                word = blk[16 * h + 8] | blk[16 * h + 9] << 8 | blk[16 * h + 10] << 16 | blk[16 * h + 11] << 24
                 for e in range(2):
                     c = 2 * qq + e
-                    byte = blk[8 * h + 4 * (c // 8) + c % 4]
+                    byte = blk[16 * h + 4 * (c // 8) + c % 4]
                     nib = (byte >> 4) if (c // 4) % 2 else (byte & 0xF)
                     pos = (word >> (2 * c)) & 3
                     dec[n, 64 * s + 4 * kappa + pos] += nib - 16 if nib >= 8 else nib
@@ -221,14 +221,14 @@ def test_sp24_test_side_packers_round_trip_and_generator_is_2of4():
             w[n, gidx, rng.choice(4, 2 + (gidx % 3 == 0), replace=False)] = 0
     w = w.reshape(N, K_b)
     panels = sp24_weight_panels(w)
-    assert panels.shape == (3, 6, 24) and not panels[:, 5].any()
+    assert panels.shape == (3, 5, 32) and not panels[:, :, 12:16].any() and not panels[:, :, 28:32].any()
     dec = _decode_sp24_weights(panels, N, K_b)
     assert np.array_equal(dec[:, :K_b], w) and not dec[:, K_b:].any()
     # index positions ascend inside every pair
     for s in range(3):
         for n in range(N):
             for h in range(2):
-                word = int.from_bytes(bytes(panels[s, n, 16 + 4 * h:20 + 4 * h]), "little")
+                word = int.from_bytes(bytes(panels[s, n, 16 * h + 8:16 * h + 12]), "little")
                 for qq in range(8):
                     assert (word >> (4 * qq)) & 3 < (word >> (4 * qq + 2)) & 3
     q = rng.integers(-8, 8, size=(4, 70))

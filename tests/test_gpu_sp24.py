@@ -112,7 +112,7 @@ def test_weight_pack_sp24_counts_groups_that_are_not_2of4(api, oracle):
     with pytest.raises(api.QuikError):
         api.quik_weight_pack_sp24(buf, K_b)
     # the raw entry point reports the count and leaves the decision to the caller
-    w24 = torch.empty((K_b // 64, N, 24), dtype=torch.uint8, device="cuda")
+    w24 = torch.empty((K_b // 64, N, 32), dtype=torch.uint8, device="cuda")
     count = torch.zeros(1, dtype=torch.int32, device="cuda")
     rc = api.load().quik_weight_pack_sp24(buf.data_ptr(), buf.stride(0), N, K_b, w24.data_ptr(), count.data_ptr(), None)
     _sync()

@@ -108,11 +108,10 @@ def sp24_act_panels(q: np.ndarray) -> np.ndarray:
 
 def sp24_weight_panels(wq: np.ndarray) -> np.ndarray:
     """Signed 4-bit weights int [N, K_b] -> the weight buffer of the 2:4-sparse path as include/quik.h
-    defines it, shaped [S, R, 24] with R = N rounded up to even (the padding row is zero).  Groups
+    defines it, shaped [S, N, 32] (per half: 8 bytes of values, the index word, 4 zero bytes).  Groups
     with more than two nonzero values keep their first two."""
     N, K_b = wq.shape
     S = (K_b + 63) // 64
-    R = (N + 1) // 2 * 2
     w = np.zeros((N, 64 * S), np.int64)
     w[:, :K_b] = wq
     grp = w.reshape(N, S, 16, 4)                        # [n, s, kappa, p]
@@ -120,18 +119,18 @@ def sp24_weight_panels(wq: np.ndarray) -> np.ndarray:
     key = np.where(grp != 0, 0, 4) + np.arange(4)
     keep = np.sort(np.argsort(key, axis=3, kind="stable")[..., :2], axis=3)      # [n, s, kappa, e]
     val = np.take_along_axis(grp, keep, axis=3) & 0xF
-    out = np.zeros((S, R, 24), np.uint8)
+    out = np.zeros((S, N, 32), np.uint8)
     index = np.zeros((N, S, 2), np.uint64)
     for kappa in range(16):
         h, qq = (kappa // 4) % 2, 4 * (kappa // 8) + kappa % 4
         for e in range(2):
             c = 2 * qq + e
-            byte = 8 * h + 4 * (c // 8) + c % 4
+            byte = 16 * h + 4 * (c // 8) + c % 4
             shift = 0 if (c // 4) % 2 == 0 else 4
             out[:, :N, byte] |= (val[:, :, kappa, e].T << shift).astype(np.uint8)
             index[:, :, h] |= keep[:, :, kappa, e].astype(np.uint64) << np.uint64(2 * c)
     for h in range(2):
         word = index[:, :, h].T.astype(np.uint32)       # [s, n]
         for b in range(4):
-            out[:, :N, 16 + 4 * h + b] = ((word >> (8 * b)) & 0xFF).astype(np.uint8)
+            out[:, :N, 16 * h + 8 + b] = ((word >> (8 * b)) & 0xFF).astype(np.uint8)
     return out
