@@ -8,9 +8,9 @@
 // A workgroup of WM x WN waves owns a BM x BN output tile.  A stage is 64 columns = one matrix step = one
 // 48-byte block per operand row; the operands are stored stage by stage (quik_fp6_device.h), so the
 // tile's rows of a stage are one contiguous run of BM * 48 (BN * 48) bytes that 16-byte-per-lane DMA
-// instructions copy global -> LDS as it is.  The K loop is bound by how many bytes a CU keeps in flight
-// (completion is in order, so every request waits like the slowest before it): the stage ring takes
-// nearly all of the LDS, seven stages for the 256 x 192 tile.  Lane (row l%32, half g = l/32) reads,
+// instructions copy global -> LDS as it is.  The K loop needs many bytes in flight per CU (completion is
+// in order, so every request waits like the slowest before it), but not as many as the LDS could hold: a
+// ring of six stages for the 256 x 192 tile (108 KB in flight) runs 5 % faster than one of seven.  Lane (row l%32, half g = l/32) reads,
 // per stage, 16 bytes (dwords 0..3 of its group) and 8 bytes (dwords 4, 5); 48-byte rows need no
 // swizzle (twelve dwords per row walk all 64 banks in sixteen rows).  One workgroup barrier per stage;
 // right after it the buffer that was read during the previous stage is refilled, the DMA
@@ -447,11 +447,12 @@ template <int MODE>
 hipError_t dispatch6(const GemmArgs& a, hipStream_t stream) {
     // One workgroup of eight waves per CU, so a launch runs in ceil(tiles / 256) rounds; a 256 x 192 tile
     // takes about 1.4x as long as a 256 x 128 one.  Few tokens or few tiles: 128 x 128 tiles, two
-    // workgroups per CU.
+    // workgroups per CU.  Ring depths as measured: six buffers for the 256 x 192 tile (five 1 %, seven, all
+    // the LDS holds, 5 % slower), eight for the 256 x 128 tile (six 2 %, seven 6 % slower).
     auto rounds = [&](int bm, int bn) { return (((long)(a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn) + 255) / 256; };
     const long tiles_128 = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
     if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 6, 0, MODE>(a, stream);
-    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 7, 4, MODE>(a, stream);
+    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 6, 4, MODE>(a, stream);
     return launch_cfg<256, 128, 4, 2, 8, 4, MODE>(a, stream);
 }
 

@@ -526,12 +526,13 @@ template <int MODE>
 hipError_t dispatch24(const GemmArgs& a, hipStream_t stream) {
     // One workgroup of eight waves per CU, so a launch runs in ceil(tiles / 256) rounds; a 256 x 192 tile
     // takes about 1.4x as long as a 256 x 128 one.  Few tokens or few tiles: 128 x 128 tiles, two
-    // workgroups per CU.
+    // workgroups per CU.  Ring of eight stage buffers everywhere (measured: 6 and 8 run alike, odd counts and
+    // deeper rings up to the LDS limit 3 - 7 % slower).
     auto rounds = [&](int bm, int bn) { return (((long)(a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn) + 255) / 256; };
     const long tiles_128 = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
-    if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 9, 2, 0, MODE>(a, stream);
-    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 10, 2, 4, MODE>(a, stream);
-    return launch_cfg<256, 128, 4, 2, 12, 2, 4, MODE>(a, stream);
+    if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 8, 2, 0, MODE>(a, stream);
+    if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 8, 2, 4, MODE>(a, stream);
+    return launch_cfg<256, 128, 4, 2, 8, 2, 4, MODE>(a, stream);
 }
 
 }  // namespace
