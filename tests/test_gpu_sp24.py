@@ -153,6 +153,21 @@ LINEAR_SHAPES = [_sparse(s) for s in [
 ]]
 
 
+LINEAR_SHAPES += [_sparse(s) for s in [
+    # degenerate sizes: one token and one channel, two groups of four columns (K and the outlier count are
+    # multiples of 8), one stage and a bit
+    synth.LayerShape("one_by_one", 1, 16, 1, 8, 4, seed=61),
+    synth.LayerShape("two_groups", 3, 24, 5, 16, 4, seed=62),
+    synth.LayerShape("stage_plus_two_groups", 33, 80, 65, 8, 4, seed=63),
+    # ring shorter than / equal to / one longer than the number of stages (eight buffers)
+    synth.LayerShape("seven_stages", 130, 448 + 16, 200, 16, 4, seed=64),
+    synth.LayerShape("eight_stages", 130, 512 + 16, 200, 16, 4, seed=65),
+    synth.LayerShape("nine_stages", 300, 576 + 16, 400, 16, 4, seed=66),
+    # odd number of integer stages followed by an odd number of outlier stages
+    synth.LayerShape("odd_odd", 280, 64 * 21 + 48, 392, 48, 4, seed=67),
+]]
+
+
 @pytest.mark.parametrize("shp", LINEAR_SHAPES, ids=lambda s: s.name)
 def test_linear_sp24_matches_oracle(api, oracle, shp):
     _linear_case(api, oracle, shp)
