@@ -28,6 +28,8 @@ PEAK_SP24_TOPS = 10000.0     # 2:4-sparse int8 matrix rate counted in dense-equi
 PEAK_HBM_GBS = 8000.0
 # profiles/gemm_kernel_llama7b_up.md: (47796 KiB * 2.0 + 44033 KiB * 1.0) * 1024
 TRAFFIC_BYTES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
+# profiles/gemm_sp24_kernel_llama7b_up.md: the sparse GEMM, same factors
+TRAFFIC_BYTES_SP24 = {"llama7b_up": int((47721 * 2.0 + 44034) * 1024)}
 
 
 def _event_ms(fn, iters, torch):
@@ -278,7 +280,8 @@ def main():
                 "roofline": {"bound": "mfma", "kernel": "gemm_sp24_kernel", "peak": PEAK_SP24_TOPS,
                              "unit": "TOP/s (dense-equivalent)",
                              "achieved": 2.0 * T * K_b * N / (ms24_gemm * 1e-3) / 1e12,
-                             "frac": 2.0 * T * K_b * N / (ms24_gemm * 1e-3) / 1e12 / PEAK_SP24_TOPS},
+                             "frac": 2.0 * T * K_b * N / (ms24_gemm * 1e-3) / 1e12 / PEAK_SP24_TOPS,
+                             "traffic": TRAFFIC_BYTES_SP24.get(args.workload)},
                 "weight_bytes_per_element": 0.5, "activation_bytes_per_element": 0.5}
         del w24, ws24, q24, w_qs, inp_s
 
