@@ -178,6 +178,11 @@ def test_linear_sp24_with_bias(api, oracle):
 
 
 @pytest.mark.parametrize("shp", [_sparse(synth.LayerShape("acc_small", 100, 1024, 160, 64, 4, seed=42)),
+                                 # the K-split kernel for up to 32 tokens: ragged T and N, stage counts that do not
+                                 # divide by four, fewer stages than waves, more than 256 outlier columns
+                                 _sparse(synth.LayerShape("acc_skinny", 19, 1160, 75, 72, 4, seed=55)),
+                                 _sparse(synth.LayerShape("acc_skinny_32", 32, 4096 + 320, 200, 320, 4, seed=56)),
+                                 _sparse(synth.LayerShape("acc_skinny_short", 5, 136, 40, 8, 4, seed=57)),
                                  _sparse(synth.LayerShape("acc_big", 530, 2048, 5000, 128, 4, seed=52)),
                                  _sparse(synth.LayerShape("acc_odd_n", 300, 1088, 777, 64, 4, seed=54))],
                          ids=lambda s: s.name)
@@ -209,7 +214,7 @@ def test_sp24_worst_case_magnitudes_stay_exact(api, oracle):
     assert np.array_equal(acc.cpu().numpy().astype(np.int64), want)
 
 
-FULL_SIZE = ["llama7b_up", "llama7b_down", "llama13b_qkv_t128", "llama13b_qkv_t1024", "llama70b_up"]
+FULL_SIZE = ["llama7b_up", "llama7b_down", "llama13b_qkv_t16", "llama13b_qkv_t128", "llama13b_qkv_t1024", "llama70b_up"]
 
 
 @pytest.mark.parametrize("name", FULL_SIZE)
