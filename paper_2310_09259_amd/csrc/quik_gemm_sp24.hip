@@ -476,7 +476,6 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
 template <int NST, int MODE>
 __global__ __launch_bounds__(256) void gemm_sp24_skinny(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
-    asm volatile("" ::: "v255");                           // as in gemm_sp24_kernel (occupancy is set by the LDS here)
     constexpr int ST_BYTES = 2048, RING = NST * ST_BYTES, LPS = 2;
     constexpr int RED_BYTES = 2 * 16 * 64 * 4;             // one wave's INT32 accumulators + fp32 outlier partials
     constexpr int LDS_BYTES = (4 * RING > 3 * RED_BYTES) ? 4 * RING : 3 * RED_BYTES;
