@@ -465,19 +465,19 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
         }
 }
 
-// Small-T variant (T <= 32): the layer is bound by streaming the weights, so the point is many bytes in
-// flight per CU and many workgroups.  A workgroup owns a 32 (tokens) x 32 (channels) output tile and its
-// four waves split K: every wave streams its own quarter of the stages (1 KB of weights and 1 KB of
-// activations each, one DMA instruction apiece) through a private ring, with no workgroup barrier in the
+// Small-T variant (T <= 32 TM): the layer is bound by streaming the weights, so the point is many bytes in
+// flight per CU and many workgroups.  A workgroup owns a 32 TM (tokens) x 32 (channels) output tile and its
+// four waves split K: every wave streams its own quarter of the stages (1 KB of weights and TM KB of
+// activations each, one DMA instruction per KB) through a private ring, with no workgroup barrier in the
 // main loop (a wave waits only for its own DMA).  The four partial INT32 accumulators are summed exactly
 // through LDS; wave 0 then dequantizes, adds the fp16 outlier product (every wave takes every fourth
 // 16-column step, operands straight from global memory, requested before the weight stream starts) and
 // stores.
-template <int NST, int MODE>
+template <int TM, int NST, int MODE>
 __global__ __launch_bounds__(256) void gemm_sp24_skinny(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
-    constexpr int ST_BYTES = 2048, RING = NST * ST_BYTES, LPS = 2;
-    constexpr int RED_BYTES = 2 * 16 * 64 * 4;             // one wave's INT32 accumulators + fp32 outlier partials
+    constexpr int BM = 32 * TM, A_BYTES = BM * 32, ST_BYTES = A_BYTES + 1024, RING = NST * ST_BYTES, LPS = TM + 1;
+    constexpr int RED_BYTES = 2 * TM * 16 * 64 * 4;        // one wave's INT32 accumulators + fp32 outlier partials
     constexpr int LDS_BYTES = (4 * RING > 3 * RED_BYTES) ? 4 * RING : 3 * RED_BYTES;
     static_assert((NST - 1) * LPS < 64, "vmcnt range");
     __shared__ __align__(1024) uint8_t lds[LDS_BYTES];
@@ -486,8 +486,8 @@ __global__ __launch_bounds__(256) void gemm_sp24_skinny(GemmArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
-    const int tiles_m = (a.T + 31) / 32;
-    const int t0 = (blockIdx.x % tiles_m) * 32, n0 = (blockIdx.x / tiles_m) * 32;
+    const int tiles_m = (a.T + BM - 1) / BM;
+    const int t0 = (blockIdx.x % tiles_m) * BM, n0 = (blockIdx.x / tiles_m) * 32;
 
     const int nk = a.fp_only ? 0 : sp24::stages(a.K_b);
     const int s_begin = (int)((long)nk * wave / 4), s_end = (int)((long)nk * (wave + 1) / 4);   // this wave's stages
@@ -501,27 +501,35 @@ __global__ __launch_bounds__(256) void gemm_sp24_skinny(GemmArgs a) {
     const uint32_t vo = (uint32_t)((lane >> 1) * 32 + (((lane & 1) ^ ((lane >> 4) & 1)) * 16));
     auto issue = [&](int s) __attribute__((always_inline)) {   // stage s of this wave's range (or beyond: nothing is read)
         const uint32_t sb = (uint32_t)((s - s_begin) % NST) * ST_BYTES;
-        const uint32_t v = s < s_end ? vo : kOob;
+        const bool live = s < s_end;
         v4i ra = advance(rA, (uint32_t)s * strideA), rb = advance(rB, (uint32_t)s * strideB);
         ra = v4i{__builtin_amdgcn_readfirstlane(ra[0]), __builtin_amdgcn_readfirstlane(ra[1]),
                  __builtin_amdgcn_readfirstlane(ra[2]), __builtin_amdgcn_readfirstlane(ra[3])};
         rb = v4i{__builtin_amdgcn_readfirstlane(rb[0]), __builtin_amdgcn_readfirstlane(rb[1]),
                  __builtin_amdgcn_readfirstlane(rb[2]), __builtin_amdgcn_readfirstlane(rb[3])};
-        dma16(ra, (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_addr + sb)), v, 0);
-        dma16(rb, (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_addr + sb + 1024)), v, 0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            dma16(ra, (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_addr + sb + i * 1024)), live ? vo + i * 1024 : kOob, 0);
+        dma16(rb, (uint32_t)__builtin_amdgcn_readfirstlane((int)(ring_addr + sb + A_BYTES)), live ? vo : kOob, 0);
     };
     const uint32_t rd = (uint32_t)(l32 * 32 + ((g ^ swz_f(l32)) << 4));   // this lane's piece of its row
 
     // ---- everything the epilogue needs is requested before the weight stream starts
-    constexpr int PF = 4;                                  // prefetched outlier steps per wave (n_out <= 256)
-    float t_s = 0.0f, t_z = 0.0f;
-    uint4 pfa[PF], pfb[PF];
+    constexpr int PF = (TM == 1) ? 4 : 2;                  // prefetched outlier steps per wave
+    float t_s[TM], t_z[TM];
+    uint4 pfa[PF][TM], pfb[PF];
     const int fsteps = (a.n_out + 15) >> 4;                // 16-column steps of the outlier product
     const __half* __restrict__ xo = static_cast<const __half*>(a.x_out);
     const __half* __restrict__ wo = static_cast<const __half*>(a.w_out);
+    const int n2 = min(n0 + l32, a.N - 1);
     if constexpr (!RAW) {
-        const int t = t0 + l32;
-        if (t < a.T && !a.fp_only) { t_s = a.scale[t]; t_z = a.zero[t]; }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int t = t0 + i * 32 + l32;
+            const bool ok = t < a.T && !a.fp_only;
+            t_s[i] = ok ? a.scale[t] : 0.0f;
+            t_z[i] = ok ? a.zero[t] : 0.0f;
+        }
         if (tid < 32) {
             const int n = min(n0 + tid, a.N - 1);
             const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
@@ -534,15 +542,20 @@ __global__ __launch_bounds__(256) void gemm_sp24_skinny(GemmArgs a) {
         for (int q = 0; q < PF; ++q) {
             const int kk = (wave + 4 * q) * 16 + g * 8;    // first of this lane's 8 outlier columns
             const bool live = (wave + 4 * q) < fsteps && kk < a.n_out;
-            const int t2 = min(t0 + l32, a.T - 1), n2 = min(n0 + l32, a.N - 1);
-            pfa[q] = live ? *reinterpret_cast<const uint4*>(xo + (size_t)t2 * a.ldo + kk) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int t2 = min(t0 + i * 32 + l32, a.T - 1);
+                pfa[q][i] = live ? *reinterpret_cast<const uint4*>(xo + (size_t)t2 * a.ldo + kk) : make_uint4(0, 0, 0, 0);
+            }
             pfb[q] = live ? *reinterpret_cast<const uint4*>(wo + (size_t)n2 * a.ldwo + kk) : make_uint4(0, 0, 0, 0);
         }
     }
 
-    v16i acc;
+    v16i acc[TM];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0;
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
 
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s_begin + s);
@@ -550,32 +563,43 @@ __global__ __launch_bounds__(256) void gemm_sp24_skinny(GemmArgs a) {
         issue(s + NST - 1);
         wait_vm<(NST - 1) * LPS>();                        // stage s has landed (this wave's own loads)
         const uint8_t* st = ring + ((s - s_begin) % NST) * ST_BYTES;
-        const uint4 wa = *reinterpret_cast<const uint4*>(st + rd);
-        const uint4 ww = *reinterpret_cast<const uint4*>(st + 1024 + rd);
         constexpr uint32_t M = 0xF0F0F0F0u;
-        const v8i ua = v8i{(int)(wa.x & M), (int)((wa.x << 4) & M), (int)(wa.y & M), (int)((wa.y << 4) & M),
-                           (int)(wa.z & M), (int)((wa.z << 4) & M), (int)(wa.w & M), (int)((wa.w << 4) & M)};
+        const uint4 ww = *reinterpret_cast<const uint4*>(st + A_BYTES + rd);
         const v4i uw = v4i{(int)((ww.x << 4) & M), (int)(ww.x & M), (int)((ww.y << 4) & M), (int)(ww.y & M)};
-        acc = __builtin_amdgcn_smfmac_i32_32x32x64_i8(uw, ua, acc, (int)ww.z, 0, 0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const uint4 wa = *reinterpret_cast<const uint4*>(st + i * 1024 + rd);
+            const v8i ua = v8i{(int)(wa.x & M), (int)((wa.x << 4) & M), (int)(wa.y & M), (int)((wa.y << 4) & M),
+                               (int)(wa.z & M), (int)((wa.z << 4) & M), (int)(wa.w & M), (int)((wa.w << 4) & M)};
+            acc[i] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(uw, ua, acc[i], (int)ww.z, 0, 0);
+        }
         // the buffer read here is refilled NST - 1 iterations later by this same wave: the LDS reads above
-        // have returned (their data fed the matrix instruction) before that DMA is issued
+        // have returned (their data fed the matrix instructions) before that DMA is issued
     }
     wait_vm<0>();
 
     // ---- this wave's share of the fp16 outlier product (weights first: same accumulator layout)
-    v16f cf;
+    v16f cf[TM];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) cf[r] = 0.0f;
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cf[i][r] = 0.0f;
     if constexpr (!RAW) {
 #pragma unroll
         for (int q = 0; q < PF; ++q)
-            cf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, pfb[q]), __builtin_bit_cast(v8h, pfa[q]), cf, 0, 0, 0);
-        for (int stp = wave + 4 * PF; stp < fsteps; stp += 4) {     // more than 16 * 4 * PF outlier columns
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                cf[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, pfb[q]), __builtin_bit_cast(v8h, pfa[q][i]),
+                                                               cf[i], 0, 0, 0);
+        for (int stp = wave + 4 * PF; stp < fsteps; stp += 4) {     // the outlier columns beyond the prefetched ones
             const int kk = stp * 16 + g * 8;
-            const int t2 = min(t0 + l32, a.T - 1), n2 = min(n0 + l32, a.N - 1);
-            const uint4 fa = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(xo + (size_t)t2 * a.ldo + kk) : make_uint4(0, 0, 0, 0);
             const uint4 fb = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(wo + (size_t)n2 * a.ldwo + kk) : make_uint4(0, 0, 0, 0);
-            cf = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, fb), __builtin_bit_cast(v8h, fa), cf, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int t2 = min(t0 + i * 32 + l32, a.T - 1);
+                const uint4 fa = (kk < a.n_out) ? *reinterpret_cast<const uint4*>(xo + (size_t)t2 * a.ldo + kk) : make_uint4(0, 0, 0, 0);
+                cf[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, fb), __builtin_bit_cast(v8h, fa), cf[i], 0, 0, 0);
+            }
         }
     }
     __syncthreads();                                       // rings are dead: reuse LDS for the reduction
@@ -583,44 +607,51 @@ __global__ __launch_bounds__(256) void gemm_sp24_skinny(GemmArgs a) {
     // ---- sum the four partial results: waves 1..3 publish, wave 0 adds (INT32 exactly; the fp32 outlier
     // partials in wave order)
     int* red = reinterpret_cast<int*>(lds);
-    float* redf = reinterpret_cast<float*>(lds) + 3 * 16 * 64;
+    float* redf = reinterpret_cast<float*>(lds) + 3 * TM * 16 * 64;
     if (wave > 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int slot = ((wave - 1) * 16 + r) * 64 + lane;
-            red[slot] = acc[r];
-            if constexpr (!RAW) redf[slot] = cf[r];
-        }
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int slot = (((wave - 1) * TM + i) * 16 + r) * 64 + lane;
+                red[slot] = acc[i][r];
+                if constexpr (!RAW) redf[slot] = cf[i][r];
+            }
     }
     __syncthreads();
     if (wave > 0) return;
-#pragma unroll
+#pragma unroll 1
     for (int w = 0; w < 3; ++w)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int slot = (w * 16 + r) * 64 + lane;
-            acc[r] += red[slot];
-            if constexpr (!RAW) cf[r] += redf[slot];
-        }
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int slot = ((w * TM + i) * 16 + r) * 64 + lane;
+                acc[i][r] += red[slot];
+                if constexpr (!RAW) cf[i][r] += redf[slot];
+            }
 
-    // lane: token t0 + l32; register r: channel n0 + 8 (r / 4) + 4 g + r % 4
-    const int t = t0 + l32;
-    if constexpr (RAW) {
+    // lane: token t0 + 32 i + l32; register r: channel n0 + 8 (r / 4) + 4 g + r % 4
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int n = n0 + 8 * (r >> 2) + 4 * g + (r & 3);
-            if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = acc[r] >> 8;   // exact: a multiple of 256
-        }
-    } else {
-        __half* __restrict__ y = static_cast<__half*>(a.y);
-        const float t_h = t_z + 8.0f * t_s;                // zeroAct + halfRange * scaleAct
+    for (int i = 0; i < TM; ++i) {
+        const int t = t0 + i * 32 + l32;
+        if constexpr (RAW) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int c = 8 * (r >> 2) + 4 * g + (r & 3), n = n0 + c;
-            const float v = __builtin_fmaf((float)acc[r], t_s * prm_sw[c], __builtin_fmaf(t_h, prm_wr[c], prm_bv[c])) + cf[r];
-            if (t < a.T && n < a.N) {
-                if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = v;
-                else y[(size_t)t * a.ldy + n] = __float2half(v);
+            for (int r = 0; r < 16; ++r) {
+                const int n = n0 + 8 * (r >> 2) + 4 * g + (r & 3);
+                if (t < a.T && n < a.N) a.acc[(size_t)t * a.ldacc + n] = acc[i][r] >> 8;   // exact: a multiple of 256
+            }
+        } else {
+            __half* __restrict__ y = static_cast<__half*>(a.y);
+            const float t_h = t_z[i] + 8.0f * t_s[i];      // zeroAct + halfRange * scaleAct
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int c = 8 * (r >> 2) + 4 * g + (r & 3), n = n0 + c;
+                const float v = __builtin_fmaf((float)acc[i][r], t_s[i] * prm_sw[c], __builtin_fmaf(t_h, prm_wr[c], prm_bv[c])) + cf[i][r];
+                if (t < a.T && n < a.N) {
+                    if (a.fp_only) reinterpret_cast<float*>(a.y)[(size_t)t * a.ldy + n] = v;
+                    else y[(size_t)t * a.ldy + n] = __float2half(v);
+                }
             }
         }
     }
@@ -685,11 +716,14 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
 
 template <int MODE>
 hipError_t dispatch24(const GemmArgs& a, hipStream_t stream) {
+    // Few tokens: weight streaming dominates.  The K-split kernel, one workgroup per 32 channels and 32 or 64
+    // tokens (ring depth at 32 tokens: 4 and 6 measured alike, 8 to 16 up to 15 % slower).
     if (a.T <= 32) {
-        // weight streaming dominates: the K-split kernel, one workgroup per 32 channels (ring depth: 4 and 6
-        // measured alike, 8 to 16 up to 15 % slower)
-        const int tiles = ((a.T + 31) / 32) * ((a.N + 31) / 32);
-        hipLaunchKernelGGL((gemm_sp24_skinny<4, MODE>), dim3(tiles), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((gemm_sp24_skinny<1, 4, MODE>), dim3((a.N + 31) / 32), dim3(256), 0, stream, a);
+        return hipGetLastError();
+    }
+    if (a.T <= 64) {
+        hipLaunchKernelGGL((gemm_sp24_skinny<2, 4, MODE>), dim3((a.N + 31) / 32), dim3(256), 0, stream, a);
         return hipGetLastError();
     }
     // One workgroup of eight waves per CU, so a launch runs in ceil(tiles / 256) rounds; a 256 x 192 tile
