@@ -186,6 +186,7 @@ def test_linear_sp24_with_bias(api, oracle):
                                  # its 64-token form: ragged second token fragment, N not a multiple of 32
                                  _sparse(synth.LayerShape("acc_skinny_64", 57, 2304 + 64, 101, 64, 4, seed=58)),
                                  _sparse(synth.LayerShape("acc_skinny_64_full", 64, 640 + 8, 64, 8, 4, seed=59)),
+                                 _sparse(synth.LayerShape("acc_skinny_64_outliers", 40, 1024 + 264, 70, 264, 4, seed=60)),
                                  _sparse(synth.LayerShape("acc_big", 530, 2048, 5000, 128, 4, seed=52)),
                                  _sparse(synth.LayerShape("acc_odd_n", 300, 1088, 777, 64, 4, seed=54))],
                          ids=lambda s: s.name)
