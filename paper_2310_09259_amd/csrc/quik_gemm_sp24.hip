@@ -50,7 +50,7 @@ __device__ __forceinline__ v4i advance(v4i r, uint32_t bytes) {
 }
 
 // MODE 0: fused epilogue, fp16 output; MODE 1: the integer accumulators as INT32.
-// NST: stage buffers of the ring; KS: stages per workgroup barrier (NST a multiple of KS).
+// NST: stage buffers of the ring; KS: stages per workgroup barrier.
 template <int BM, int BN, int WM, int WN, int NST, int KS, int GM, int MODE>
 __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp24_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
