@@ -94,9 +94,30 @@ def run_sweep(args, shp, torch, api, synth):
         for _ in range(5):
             torch.nn.functional.linear(x, wf)
         ms16 = _event_ms(lambda: torch.nn.functional.linear(x, wf), args.steps, torch)
-        rows.append({"T": p.T, "n_out": p.n_out, "quik_ms": ms, "fp16_ms": ms16, "speedup": ms16 / ms,
-                     "tops": 2.0 * p.T * p.K * p.N / (ms * 1e-3) / 1e12})
-        del wf, x, w_q, y, ws
+        row = {"T": p.T, "n_out": p.n_out, "quik_ms": ms, "fp16_ms": ms16, "speedup": ms16 / ms,
+               "tops": 2.0 * p.T * p.K * p.N / (ms * 1e-3) / 1e12}
+        del wf
+        if p.bits == 4 and p.weight_bits == 4 and p.K <= 16384:
+            # the other two forms of the 4-bit layer on the same shape (the sparse one on the same
+            # weights with two of every four base columns cleared)
+            w6 = api.quik_weight_pack_fp6(w_q, p.K_b)
+            step6, _ = api.prepare_linear_fp6(x, idx, w6, w_scale, w_red, w_out, out=y)
+            for _ in range(max(5, args.warmup // 4)):
+                step6()
+            row["fp6_ms"] = _event_ms(step6, args.steps, torch)
+            del w6, step6
+            if p.K_b % 4 == 0:
+                inp_s = synth.make_inputs(dataclasses.replace(p, sparse24=True))
+                w_qs = torch.from_numpy(inp_s.w_packed).to(dev)
+                w_red_s, _ = api.quik_weight_reduce(w_qs, w_scale, p.K_b, 4)
+                w24 = api.quik_weight_pack_sp24(w_qs, p.K_b)
+                step24, _ = api.prepare_linear_sp24(x, idx, w24, w_scale, w_red_s, w_out, out=y)
+                for _ in range(max(5, args.warmup // 4)):
+                    step24()
+                row["sp24_ms"] = _event_ms(step24, args.steps, torch)
+                del w24, step24, w_qs, inp_s
+        rows.append(row)
+        del x, w_q, y, ws
     return {"sweep": args.sweep, "workload": f"{shp.name}: K={shp.K} N={shp.N} bits={shp.bits}",
             "steps": args.steps, "rows": rows}
 
