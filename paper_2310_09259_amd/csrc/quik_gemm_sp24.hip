@@ -78,7 +78,7 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN == 8) ? 1 : 2) void gemm_sp2
     // stages 0 .. NST - 1.  (fp16 stages: read one stage ahead, a barrier before every stage.)
     constexpr int AHEAD = NST;
     constexpr int WAIT_BAR = (NST - KS - 2) * LPS;        // requests that may still be in flight at a barrier
-    static_assert(SL >= 4 && SL >= LPS && TM <= (TM - 1) * TN, "a stage has too few matrix instructions to place its reads and copies");
+    static_assert(SL >= 2 && SL >= LPS && SL >= TM, "a stage has too few matrix instructions to place its reads and copies");
     constexpr int DUMMY = NST * ST_BYTES;                 // 1 KB that empty DMA instructions clear
 
     __shared__ __align__(1024) uint8_t lds[NST * ST_BYTES + 1024];
@@ -735,12 +735,15 @@ hipError_t dispatch24(const GemmArgs& a, hipStream_t stream) {
         return hipGetLastError();
     }
     // One workgroup of eight waves per CU, so a launch runs in ceil(tiles / 256) rounds; a 256 x 192 tile
-    // takes about 1.4x as long as a 256 x 128 one.  Few tokens or few tiles: 128 x 128 tiles, two
-    // workgroups per CU.  Ring of eight stage buffers everywhere (measured: 6 and 8 run alike, odd counts and
+    // takes about 1.4x as long as a 256 x 128 one.  Few tiles: 128 x 128 tiles, two workgroups per CU.
+    // Ring of eight stage buffers everywhere (measured: 6 and 8 run alike, odd counts and
     // deeper rings up to the LDS limit 3 - 7 % slower).
     auto rounds = [&](int bm, int bn) { return (((long)(a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn) + 255) / 256; };
     const long tiles_128 = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
-    if (a.T <= 128 || tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 8, 2, 0, MODE>(a, stream);
+    // 65 .. 128 tokens: 128 x 64 tiles (twice the workgroups of 128 x 128 tiles: 15 % faster there, slower
+    // from 192 tokens on)
+    if (a.T <= 128) return launch_cfg<128, 64, 2, 2, 8, 2, 0, MODE>(a, stream);
+    if (tiles_128 < 256) return launch_cfg<128, 128, 2, 2, 8, 2, 0, MODE>(a, stream);
     if (1.4 * (double)rounds(256, 192) <= (double)rounds(256, 128)) return launch_cfg<256, 192, 4, 2, 8, 2, 4, MODE>(a, stream);
     return launch_cfg<256, 128, 4, 2, 8, 2, 4, MODE>(a, stream);
 }

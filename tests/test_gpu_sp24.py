@@ -163,6 +163,9 @@ LINEAR_SHAPES += [_sparse(s) for s in [
     synth.LayerShape("seven_stages", 130, 448 + 16, 200, 16, 4, seed=64),
     synth.LayerShape("eight_stages", 130, 512 + 16, 200, 16, 4, seed=65),
     synth.LayerShape("nine_stages", 300, 576 + 16, 400, 16, 4, seed=66),
+    # 65 .. 128 tokens: 128 x 64 tiles (two matrix instructions per wave and stage), ragged T and N
+    synth.LayerShape("tiles_128x64", 97, 1096, 150, 72, 4, seed=68),
+    synth.LayerShape("tiles_128x64_full", 128, 2048 + 128, 192, 128, 4, seed=69),
     # odd number of integer stages followed by an odd number of outlier stages
     synth.LayerShape("odd_odd", 280, 64 * 21 + 48, 392, 48, 4, seed=67),
 ]]
@@ -188,7 +191,8 @@ def test_linear_sp24_with_bias(api, oracle):
                                  _sparse(synth.LayerShape("acc_skinny_64_full", 64, 640 + 8, 64, 8, 4, seed=59)),
                                  _sparse(synth.LayerShape("acc_skinny_64_outliers", 40, 1024 + 264, 70, 264, 4, seed=60)),
                                  _sparse(synth.LayerShape("acc_big", 530, 2048, 5000, 128, 4, seed=52)),
-                                 _sparse(synth.LayerShape("acc_odd_n", 300, 1088, 777, 64, 4, seed=54))],
+                                 _sparse(synth.LayerShape("acc_odd_n", 300, 1088, 777, 64, 4, seed=54)),
+                                 _sparse(synth.LayerShape("acc_128x64", 120, 1344 + 24, 333, 24, 4, seed=70))],
                          ids=lambda s: s.name)
 def test_sp24_accumulators_are_the_exact_integers(api, oracle, shp):
     inp, d, ref, w_red, w24, y = _linear_case(api, oracle, shp)
