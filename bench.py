@@ -32,6 +32,11 @@ TRAFFIC_BYTES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
 TRAFFIC_BYTES_SP24 = {"llama7b_up": int((47721 * 2.0 + 44034) * 1024)}
 
 
+PREHEAT_MS = 150.0           # continuous load before any timing (the clocks need ~40-100 ms to settle)
+MIN_EVENT_ITERS = 200        # launches per HIP-event timing of a single kernel
+MIN_TIMED_MS = 200.0         # the --steps batch is repeated until this much has been timed
+
+
 def _event_ms(fn, iters, torch):
     """Average duration of fn() in ms over `iters` back-to-back launches, measured with
     HIP events recorded on the stream the kernels are launched on (torch's current one)."""
@@ -42,6 +47,27 @@ def _event_ms(fn, iters, torch):
     stop.record()
     stop.synchronize()
     return start.elapsed_time(stop) / iters
+
+
+def _preheat(fn, torch, ms=PREHEAT_MS):
+    """Run fn() back to back for at least `ms` of GPU time, whatever --warmup says: after idle the
+    chip runs short bursts up to 20 % slower than its sustained rate.  Returns the ms spent."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while True:
+        for _ in range(50):
+            fn()
+        torch.cuda.synchronize()
+        spent = (time.perf_counter() - t0) * 1e3
+        if spent >= ms:
+            return spent
+
+
+def _kernel_ms(fn, torch, iters=MIN_EVENT_ITERS):
+    """HIP-event time of one launch of fn at sustained clocks: a short pre-heat with the same launch,
+    then the average over `iters` back-to-back launches."""
+    _preheat(fn, torch, 30.0)
+    return _event_ms(fn, iters, torch)
 
 
 def cpu_baseline(inp, shp, budget_s=15.0):
@@ -82,11 +108,11 @@ def run_sweep(args, shp, torch, api, synth):
         w_q = torch.from_numpy(inp.w_packed).to(dev)
         w_scale = torch.from_numpy(inp.w_scale).to(dev)
         w_out = torch.from_numpy(inp.w_out).to(dev) if p.n_out else None
-        w_red, w_cs = api.quik_weight_reduce(w_q, w_scale, p.K_b, p.bits)
+        w_red = api.quik_weight_reduce(w_q, w_scale, p.K_b, p.bits)
         ws = torch.empty(api.quik_workspace_bytes(p.T, p.K, p.N, p.n_out, p.bits), dtype=torch.uint8,
                          device=dev)
         y = torch.empty((p.T, p.N), dtype=torch.float16, device=dev)
-        step, _ = api.prepare_linear(x, idx, p.bits, w_q, w_scale, w_red, w_cs, w_out, out=y, workspace=ws)
+        step, _ = api.prepare_linear(x, idx, p.bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
         for _ in range(args.warmup):
             step()
         ms = _event_ms(step, args.steps, torch)
@@ -109,7 +135,7 @@ def run_sweep(args, shp, torch, api, synth):
             if p.K_b % 4 == 0:
                 inp_s = synth.make_inputs(dataclasses.replace(p, sparse24=True))
                 w_qs = torch.from_numpy(inp_s.w_packed).to(dev)
-                w_red_s, _ = api.quik_weight_reduce(w_qs, w_scale, p.K_b, 4)
+                w_red_s = api.quik_weight_reduce(w_qs, w_scale, p.K_b, 4)
                 w24 = api.quik_weight_pack_sp24(w_qs, p.K_b)
                 step24, _ = api.prepare_linear_sp24(x, idx, w24, w_scale, w_red_s, w_out, out=y)
                 for _ in range(max(5, args.warmup // 4)):
@@ -120,6 +146,41 @@ def run_sweep(args, shp, torch, api, synth):
         del x, w_q, y, ws
     return {"sweep": args.sweep, "workload": f"{shp.name}: K={shp.K} N={shp.N} bits={shp.bits}",
             "steps": args.steps, "rows": rows}
+
+
+def run_only(args, api, torch, shp, x, idx, w_q, w_scale, w_red, w_out, y, ws, step):
+    """--only: `--steps` launches of one kernel on the workload's buffers, for counter runs."""
+    import dataclasses
+    from paper_2310_09259_amd import synth
+    T, K, N, K_b, n_out, bits = shp.T, shp.K, shp.N, shp.K_b, shp.n_out, shp.bits
+    xo = lambda q: q[3] if n_out else None
+    if args.only == "layer":
+        fn = step
+    elif args.only == "quantize":
+        fn = api.prepare_quantize(x, idx, bits, api.quik_quantize(x, idx, bits))
+    elif args.only == "gemm":
+        q = api.quik_quantize(x, idx, bits)
+        fn = api.prepare_gemm_dequant(q[0], q[1], q[2], xo(q), K_b, bits, w_q, w_scale, w_red, w_out, None, y, q[4])
+    elif args.only == "gemm_fp6":
+        w6 = api.quik_weight_pack_fp6(w_q, K_b)
+        q = api.quik_quantize_fp6(x, idx)
+        fn = api.prepare_gemm_dequant_fp6(q[0], q[1], q[2], xo(q), K_b, w6, w_scale, w_red, w_out, None, y)
+    elif args.only == "gemm_sp24":
+        inp_s = synth.make_inputs(dataclasses.replace(shp, sparse24=True))
+        w_qs = torch.from_numpy(inp_s.w_packed).to("cuda")
+        w_red_s = api.quik_weight_reduce(w_qs, w_scale, K_b, 4)
+        w24 = api.quik_weight_pack_sp24(w_qs, K_b)
+        q = api.quik_quantize_sp24(x, idx)
+        fn = api.prepare_gemm_dequant_sp24(q[0], q[1], q[2], xo(q), K_b, w24, w_scale, w_red_s, w_out, None, y)
+    else:                                       # a kernel of known traffic, to scale FETCH_SIZE / WRITE_SIZE
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        fn = lambda: api.quik_debug_copy_probe(src, dst)
+    for _ in range(args.warmup):
+        fn()
+    torch.cuda.synchronize()
+    ms = _event_ms(fn, args.steps, torch)
+    print(json.dumps({"only": args.only, "workload": shp.name, "launches": args.steps, "ms_per_launch": ms}))
 
 
 def main():
@@ -146,6 +207,9 @@ def main():
                     help="skip the timing of the FP6-matrix-pipe form of the 4-bit layer")
     ap.add_argument("--no-sp24", action="store_true",
                     help="skip the timing of the 2:4-sparse form of the 4-bit layer")
+    ap.add_argument("--only", choices=["layer", "gemm", "quantize", "gemm_fp6", "gemm_sp24", "copy"], default=None,
+                    help="launch just this kernel (or the two of the layer) --steps times after --warmup "
+                         "launches and exit: a short command line for rocprofv3 counter runs")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (a kernel of known "
                          "traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
@@ -174,7 +238,7 @@ def main():
     w_q = torch.from_numpy(inp.w_packed).to(dev)
     w_scale = torch.from_numpy(inp.w_scale).to(dev)
     w_out = torch.from_numpy(inp.w_out).to(dev) if shp.n_out else None
-    w_red, w_cs = api.quik_weight_reduce(w_q, w_scale, shp.K_b, shp.weight_bits)
+    w_red = api.quik_weight_reduce(w_q, w_scale, shp.K_b, shp.weight_bits)
     T, K, N, K_b, n_out, bits = shp.T, shp.K, shp.N, shp.K_b, shp.n_out, shp.bits
     mixed = shp.weight_bits != bits        # 4-bit weights under 8-bit activations
     ws = torch.empty(api.quik_workspace_bytes(T, K, N, n_out, bits), dtype=torch.uint8, device=dev)
@@ -186,9 +250,9 @@ def main():
         step, _ = api.prepare_linear_w4a8(x, idx, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
     elif args.graph:
         def step():
-            api.quik_linear(x, idx, bits, w_q, w_scale, w_red, w_cs, w_out, out=y, workspace=ws)
+            api.quik_linear(x, idx, bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
     else:
-        step, _ = api.prepare_linear(x, idx, bits, w_q, w_scale, w_red, w_cs, w_out, out=y, workspace=ws)
+        step, _ = api.prepare_linear(x, idx, bits, w_q, w_scale, w_red, w_out, out=y, workspace=ws)
 
     # --graph: the timed region replays a HIP graph that holds one step (both launches, captured
     # from the same C-ABI call on the capture stream).
@@ -205,30 +269,70 @@ def main():
         with torch.cuda.graph(graph):
             step()
     run = graph.replay if graph is not None else step
+    if args.only:
+        # a short, single-kernel command line for counter runs (rocprofv3 --pmc): `--steps` launches of
+        # one kernel, nothing else
+        run_only(args, api, torch, shp, x, idx, w_q, w_scale, w_red, w_out, y, ws, step)
+        return
+    preheat_ms = _preheat(run, torch)
     for _ in range(args.warmup):
         run()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # EXACTLY --steps steps per timed batch, bracketed by synchronizations; the batch is repeated until
+    # MIN_TIMED_MS have been timed and the median batch is reported
+    batches = []
+    while True:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        batches.append((time.perf_counter() - t0) * 1e3)
+        if sum(batches) >= MIN_TIMED_MS and len(batches) >= 3:
+            break
+    ms_step = float(np.median(batches)) / args.steps
 
     # per-kernel durations (HIP events on the launch stream), same buffers
-    xq, scale, zero, x_out, cs = api.quik_quantize(x, idx, bits)
-    q_out = (xq, scale, zero, x_out, cs)
-    it = max(20, args.steps // 2)
+    q_out = api.quik_quantize(x, idx, bits)
+    xq, scale, zero, x_out, side = q_out
+    it = max(MIN_EVENT_ITERS, args.steps // 2)
     quant_call = api.prepare_quantize(x, idx, bits, q_out)
     if mixed:
         def gemm_call():
             api.quik_gemm_dequant_w4a8(xq, scale, zero, x_out if n_out else None, K_b, w_q, w_scale, w_red,
                                        w_out, out=y)
     else:
-        gemm_call = api.prepare_gemm_dequant(xq, scale, zero, cs, x_out if n_out else None, K_b, bits, w_q,
-                                             w_scale, w_red, w_cs, w_out, None, y)
-    ms_quant = _event_ms(quant_call, it, torch)
-    ms_gemm = _event_ms(gemm_call, it, torch)
-    ms_layer_ev = _event_ms(step, it, torch)
+        gemm_call = api.prepare_gemm_dequant(xq, scale, zero, x_out if n_out else None, K_b, bits, w_q,
+                                             w_scale, w_red, w_out, None, y, side)
+    ms_quant = _kernel_ms(quant_call, torch, it)
+    ms_gemm = _kernel_ms(gemm_call, torch, it)
+    ms_layer_ev = _kernel_ms(step, torch, it)
+
+    # the quantization kernel on inputs that are NOT cache-resident: a rotation of distinct input and
+    # output buffer sets larger than the 256 MB last-level cache (the figure above re-reads one 17 MB
+    # input, which stays in that cache)
+    quant_bytes = T * (2 * K + K_b * bits // 8 + 2 * n_out + 8 + (4 if bits == 4 else 0))
+    n_rot = max(32, int(2 * (256 << 20) / quant_bytes) + 1)
+    rot_x = [x.clone() for _ in range(n_rot)]
+    rot_out = [tuple(torch.empty_like(t) for t in q_out) for _ in range(n_rot)]
+    rot_calls = [api.prepare_quantize(rx, idx, bits, ro) for rx, ro in zip(rot_x, rot_out)]
+
+    def quant_rotation():
+        for c in rot_calls:
+            c()
+    _preheat(quant_rotation, torch, 30.0)
+    ms_quant_cold = _event_ms(quant_rotation, max(2, MIN_EVENT_ITERS // n_rot), torch) / n_rot
+    del rot_x, rot_out, rot_calls
+
+    # what the chip sustains: the int8 matrix instruction alone, and a plain streaming copy
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    probe_ops = api.quik_debug_mfma_probe(2048, 2000, sink)
+    ms_probe = _kernel_ms(lambda: api.quik_debug_mfma_probe(2048, 2000, sink), torch, 20)
+    measured_mfma_tops = probe_ops / (ms_probe * 1e-3) / 1e12
+    src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    ms_copy = _kernel_ms(lambda: api.quik_debug_copy_probe(src, dst), torch, 20)
+    measured_hbm_gbs = 2.0 * src.numel() / (ms_copy * 1e-3) / 1e9
+    del src, dst
 
     if args.calibration_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -244,11 +348,9 @@ def main():
     ablation = {}
     no_ablation = args.no_ablation or mixed          # the unfused variants exist for equal widths only
     for version in (() if no_ablation else (1, 2, 3)):
-        fn = lambda v=version: api.quik_linear_ablation(v, x, idx, bits, w_q, w_scale, w_red, w_cs, w_out,
+        fn = lambda v=version: api.quik_linear_ablation(v, x, idx, bits, w_q, w_scale, w_red, w_out,
                                                         out=y, workspace=ws_abl)
-        for _ in range(5):
-            fn()
-        ablation[f"v{version}"] = _event_ms(fn, it, torch)
+        ablation[f"v{version}"] = _kernel_ms(fn, torch, it)
     del ws_abl
 
     # the same 4-bit layer with the integer product on the FP6 matrix pipe (exact; reported beside the
@@ -262,11 +364,9 @@ def main():
         gemm6 = api.prepare_gemm_dequant_fp6(q6[0], q6[1], q6[2], q6[3] if n_out else None, K_b, w6, w_scale,
                                              w_red, w_out, None, y)
         quant6 = api.prepare_quantize_fp6(x, idx, q6)
-        for _ in range(max(10, args.warmup // 2)):
-            step6()
-        ms6_layer = _event_ms(step6, it, torch)
-        ms6_gemm = _event_ms(gemm6, it, torch)
-        ms6_quant = _event_ms(quant6, it, torch)
+        ms6_layer = _kernel_ms(step6, torch, it)
+        ms6_gemm = _kernel_ms(gemm6, torch, it)
+        ms6_quant = _kernel_ms(quant6, torch, it)
         fp6 = {"layer_ms": ms6_layer, "layer_TOPS": 2.0 * T * K * N / (ms6_layer * 1e-3) / 1e12,
                "kernels_ms": {"quik_quantize_fp6": ms6_quant, "quik_gemm_dequant_fp6": ms6_gemm},
                "roofline": {"bound": "mfma", "kernel": "gemm_fp6_kernel", "peak": PEAK_FP6_TOPS, "unit": "TOP/s",
@@ -283,7 +383,7 @@ def main():
         import dataclasses
         inp_s = synth.make_inputs(dataclasses.replace(shp, sparse24=True))
         w_qs = torch.from_numpy(inp_s.w_packed).to(dev)
-        w_red_s, _ = api.quik_weight_reduce(w_qs, w_scale, K_b, 4)
+        w_red_s = api.quik_weight_reduce(w_qs, w_scale, K_b, 4)
         w24 = api.quik_weight_pack_sp24(w_qs, K_b)
         ws24 = torch.empty(api.quik_workspace_bytes_sp24(T, K, N, n_out), dtype=torch.uint8, device=dev)
         step24, _ = api.prepare_linear_sp24(x, idx, w24, w_scale, w_red_s, w_out, out=y, workspace=ws24)
@@ -291,11 +391,9 @@ def main():
         gemm24 = api.prepare_gemm_dequant_sp24(q24[0], q24[1], q24[2], q24[3] if n_out else None, K_b, w24,
                                                w_scale, w_red_s, w_out, None, y)
         quant24 = api.prepare_quantize_sp24(x, idx, q24)
-        for _ in range(max(10, args.warmup // 2)):
-            step24()
-        ms24_layer = _event_ms(step24, it, torch)
-        ms24_gemm = _event_ms(gemm24, it, torch)
-        ms24_quant = _event_ms(quant24, it, torch)
+        ms24_layer = _kernel_ms(step24, torch, it)
+        ms24_gemm = _kernel_ms(gemm24, torch, it)
+        ms24_quant = _kernel_ms(quant24, torch, it)
         sp24 = {"layer_ms": ms24_layer, "layer_TOPS_dense_equivalent": 2.0 * T * K * N / (ms24_layer * 1e-3) / 1e12,
                 "kernels_ms": {"quik_quantize_sp24": ms24_quant, "quik_gemm_dequant_sp24": ms24_gemm},
                 "roofline": {"bound": "mfma", "kernel": "gemm_sp24_kernel", "peak": PEAK_SP24_TOPS,
@@ -309,19 +407,17 @@ def main():
     ms_fp16 = None
     if not args.no_fp16:
         wf = (torch.randn((N, K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
-        for _ in range(max(10, args.warmup // 2)):
-            torch.nn.functional.linear(x, wf)
-        ms_fp16 = _event_ms(lambda: torch.nn.functional.linear(x, wf), it, torch)
+        ms_fp16 = _kernel_ms(lambda: torch.nn.functional.linear(x, wf), torch, it)
         del wf
 
     ops_layer = 2.0 * T * K * N
     ops_int = 2.0 * T * K_b * N
     tops = ops_layer / (ms_step * 1e-3) / 1e12
     gemm_tops = ops_int / (ms_gemm * 1e-3) / 1e12
-    quant_bytes = T * (2 * K + K_b * bits // 8 + 2 * n_out + 8 + (4 if bits == 4 else 0))
     out = {
         "metric": "QUIK linear TOPS (whole layer: quantize + INT4 GEMM + dequant + fp16 outliers)",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "preheat_ms": preheat_ms, "timed_batches": len(batches),
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": (f"int{shp.weight_bits} weights x int{bits} activations" if mixed else f"int{bits} operands") +
                  " on int8 MFMA, int32 accumulate, fp16 outliers",
@@ -329,7 +425,7 @@ def main():
         "config": {"workload": f"{shp.name}: T={T} K={K} N={N} n_out={n_out} bits={bits}" + (f" w_bits={shp.weight_bits}" if mixed else ""),
                    "launches_per_step": 2, "hip_graph_replay": graph is not None},
         "frac_int8_mfma_peak_layer": tops / PEAK_INT8_TOPS,
-        "speedup_vs_fp16_gemm": (ms_fp16 / ms_layer_ev) if ms_fp16 else None,
+        "speedup_vs_fp16_gemm": (ms_fp16 / ms_step) if ms_fp16 else None,
         "fp16_gemm_ms": ms_fp16,
         "kernels_ms": {"quik_quantize": ms_quant, "quik_gemm_dequant": ms_gemm,
                        "quik_linear_events": ms_layer_ev},
@@ -337,12 +433,23 @@ def main():
             "v1_unfused_quant_unfused_dequant": ablation["v1"],
             "v2_fused_quant_unfused_dequant": ablation["v2"],
             "v3_fused_quant_fused_dequant": ablation["v3"]},
-        "quantize_hbm": {"algorithmic_bytes": quant_bytes,
-                         "achieved_GBs": quant_bytes / (ms_quant * 1e-3) / 1e9,
-                         "frac": quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "quantize_hbm": {"algorithmic_bytes": quant_bytes, "peak_GBs": PEAK_HBM_GBS,
+                         "warm": {"ms": ms_quant, "achieved_GBs": quant_bytes / (ms_quant * 1e-3) / 1e9,
+                                  "frac": quant_bytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                  "what": "one input re-read: resident in the 256 MB last-level cache"},
+                         "cold": {"ms": ms_quant_cold, "achieved_GBs": quant_bytes / (ms_quant_cold * 1e-3) / 1e9,
+                                  "frac": quant_bytes / (ms_quant_cold * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                  "frac_of_measured_copy": quant_bytes / (ms_quant_cold * 1e-3) / 1e9 / measured_hbm_gbs,
+                                  "what": f"rotation of {n_rot} distinct input/output sets "
+                                          f"({n_rot * quant_bytes / 2**20:.0f} MiB): served by HBM"}},
+        "measured_peaks": {"int8_mfma_TOPS": measured_mfma_tops, "copy_GBs": measured_hbm_gbs,
+                           "what": "quik_debug_mfma_probe (independent 32x32x32 int8 matrix instructions, "
+                                   "register-resident) and quik_debug_copy_probe (512 MiB streaming copy, "
+                                   "read + write bytes)"},
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel (INT GEMM + dequant + outlier GEMM)",
                      "achieved": gemm_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": gemm_tops / PEAK_INT8_TOPS,
+                     "frac_of_measured_mfma_peak": gemm_tops / measured_mfma_tops,
                      # HBM-side bytes per launch from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
                      # (factors from a 256 MiB copy; see profiles/), measured for the default
                      # workload only

@@ -31,13 +31,16 @@
  *     widen each operand register with a single AND.  bits = 8 stores one signed
  *     byte per element.  Quantized activations lie in
  *     [-2^(bits-1), 2^(bits-1) - 1], weights likewise.
- *   - Code sums (bits = 4 only; an implementation device, not part of the
- *     paper's algorithm): code_sum[t] = sum of the signed activation codes at
- *     EVEN k, w_code_sum[n] = sum of the signed weight codes at ODD k.  The
- *     widened operands carry an offset of 8 on their low nibbles; these two
- *     INT32 vectors let the epilogue remove that offset exactly, so the
- *     accumulator used for dequantization is the exact integer dot product.
- *     For bits = 8 the pointers are ignored and may be NULL.
+ *   - Side data (bits = 4 only; an implementation device that the argument
+ *     lists do not show): the GEMM widens each packed operand register with a
+ *     single AND, which leaves an offset of 8 on the low nibbles.  Two INT32
+ *     vectors remove it exactly in the epilogue, so the accumulator that is
+ *     dequantized is the exact integer dot product: the sum of a token's signed
+ *     codes at EVEN k, which quik_quantize leaves in its `workspace` and
+ *     quik_gemm_dequant reads from there, and the sum of a channel's signed
+ *     weight codes at ODD k, which quik_weight_reduce appends to `w_reduced`
+ *     (entries N .. 2N-1, as INT32 bit patterns).  Callers only carry the two
+ *     buffers from the producing call to the consuming one.
  *   - Base columns keep their ascending original order; outlier column j of
  *     x_out and w_out corresponds to input column outlier_idx[j].
  *   - Return value: QUIK_OK (0) or a negative quik_status.  When an error is
@@ -88,11 +91,30 @@ int quik_packed_row_bytes(int K_b, int bits);
 /*
  * Bytes of device workspace quik_linear needs for a [T, K] input with n_out
  * outlier columns: packed activations [T, quik_packed_row_bytes], per-token
- * scale and zero (fp32 each), code sums (int32) and the fp16 outlier block [T, n_out], each region
- * aligned to 256 bytes.  Returns 0 on invalid input.  N is accepted for
- * symmetry and does not change the result.
+ * scale and zero (fp32 each), the side data of quik_quantize and the fp16
+ * outlier block [T, n_out], each region aligned to 256 bytes.  Returns 0 on
+ * invalid input.  N is accepted for symmetry and does not change the result.
  */
 size_t quik_workspace_bytes(int T, int K, int N, int n_out, int bits);
+
+/*
+ * Where quik_linear (and quik_linear_ablation) keep their intermediate results
+ * inside `workspace`, for callers that want to look at them (tests, debugging):
+ * byte offsets of the packed activations, scale, zero and the outlier block
+ * are written to offsets[0..3] (HOST pointer), the row stride of the packed
+ * activations to *ldq (HOST pointer).  Returns QUIK_OK or QUIK_EINVAL / QUIK_ENULL.
+ */
+int quik_workspace_regions(int T, int K, int N, int n_out, int bits, size_t *offsets, int *ldq);
+
+/*
+ * Bytes of the `workspace` of quik_quantize / quik_gemm_dequant /
+ * quik_debug_int_gemm (4 T for bits = 4, nothing for bits = 8; never 0 for
+ * valid input, so that a buffer of this size can always be allocated), and of
+ * the `w_reduced` buffer of quik_weight_reduce (8 N for bits = 4, 4 N for
+ * bits = 8).  Return 0 on invalid input.
+ */
+size_t quik_quantize_workspace_bytes(int T, int bits);
+size_t quik_w_reduced_bytes(int N, int bits);
 
 /*
  * Fused split + per-token asymmetric quantization (Algorithm 1, "split" and
@@ -109,14 +131,17 @@ size_t quik_workspace_bytes(int T, int K, int N, int n_out, int bits);
  *   xq           out  packed [T, ldq bytes], ldq >= K_b*bits/8; bytes of each row
  *                     past the packed data up to ldq are written as zero
  *   scale, zero  out  fp32 [T]
- *   code_sum     out  int32 [T], sum of q[t, k] over even k (see "Code sums");
- *                     written for bits = 4 only; NULL = not wanted
  *   x_out        out  fp16 [T, ldo], ldo >= n_out; may be NULL if n_out = 0
+ *   workspace    out  device scratch of at least quik_quantize_workspace_bytes(T, bits)
+ *                     bytes, 4-byte aligned: receives the side data that
+ *                     quik_gemm_dequant needs beside xq (see "Side data").  NULL =
+ *                     not wanted (the result can then only feed quik_debug_int_gemm
+ *                     without side data).  QUIK_EWORKSPACE if given and too small.
  */
 int quik_quantize(const void *x, int T, int K, int ldx,
                   const int32_t *outlier_idx, int n_out, int bits,
-                  void *xq, int ldq, float *scale, float *zero, int32_t *code_sum,
-                  void *x_out, int ldo, void *stream);
+                  void *xq, int ldq, float *scale, float *zero,
+                  void *x_out, int ldo, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * wReduced (Section 3.3, text after Eq. (1)): the static per-output-channel
@@ -126,13 +151,11 @@ int quik_quantize(const void *x, int T, int K, int ldx,
  *
  *   w_q         in   packed [N, ldw bytes]
  *   w_scale     in   fp16 [N]
- *   w_reduced   out  fp32 [N]
- *   w_code_sum  out  int32 [N], sum of w_q[n, k] over odd k (see "Code sums");
- *                    written for bits = 4 only; NULL = not wanted
+ *   w_reduced   out  quik_w_reduced_bytes(N, bits) bytes: fp32 [N] = wReduced; for
+ *                    bits = 4 followed by N INT32 values of side data (see "Side data")
  */
 int quik_weight_reduce(const void *w_q, int ldw, const void *w_scale,
-                       int N, int K_b, int bits, float *w_reduced, int32_t *w_code_sum,
-                       void *stream);
+                       int N, int K_b, int bits, float *w_reduced, void *stream);
 
 /*
  * Integer GEMM + dequantization epilogue + outlier GEMM (Algorithm 1,
@@ -150,35 +173,45 @@ int quik_weight_reduce(const void *w_q, int ldw, const void *w_scale,
  *   xq       in  packed [T, ldq bytes]; bytes of a row between K_b*bits/8 and
  *                ldq MUST be zero (quik_quantize writes them so)
  *   scale, zero  in  fp32 [T]
- *   code_sum in  int32 [T] as written by quik_quantize (required for bits = 4)
  *   x_out    in  fp16 [T, ldo]        (ignored if n_out = 0, may be NULL)
  *   w_q      in  packed [N, ldw bytes]; pad bytes may hold anything
- *   w_scale  in  fp16 [N];  w_reduced in fp32 [N]
- *   w_code_sum in int32 [N] as written by quik_weight_reduce (required for bits = 4)
+ *   w_scale  in  fp16 [N]
+ *   w_reduced in the buffer quik_weight_reduce wrote for these weights and `bits`
  *   w_out    in  fp16 [N, ldwo]       (ignored if n_out = 0, may be NULL)
  *   bias     in  fp16 [N] or NULL
  *   y        out fp16 [T, ldy], ldy >= N
+ *   workspace in the workspace quik_quantize filled together with xq (required for
+ *                bits = 4: QUIK_ENULL / QUIK_EWORKSPACE; ignored for bits = 8)
  * K_b must be below 131072 (INT32 headroom of the 4-bit path).
  */
 int quik_gemm_dequant(const void *xq, int ldq, const float *scale, const float *zero,
-                      const int32_t *code_sum, const void *x_out, int ldo,
+                      const void *x_out, int ldo,
                       int T, int K_b, int n_out, int bits,
                       const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
-                      const int32_t *w_code_sum, const void *w_out, int ldwo,
-                      const void *bias, int N, void *y, int ldy, void *stream);
+                      const void *w_out, int ldwo,
+                      const void *bias, int N, void *y, int ldy,
+                      const void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Test hook: the same integer K-loop as quik_gemm_dequant, writing the exact
- * INT32 accumulators instead of running the epilogue ("INTmatmul" alone).
- *   code_sum, w_code_sum  in  both given: the single-AND operand widening of the
- *                fused kernel plus its exact correction; both NULL: a widening
- *                that needs no correction (one more shift per register pair).
- *                Giving exactly one of them is QUIK_ENULL.  Same result either way.
+ * Test hook: the same integer K-loop as quik_gemm_dequant -- same kernel, same
+ * tile choice -- writing the exact INT32 accumulators instead of running the
+ * epilogue ("INTmatmul" alone).
+ *   workspace, w_reduced  in  both given (as for quik_gemm_dequant): the single-AND
+ *                operand widening of the fused kernel plus its exact correction from
+ *                the side data; both NULL: a widening that needs no side data (one
+ *                more shift per register pair).  Giving exactly one of them is
+ *                QUIK_ENULL.  Same result either way.  Ignored for bits = 8.
  *   acc  out  int32 [T, ldacc], ldacc >= N
+ * quik_int_gemm is the same function under its earlier name.
  */
-int quik_int_gemm(const void *xq, int ldq, const int32_t *code_sum,
-                  const void *w_q, int ldw, const int32_t *w_code_sum,
-                  int T, int N, int K_b, int bits, int32_t *acc, int ldacc, void *stream);
+int quik_debug_int_gemm(const void *xq, int ldq, const void *w_q, int ldw,
+                        int T, int N, int K_b, int bits, int32_t *acc, int ldacc,
+                        const void *workspace, size_t workspace_bytes, const float *w_reduced,
+                        void *stream);
+int quik_int_gemm(const void *xq, int ldq, const void *w_q, int ldw,
+                  int T, int N, int K_b, int bits, int32_t *acc, int ldacc,
+                  const void *workspace, size_t workspace_bytes, const float *w_reduced,
+                  void *stream);
 
 /*
  * The whole layer: quik_quantize into `workspace`, then quik_gemm_dequant
@@ -186,16 +219,17 @@ int quik_int_gemm(const void *xq, int ldq, const int32_t *code_sum,
  *
  *   x            in   fp16 [T, ldx]
  *   outlier_idx  in   int32 [n_out]
- *   w_q, w_scale, w_reduced, w_code_sum, w_out, bias: as in quik_gemm_dequant
+ *   w_q, w_scale, w_reduced, w_out, bias: as in quik_gemm_dequant
  *   y            out  fp16 [T, ldy]
  *   workspace    device scratch of at least quik_workspace_bytes(...) bytes,
  *                256-byte aligned; contents after the call: packed activations,
- *                scale, zero, code sums, x_out (layout private to the library)
+ *                scale, zero, x_out (at the places quik_workspace_regions reports)
+ *                and side data
  */
 int quik_linear(const void *x, int T, int K, int ldx,
                 const int32_t *outlier_idx, int n_out, int bits,
                 const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
-                const int32_t *w_code_sum, const void *w_out, int ldwo, const void *bias, int N,
+                const void *w_out, int ldwo, const void *bias, int N,
                 void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -216,7 +250,7 @@ size_t quik_ablation_workspace_bytes(int T, int K, int N, int n_out, int bits);
 int quik_linear_ablation(int version, const void *x, int T, int K, int ldx,
                          const int32_t *outlier_idx, int n_out, int bits,
                          const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
-                         const int32_t *w_code_sum, const void *w_out, int ldwo,
+                         const void *w_out, int ldwo,
                          const void *bias, int N,
                          void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
@@ -232,7 +266,7 @@ int quik_linear_ablation(int version, const void *x, int T, int K, int ldx,
  *            + sum_j x_out[t,j] * w_out[n,j]  (+ bias[n])               -> fp16
  * Other arguments, limits and error behaviour as for quik_gemm_dequant /
  * quik_int_gemm / quik_linear with bits = 8 (the workspace is
- * quik_workspace_bytes(T, K, N, n_out, 8)).  No code-sum vectors are involved.
+ * quik_workspace_bytes(T, K, N, n_out, 8)).  No side data is involved.
  */
 int quik_gemm_dequant_w4a8(const void *xq, int ldq, const float *scale, const float *zero,
                            const void *x_out, int ldo, int T, int K_b, int n_out,
@@ -265,7 +299,7 @@ int quik_linear_w4a8(const void *x, int T, int K, int ldx,
  *
  *  quik_weight_pack_fp6   offline: packed signed 4-bit weights w_q [N, ldw] (weight nibble
  *                         order of quik.h, ldw >= K_b/2, K_b even) -> FP6 panels w6 (R = N).
- *                         w_scale, w_reduced, w_out stay as for bits = 4 (no code sums).
+ *                         w_scale, w_reduced, w_out stay as for bits = 4 (the side data is not read).
  *  quik_quantize_fp6      quik_quantize(bits = 4) with the packed output as FP6 panels xq6
  *                         (R = T); scale, zero, x_out as there; K <= 16384.
  *  quik_gemm_dequant_fp6  quik_gemm_dequant for FP6 panels.
@@ -294,7 +328,8 @@ int quik_linear_fp6(const void *x, int T, int K, int ldx, const int32_t *outlier
                     void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * QUIK-4B for 2:4-sparse weights (the joint INT4 + 2:4 format of Section 4.3.2, "Sparsity"; the
+ * QUIK-4B for 2:4-sparse weights (the joint INT4 + 2:4 format of Section 4.3, paragraph
+ * "Joint INT-4 Quantization and 2:4 Sparsification"; the
  * arithmetic is Algorithm 1 unchanged, with a weight matrix in which at most two of every four
  * consecutive base columns 4i .. 4i+3 are nonzero).  The integer product runs on the sparse int8
  * matrix instruction of gfx950 (twice the dense int8 rate, exact INT32 accumulation); results are
@@ -322,7 +357,7 @@ int quik_linear_fp6(const void *x, int T, int K, int ldx, const int32_t *outlier
  *                          nonzero values (such a group keeps only its first two: clear the counter
  *                          before the call, read it after the stream has finished, and reject the
  *                          matrix unless it is 0).  w_scale, w_reduced, w_out stay as for bits = 4
- *                          (no code sums).
+ *                          (the side data is not read).
  *  quik_quantize_sp24      quik_quantize(bits = 4) with the packed output as xq24; scale, zero,
  *                          x_out as there; K <= 16384.
  *  quik_gemm_dequant_sp24  quik_gemm_dequant for these operands.
@@ -350,6 +385,19 @@ int quik_linear_sp24(const void *x, int T, int K, int ldx, const int32_t *outlie
                      const void *w24, const void *w_scale, const float *w_reduced,
                      const void *w_out, int ldwo, const void *bias, int N,
                      void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Measurement probes (not part of the layer): what the chip sustains, so that a kernel's rate can
+ * be quoted against a measured ceiling beside the data-sheet one.
+ *  quik_debug_mfma_probe  `workgroups` workgroups of four waves, each wave issuing 4 * iters
+ *                         independent 32x32x32 int8 matrix instructions on register-resident
+ *                         operands: 2 * 32 * 32 * 32 * 16 * workgroups * iters integer operations.
+ *                         `sink` (DEVICE int32 [1]) is never written in practice.
+ *  quik_debug_copy_probe  plain streaming copy of `bytes` (a multiple of 16; both pointers DEVICE,
+ *                         16-byte aligned): reads `bytes`, writes `bytes`.
+ */
+int quik_debug_mfma_probe(int workgroups, int iters, int32_t *sink, void *stream);
+int quik_debug_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
 
 /*
  * Host-side validator for an outlier index list (HOST pointer): returns QUIK_OK

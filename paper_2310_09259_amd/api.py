@@ -40,22 +40,29 @@ def load() -> C.CDLL:
         lib.quik_packed_row_bytes.argtypes = [i, i]
         lib.quik_workspace_bytes.restype = C.c_size_t
         lib.quik_workspace_bytes.argtypes = [i, i, i, i, i]
+        lib.quik_workspace_regions.restype = i
+        lib.quik_workspace_regions.argtypes = [i, i, i, i, i, vp, vp]
+        lib.quik_quantize_workspace_bytes.restype = C.c_size_t
+        lib.quik_quantize_workspace_bytes.argtypes = [i, i]
+        lib.quik_w_reduced_bytes.restype = C.c_size_t
+        lib.quik_w_reduced_bytes.argtypes = [i, i]
         lib.quik_quantize.restype = i
-        lib.quik_quantize.argtypes = [vp, i, i, i, vp, i, i, vp, i, f, f, vp, vp, i, vp]
+        lib.quik_quantize.argtypes = [vp, i, i, i, vp, i, i, vp, i, f, f, vp, i, vp, C.c_size_t, vp]
         lib.quik_weight_reduce.restype = i
-        lib.quik_weight_reduce.argtypes = [vp, i, vp, i, i, i, f, vp, vp]
+        lib.quik_weight_reduce.argtypes = [vp, i, vp, i, i, i, f, vp]
         lib.quik_gemm_dequant.restype = i
-        lib.quik_gemm_dequant.argtypes = [vp, i, f, f, vp, vp, i, i, i, i, i, vp, i, vp, f, vp, vp, i,
-                                          vp, i, vp, i, vp]
-        lib.quik_int_gemm.restype = i
-        lib.quik_int_gemm.argtypes = [vp, i, vp, vp, i, vp, i, i, i, i, vp, i, vp]
+        lib.quik_gemm_dequant.argtypes = [vp, i, f, f, vp, i, i, i, i, i, vp, i, vp, f, vp, i,
+                                          vp, i, vp, i, vp, C.c_size_t, vp]
+        for fn in (lib.quik_debug_int_gemm, lib.quik_int_gemm):
+            fn.restype = i
+            fn.argtypes = [vp, i, vp, i, i, i, i, i, vp, i, vp, C.c_size_t, vp, vp]
         lib.quik_linear.restype = i
-        lib.quik_linear.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, vp, i, vp, i, vp, i, vp,
+        lib.quik_linear.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
                                     C.c_size_t, vp]
         lib.quik_ablation_workspace_bytes.restype = C.c_size_t
         lib.quik_ablation_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.quik_linear_ablation.restype = i
-        lib.quik_linear_ablation.argtypes = [i, vp, i, i, i, vp, i, i, vp, i, vp, f, vp, vp, i, vp, i, vp, i,
+        lib.quik_linear_ablation.argtypes = [i, vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i,
                                              vp, C.c_size_t, vp]
         lib.quik_gemm_dequant_w4a8.restype = i
         lib.quik_gemm_dequant_w4a8.argtypes = [vp, i, f, f, vp, i, i, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp]
@@ -94,6 +101,10 @@ def load() -> C.CDLL:
         lib.quik_linear_sp24.argtypes = [vp, i, i, i, vp, i, vp, vp, f, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
         lib.quik_linear_fp6.restype = i
         lib.quik_linear_fp6.argtypes = [vp, i, i, i, vp, i, vp, vp, f, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
+        lib.quik_debug_mfma_probe.restype = i
+        lib.quik_debug_mfma_probe.argtypes = [i, i, vp, vp]
+        lib.quik_debug_copy_probe.restype = i
+        lib.quik_debug_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
         lib.quik_check_outlier_idx_host.restype = i
         lib.quik_check_outlier_idx_host.argtypes = [vp, i, i]
         _lib = lib
@@ -139,15 +150,39 @@ def quik_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int) -> int:
     return load().quik_workspace_bytes(T, K, N, n_out, bits)
 
 
+def quik_debug_mfma_probe(workgroups: int, iters: int, sink):
+    """Enqueue the int8 matrix-instruction probe; returns the integer operations it performs."""
+    _check(load().quik_debug_mfma_probe(workgroups, iters, _ptr(sink), _stream()), "quik_debug_mfma_probe")
+    return 2.0 * 32 * 32 * 32 * 16 * workgroups * iters
+
+
+def quik_debug_copy_probe(src, dst):
+    """Enqueue a plain streaming copy src -> dst (uint8 device tensors of equal size)."""
+    _check(load().quik_debug_copy_probe(_ptr(src), _ptr(dst), src.numel(), _stream()), "quik_debug_copy_probe")
+
+
 def quik_check_outlier_idx_host(idx_host, K: int) -> int:
     import numpy as np
     a = np.ascontiguousarray(idx_host, dtype=np.int32)
     return load().quik_check_outlier_idx_host(a.ctypes.data_as(C.c_void_p), int(a.size), K)
 
 
+def quik_quantize_workspace_bytes(T: int, bits: int) -> int:
+    return load().quik_quantize_workspace_bytes(T, bits)
+
+
+def quik_w_reduced_bytes(N: int, bits: int) -> int:
+    return load().quik_w_reduced_bytes(N, bits)
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
 def quik_quantize(x, outlier_idx, bits: int, out=None):
     """x fp16 [T,K] -> (xq uint8 [T,ldq], scale f32 [T], zero f32 [T], x_out f16 [T,n_out],
-    code_sum i32 [T]).  code_sum is written for bits = 4 only."""
+    workspace uint8 [quik_quantize_workspace_bytes]).  The workspace carries the side data that
+    quik_gemm_dequant needs beside xq for bits = 4."""
     x = _dev(x, torch.float16, "x")
     T, K = x.shape
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
@@ -162,60 +197,70 @@ def quik_quantize(x, outlier_idx, bits: int, out=None):
         scale = torch.empty(T, dtype=torch.float32, device=x.device)
         zero = torch.empty(T, dtype=torch.float32, device=x.device)
         x_out = torch.empty((T, n_out), dtype=torch.float16, device=x.device)
-        code_sum = torch.empty(T, dtype=torch.int32, device=x.device)
+        side = torch.empty(quik_quantize_workspace_bytes(T, bits), dtype=torch.uint8, device=x.device)
     else:
-        xq, scale, zero, x_out, code_sum = out
+        xq, scale, zero, x_out, side = out
     rc = load().quik_quantize(_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out,
-                              bits, _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum),
+                              bits, _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero),
                               _ptr(x_out) if n_out else None, x_out.stride(0) if n_out else 0,
-                              _stream())
+                              _ptr(side), _nbytes(side), _stream())
     _check(rc, "quik_quantize")
-    return xq, scale, zero, x_out, code_sum
+    return xq, scale, zero, x_out, side
 
 
 def quik_weight_reduce(w_q, w_scale, K_b: int, bits: int):
-    """-> (w_reduced f32 [N], w_code_sum i32 [N]); w_code_sum is written for bits = 4 only."""
+    """-> w_reduced f32 [quik_w_reduced_bytes / 4]: wReduced in the first N entries (for bits = 4
+    followed by N entries of side data for the 4-bit GEMM)."""
     w_q = _dev(w_q, torch.uint8, "w_q")
     w_scale = _dev(w_scale, torch.float16, "w_scale")
     N = w_q.shape[0]
-    out = torch.empty(N, dtype=torch.float32, device=w_q.device)
-    w_code_sum = torch.zeros(N, dtype=torch.int32, device=w_q.device)
-    rc = load().quik_weight_reduce(_ptr(w_q), w_q.stride(0), _ptr(w_scale), N, K_b, bits, _ptr(out),
-                                   _ptr(w_code_sum), _stream())
+    out = torch.empty(quik_w_reduced_bytes(N, bits) // 4, dtype=torch.float32, device=w_q.device)
+    rc = load().quik_weight_reduce(_ptr(w_q), w_q.stride(0), _ptr(w_scale), N, K_b, bits, _ptr(out), _stream())
     _check(rc, "quik_weight_reduce")
-    return out, w_code_sum
+    return out
 
 
-def quik_gemm_dequant(xq, scale, zero, code_sum, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced,
-                      w_code_sum, w_out, bias=None, out=None):
+def _gemm_dequant_args(xq, scale, zero, x_out, K_b, bits, w_q, w_scale, w_reduced, w_out, bias, y, workspace):
+    T, N = xq.shape[0], w_q.shape[0]
+    n_out = 0 if x_out is None else int(x_out.shape[1])
+    return (_ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
+            x_out.stride(0) if n_out else 0, T, K_b, n_out, bits, _ptr(w_q), w_q.stride(0), _ptr(w_scale),
+            _ptr(w_reduced), _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias), N,
+            _ptr(y), y.stride(0), _ptr(workspace), _nbytes(workspace), _stream())
+
+
+def quik_gemm_dequant(xq, scale, zero, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced, w_out, bias=None,
+                      out=None, workspace=None):
+    """workspace: the one quik_quantize returned together with xq (needed for bits = 4)."""
     xq = _dev(xq, torch.uint8, "xq")
     w_q = _dev(w_q, torch.uint8, "w_q")
     T, N = xq.shape[0], w_q.shape[0]
     n_out = 0 if x_out is None else int(x_out.shape[1])
     y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=xq.device)
-    rc = load().quik_gemm_dequant(
-        _ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum), _ptr(x_out) if n_out else None,
-        x_out.stride(0) if n_out else 0, T, K_b, n_out, bits, _ptr(w_q), w_q.stride(0), _ptr(w_scale),
-        _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
-        w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _stream())
+    rc = load().quik_gemm_dequant(*_gemm_dequant_args(xq, scale, zero, x_out, K_b, bits, w_q, w_scale, w_reduced,
+                                                      w_out, bias, y, workspace))
     _check(rc, "quik_gemm_dequant")
     return y
 
 
-def quik_int_gemm(xq, w_q, K_b: int, bits: int, code_sum=None, w_code_sum=None):
+def quik_debug_int_gemm(xq, w_q, K_b: int, bits: int, workspace=None, w_reduced=None):
+    """Raw INT32 accumulators.  workspace (from quik_quantize) and w_reduced (from quik_weight_reduce)
+    together select the fused kernel's operand widening; neither: the widening without side data."""
     xq = _dev(xq, torch.uint8, "xq")
     w_q = _dev(w_q, torch.uint8, "w_q")
     T, N = xq.shape[0], w_q.shape[0]
     acc = torch.empty((T, N), dtype=torch.int32, device=xq.device)
-    rc = load().quik_int_gemm(_ptr(xq), xq.stride(0), _ptr(code_sum), _ptr(w_q), w_q.stride(0),
-                              _ptr(w_code_sum), T, N, K_b, bits, _ptr(acc), acc.stride(0), _stream())
-    _check(rc, "quik_int_gemm")
+    rc = load().quik_debug_int_gemm(_ptr(xq), xq.stride(0), _ptr(w_q), w_q.stride(0), T, N, K_b, bits,
+                                    _ptr(acc), acc.stride(0), _ptr(workspace), _nbytes(workspace),
+                                    _ptr(w_reduced), _stream())
+    _check(rc, "quik_debug_int_gemm")
     return acc
 
 
-def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum, w_out, bias=None,
-                out=None, workspace=None):
-    """Whole layer.  Returns y fp16 [T, N]."""
+quik_int_gemm = quik_debug_int_gemm
+
+
+def _linear_buffers(x, outlier_idx, bits, w_q, out, workspace):
     x = _dev(x, torch.float16, "x")
     w_q = _dev(w_q, torch.uint8, "w_q")
     T, K = x.shape
@@ -225,43 +270,37 @@ def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum, 
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
     y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
-    rc = load().quik_linear(
-        _ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(w_q),
-        w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
-        w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
-        workspace.numel(), _stream())
+    return y, workspace
+
+
+def _linear_args(x, outlier_idx, bits, w_q, w_scale, w_reduced, w_out, bias, y, workspace):
+    T, K = x.shape
+    N = w_q.shape[0]
+    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
+    return (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(w_q),
+            w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_out) if n_out else None,
+            w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
+            _nbytes(workspace), _stream())
+
+
+def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, bias=None, out=None, workspace=None):
+    """Whole layer.  Returns y fp16 [T, N]."""
+    y, workspace = _linear_buffers(x, outlier_idx, bits, w_q, out, workspace)
+    rc = load().quik_linear(*_linear_args(x, outlier_idx, bits, w_q, w_scale, w_reduced, w_out, bias, y, workspace))
     _check(rc, "quik_linear")
     return y
 
 
-def prepare_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum, w_out, bias=None,
-                   out=None, workspace=None):
+def prepare_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, bias=None, out=None,
+                   workspace=None):
     """quik_linear with the argument marshalling done once: returns (call, y) where call() enqueues
     one layer on the stream that was current here, on the same buffers every time.  For loops that
     launch the same layer many times (serving, benchmarking), where building the ctypes arguments
     would otherwise cost more host time than a small layer takes on the GPU."""
-    x = _dev(x, torch.float16, "x")
-    w_q = _dev(w_q, torch.uint8, "w_q")
-    T, K = x.shape
-    N = w_q.shape[0]
-    n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
-    need = quik_workspace_bytes(T, K, N, n_out, bits)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
-    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
-    keep = (x, outlier_idx, w_q, w_scale, w_reduced, w_code_sum, w_out, bias, y, workspace)
-    args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(w_q),
-            w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
-            w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y), y.stride(0), _ptr(workspace),
-            workspace.numel(), _stream())
-    fn = load().quik_linear
-
-    def call(_keep=keep):
-        rc = fn(*args)
-        if rc != 0:
-            raise QuikError(rc, "quik_linear")
-
-    return call, y
+    y, workspace = _linear_buffers(x, outlier_idx, bits, w_q, out, workspace)
+    args = _linear_args(x, outlier_idx, bits, w_q, w_scale, w_reduced, w_out, bias, y, workspace)
+    keep = (x, outlier_idx, w_q, w_scale, w_reduced, w_out, bias, y, workspace)
+    return _prepared(load().quik_linear, "quik_linear", args, keep), y
 
 
 def quik_gemm_dequant_w4a8(xq, scale, zero, x_out, K_b: int, w_q, w_scale, w_reduced, w_out, bias=None,
@@ -338,27 +377,23 @@ def prepare_linear_w4a8(x, outlier_idx, w_q, w_scale, w_reduced, w_out, bias=Non
 
 
 def prepare_quantize(x, outlier_idx, bits: int, out):
-    """Marshal-once form of quik_quantize writing into out = (xq, scale, zero, x_out, code_sum)."""
+    """Marshal-once form of quik_quantize writing into out = (xq, scale, zero, x_out, workspace)."""
     x = _dev(x, torch.float16, "x")
     T, K = x.shape
     n_out = 0 if outlier_idx is None else int(outlier_idx.numel())
-    xq, scale, zero, x_out, code_sum = out
+    xq, scale, zero, x_out, side = out
     args = (_ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits, _ptr(xq),
-            xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum), _ptr(x_out) if n_out else None,
-            x_out.stride(0) if n_out else 0, _stream())
+            xq.stride(0), _ptr(scale), _ptr(zero), _ptr(x_out) if n_out else None,
+            x_out.stride(0) if n_out else 0, _ptr(side), _nbytes(side), _stream())
     return _prepared(load().quik_quantize, "quik_quantize", args, (x, outlier_idx, out))
 
 
-def prepare_gemm_dequant(xq, scale, zero, code_sum, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced,
-                         w_code_sum, w_out, bias, out):
+def prepare_gemm_dequant(xq, scale, zero, x_out, K_b: int, bits: int, w_q, w_scale, w_reduced, w_out, bias, out,
+                         workspace):
     """Marshal-once form of quik_gemm_dequant writing into `out`."""
-    T, N = xq.shape[0], w_q.shape[0]
-    n_out = 0 if x_out is None else int(x_out.shape[1])
-    args = (_ptr(xq), xq.stride(0), _ptr(scale), _ptr(zero), _ptr(code_sum), _ptr(x_out) if n_out else None,
-            x_out.stride(0) if n_out else 0, T, K_b, n_out, bits, _ptr(w_q), w_q.stride(0), _ptr(w_scale),
-            _ptr(w_reduced), _ptr(w_code_sum), _ptr(w_out) if n_out else None,
-            w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(out), out.stride(0), _stream())
-    keep = (xq, scale, zero, code_sum, x_out, w_q, w_scale, w_reduced, w_code_sum, w_out, bias, out)
+    args = _gemm_dequant_args(xq, scale, zero, x_out, K_b, bits, w_q, w_scale, w_reduced, w_out, bias, out,
+                              workspace)
+    keep = (xq, scale, zero, x_out, w_q, w_scale, w_reduced, w_out, bias, out, workspace)
     return _prepared(load().quik_gemm_dequant, "quik_gemm_dequant", args, keep)
 
 
@@ -641,7 +676,7 @@ def quik_ablation_workspace_bytes(T: int, K: int, N: int, n_out: int, bits: int)
     return load().quik_ablation_workspace_bytes(T, K, N, n_out, bits)
 
 
-def quik_linear_ablation(version: int, x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_code_sum,
+def quik_linear_ablation(version: int, x, outlier_idx, bits: int, w_q, w_scale, w_reduced,
                          w_out, bias=None, out=None, workspace=None):
     """The layer with unfused stages (version 1 or 2; 3 = quik_linear).  Returns (y, workspace)."""
     x = _dev(x, torch.float16, "x")
@@ -655,26 +690,23 @@ def quik_linear_ablation(version: int, x, outlier_idx, bits: int, w_q, w_scale, 
     y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
     rc = load().quik_linear_ablation(
         version, _ptr(x), T, K, x.stride(0), _ptr(outlier_idx) if n_out else None, n_out, bits,
-        _ptr(w_q), w_q.stride(0), _ptr(w_scale), _ptr(w_reduced), _ptr(w_code_sum),
+        _ptr(w_q), w_q.stride(0), _ptr(w_scale), _ptr(w_reduced),
         _ptr(w_out) if n_out else None, w_out.stride(0) if n_out else 0, _ptr(bias), N, _ptr(y),
         y.stride(0), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "quik_linear_ablation")
     return y, workspace
 
 
-def workspace_views(workspace, T: int, K: int, n_out: int, bits: int):
-    """Views (xq, scale, zero, x_out, code_sum) into a workspace filled by quik_linear or
-    quik_linear_ablation, following the layout documented for quik_workspace_bytes."""
-    def up256(v):
-        return (v + 255) & ~255
-    ldq = quik_packed_row_bytes(K - n_out, bits)
-    o_scale = up256(T * ldq)
-    o_zero = o_scale + up256(T * 4)
-    o_csum = o_zero + up256(T * 4)
-    o_xout = o_csum + up256(T * 4)
-    xq = workspace[: T * ldq].view(T, ldq)
-    scale = workspace[o_scale: o_scale + T * 4].view(torch.float32)
-    zero = workspace[o_zero: o_zero + T * 4].view(torch.float32)
-    x_out = workspace[o_xout: o_xout + T * n_out * 2].view(torch.float16).view(T, n_out)
-    code_sum = workspace[o_csum: o_csum + T * 4].view(torch.int32)
-    return xq, scale, zero, x_out, code_sum
+def workspace_views(workspace, T: int, K: int, N: int, n_out: int, bits: int):
+    """Views (xq, scale, zero, x_out) into a workspace filled by quik_linear or quik_linear_ablation,
+    at the places quik_workspace_regions reports."""
+    off = (C.c_size_t * 4)()
+    ldq = C.c_int(0)
+    _check(load().quik_workspace_regions(T, K, N, n_out, bits, C.cast(off, C.c_void_p),
+                                         C.cast(C.pointer(ldq), C.c_void_p)), "quik_workspace_regions")
+    ldq = ldq.value
+    xq = workspace[off[0]: off[0] + T * ldq].view(T, ldq)
+    scale = workspace[off[1]: off[1] + T * 4].view(torch.float32)
+    zero = workspace[off[2]: off[2] + T * 4].view(torch.float32)
+    x_out = workspace[off[3]: off[3] + T * n_out * 2].view(torch.float16).view(T, n_out)
+    return xq, scale, zero, x_out

@@ -35,6 +35,12 @@ bool workspace_layout(int T, int K, int n_out, int bits, WorkspaceLayout* w) {
     return true;
 }
 
+// the side data of the 4-bit path inside the buffers the ABI calls `workspace` and `w_reduced`
+inline size_t side_bytes(int T, int bits) { return bits == 4 ? (size_t)T * sizeof(int32_t) : 4; }
+inline const int32_t* w_side(const float* w_reduced, int N) {
+    return reinterpret_cast<const int32_t*>(w_reduced + N);
+}
+
 int check_quantize(const void* x, int T, int K, int ldx, const int32_t* idx, int n_out, int bits,
                    void* xq, int ldq, float* scale, float* zero, void* x_out, int ldo) {
     if (bits != 4 && bits != 8) return QUIK_EINVAL;
@@ -106,23 +112,47 @@ size_t quik_workspace_bytes(int T, int K, int N, int n_out, int bits) {
     return w.total;
 }
 
+int quik_workspace_regions(int T, int K, int N, int n_out, int bits, size_t* offsets, int* ldq) {
+    (void)N;
+    WorkspaceLayout w;
+    if (!workspace_layout(T, K, n_out, bits, &w)) return QUIK_EINVAL;
+    if (!offsets || !ldq) return QUIK_ENULL;
+    offsets[0] = w.xq; offsets[1] = w.scale; offsets[2] = w.zero; offsets[3] = w.x_out;
+    *ldq = w.ldq;
+    return QUIK_OK;
+}
+
+size_t quik_quantize_workspace_bytes(int T, int bits) {
+    if (T <= 0 || (bits != 4 && bits != 8)) return 0;
+    return side_bytes(T, bits);
+}
+
+size_t quik_w_reduced_bytes(int N, int bits) {
+    if (N <= 0 || (bits != 4 && bits != 8)) return 0;
+    return (size_t)N * (bits == 4 ? 8 : 4);
+}
+
 int quik_quantize(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out,
-                  int bits, void* xq, int ldq, float* scale, float* zero, int32_t* code_sum,
-                  void* x_out, int ldo, void* stream) {
+                  int bits, void* xq, int ldq, float* scale, float* zero, void* x_out, int ldo,
+                  void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo);
     if (rc != QUIK_OK) return rc;
-    if (reinterpret_cast<uintptr_t>(code_sum) & 3u) return QUIK_EALIGN;
+    if (reinterpret_cast<uintptr_t>(workspace) & 3u) return QUIK_EALIGN;
+    if (workspace && workspace_bytes < side_bytes(T, bits)) return QUIK_EWORKSPACE;
+    int32_t* code_sum = bits == 4 ? static_cast<int32_t*>(workspace) : nullptr;
     quik::QuantizeArgs a{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo, code_sum};
     return quik::launch_quantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
                                                                                    : QUIK_ELAUNCH;
 }
 
 int quik_weight_reduce(const void* w_q, int ldw, const void* w_scale, int N, int K_b, int bits,
-                       float* w_reduced, int32_t* w_code_sum, void* stream) {
+                       float* w_reduced, void* stream) {
     if (bits != 4 && bits != 8) return QUIK_EINVAL;
     if (N <= 0 || K_b <= 0 || (K_b * bits) % 8 || ldw < K_b * bits / 8) return QUIK_EINVAL;
     if (!w_q || !w_scale || !w_reduced) return QUIK_ENULL;
     if (K_b >= kMaxKb) return QUIK_EUNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(w_reduced) & 3u) return QUIK_EALIGN;
+    int32_t* w_code_sum = bits == 4 ? reinterpret_cast<int32_t*>(w_reduced + N) : nullptr;
     quik::WeightReduceArgs a{w_q, ldw, w_scale, N, K_b, bits, w_reduced, w_code_sum};
     return quik::launch_weight_reduce(a, static_cast<hipStream_t>(stream)) == hipSuccess
                ? QUIK_OK
@@ -130,19 +160,21 @@ int quik_weight_reduce(const void* w_q, int ldw, const void* w_scale, int N, int
 }
 
 int quik_gemm_dequant(const void* xq, int ldq, const float* scale, const float* zero,
-                      const int32_t* code_sum, const void* x_out, int ldo, int T, int K_b, int n_out,
+                      const void* x_out, int ldo, int T, int K_b, int n_out,
                       int bits, const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
-                      const int32_t* w_code_sum, const void* w_out, int ldwo, const void* bias, int N,
-                      void* y, int ldy, void* stream) {
+                      const void* w_out, int ldwo, const void* bias, int N,
+                      void* y, int ldy, const void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_gemm(xq, ldq, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_out, ldwo, N);
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!scale || !zero || !w_scale || !w_reduced || !y) return QUIK_ENULL;
-    if (bits == 4 && (!code_sum || !w_code_sum)) return QUIK_ENULL;
+    if (bits == 4 && !workspace) return QUIK_ENULL;
+    if (bits == 4 && (reinterpret_cast<uintptr_t>(workspace) & 3u)) return QUIK_EALIGN;
+    if (bits == 4 && workspace_bytes < side_bytes(T, bits)) return QUIK_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
     quik::GemmArgs a{};
     a.xq = xq; a.ldq = ldq; a.scale = scale; a.zero = zero; a.x_out = x_out; a.ldo = ldo;
-    a.code_sum = code_sum; a.w_code_sum = w_code_sum;
+    if (bits == 4) { a.code_sum = static_cast<const int32_t*>(workspace); a.w_code_sum = w_side(w_reduced, N); }
     a.T = T; a.K_b = K_b; a.n_out = n_out; a.bits = bits;
     a.w_q = w_q; a.ldw = ldw; a.w_scale = w_scale; a.w_reduced = w_reduced;
     a.w_out = w_out; a.ldwo = ldwo; a.bias = bias; a.N = N;
@@ -151,25 +183,34 @@ int quik_gemm_dequant(const void* xq, int ldq, const float* scale, const float* 
                                                                                : QUIK_ELAUNCH;
 }
 
-int quik_int_gemm(const void* xq, int ldq, const int32_t* code_sum, const void* w_q, int ldw,
-                  const int32_t* w_code_sum, int T, int N, int K_b, int bits, int32_t* acc, int ldacc,
-                  void* stream) {
+int quik_debug_int_gemm(const void* xq, int ldq, const void* w_q, int ldw, int T, int N, int K_b, int bits,
+                        int32_t* acc, int ldacc, const void* workspace, size_t workspace_bytes,
+                        const float* w_reduced, void* stream) {
     int rc = check_gemm(xq, ldq, nullptr, 0, T, K_b, 0, bits, w_q, ldw, nullptr, 0, N);
     if (rc != QUIK_OK) return rc;
     if (ldacc < N) return QUIK_EINVAL;
     if (!acc) return QUIK_ENULL;
-    if ((code_sum == nullptr) != (w_code_sum == nullptr)) return QUIK_ENULL;   // both or neither
+    if ((workspace == nullptr) != (w_reduced == nullptr)) return QUIK_ENULL;   // both or neither
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 3u)) return QUIK_EALIGN;
+    if (workspace && workspace_bytes < side_bytes(T, bits)) return QUIK_EWORKSPACE;
     quik::GemmArgs a{};
-    a.code_sum = code_sum; a.w_code_sum = w_code_sum;
+    if (bits == 4 && workspace) { a.code_sum = static_cast<const int32_t*>(workspace); a.w_code_sum = w_side(w_reduced, N); }
     a.xq = xq; a.ldq = ldq; a.T = T; a.K_b = K_b; a.n_out = 0; a.bits = bits;
     a.w_q = w_q; a.ldw = ldw; a.N = N; a.y = nullptr; a.acc = acc; a.ldacc = ldacc;
     return quik::launch_gemm(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
                                                                                : QUIK_ELAUNCH;
 }
 
+int quik_int_gemm(const void* xq, int ldq, const void* w_q, int ldw, int T, int N, int K_b, int bits,
+                  int32_t* acc, int ldacc, const void* workspace, size_t workspace_bytes,
+                  const float* w_reduced, void* stream) {
+    return quik_debug_int_gemm(xq, ldq, w_q, ldw, T, N, K_b, bits, acc, ldacc, workspace, workspace_bytes,
+                               w_reduced, stream);
+}
+
 int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out,
                 int bits, const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
-                const int32_t* w_code_sum, const void* w_out, int ldwo, const void* bias, int N, void* y,
+                const void* w_out, int ldwo, const void* bias, int N, void* y,
                 int ldy, void* workspace, size_t workspace_bytes, void* stream) {
     WorkspaceLayout w;
     if (!workspace_layout(T, K, n_out, bits, &w)) return QUIK_EINVAL;
@@ -190,13 +231,13 @@ int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
-    if (bits == 4 && !w_code_sum) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
-    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, w.ldq, scale, zero, code_sum, x_out,
-                       n_out, stream);
+    const size_t side = side_bytes(T, bits);
+    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, bits, xq, w.ldq, scale, zero, x_out, n_out,
+                       code_sum, side, stream);
     if (rc != QUIK_OK) return rc;
-    return quik_gemm_dequant(xq, w.ldq, scale, zero, code_sum, x_out, n_out, T, K_b, n_out, bits, w_q,
-                             ldw, w_scale, w_reduced, w_code_sum, w_out, ldwo, bias, N, y, ldy, stream);
+    return quik_gemm_dequant(xq, w.ldq, scale, zero, x_out, n_out, T, K_b, n_out, bits, w_q, ldw, w_scale,
+                             w_reduced, w_out, ldwo, bias, N, y, ldy, code_sum, side, stream);
 }
 
 // ---- 4-bit weights under 8-bit activations (the W4A8 rows of the paper's precision ablation)
@@ -255,7 +296,7 @@ int quik_linear_w4a8(const void* x, int T, int K, int ldx, const int32_t* outlie
     if (ldy < N) return QUIK_EINVAL;
     if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
-    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, 8, xq, w.ldq, scale, zero, nullptr, x_out, n_out,
+    rc = quik_quantize(x, T, K, ldx, outlier_idx, n_out, 8, xq, w.ldq, scale, zero, x_out, n_out, nullptr, 0,
                        stream);
     if (rc != QUIK_OK) return rc;
     return quik_gemm_dequant_w4a8(xq, w.ldq, scale, zero, x_out, n_out, T, K_b, n_out, w_q, ldw, w_scale,
@@ -290,12 +331,12 @@ size_t quik_ablation_workspace_bytes(int T, int K, int N, int n_out, int bits) {
 
 int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, const int32_t* outlier_idx,
                          int n_out, int bits, const void* w_q, int ldw, const void* w_scale,
-                         const float* w_reduced, const int32_t* w_code_sum, const void* w_out, int ldwo,
+                         const float* w_reduced, const void* w_out, int ldwo,
                          const void* bias, int N, void* y, int ldy, void* workspace,
                          size_t workspace_bytes, void* stream) {
     if (version == 3)
         return quik_linear(x, T, K, ldx, outlier_idx, n_out, bits, w_q, ldw, w_scale, w_reduced,
-                           w_code_sum, w_out, ldwo, bias, N, y, ldy, workspace, workspace_bytes, stream);
+                           w_out, ldwo, bias, N, y, ldy, workspace, workspace_bytes, stream);
     if (version != 1 && version != 2) return QUIK_EINVAL;
     AblationLayout w;
     if (!ablation_layout(T, K, N, n_out, bits, &w)) return QUIK_EINVAL;
@@ -320,8 +361,8 @@ int quik_linear_ablation(int version, const void* x, int T, int K, int ldx, cons
     if (rc != QUIK_OK) return rc;
     if (ldy < N) return QUIK_EINVAL;
     if (!w_scale || !w_reduced || !y) return QUIK_ENULL;
-    if (bits == 4 && !w_code_sum) return QUIK_ENULL;
     if (reinterpret_cast<uintptr_t>(y) & 1u) return QUIK_EALIGN;
+    const int32_t* w_code_sum = bits == 4 ? w_side(w_reduced, N) : nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
     quik::QuantizeArgs qa{x, T, K, ldx, outlier_idx, n_out, bits, xq, ldq, scale, zero, x_out, n_out, code_sum};
     if (version == 1) {
@@ -581,6 +622,24 @@ int quik_linear_sp24(const void* x, int T, int K, int ldx, const int32_t* outlie
     if (rc != QUIK_OK) return rc;
     return quik_gemm_dequant_sp24(xq24, scale, zero, x_out, n_out, T, K_b, n_out, w24, w_scale, w_reduced, w_out,
                                   ldwo, bias, N, y, ldy, stream);
+}
+
+// ---- measurement probes
+
+int quik_debug_mfma_probe(int workgroups, int iters, int32_t* sink, void* stream) {
+    if (workgroups <= 0 || iters <= 0) return QUIK_EINVAL;
+    if (!sink) return QUIK_ENULL;
+    return quik::launch_mfma_probe(workgroups, iters, sink, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUIK_OK
+               : QUIK_ELAUNCH;
+}
+
+int quik_debug_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
+    if (bytes == 0 || bytes % 16) return QUIK_EINVAL;
+    if (!src || !dst) return QUIK_ENULL;
+    if (!aligned16(src) || !aligned16(dst)) return QUIK_EALIGN;
+    return quik::launch_copy_probe(src, dst, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? QUIK_OK
+                                                                                                   : QUIK_ELAUNCH;
 }
 
 int quik_check_outlier_idx_host(const int32_t* idx, int n_out, int K) {

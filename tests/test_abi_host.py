@@ -62,43 +62,76 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     u = C.c_void_p(0x1004)          # misaligned
     null = C.c_void_p(0)
     q = lib.quik_quantize
-    # (x, T, K, ldx, idx, n_out, bits, xq, ldq, scale, zero, code_sum, x_out, ldo, stream)
-    assert q(p, 4, 64, 64, p, 8, 5, p, 32, p, p, p, p, 8, null) == -1        # bits
-    assert q(p, 0, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -1        # T
-    assert q(p, 4, 64, 64, p, 64, 4, p, 32, p, p, p, p, 64, null) == -1      # n_out == K
-    assert q(p, 4, 64, 32, p, 8, 4, p, 32, p, p, p, p, 8, null) == -1        # ldx < K
-    assert q(p, 4, 64, 64, p, 8, 4, p, 16, p, p, p, p, 8, null) == -1        # ldq too small
-    assert q(null, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -2     # x NULL
-    assert q(p, 4, 64, 64, null, 8, 4, p, 32, p, p, p, p, 8, null) == -2     # idx NULL with n_out
-    assert q(u, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -3        # x misaligned
-    assert q(p, 4, 64, 64, p, 8, 4, p, 40, p, p, p, p, 8, null) == -3        # ldq % 16
-    assert q(p, 4, 60, 64, p, 8, 4, p, 32, p, p, p, p, 8, null) == -4        # K % 8
-    assert q(p, 4, 64, 64, p, 4, 4, p, 32, p, p, p, p, 8, null) == -4        # n_out % 8
-    assert q(p, 4, 65536, 65536, p, 8, 4, p, 32768, p, p, p, p, 8, null) == -4   # K too large
+    q.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int,
+                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    # (x, T, K, ldx, idx, n_out, bits, xq, ldq, scale, zero, x_out, ldo, workspace, workspace_bytes, stream)
+    assert q(p, 4, 64, 64, p, 8, 5, p, 32, p, p, p, 8, p, 16, null) == -1        # bits
+    assert q(p, 0, 64, 64, p, 8, 4, p, 32, p, p, p, 8, p, 16, null) == -1        # T
+    assert q(p, 4, 64, 64, p, 64, 4, p, 32, p, p, p, 64, p, 16, null) == -1      # n_out == K
+    assert q(p, 4, 64, 32, p, 8, 4, p, 32, p, p, p, 8, p, 16, null) == -1        # ldx < K
+    assert q(p, 4, 64, 64, p, 8, 4, p, 16, p, p, p, 8, p, 16, null) == -1        # ldq too small
+    assert q(null, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, p, 16, null) == -2     # x NULL
+    assert q(p, 4, 64, 64, null, 8, 4, p, 32, p, p, p, 8, p, 16, null) == -2     # idx NULL with n_out
+    assert q(u, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, p, 16, null) == -3        # x misaligned
+    assert q(p, 4, 64, 64, p, 8, 4, p, 40, p, p, p, 8, p, 16, null) == -3        # ldq % 16
+    assert q(p, 4, 60, 64, p, 8, 4, p, 32, p, p, p, 8, p, 16, null) == -4        # K % 8
+    assert q(p, 4, 64, 64, p, 4, 4, p, 32, p, p, p, 8, p, 16, null) == -4        # n_out % 8
+    assert q(p, 4, 65536, 65536, p, 8, 4, p, 32768, p, p, p, 8, p, 16, null) == -4   # K too large
+    assert q(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, p, 15, null) == -5        # workspace too small
+    assert q(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, C.c_void_p(0x1002), 16, null) == -3
     g = lib.quik_gemm_dequant
-    # (xq, ldq, scale, zero, code_sum, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_scale, w_red,
-    #  w_code_sum, w_out, ldwo, bias, N, y, ldy, stream)
-    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 16, p, p, p, p, 8, null, 8, p, 8, null) == -1   # ldw small
-    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, p, 8, null, 8, null, 8, null) == -2
-    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 4, null) == -1   # ldy < N
-    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, u, 32, p, p, p, p, 8, null, 8, p, 8, null) == -3
-    # 4-bit layers need both code-sum vectors; 8-bit layers do not
-    assert g(p, 32, p, p, null, p, 8, 4, 64, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, null) == -2
-    assert g(p, 32, p, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, null, p, 8, null, 8, p, 8, null) == -2   # w_q align
-    # (xq, ldq, code_sum, w_q, ldw, w_code_sum, T, N, K_b, bits, acc, ldacc, stream): the two
-    # code-sum vectors come together or not at all
-    ig = lib.quik_int_gemm
-    assert ig(p, 32, p, p, 32, null, 4, 8, 64, 4, p, 8, null) == -2
-    assert ig(p, 32, null, p, 32, p, 4, 8, 64, 4, p, 8, null) == -2
-    assert ig(p, 32, null, p, 32, null, 4, 8, 64, 4, null, 8, null) == -2     # acc NULL
+    g.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                  C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+                  C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+    # (xq, ldq, scale, zero, x_out, ldo, T, K_b, n_out, bits, w_q, ldw, w_scale, w_red, w_out, ldwo, bias, N,
+    #  y, ldy, workspace, workspace_bytes, stream)
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 16, p, p, p, 8, null, 8, p, 8, p, 16, null) == -1   # ldw small
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, null, 8, p, 16, null) == -2
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, p, 4, p, 16, null) == -1   # ldy < N
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, u, 32, p, p, p, 8, null, 8, p, 8, p, 16, null) == -3   # w_q align
+    # 4-bit layers need the quantization workspace (side data); 8-bit layers do not look at it
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, null, 0, null) == -2
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, p, 12, null) == -5
+    assert g(p, 32, p, p, p, 8, 4, 64, 8, 4, p, 32, p, null, p, 8, null, 8, p, 8, p, 16, null) == -2
+    # (xq, ldq, w_q, ldw, T, N, K_b, bits, acc, ldacc, workspace, workspace_bytes, w_reduced, stream): the
+    # workspace and w_reduced come together or not at all; both names of the hook behave alike
+    for ig in (lib.quik_debug_int_gemm, lib.quik_int_gemm):
+        ig.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                       C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        assert ig(p, 32, p, 32, 4, 8, 64, 4, p, 8, p, 16, null, null) == -2
+        assert ig(p, 32, p, 32, 4, 8, 64, 4, p, 8, null, 0, p, null) == -2
+        assert ig(p, 32, p, 32, 4, 8, 64, 4, null, 8, null, 0, null, null) == -2     # acc NULL
+        assert ig(p, 32, p, 32, 4, 8, 64, 4, p, 8, p, 12, p, null) == -5
+        assert ig(p, 32, p, 32, 4, 8, 64, 4, p, 4, null, 0, null, null) == -1        # ldacc < N
     lin = lib.quik_linear
     lin.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
-                    C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+                    C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
                     C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
     need = lib.quik_workspace_bytes(4, 64, 8, 8, 4)
-    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, C.c_void_p(0x1000), need - 1,
+    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, C.c_void_p(0x1000), need - 1,
                null) == -5
-    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, p, 8, null, 8, p, 8, null, need, null) == -2
+    assert lin(p, 4, 64, 64, p, 8, 4, p, 32, p, p, p, 8, null, 8, p, 8, null, need, null) == -2
+
+
+def test_side_buffer_sizes_and_workspace_regions(lib):
+    lib.quik_quantize_workspace_bytes.restype = C.c_size_t
+    lib.quik_w_reduced_bytes.restype = C.c_size_t
+    assert lib.quik_quantize_workspace_bytes(2048, 4) == 4 * 2048
+    assert lib.quik_quantize_workspace_bytes(2048, 8) > 0
+    assert lib.quik_quantize_workspace_bytes(0, 4) == 0 and lib.quik_quantize_workspace_bytes(4, 5) == 0
+    assert lib.quik_w_reduced_bytes(11008, 4) == 8 * 11008 and lib.quik_w_reduced_bytes(11008, 8) == 4 * 11008
+    assert lib.quik_w_reduced_bytes(0, 4) == 0
+    off = (C.c_size_t * 4)()
+    ldq = C.c_int(0)
+    reg = lib.quik_workspace_regions
+    reg.argtypes = [C.c_int] * 5 + [C.c_void_p, C.c_void_p]
+    assert reg(2048, 4096, 11008, 256, 4, C.cast(off, C.c_void_p), C.cast(C.pointer(ldq), C.c_void_p)) == 0
+    assert ldq.value == 1920 and off[0] == 0 and off[1] >= 2048 * 1920
+    assert off[2] >= off[1] + 4 * 2048 and off[3] >= off[2] + 4 * 2048
+    assert off[3] + 2048 * 256 * 2 <= lib.quik_workspace_bytes(2048, 4096, 11008, 256, 4)
+    assert all(o % 256 == 0 for o in off)
+    assert reg(2048, 4096, 11008, 256, 4, None, None) == -2
+    assert reg(0, 4096, 11008, 256, 4, C.cast(off, C.c_void_p), C.cast(C.pointer(ldq), C.c_void_p)) == -1
 
 
 def test_fp6_sizes_and_bad_arguments(lib):

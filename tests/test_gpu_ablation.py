@@ -35,16 +35,14 @@ def test_ablation_versions_match_oracle(api, oracle, shp, version):
     inp = synth.make_inputs(shp)
     d = upload(inp)
     ref = oracle.linear(inp.x, inp.outlier_idx, shp.bits, inp.w_packed, inp.w_scale, inp.w_out)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
     ws = torch.full((api.quik_ablation_workspace_bytes(shp.T, shp.K, shp.N, shp.n_out, shp.bits),), 0xAB,
                     dtype=torch.uint8, device="cuda")
     y, ws = api.quik_linear_ablation(version, d["x"], d["idx"], shp.bits, d["w_q"], d["w_scale"], w_red,
-                                     w_cs, d["w_out"], workspace=ws)
+                                     d["w_out"], workspace=ws)
     torch.cuda.synchronize()
-    xq, scale, zero, x_out, cs = api.workspace_views(ws, shp.T, shp.K, shp.n_out, shp.bits)
+    xq, scale, zero, x_out = api.workspace_views(ws, shp.T, shp.K, shp.N, shp.n_out, shp.bits)
     assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, ref.q, shp.bits, xq.shape[1]))
-    if shp.bits == 4:
-        assert np.array_equal(cs.cpu().numpy(), ref.q[:, 0::2].astype(np.int32).sum(axis=1))
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), ref.scale.view(np.uint32))
     assert np.array_equal(zero.cpu().numpy().view(np.uint32), ref.zero.view(np.uint32))
     if shp.n_out:
@@ -58,14 +56,14 @@ def test_ablation_full_size_sampled(api, oracle):
     shp = synth.CONFIGS["llama7b_up"]
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
     sel = np.array([0, 5, 777, 1024, 2047])
     ref = oracle.linear(inp.x[sel], inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
     for version in (1, 2):
         y, ws = api.quik_linear_ablation(version, d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red,
-                                         w_cs, d["w_out"])
+                                         d["w_out"])
         torch.cuda.synchronize()
-        xq, scale, zero, x_out, cs = api.workspace_views(ws, shp.T, shp.K, shp.n_out, 4)
+        xq, scale, zero, x_out = api.workspace_views(ws, shp.T, shp.K, shp.N, shp.n_out, 4)
         assert np.array_equal(xq.cpu().numpy()[sel], expected_xq(oracle, ref.q, 4, xq.shape[1]))
         ok, worst = output_within_tolerance(y.cpu().numpy()[sel], ref.y)
         assert ok, (version, worst)
@@ -76,10 +74,9 @@ def test_ablation_rejects_bad_arguments(api):
     x = torch.zeros((4, 64), dtype=torch.float16, device="cuda")
     w = torch.zeros((8, 32), dtype=torch.uint8, device="cuda")
     sw = torch.ones(8, dtype=torch.float16, device="cuda")
-    wr = torch.zeros(8, dtype=torch.float32, device="cuda")
-    wc = torch.zeros(8, dtype=torch.int32, device="cuda")
+    wr = torch.zeros(16, dtype=torch.float32, device="cuda")
     with pytest.raises(api.QuikError):
-        api.quik_linear_ablation(4, x, None, 4, w, sw, wr, wc, None)
+        api.quik_linear_ablation(4, x, None, 4, w, sw, wr, None)
     small = torch.zeros(256, dtype=torch.uint8, device="cuda")
     with pytest.raises(api.QuikError):
-        api.quik_linear_ablation(1, x, None, 4, w, sw, wr, wc, None, workspace=small)
+        api.quik_linear_ablation(1, x, None, 4, w, sw, wr, None, workspace=small)

@@ -86,7 +86,7 @@ def _linear_case(api, oracle, shp, bias=False):
     d = upload(inp)
     b = np.random.default_rng(1).standard_normal(shp.N).astype(np.float16) if bias else None
     ref = oracle.linear(inp.x, inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out, bias=b)
-    w_red, _ = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
     w6 = api.quik_weight_pack_fp6(d["w_q"], shp.K_b)
     y = api.quik_linear_fp6(d["x"], d["idx"], w6, d["w_scale"], w_red, d["w_out"], bias=to_dev(b) if bias else None)
     _sync()
@@ -128,8 +128,8 @@ def test_fp6_accumulators_are_the_exact_integers_and_the_output_equals_the_int8_
     xq6, scale, zero, x_out = api.quik_quantize_fp6(d["x"], d["idx"])
     acc = api.quik_int_gemm_fp6(xq6, w6, shp.K_b)
     y2 = api.quik_gemm_dequant_fp6(xq6, scale, zero, x_out, shp.K_b, w6, d["w_scale"], w_red, d["w_out"])
-    _, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
-    y_int = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    _ = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    y_int = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
     assert np.array_equal(acc.cpu().numpy(), ref.acc)
     assert np.array_equal(y.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
@@ -167,7 +167,7 @@ def test_full_size_workloads_on_sampled_tokens_fp6(api, oracle, name):
     shp = synth.CONFIGS[name]
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
     w6 = api.quik_weight_pack_fp6(d["w_q"], shp.K_b)
     xq6, scale, zero, x_out = api.quik_quantize_fp6(d["x"], d["idx"])
     y = api.quik_linear_fp6(d["x"], d["idx"], w6, d["w_scale"], w_red, d["w_out"])
@@ -182,7 +182,7 @@ def test_full_size_workloads_on_sampled_tokens_fp6(api, oracle, name):
     ref = oracle.linear(inp.x[sel], inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
     ok, worst = output_within_tolerance(y[torch.from_numpy(sel).cuda()].cpu().numpy(), ref.y)
     assert ok, worst
-    y_int = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    y_int = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
     assert torch.equal(y.view(torch.int16), y_int.view(torch.int16))
     del y, y_int

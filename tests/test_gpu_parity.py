@@ -32,12 +32,10 @@ def _quantize_case(api, oracle, x, idx, bits):
     T, K = x.shape
     xd = to_dev(x)
     idxd = to_dev(idx) if idx.size else None
-    xq, scale, zero, x_out, code_sum = api.quik_quantize(xd, idxd, bits)
+    xq, scale, zero, x_out, side = api.quik_quantize(xd, idxd, bits)
     _sync()
     q, s, z, xo = oracle.quantize(x, idx, bits)
     want = expected_xq(oracle, q, bits, xq.shape[1])
-    if bits == 4:                                # sum of the signed codes at even base positions
-        assert np.array_equal(code_sum.cpu().numpy(), q[:, 0::2].astype(np.int32).sum(axis=1)), "code_sum"
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32)), "scale"
     assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32)), "zero"
     got = xq.cpu().numpy()
@@ -83,7 +81,7 @@ def test_quantize_many_rows_per_workgroup_repeated(api, oracle, K, bits):
     xd, idxd = to_dev(inp.x), to_dev(inp.outlier_idx)
     want = None
     for rep in range(3):
-        xq, scale, zero, x_out, cs = api.quik_quantize(xd, idxd, bits)
+        xq, scale, zero, x_out, side = api.quik_quantize(xd, idxd, bits)
         _sync()
         if want is None:
             want = expected_xq(oracle, q, bits, xq.shape[1])
@@ -131,6 +129,7 @@ INT_GEMM_SHAPES = [
 def test_int32_accumulators_are_bit_exact(api, oracle, T, N, K_b, bits, widening):
     """Both operand widenings of the 4-bit K loop: the one that needs no correction, and the
     single-AND one of the fused kernel whose offset is removed with the two code-sum vectors."""
+    import torch
     if widening == "corrected" and bits != 4:
         pytest.skip("the 8-bit path has one widening")
     rng = np.random.default_rng(T * 7 + N * 3 + K_b + bits)
@@ -144,11 +143,15 @@ def test_int32_accumulators_are_bit_exact(api, oracle, T, N, K_b, bits, widening
     # weight pad bytes may hold anything: fill them with 0xFF to prove it
     wp = np.full((N, ld), 0xFF, np.uint8)
     wp[:, : K_b * bits // 8] = oracle.pack(w, bits)
-    cs = wcs = None
+    wpd = to_dev(wp)
+    side = w_red = None
     if widening == "corrected":
-        cs = to_dev(q[:, 0::2].astype(np.int32).sum(axis=1).astype(np.int32))
-        wcs = to_dev(w[:, 1::2].astype(np.int32).sum(axis=1).astype(np.int32))
-    acc = api.quik_int_gemm(xq, to_dev(wp), K_b, bits, code_sum=cs, w_code_sum=wcs)
+        # side data as the library's own producers write it: quik_weight_reduce for the weights; for
+        # the activations (given here as codes, not as fp16 input) the documented content of the
+        # quantization workspace, one INT32 per token = sum of the codes at even k
+        w_red = api.quik_weight_reduce(wpd, to_dev(np.ones(N, np.float16)), K_b, bits)
+        side = to_dev(q[:, 0::2].astype(np.int32).sum(axis=1).astype(np.int32)).view(torch.uint8)
+    acc = api.quik_debug_int_gemm(xq, wpd, K_b, bits, workspace=side, w_reduced=w_red)
     _sync()
     want = oracle.int_gemm(q, w, bits)
     got = acc.cpu().numpy()
@@ -166,13 +169,14 @@ def test_weight_reduce_is_bit_exact(api, oracle, N, K_b, bits):
     ld = api.quik_packed_row_bytes(K_b, bits)
     buf = np.full((N, ld), 0xFF, np.uint8)
     buf[:, : wp.shape[1]] = wp
-    got, w_code_sum = api.quik_weight_reduce(to_dev(buf), to_dev(sw), K_b, bits)
+    got = api.quik_weight_reduce(to_dev(buf), to_dev(sw), K_b, bits)
     _sync()
     wq = oracle.unpack(wp, K_b, bits)
     want = oracle.weight_reduce(wq, sw)
-    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
-    if bits == 4:                                # sum of the signed codes at odd positions
-        assert np.array_equal(w_code_sum.cpu().numpy(), wq[:, 1::2].astype(np.int32).sum(axis=1))
+    assert got.numel() * 4 == api.quik_w_reduced_bytes(N, bits)
+    assert np.array_equal(got[:N].cpu().numpy().view(np.uint32), want.view(np.uint32))
+    if bits == 4:                                # side data: sum of the signed codes at odd positions
+        assert np.array_equal(got[N:].cpu().numpy().view(np.int32), wq[:, 1::2].astype(np.int32).sum(axis=1))
 
 
 def _linear_case(api, oracle, shp, bias=False, gain=40.0):
@@ -182,15 +186,15 @@ def _linear_case(api, oracle, shp, bias=False, gain=40.0):
     if bias:
         b = np.random.default_rng(1).standard_normal(shp.N).astype(np.float16)
     ref = oracle.linear(inp.x, inp.outlier_idx, shp.bits, inp.w_packed, inp.w_scale, inp.w_out, bias=b)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
-    y = api.quik_linear(d["x"], d["idx"], shp.bits, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"],
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
+    y = api.quik_linear(d["x"], d["idx"], shp.bits, d["w_q"], d["w_scale"], w_red, d["w_out"],
                         bias=to_dev(b) if bias else None)
     _sync()
-    assert np.array_equal(w_red.cpu().numpy().view(np.uint32), ref.w_reduced.view(np.uint32))
+    assert np.array_equal(w_red[: shp.N].cpu().numpy().view(np.uint32), ref.w_reduced.view(np.uint32))
     ok, worst = output_within_tolerance(y.cpu().numpy(), ref.y)
     assert ok, f"fp16 output outside 5e-3 (worst error / tolerance = {worst:.2f})"
     assert worst > 0                                   # not a trivially equal array
-    return inp, d, ref, w_red, w_cs
+    return inp, d, ref, w_red
 
 
 LINEAR_SHAPES = [
@@ -227,13 +231,13 @@ def test_linear_with_bias(api, oracle):
 
 def test_stages_called_separately_agree_with_the_fused_entry_point(api, oracle):
     shp = synth.LayerShape("stages", 100, 1024, 160, 64, 4, seed=42)
-    inp, d, ref, w_red, w_cs = _linear_case(api, oracle, shp)
-    xq, scale, zero, x_out, cs = api.quik_quantize(d["x"], d["idx"], 4)
-    y2 = api.quik_gemm_dequant(xq, scale, zero, cs, x_out, shp.K_b, 4, d["w_q"], d["w_scale"], w_red,
-                               w_cs, d["w_out"])
-    acc = api.quik_int_gemm(xq, d["w_q"], shp.K_b, 4)
-    acc2 = api.quik_int_gemm(xq, d["w_q"], shp.K_b, 4, code_sum=cs, w_code_sum=w_cs)
-    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    inp, d, ref, w_red = _linear_case(api, oracle, shp)
+    xq, scale, zero, x_out, side = api.quik_quantize(d["x"], d["idx"], 4)
+    y2 = api.quik_gemm_dequant(xq, scale, zero, x_out, shp.K_b, 4, d["w_q"], d["w_scale"], w_red,
+                               d["w_out"], workspace=side)
+    acc = api.quik_debug_int_gemm(xq, d["w_q"], shp.K_b, 4)
+    acc2 = api.quik_debug_int_gemm(xq, d["w_q"], shp.K_b, 4, workspace=side, w_reduced=w_red)
+    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
     assert np.array_equal(y1.cpu().numpy().view(np.uint16), y2.cpu().numpy().view(np.uint16))
     assert np.array_equal(acc.cpu().numpy(), ref.acc)
@@ -250,8 +254,8 @@ def test_strided_input_and_output(api, oracle):
     xbig = torch.full((shp.T, shp.K + 64), 777.0, dtype=torch.float16, device="cuda")
     xbig[:, : shp.K] = d["x"]
     ybig = torch.full((shp.T, shp.N + 24), -5.0, dtype=torch.float16, device="cuda")
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
-    api.quik_linear(xbig[:, : shp.K], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"],
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    api.quik_linear(xbig[:, : shp.K], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"],
                     out=ybig[:, : shp.N])
     _sync()
     yh = ybig.cpu().numpy()
@@ -264,44 +268,56 @@ FULL_SIZE = ["llama7b_up", "llama7b_down", "llama7b_down_w8a8", "llama13b_qkv_t1
              "llama13b_qkv_t128", "llama13b_qkv_t1024", "llama13b_qkv_t4096", "llama70b_up"]
 
 
+def _sampled_rows(T, seed):
+    """One seeded random row out of every block of 32 token rows, plus the first and the last row:
+    every row block of every tile shape the library uses (32-row MFMA blocks inside 64 .. 256-row
+    tiles) is compared."""
+    rng = np.random.default_rng(seed)
+    rows = np.arange(0, T, 32) + rng.integers(0, 32, size=(T + 31) // 32)
+    return np.unique(np.concatenate([np.minimum(rows, T - 1), [0, T - 1]]))
+
+
 @pytest.mark.parametrize("name", FULL_SIZE)
-def test_full_size_workloads_on_sampled_tokens(api, oracle, name):
-    """Every benchmark workload at full size, in the launch configuration bench.py times:
-    quantization checked in full, accumulators and output on sampled token rows (tokens are
-    independent, so the oracle is run on those rows alone)."""
+def test_full_size_workloads(api, oracle, name):
+    """Every benchmark workload at full size, through the launches bench.py times (quik_linear on all
+    T tokens; the accumulator hook on all T tokens, which picks the same kernel and tiles).
+    Quantization is checked in full.  The fp16 output and the INT32 accumulators are compared with the
+    oracle on the whole matrix for the headline workload (llama7b_up) and the small ones, else on one
+    random row of every 32-row block (tokens are independent, so the oracle runs on those rows alone)."""
     import torch
     shp = synth.CONFIGS[name]
     bits = shp.bits
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, bits)
-    xq, scale, zero, x_out, cs = api.quik_quantize(d["x"], d["idx"], bits)
-    y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, bits)
+    xq, scale, zero, x_out, side = api.quik_quantize(d["x"], d["idx"], bits)
+    y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
     q, s, z, xo = oracle.quantize(inp.x, inp.outlier_idx, bits)
     assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, q, bits, xq.shape[1]))
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
     assert np.array_equal(zero.cpu().numpy().view(np.uint32), z.view(np.uint32))
     assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16))
-    if bits == 4:
-        assert np.array_equal(cs.cpu().numpy(), q[:, 0::2].astype(np.int32).sum(axis=1))
     T = shp.T
-    sel = np.unique(np.array([0, 1, 31, 32, 127, 128, 255, 256, T // 2 - 1, T // 2, T - 2, T - 1]) % T)
+    whole = name == "llama7b_up" or T <= 128
+    sel = np.arange(T) if whole else _sampled_rows(T, shp.seed)
     ref = oracle.linear(inp.x[sel], inp.outlier_idx, bits, inp.w_packed, inp.w_scale, inp.w_out)
-    ok, worst = output_within_tolerance(y[torch.from_numpy(sel).cuda()].cpu().numpy(), ref.y)
+    rows = torch.from_numpy(sel).cuda()
+    ok, worst = output_within_tolerance(y[rows].cpu().numpy(), ref.y)
     assert ok, worst
     del y
-    # raw accumulators of the sampled rows (the hook is run on those rows only: the int32
-    # matrix of the largest workload would not be worth its 470 MB)
-    rows = torch.from_numpy(sel).cuda()
-    acc = api.quik_int_gemm(xq[rows].contiguous(), d["w_q"], shp.K_b, bits)
+    # raw accumulators: the hook runs on all T rows, the sampled ones are compared
+    acc = api.quik_debug_int_gemm(xq, d["w_q"], shp.K_b, bits)
     _sync()
-    assert np.array_equal(acc.cpu().numpy(), ref.acc)
+    got = acc[rows].cpu().numpy()
+    del acc
+    assert np.array_equal(got, ref.acc), f"{int((got != ref.acc).sum())} accumulators differ"
     if bits == 4:
-        acc = api.quik_int_gemm(xq[rows].contiguous(), d["w_q"], shp.K_b, bits,
-                                code_sum=cs[rows].contiguous(), w_code_sum=w_cs)
+        acc = api.quik_debug_int_gemm(xq, d["w_q"], shp.K_b, bits, workspace=side, w_reduced=w_red)
         _sync()
-        assert np.array_equal(acc.cpu().numpy(), ref.acc)
+        got = acc[rows].cpu().numpy()
+        del acc
+        assert np.array_equal(got, ref.acc), f"{int((got != ref.acc).sum())} accumulators differ (side data)"
 
 
 def test_prepared_call_matches_direct_call(api, oracle):
@@ -309,9 +325,9 @@ def test_prepared_call_matches_direct_call(api, oracle):
     shp = synth.LayerShape("prepared", 90, 1024, 200, 64, 4, seed=47)
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
-    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
-    call, y2 = api.prepare_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    y1 = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
+    call, y2 = api.prepare_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
     call()
     call()
     _sync()
@@ -360,10 +376,10 @@ def test_w4a8_linear_matches_oracle(api, oracle, shp):
     inp = synth.make_inputs(shp)
     d = upload(inp)
     ref = oracle.linear(inp.x, inp.outlier_idx, 8, inp.w_packed, inp.w_scale, inp.w_out, w_bits=4)
-    w_red, _ = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
     y = api.quik_linear_w4a8(d["x"], d["idx"], d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
-    assert np.array_equal(w_red.cpu().numpy().view(np.uint32), ref.w_reduced.view(np.uint32))
+    assert np.array_equal(w_red[: shp.N].cpu().numpy().view(np.uint32), ref.w_reduced.view(np.uint32))
     ok, worst = output_within_tolerance(y.cpu().numpy(), ref.y)
     assert ok, f"fp16 output outside 5e-3 (worst error / tolerance = {worst:.2f})"
     assert worst > 0
@@ -374,7 +390,7 @@ def test_w4a8_full_size_on_sampled_tokens(api, oracle):
     shp = synth.CONFIGS["llama7b_down_w4a8"]
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red, _ = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
     xq, scale, zero, x_out, _ = api.quik_quantize(d["x"], d["idx"], 8)
     y = api.quik_linear_w4a8(d["x"], d["idx"], d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
@@ -406,8 +422,8 @@ def test_vector_store_path_with_a_ragged_last_piece(api, oracle):
     d = upload(inp)
     ref = oracle.linear(inp.x, inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
     ybig = torch.full((shp.T, 344), -7.0, dtype=torch.float16, device="cuda")
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
-    api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"], out=ybig[:, : shp.N])
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"], out=ybig[:, : shp.N])
     _sync()
     yh = ybig.cpu().numpy()
     ok, worst = output_within_tolerance(yh[:, : shp.N], ref.y)
@@ -445,15 +461,15 @@ def test_random_shapes_match_oracle(api, oracle, seed):
     d = upload(inp)
     ref = oracle.linear(inp.x, inp.outlier_idx, bits, inp.w_packed, inp.w_scale, inp.w_out,
                         w_bits=None if w_bits == bits else w_bits)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, w_bits)
-    xq, scale, zero, x_out, cs = api.quik_quantize(d["x"], d["idx"], bits)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, w_bits)
+    xq, scale, zero, x_out, side = api.quik_quantize(d["x"], d["idx"], bits)
     if mode == "w4a8":
         y = api.quik_linear_w4a8(d["x"], d["idx"], d["w_q"], d["w_scale"], w_red, d["w_out"])
         acc = api.quik_int_gemm_w4a8(xq, d["w_q"], shp.K_b)
     else:
-        y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
-        acc = api.quik_int_gemm(xq, d["w_q"], shp.K_b, bits, code_sum=cs if bits == 4 else None,
-                                w_code_sum=w_cs if bits == 4 else None)
+        y = api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, d["w_out"])
+        acc = api.quik_debug_int_gemm(xq, d["w_q"], shp.K_b, bits, workspace=side if bits == 4 else None,
+                                      w_reduced=w_red if bits == 4 else None)
     _sync()
     what = f"T={T} K={K} N={N} n_out={n_out} {mode}"
     assert np.array_equal(xq.cpu().numpy(), expected_xq(oracle, ref.q, bits, xq.shape[1])), what

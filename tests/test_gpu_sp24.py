@@ -121,13 +121,11 @@ def test_weight_pack_sp24_counts_groups_that_are_not_2of4(api, oracle):
 
 def _linear_case(api, oracle, shp, bias=False):
     inp = synth.make_inputs(shp)
-    wq = oracle.unpack(inp.w_packed, shp.K_b, 4) if hasattr(oracle, "unpack") else None
-    if wq is not None:
-        assert is_2of4(wq).all(), "the generator's weights are not 2:4"
+    assert is_2of4(oracle.unpack(inp.w_packed, shp.K_b, 4)).all(), "the generator's weights are not 2:4"
     d = upload(inp)
     b = np.random.default_rng(1).standard_normal(shp.N).astype(np.float16) if bias else None
     ref = oracle.linear(inp.x, inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out, bias=b)
-    w_red, _ = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
     w24 = api.quik_weight_pack_sp24(d["w_q"], shp.K_b)
     y = api.quik_linear_sp24(d["x"], d["idx"], w24, d["w_scale"], w_red, d["w_out"], bias=to_dev(b) if bias else None)
     _sync()
@@ -235,7 +233,7 @@ def test_full_size_workloads_on_sampled_tokens_sp24(api, oracle, name):
     shp = _sparse(synth.CONFIGS[name])
     inp = synth.make_inputs(shp)
     d = upload(inp)
-    w_red, w_cs = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
     w24 = api.quik_weight_pack_sp24(d["w_q"], shp.K_b)
     xq24, scale, zero, x_out = api.quik_quantize_sp24(d["x"], d["idx"])
     y = api.quik_linear_sp24(d["x"], d["idx"], w24, d["w_scale"], w_red, d["w_out"])
@@ -250,7 +248,7 @@ def test_full_size_workloads_on_sampled_tokens_sp24(api, oracle, name):
     ref = oracle.linear(inp.x[sel], inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out)
     ok, worst = output_within_tolerance(y[torch.from_numpy(sel).cuda()].cpu().numpy(), ref.y)
     assert ok, worst
-    y_int = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, w_cs, d["w_out"])
+    y_int = api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"])
     _sync()
     diff = (y.float() - y_int.float()).abs()
     floor = 1e-3 * float(y_int.float().abs().max())

@@ -68,6 +68,65 @@ def test_hand_worked_example_of_algorithm_1(oracle):
     assert r.y[0].tolist() == g["y"]
 
 
+# ---------------------------------------------------------------- evaluation order of the Quantization line
+def _rn32(fr):
+    """Positive exact fraction -> nearest IEEE binary32 value (normal range), ties to even, from the
+    format's definition: 24 significant bits.  Returns an exact fraction."""
+    import math
+    from fractions import Fraction as F
+    if fr == 0:
+        return F(0)
+    e = math.floor(math.log2(fr))
+    while F(2) ** e > fr:
+        e -= 1
+    while F(2) ** (e + 1) <= fr:
+        e += 1
+    ulp = F(2) ** (e - 23)
+    n = fr / ulp
+    fl = n.numerator // n.denominator
+    rem = n - fl
+    if rem > F(1, 2) or (rem == F(1, 2) and fl % 2 == 1):
+        fl += 1
+    return fl * ulp
+
+
+def _rne(fr):
+    from fractions import Fraction as F
+    fl = fr.numerator // fr.denominator
+    rem = fr - fl
+    return fl + 1 if rem > F(1, 2) or (rem == F(1, 2) and fl % 2 == 1) else fl
+
+
+def test_quantization_multiplies_by_a_once_per_token_reciprocal(oracle):
+    """A row on which (x - zero) * (1 / scale) and (x - zero) / scale round to different codes in
+    binary32 (tests/golden/reciprocal_reading_row.txt, worked by hand).  The file's numbers are first
+    re-derived here in exact rational arithmetic with a rounding routine written from the IEEE
+    definition; then the oracle must give the codes of the reciprocal reading."""
+    from fractions import Fraction as F
+    vals = {}
+    with open(os.path.join(os.path.dirname(GOLDEN), "reciprocal_reading_row.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                key, rhs = line.split("=", 1)
+                vals[key.strip()] = rhs.split()
+    x = [F(v) for v in vals["x"]]
+    q_want = [int(v) for v in vals["q"]]
+    q_div = [int(v) for v in vals["q_if_divided"]]
+    scale = _rn32((max(x) - min(x)) / 15)
+    inv = _rn32(1 / scale)
+    as_bits = lambda fr: int(np.float32(float(fr)).view(np.uint32))
+    assert float(scale) == float(np.float32(float(scale)))        # exactly representable
+    assert as_bits(scale) == int(vals["scale_bits"][0], 16) and as_bits(inv) == int(vals["inv_bits"][0], 16)
+    assert [_rne(_rn32((v - min(x)) * inv)) - 8 for v in x] == q_want
+    assert [_rne(_rn32((v - min(x)) / scale)) - 8 for v in x] == q_div
+    assert q_want != q_div                                         # the row tells the two readings apart
+    xh = np.array([[float(v) for v in x]], np.float16)
+    q, s, z, _ = oracle.quantize(xh, np.zeros(0, np.int32), 4)
+    assert int(s.view(np.uint32)[0]) == int(vals["scale_bits"][0], 16) and z[0] == float(vals["zero"][0])
+    assert q[0].tolist() == q_want
+
+
 # ---------------------------------------------------------------- split
 def test_base_columns_brute_force(oracle):
     K = 11
