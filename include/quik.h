@@ -233,6 +233,26 @@ int quik_linear(const void *x, int T, int K, int ldx,
                 void *y, int ldy, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * quik_linear for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without
+ * the workspace), same kernels and bit-identical results; the intermediate results live in a
+ * static device array of QUIK_NOALLOC_SCRATCH_BYTES that the library holds on every GPU it runs on
+ * until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating
+ * library routine).  QUIK_EWORKSPACE if quik_workspace_bytes(T, K, N, n_out, bits) exceeds
+ * QUIK_NOALLOC_SCRATCH_BYTES (the LLaMA-7B up-projection shape at 2048 tokens needs 5.0 MB;
+ * roughly T * (K_b * bits / 8 + 2 * n_out + 12) bytes in general).  All calls on one GPU share
+ * that GPU's array: calls that may overlap in time on one GPU (different streams, different host
+ * threads) race on it and must be serialized by the caller; calls on different GPUs are
+ * independent.  Nothing in the array has to be cleared between calls.
+ */
+#define QUIK_NOALLOC_SCRATCH_BYTES (8u << 20)
+int quik_linear_noalloc(const void *x, int T, int K, int ldx,
+                        const int32_t *outlier_idx, int n_out, int bits,
+                        const void *w_q, int ldw, const void *w_scale, const float *w_reduced,
+                        const void *w_out, int ldwo, const void *bias, int N,
+                        void *y, int ldy, void *stream);
+
+/*
  * Fusion ablation of Section 3.4 ("Performance Impact", the kernel versions 1-3): the same layer
  * with its stages left unfused, for measuring what the fusions buy.
  *   version 1: unfused quantization (separate passes: move the outlier part, move the base part,

@@ -59,6 +59,8 @@ def load() -> C.CDLL:
         lib.quik_linear.restype = i
         lib.quik_linear.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp,
                                     C.c_size_t, vp]
+        lib.quik_linear_noalloc.restype = i
+        lib.quik_linear_noalloc.argtypes = [vp, i, i, i, vp, i, i, vp, i, vp, f, vp, i, vp, i, vp, i, vp]
         lib.quik_ablation_workspace_bytes.restype = C.c_size_t
         lib.quik_ablation_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.quik_linear_ablation.restype = i
@@ -288,6 +290,18 @@ def quik_linear(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, bias=
     y, workspace = _linear_buffers(x, outlier_idx, bits, w_q, out, workspace)
     rc = load().quik_linear(*_linear_args(x, outlier_idx, bits, w_q, w_scale, w_reduced, w_out, bias, y, workspace))
     _check(rc, "quik_linear")
+    return y
+
+
+def quik_linear_noalloc(x, outlier_idx, bits: int, w_q, w_scale, w_reduced, w_out, out, bias=None):
+    """quik_linear without a workspace argument (the library's static device array holds the
+    intermediate results).  `out` (fp16 [T, N]) is required: the call itself allocates nothing."""
+    x = _dev(x, torch.float16, "x")
+    w_q = _dev(w_q, torch.uint8, "w_q")
+    y = _dev(out, torch.float16, "out")
+    args = _linear_args(x, outlier_idx, bits, w_q, w_scale, w_reduced, w_out, bias, y, None)
+    rc = load().quik_linear_noalloc(*args[:-3], args[-1])
+    _check(rc, "quik_linear_noalloc")
     return y
 
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "quik.h"
@@ -238,6 +239,49 @@ int quik_linear(const void* x, int T, int K, int ldx, const int32_t* outlier_idx
     if (rc != QUIK_OK) return rc;
     return quik_gemm_dequant(xq, w.ldq, scale, zero, x_out, n_out, T, K_b, n_out, bits, w_q, ldw, w_scale,
                              w_reduced, w_out, ldwo, bias, N, y, ldy, code_sum, side, stream);
+}
+
+// ---- quik_linear for callers that cannot allocate: the workspace is a static device array
+
+namespace {
+// The intermediate results of one layer (packed activations, scale, zero, side data, outlier
+// block).  Every GPU the library runs on holds its own copy of this array, at its own address, until the
+// process ends; the name below is only a host-side handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[QUIK_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QUIK_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QUIK_ELAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return QUIK_OK;
+}
+}  // namespace
+
+int quik_linear_noalloc(const void* x, int T, int K, int ldx, const int32_t* outlier_idx, int n_out, int bits,
+                        const void* w_q, int ldw, const void* w_scale, const float* w_reduced,
+                        const void* w_out, int ldwo, const void* bias, int N, void* y, int ldy,
+                        void* stream) {
+    WorkspaceLayout w;
+    if (!workspace_layout(T, K, n_out, bits, &w)) return QUIK_EINVAL;
+    if (w.total > (size_t)QUIK_NOALLOC_SCRATCH_BYTES) return QUIK_EWORKSPACE;
+    void* ws = nullptr;
+    int rc = scratch_of_current_device(&ws);
+    if (rc != QUIK_OK) return rc;
+    // quik_quantize writes every byte of the regions quik_gemm_dequant reads (the zero tail of the
+    // packed rows included), so what an earlier call left in the array does not matter
+    return quik_linear(x, T, K, ldx, outlier_idx, n_out, bits, w_q, ldw, w_scale, w_reduced, w_out, ldwo, bias,
+                       N, y, ldy, ws, (size_t)QUIK_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 // ---- 4-bit weights under 8-bit activations (the W4A8 rows of the paper's precision ablation)
