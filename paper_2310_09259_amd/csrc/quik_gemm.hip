@@ -137,6 +137,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     const int t0 = tile_m * BM, n0 = tile_n * BN;
 
     const int row_bytes = a.K_b * BITS / 8;
+    const int int_bytes = (row_bytes + 15) & ~15;
     const int nk_int = a.fp_only ? 0 : (row_bytes + BKB - 1) / BKB;
     const int fp_bytes = a.n_out * 2;
     const int nk_fp = RAW ? 0 : (fp_bytes + BKB - 1) / BKB;
@@ -206,7 +207,10 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         const uint32_t sb = (uint32_t)(s % NST) * ST_BYTES;
         const bool fp = s >= nk_int;
         const int koff = (fp ? s - nk_int : s) * BKB;
-        const int lima = s < nk ? (fp ? fp_bytes : a.ldq) : 0, limb = s < nk ? (fp ? fp_bytes : a.ldw) : 0;
+        // integer stages stop at the 16-byte piece that holds a row's last packed byte: what lies beyond may
+        // be anything in the weight matrix
+        const int lima = s < nk ? (fp ? fp_bytes : int_bytes) : 0;
+        const int limb = s < nk ? (fp ? fp_bytes : (MIXED ? (((a.K_b / 2) + 15) & ~15) : int_bytes)) : 0;
         const int lda = fp ? lda_fp : a.ldq, ldb = fp ? ldb_fp : a.ldw;
         const v4i ra_ = fp ? rAf : rA;
         const v4i rb_ = fp ? rBf : rB;
@@ -585,6 +589,7 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
     const int t0 = (blockIdx.x % tiles_m) * BM, n0 = (blockIdx.x / tiles_m) * BN;
 
     const int row_bytes = a.K_b * BITS / 8;
+    const int int_bytes = (row_bytes + 15) & ~15;      // up to the 16-byte piece that holds the last packed byte
     const int nk = a.fp_only ? 0 : (row_bytes + BKB - 1) / BKB;
     // this wave's K range, in stages
     const int s_begin = (int)((long)nk * wave / 4), s_end = (int)((long)nk * (wave + 1) / 4);
@@ -604,14 +609,14 @@ __global__ __launch_bounds__(256) void gemm_skinny(GemmArgs a) {
         for (int i = 0; i < A_INSTR; ++i) {
             int row = i * RPI + lrow;
             int c = (lslot ^ swz<BKB>(row)) * 16;
-            uint32_t vo = (live && koff + c < a.ldq) ? (uint32_t)(row * a.ldq + koff + c) : kOob;
+            uint32_t vo = (live && koff + c < int_bytes) ? (uint32_t)(row * a.ldq + koff + c) : kOob;
             dma16(rA, ring_addr + sb + i * 1024, vo, 0);
         }
 #pragma unroll
         for (int i = 0; i < B_INSTR; ++i) {
             int row = i * RPI + lrow;
             int c = (lslot ^ swz<BKB>(row)) * 16;
-            uint32_t vo = (live && koff + c < a.ldw) ? (uint32_t)(row * a.ldw + koff + c) : kOob;
+            uint32_t vo = (live && koff + c < int_bytes) ? (uint32_t)(row * a.ldw + koff + c) : kOob;
             dma16(rB, ring_addr + sb + A_BYTES + i * 1024, vo, 0);
         }
     };
@@ -914,6 +919,14 @@ __global__ __launch_bounds__(kThreads) void weight_reduce_kernel(WeightReduceArg
             s += (int)(int8_t)b;
         }
     }
+    if constexpr (BITS == 4) {
+        // The GEMM reads a row up to the end of the 16-byte piece that holds its last packed byte.  Against
+        // the zero bytes the activations have there, the single-AND widening turns whatever the weight
+        // matrix holds in those pad bytes into 128 x (their high nibbles); counting them in the side data
+        // makes the epilogue's correction remove exactly that, so pad bytes may hold anything.
+        const int padded = min((row_bytes + 15) & ~15, a.ldw);
+        for (int p = row_bytes + lane; p < padded; p += 64) s_odd += (((int)row[p] >> 4) ^ 8) - 8;
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         s += __shfl_xor(s, o, 64);
@@ -927,7 +940,30 @@ __global__ __launch_bounds__(kThreads) void weight_reduce_kernel(WeightReduceArg
 
 }  // namespace
 
+// compute units of the current device (looked up once per device)
+static int compute_units() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
+    if (a.bits == 4 && !a.fp_only) {
+        // large token counts: the persistent kernel with balanced tile widths
+        StreamPlan plan;
+        if (plan_gemm_stream(a.T, a.N, a.K_b, compute_units(), &plan)) return launch_gemm_stream(a, plan, stream);
+    }
+    return launch_gemm_tiles(a, stream);
+}
+
+// one workgroup per output tile (every shape the persistent kernel does not take)
+hipError_t launch_gemm_tiles(const GemmArgs& a, hipStream_t stream) {
     const bool raw = a.y == nullptr;
     if (a.bits == 4) {
         if (!raw) return dispatch<4, 4, 0>(a, stream);

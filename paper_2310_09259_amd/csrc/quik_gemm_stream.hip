@@ -1,0 +1,646 @@
+// Persistent form of the 4-bit integer GEMM + dequantization epilogue + fp16 outlier GEMM for
+// large token counts (Algorithm 1 of arXiv 2310.09259: "INTmatmul", "Dequantization", "FPmatmul"
+// and the final add; epilogue fusion as in Section 3.4).  Same arithmetic, operand formats and
+// widening as gemm_kernel in quik_gemm.hip (see the header of that file); what differs is how the
+// work is laid over the chip:
+//
+//  * One workgroup of eight waves per CU stays resident and walks through a list of output tiles
+//    (256 token rows x 128 / 160 / 192 output channels).  The two-slot stage ring keeps running
+//    across the tile boundary: while a tile's last two stages are multiplied, the slots they free
+//    are already being filled with the first two stages of the workgroup's next tile.  A tile
+//    therefore starts its matrix instructions right after the previous tile's stores were issued,
+//    instead of after a workgroup launch, a parameter fetch and a first-stage round trip to memory.
+//  * Tile widths are chosen per launch so that every CU gets the same number of 32-channel
+//    column blocks (+-1): N / 32 blocks are cut into `tn` tiles per token-row panel, `rem` of them
+//    one block wider than the others, spread evenly.  (With one fixed 256 x 192 tile the LLaMA-7B
+//    up-projection at 2048 tokens is 464 tiles on 256 CUs: two rounds for 1.81 rounds of work.)
+//    The two wave columns of the workgroup split a tile's blocks 3 + 3, 3 + 2 or 2 + 2; a wave with
+//    two blocks runs a K loop instantiated for two.  Waves w and w + 4 take different wave columns,
+//    so the two waves that share a SIMD carry 3 + 2 blocks on a five-block tile.
+//  * XCD-aware order: each XCD owns a contiguous range of the tile list (channel panels outermost,
+//    all token-row panels of a channel panel adjacent), and its CUs take neighbouring tiles of that
+//    range at the same time, so a weight panel is fetched by one XCD only and the activation
+//    panels it needs stay in that XCD's L2.
+//  * One stage body serves every integer stage of a tile, whatever ring slot it sits in: the two slots
+//    of an operand lie 32 KB apart, and the fragment address registers are flipped between them
+//    (one XOR each per stage) right before the reads that need the other slot.
+//  * The epilogue parameters (per token: scale, zero, code sum; per channel: weight scale, wReduced,
+//    code sum, bias) are copied global -> LDS by the same DMA path as the operands, two stages
+//    before they are needed, so they never occupy registers during the K loop.
+//  * The output tile leaves through a small per-wave LDS buffer, sixteen rows at a time, so the
+//    stage ring is never needed for it.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "quik_kernels.h"
+#include "quik_gemm_device.h"
+
+namespace quik {
+
+namespace {
+
+using namespace gemm_dev;
+
+template <int V> using ic = std::integral_constant<int, V>;
+#define QUIK_INLINE __attribute__((always_inline))
+
+constexpr int BM = 256;                 // token rows per tile
+constexpr int TNX = 3;                  // most 32-channel blocks per wave
+constexpr int BNX = 2 * TNX * 32;       // widest tile
+constexpr int BKB = 128;                // bytes of every packed row per stage (256 columns)
+constexpr int TM = 2;                   // 32-row blocks per wave
+constexpr int NWAVES = 8, NT = NWAVES * 64;
+constexpr int CPR = BKB / 16, RPI = 64 / CPR;
+constexpr int IROWS = NWAVES * RPI;     // rows between a wave's consecutive copy instructions
+constexpr int A_INSTR = BM / IROWS, B_INSTR = BNX / IROWS, LPS = A_INSTR + B_INSTR;
+constexpr int KSUB = BKB / 32;
+constexpr int A_BYTES = BM * BKB, B_BYTES = BNX * BKB;
+// LDS map.  The two ring slots of an operand are SLOT_STRIDE apart (a power of two, so that a fragment
+// address switches slots with one XOR); the gaps hold the epilogue parameters:
+//   0       weights, slot 0 (24 KB)      24576  parameters (7 KB)
+//   32768   weights, slot 1              57344  (free)
+//   65536   activations, slot 0 (32 KB)  98304  activations, slot 1
+//   131072  per-wave output buffers
+constexpr int SLOT_STRIDE = 32768;
+constexpr int OFF_B = 0, OFF_A = 65536;
+static_assert(B_BYTES <= SLOT_STRIDE && A_BYTES <= SLOT_STRIDE, "ring slots overlap");
+constexpr int PARK_ROWS = 16, PARK_ROW_BYTES = TNX * 64 + 16, PARK_BYTES = PARK_ROWS * PARK_ROW_BYTES;
+constexpr int OFF_PARK = OFF_A + 2 * SLOT_STRIDE;
+// parameter area: three per-token arrays of BM words, then four per-channel arrays of 256 words
+// (weight scale and bias are fp16: 96 words used)
+constexpr int OFF_PRM = B_BYTES;
+constexpr int PRM_SCALE = 0, PRM_ZERO = BM * 4, PRM_CSUM = 2 * BM * 4;
+constexpr int PRM_WSCALE = 3 * BM * 4, PRM_WRED = PRM_WSCALE + 1024, PRM_WCSUM = PRM_WRED + 1024,
+              PRM_BIAS = PRM_WCSUM + 1024;
+static_assert(OFF_PRM + PRM_BIAS + 1024 <= SLOT_STRIDE, "parameters do not fit the gap");
+constexpr int SMEM_BYTES = OFF_PARK + NWAVES * PARK_BYTES;
+static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+static_assert(KSUB == 4, "the stage code below is written for four sub-steps");
+
+// 4 bytes per lane, global -> LDS at lds_base + lane * 4 (see dma16 in quik_gemm_device.h)
+__device__ __forceinline__ void dma4(v4i rsrc, uint32_t lds_base, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
+
+// MODE 0: fused epilogue (single-AND widening + correction); MODE 1: raw INT32 accumulators, widening
+// without side data; MODE 2: raw accumulators, single-AND widening + correction.
+template <int MODE>
+__global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPlan p) {
+    constexpr bool RAW = MODE != 0;
+    constexpr bool ASYM = MODE != 1;
+    constexpr int SHIFT = ASYM ? 4 : 8;
+
+    // One workgroup per CU owns half of every SIMD's register file: claim all 256 registers, so that the top
+    // of the allocation is never a live register (the row-quantization kernel misread such a register on
+    // MI355X when its allocation ended below its share of the file).
+    asm volatile("" ::: "v255");
+    __shared__ __align__(1024) uint8_t smem[SMEM_BYTES];
+    uint8_t* const lds = smem;
+    const uint8_t* const prm = smem + OFF_PRM;
+
+    const int lane = threadIdx.x & 63;
+    const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave_u & 3, wn = wave_u >> 2;
+    // Per-lane address registers are set from an opaque copy of the lane id right before the phase that
+    // uses them.  Computed once from the lane id, they would stay alive across the register-hungry
+    // dequantization and output phases of every tile, be spilled there, and be re-read from scratch
+    // memory inside the K loops, where a wait for such a reload is also a wait for the copies.
+    auto opaque_lane = [&]() QUIK_INLINE -> int {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        return ln;
+    };
+
+    // ---- this workgroup's tiles
+    const int xcd = blockIdx.x % kXcds, cu = blockIdx.x / kXcds, per_xcd = gridDim.x / kXcds;
+    const int total = p.tiles_m * p.tn;
+    const int tq = total / kXcds, tr = total % kXcds;
+    const int first = (xcd < tr) ? xcd * (tq + 1) : tr * (tq + 1) + (xcd - tr) * tq;
+    const int count = tq + (xcd < tr ? 1 : 0);
+    // k-th tile of this workgroup: first token row, first channel, channels that exist, width in blocks
+    // (plain scalars on purpose: a struct selected at run time ends up in scratch memory)
+    auto geo = [&](int k, int& t0, int& n0, int& ncols, int& w) QUIK_INLINE -> bool {
+        const int local = cu + k * per_xcd;
+        if (local >= count) return false;
+        const int id = first + local;
+        const int nt = id / p.tiles_m, m = id % p.tiles_m;
+        const int lo = (nt * p.rem) / p.tn, hi = ((nt + 1) * p.rem) / p.tn;
+        t0 = m * BM;
+        n0 = (nt * p.base + lo) * 32;
+        w = p.base + hi - lo;
+        ncols = min(w * 32, a.N - n0);
+        return true;
+    };
+
+    // stages of a tile: integer stages 0 .. nk_int-1, then the fp16 stages; stage v of a tile that starts
+    // in ring slot P sits in slot (P + v) & 1
+    const int row_bytes = a.K_b / 2;
+    const int int_bytes = (row_bytes + 15) & ~15;        // up to the 16-byte piece that holds the last packed byte
+    const int nk_int = (row_bytes + BKB - 1) / BKB;
+    const int fp_bytes = a.n_out * 2;
+    const int nk_fp = RAW ? 0 : (fp_bytes + BKB - 1) / BKB;
+    const int nk = nk_int + nk_fp;
+    const int lda_fp = a.ldo * 2, ldb_fp = a.ldwo * 2;
+
+    // ---- copy geometry (the same for every tile: offsets are relative to the tile's descriptors).
+    // Copy instruction i of a wave moves 16 bytes per lane: rows (i * 8 + wave) * 8 + lane / 8 of the
+    // operand panel, 16-byte slot lane % 8 of the row, XOR-swizzled with the row.  With this row order the
+    // swizzle term does not depend on i, so one register per operand holds a lane's offset and
+    // instruction i adds i * 64 rows.
+    const uint32_t lds_base = lds_addr(lds);
+    const uint32_t m0A = lds_base + OFF_A + wave_u * 1024;
+    const uint32_t m0B = lds_base + OFF_B + wave_u * 1024;
+    // One stage's copy: descriptors, per-lane offsets of copy instruction 0 (or out of range), the
+    // offset of the stage inside a row and the step between a wave's consecutive copy instructions.
+    struct Copy {
+        v4i A, B;
+        uint32_t va, vb, so, stepA, stepB;
+    };
+    // stage j (integer, or fp16 if `fp`) of the tile at token row t0, channel n0 with `ncols` channels.  The
+    // two descriptors are rebuilt here from the tile's origin (a few scalar operations) rather than kept
+    // for every tile and kind.  Lanes whose 16-byte piece lies beyond the row's data (last, partial stage)
+    // are pointed out of range and deliver zeros; so are all lanes of a copy that is switched off (`on`
+    // false: no next tile -- the slot's content is dead then), which keeps the stage code free of branches.
+    auto prep_copy = [&](Copy& r, int t0, int n0, int ncols, bool fp, int j, bool on) QUIK_INLINE {
+        const uint32_t ln = (uint32_t)opaque_lane();
+        const uint32_t row0 = (uint32_t)wave_u * RPI + ln / CPR, c = ((ln % CPR) ^ (uint32_t)swz<BKB>((int)row0)) * 16;
+        const int lda = fp ? lda_fp : a.ldq, ldb = fp ? ldb_fp : a.ldw;
+        const uint8_t* pa = static_cast<const uint8_t*>(fp ? a.x_out : a.xq);
+        const uint8_t* pb = static_cast<const uint8_t*>(fp ? a.w_out : a.w_q);
+        r.A = make_rsrc(pa + (size_t)t0 * lda, (size_t)(a.T - t0) * lda);
+        r.B = make_rsrc(pb + (size_t)n0 * ldb, (size_t)ncols * ldb);
+        const bool live = on && ((uint32_t)(j * BKB) + c < (uint32_t)(fp ? fp_bytes : int_bytes));
+        r.va = live ? row0 * (uint32_t)lda + c : kOob;
+        r.vb = live ? row0 * (uint32_t)ldb + c : kOob;
+        r.so = (uint32_t)(j * BKB);
+        r.stepA = (uint32_t)(IROWS * lda);
+        r.stepB = (uint32_t)(IROWS * ldb);
+    };
+    // copy instruction d (0 .. LPS-1) of that stage into ring slot `slot`
+    auto issue_copy = [&](const Copy& r, int slot, int d) QUIK_INLINE {
+        const uint32_t so = (uint32_t)slot * SLOT_STRIDE;
+        if (d < A_INSTR) dma16(r.A, m0A + so + d * (IROWS * BKB), r.va + (uint32_t)d * r.stepA, r.so);
+        else dma16(r.B, m0B + so + (d - A_INSTR) * (IROWS * BKB), r.vb + (uint32_t)(d - A_INSTR) * r.stepB, r.so);
+    };
+    // the epilogue parameters of a tile, global -> LDS (each wave copies a share)
+    auto issue_params = [&](int t0, int n0, int ncols) QUIK_INLINE {
+        if constexpr (!RAW) {
+            const uint32_t pb = lds_base + OFF_PRM;
+            const uint32_t l4 = (uint32_t)opaque_lane() * 4u;
+            const size_t rows = (size_t)(a.T - t0), cols = (size_t)ncols;
+            if (wave_u < 4) {                              // 64 token rows each
+                const uint32_t o = (uint32_t)wave_u * 256u;
+                dma4(make_rsrc(a.scale + t0, rows * 4), pb + PRM_SCALE + o, l4 + o);
+                dma4(make_rsrc(a.zero + t0, rows * 4), pb + PRM_ZERO + o, l4 + o);
+                dma4(make_rsrc(a.code_sum + t0, rows * 4), pb + PRM_CSUM + o, l4 + o);
+            } else if (wave_u < 7) {                       // 64 channels each
+                const uint32_t o = (uint32_t)(wave_u - 4) * 256u;
+                dma4(make_rsrc(a.w_reduced + n0, cols * 4), pb + PRM_WRED + o, l4 + o);
+                dma4(make_rsrc(a.w_code_sum + n0, cols * 4), pb + PRM_WCSUM + o, l4 + o);
+            } else {                                       // fp16 arrays: 128 channels per instruction
+                const __half* ws = static_cast<const __half*>(a.w_scale) + n0;
+                const __half* bs = a.bias ? static_cast<const __half*>(a.bias) + n0 : ws;
+                const size_t bb = a.bias ? cols * 2 : 0;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    dma4(make_rsrc(ws, cols * 2), pb + PRM_WSCALE + h * 256, l4 + h * 256);
+                    dma4(make_rsrc(bs, bb), pb + PRM_BIAS + h * 256, l4 + h * 256);
+                }
+            }
+        }
+    };
+
+    // The compiler does not see the DMA's writes to LDS, so it is free to move an ordinary LDS read up to
+    // the last barrier; for the reads that start a phase that means registers held across the whole phase
+    // before.  tie() makes an address register depend (without any instruction) on a value computed at
+    // the end of that phase, which keeps the reads behind it.
+    auto tie = [&](uint32_t& addr, uint32_t dep) QUIK_INLINE { asm volatile("" : "+v"(addr) : "v"(dep)); };
+
+    // ---- fragment addresses: one register per operand and sub-step (row l of the wave's first block,
+    // swizzled 16-byte slot of k-group kg); the 32-row block is an immediate.  Registers 0, 1 point into
+    // ring slot `slot`, registers 2, 3 into the other one: a stage flips the register of sub-step q to its
+    // own slot right before it reads that sub-step (see int_stage).
+    uint32_t rdA[KSUB], rdB[KSUB];
+    auto set_rd = [&](int cb0, int slot, uint32_t dep) QUIK_INLINE {
+        uint32_t lnu = (uint32_t)lane;
+        tie(lnu, dep);
+        const int ln = (int)lnu;
+        const int l = ln & 31, kg = (ln >> 5) & 1;
+        const int ra = wm * TM * 32 + l, rb = cb0 * 32 + l;
+#pragma unroll
+        for (int ks = 0; ks < KSUB; ++ks) {
+            const int so = (ks < 2 ? slot : slot ^ 1) * SLOT_STRIDE;
+            rdA[ks] = OFF_A + so + ra * BKB + (((ks * 2 + kg) ^ swz<BKB>(ra)) << 4);
+            rdB[ks] = OFF_B + so + rb * BKB + (((ks * 2 + kg) ^ swz<BKB>(rb)) << 4);
+        }
+    };
+    // first block and block count of this wave in a tile of width w (tiles narrower than four blocks
+    // are run as four: the surplus rows of the weight panel arrive as zeros)
+    auto wave_cols = [&](int w, int& cb0, int& tna) QUIK_INLINE {
+        const int we = max(w, 4);
+        cb0 = wn ? (we + 1) / 2 : 0;
+        tna = wn ? we / 2 : (we + 1) / 2;
+    };
+
+    // Raw fragments of two sub-steps (32 packed bytes of every row = 64 columns each; words 0, 1 of a
+    // fragment feed the first half of a sub-step, words 2, 3 the second) and the widened operands: the
+    // activation operands of both halves, and two weight operands that take turns -- a weight fragment is
+    // widened while the two MFMAs of the fragment before it issue.
+    uint4 R[2][TM + TNX];
+    v4i Aop[2][TM], Bop[2];
+    auto read_frag = [&](int set, int f, int ks) QUIK_INLINE {
+        const uint32_t off = (f < TM) ? rdA[ks] + (uint32_t)(f * 4096) : rdB[ks] + (uint32_t)((f - TM) * 4096);
+        R[set][f] = *reinterpret_cast<const uint4*>(lds + off);
+    };
+    // words 2 * half, 2 * half + 1 of fragment f of raw set `rset`, widened into `dst`
+    auto widen_pair = [&](v4i& dst, int rset, int f, int half) QUIK_INLINE {
+        constexpr uint32_t M = 0xF0F0F0F0u;
+        const bool act = f < TM;                         // activations: even k in the high nibble
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const uint32_t x = half == 0 ? (kk == 0 ? R[rset][f].x : R[rset][f].y) : (kk == 0 ? R[rset][f].z : R[rset][f].w);
+            const uint32_t hi = x & M;                   // 16 * signed high nibble
+            const uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)   // low nibble + 8
+                                     : ((x << 4) & M);                     // 16 * signed low nibble
+            dst[kk * 2] = (int)(act ? hi : lo);
+            dst[kk * 2 + 1] = (int)(act ? lo : hi);
+        }
+    };
+    // a tile's first two sub-steps' fragments (its stage 0, in ring slot `slot`), and the operands its
+    // first half sub-step starts with
+    auto first_reads = [&](int cb0, int slot, uint32_t dep) QUIK_INLINE {
+        set_rd(cb0, slot, dep);
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int f = 0; f < TM + TNX; ++f) read_frag(q, f, q);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) widen_pair(Aop[0][i], 0, i, 0);
+        widen_pair(Bop[0], 0, TM, 0);
+    };
+
+    int cur_t0 = 0, cur_n0 = 0, cur_nc = 0, cur_w = 0, nxt_t0 = 0, nxt_n0 = 0, nxt_nc = 0, nxt_w = 0;
+    if (!geo(0, cur_t0, cur_n0, cur_nc, cur_w)) return;
+
+    // ---- first tile: its first two stages
+    {
+        Copy c0;
+        prep_copy(c0, cur_t0, cur_n0, cur_nc, false, 0, true);
+#pragma unroll
+        for (int d = 0; d < LPS; ++d) issue_copy(c0, 0, d);
+        prep_copy(c0, cur_t0, cur_n0, cur_nc, false, 1, true);
+#pragma unroll
+        for (int d = 0; d < LPS; ++d) issue_copy(c0, 1, d);
+    }
+    wait_vm<LPS>();                                       // stage 0 has landed
+    __syncthreads();
+    {
+        int cb0, tna;
+        wave_cols(cur_w, cb0, tna);
+        first_reads(cb0, 0, 0u);
+    }
+
+    int P = 0;                                            // ring slot of the current tile's stage 0
+    for (int k = 0;; ++k) {
+        const bool more = geo(k + 1, nxt_t0, nxt_n0, nxt_nc, nxt_w);
+        int cb0, tna, cb0n = 0, tnan = 0;
+        wave_cols(cur_w, cb0, tna);
+        if (more) wave_cols(nxt_w, cb0n, tnan);
+
+        // What goes into the slot that the barrier of stage v frees: stage v + 2 of this tile, else a stage of
+        // the next tile (the ring simply runs on).
+        auto prep_refill = [&](Copy& r, int v) QUIK_INLINE {
+            const int u = v + 2;
+            const bool next = u >= nk, fp = !next && u >= nk_int;
+            const int j = next ? u - nk : (fp ? u - nk_int : u);
+            prep_copy(r, next ? nxt_t0 : cur_t0, next ? nxt_n0 : cur_n0, next ? nxt_nc : cur_nc, fp, j, !next || more);
+        };
+
+        auto tile = [&](auto tna_c) QUIK_INLINE {
+            constexpr int TNA = decltype(tna_c)::value;
+            constexpr int NFA = TM + TNA;
+            constexpr int MH = TM * TNA;                              // MFMAs per half sub-step
+            static_assert(2 * MH >= LPS && MH >= NFA && TNA >= TM, "copy, read and widening work is spread over the MFMA slots");
+
+            v16i acc[TM][TNA];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TNA; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+            // One integer stage (stage s of the tile, in ring slot `slot`).  The refill of the slot it frees
+            // is spread over the MFMA slots after the barrier.  A half sub-step issues its MFMAs weight
+            // fragment by weight fragment (two MFMAs each); meanwhile the next weight fragment (in the order
+            // j0h0, j1h0, .., j0h1, .., then the next sub-step's) is widened into the weight operand not in
+            // use, the activation operands of the other half are widened, and, in the second half, the raw
+            // registers that are done are refilled from LDS with the fragments of the sub-step after the
+            // next -- which, in the last two sub-steps, belongs to the next stage in the other slot (after
+            // the last integer stage that is an fp16 stage, or the next tile: its fragments are simply not
+            // used as integers).
+            auto int_stage = [&](int s, int slot) QUIK_INLINE {
+                Copy rf;
+#pragma unroll
+                for (int ks = 0; ks < KSUB; ++ks) {
+                    const int par = ks & 1;                           // raw set of this sub-step; the other holds the next one
+                    const int tks = (ks + 2) % KSUB;
+                    if (ks == 2) {
+                        wait_vm<0>();
+                        __syncthreads();          // stage s + 1 has landed for everybody; nobody reads this stage's slot any more
+                        prep_refill(rf, s);
+                        if (s == nk_int - 2) issue_params(cur_t0, cur_n0, cur_nc);
+                    }
+                    // sub-step tks was last read in the other slot
+                    rdA[tks] ^= SLOT_STRIDE;
+                    rdB[tks] ^= SLOT_STRIDE;
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int hm = 0; hm < 2 * MH; ++hm) {
+                        const int h = hm / MH, m = hm % MH, j = m / TM, i = m % TM;
+                        const int seq = h * TNA + j;                  // this weight fragment's place in the sub-step
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Aop[h][i], Bop[seq & 1], acc[i][j], 0, 0, 0);
+                        if (ks == 2 && hm < LPS) issue_copy(rf, slot, hm);
+                        if (i == 0) {
+                            // the weight fragment after this one
+                            const int nseq = seq + 1;
+                            if (nseq < 2 * TNA) widen_pair(Bop[nseq & 1], par, TM + nseq % TNA, nseq / TNA);
+                            else widen_pair(Bop[0], par ^ 1, TM, 0);
+                        } else if (j < TM) {
+                            // activation fragment j of the other half: this sub-step's second half, or the next
+                            // sub-step's first
+                            if (h == 0) widen_pair(Aop[1][j], par, j, 1);
+                            else widen_pair(Aop[0][j], par ^ 1, j, 0);
+                        }
+                        // second half: every raw register of this sub-step has been widened by the time its
+                        // turn comes here (activations in the first half, weight fragment j at MFMA 2 j - 2)
+                        if (h == 1 && m < NFA) read_frag(par, m, tks);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            };
+
+            int slot = P;
+            for (int s = 0; s < nk_int; ++s) {
+                int_stage(s, slot);
+                slot ^= 1;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+
+            // The epilogue's per-lane addresses depend only on the lane, so the compiler would compute them
+            // once, before the tile loop, and keep dozens of registers alive through the K loops.  An
+            // opaque copy of the lane id per tile keeps that arithmetic here.
+            const int lane_e = opaque_lane();
+            const int l32e = lane_e & 31, ge = lane_e >> 5;
+            const int tw = cur_t0 + wm * TM * 32, nw = cur_n0 + cb0 * 32, n_end = cur_n0 + cur_nc;
+            uint32_t done = 0;                            // a value from the end of this tile's output
+            if constexpr (RAW) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TNA; ++j) {
+                        const int n = nw + j * 32 + l32e;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int t = tw + i * 32 + 8 * (r >> 2) + 4 * ge + (r & 3);
+                            if (t < a.T && n < n_end) {
+                                int v = acc[i][j][r] >> SHIFT;
+                                if constexpr (ASYM) v -= 8 * (a.code_sum[t] + a.w_code_sum[n]);
+                                a.acc[(size_t)t * a.ldacc + n] = v;
+                            }
+                        }
+                    }
+            } else {
+                // Dequantization: the raw accumulator is 16 x the integer dot product plus
+                // 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes the latter, the
+                // conversion to binary32 is exact, and 2^-4 rides on the weight scale.
+                float c_sw[TNA], c_wr[TNA], c_bv[TNA];
+                int c_nc[TNA];
+#pragma unroll
+                for (int j = 0; j < TNA; ++j) {
+                    const int col = (cb0 + j) * 32 + l32e;            // inside the tile
+                    c_sw[j] = __half2float(*reinterpret_cast<const __half*>(prm + PRM_WSCALE + col * 2)) *
+                              (1.0f / (float)(1 << SHIFT));           // exact power-of-two factor
+                    c_bv[j] = a.bias ? __half2float(*reinterpret_cast<const __half*>(prm + PRM_BIAS + col * 2)) : 0.0f;
+                    c_wr[j] = *reinterpret_cast<const float*>(prm + PRM_WRED + col * 4);
+                    c_nc[j] = -128 * *reinterpret_cast<const int*>(prm + PRM_WCSUM + col * 4);
+                }
+                // Per-token parameters of eight rows at a time (group gq = row block i, row quad rq), read one
+                // group ahead of their use; tied to the results of the group before, or the scheduler would
+                // hoist all 24 reads (96 registers) to the top.
+                uint32_t dq_dep = 0;
+                v16f cf[TM][TNA];
+                float4 sa4[2], z4[2];
+                int4 cs4[2];
+                auto load_group = [&](int gq) QUIK_INLINE {
+                    const int lr = wm * TM * 32 + (gq >> 2) * 32 + 8 * (gq & 3) + 4 * ge;
+                    uint32_t o = (uint32_t)lr * 4u;
+                    tie(o, dq_dep);
+                    sa4[gq & 1] = *reinterpret_cast<const float4*>(prm + PRM_SCALE + o);
+                    z4[gq & 1] = *reinterpret_cast<const float4*>(prm + PRM_ZERO + o);
+                    cs4[gq & 1] = *reinterpret_cast<const int4*>(prm + PRM_CSUM + o);
+                };
+                load_group(0);
+#pragma unroll
+                for (int gq = 0; gq < TM * 4; ++gq) {
+                    const int i = gq >> 2, rq = gq & 3, b = gq & 1;
+                    if (gq + 1 < TM * 4) load_group(gq + 1);
+                    const float sa_[4] = {sa4[b].x, sa4[b].y, sa4[b].z, sa4[b].w};
+                    const float sh_[4] = {z4[b].x + 8.0f * sa4[b].x, z4[b].y + 8.0f * sa4[b].y, z4[b].z + 8.0f * sa4[b].z,
+                                          z4[b].w + 8.0f * sa4[b].w};    // zeroAct + halfRange * scaleAct
+                    const int ct_[4] = {-128 * cs4[b].x, -128 * cs4[b].y, -128 * cs4[b].z, -128 * cs4[b].w};
+#pragma unroll
+                    for (int j = 0; j < TNA; ++j)
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) {
+                            const int r = rq * 4 + rr;
+                            const int ai = acc[i][j][r] + ct_[rr] + c_nc[j];
+                            cf[i][j][r] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j],
+                                                         __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
+                        }
+                    dq_dep = __float_as_uint(cf[i][TNA - 1][rq * 4 + 3]);
+                }
+
+                // fp16 outlier stages on the dequantized tile (stage nk_int + f of the tile).  The first two
+                // sub-steps of the first one are read again here (the last integer stage has read them, but
+                // keeping them in registers across the dequantization costs more than this read).
+                // LAST: the tile's last stage -- no look-ahead into the next tile, whose waves' column blocks
+                // may differ.
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    tie(rdA[q], dq_dep);
+                    tie(rdB[q], dq_dep);
+#pragma unroll
+                    for (int f = 0; f < NFA; ++f) read_frag(q, f, q);
+                }
+                auto fp_stage = [&](auto last_c, int f, int slot) QUIK_INLINE {
+                    constexpr bool LAST = decltype(last_c)::value != 0;
+                    Copy rf;
+#pragma unroll
+                    for (int ks = 0; ks < KSUB; ++ks) {
+                        const int tks = (ks + 2) % KSUB;
+                        if (ks == 2) {
+                            wait_vm<0>();
+                            __syncthreads();
+                            prep_refill(rf, nk_int + f);
+                        }
+                        rdA[tks] ^= SLOT_STRIDE;
+                        rdB[tks] ^= SLOT_STRIDE;
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int m = 0; m < MH; ++m) {
+                            const int i = m / TNA, j = m % TNA;
+                            cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, R[ks & 1][i]),
+                                                                             __builtin_bit_cast(v8h, R[ks & 1][TM + j]),
+                                                                             cf[i][j], 0, 0, 0);
+                            // the refill, spread over the MFMAs of the two sub-steps after the barrier
+                            if (ks >= 2) {
+#pragma unroll
+                                for (int d = 0; d < LPS; ++d)
+                                    if (d * 2 * MH / LPS == (ks - 2) * MH + m) issue_copy(rf, slot, d);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        // this sub-step's raw registers are free now
+                        if (ks + 2 < KSUB || !LAST) {
+#pragma unroll
+                            for (int q = 0; q < NFA; ++q) read_frag(ks & 1, q, tks);
+                        }
+                    }
+                };
+                for (int f = 0; f + 1 < nk_fp; ++f) {
+                    fp_stage(ic<0>{}, f, slot);
+                    slot ^= 1;
+                }
+                if (nk_fp > 0) fp_stage(ic<1>{}, nk_fp - 1, slot);
+                __builtin_amdgcn_sched_barrier(0);
+
+                // Output: a lane owns one column of sixteen rows of every 32 x 32 block, so direct stores
+                // would be 2 bytes per lane.  Each wave parks sixteen rows of its fp16 tile at a time in
+                // its own LDS buffer and writes them out as 16-byte pieces, whole row segments per store
+                // instruction.  Needs 16-byte aligned output rows; otherwise the direct path below.
+                __half* __restrict__ y = static_cast<__half*>(a.y);
+                const bool vec_ok = ((reinterpret_cast<uintptr_t>(a.y) & 15u) == 0) && (a.ldy % 8 == 0);
+                if (vec_ok) {
+                    uint8_t* wbuf = smem + OFF_PARK + wave_u * PARK_BYTES;
+                    constexpr int CH = TNA * 4;                  // 16-byte pieces per row
+                    constexpr int RPS = 64 / CH;                 // rows per store instruction
+                    const int prow = lane_e / CH, pch = lane_e % CH;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int hf = 0; hf < 2; ++hf) {         // rows 16 hf .. 16 hf + 15 of block row i
+#pragma unroll
+                            for (int j = 0; j < TNA; ++j)
+#pragma unroll
+                                for (int rr = 0; rr < 8; ++rr) {
+                                    const int r = hf * 8 + rr;
+                                    const int row = 8 * (rr >> 2) + 4 * ge + (rr & 3);     // inside the 16 rows
+                                    *reinterpret_cast<__half*>(wbuf + row * PARK_ROW_BYTES + (j * 32 + l32e) * 2) =
+                                        __float2half(cf[i][j][r]);
+                                }
+#pragma unroll
+                            for (int q = 0; q < (PARK_ROWS + RPS - 1) / RPS; ++q) {
+                                const int row = q * RPS + prow;
+                                if (prow < RPS && row < PARK_ROWS) {
+                                    const uint4 v = *reinterpret_cast<const uint4*>(wbuf + row * PARK_ROW_BYTES + pch * 16);
+                                    done = v.x;
+                                    const int t = tw + i * 32 + hf * 16 + row, n = nw + pch * 8;
+                                    if (t < a.T) {
+                                        __half* dst = y + (size_t)t * a.ldy + n;
+                                        if (n + 8 <= n_end) {
+                                            *reinterpret_cast<uint4*>(dst) = v;
+                                        } else {
+                                            const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                                            for (int e = 0; e < 8; ++e)
+                                                if (n + e < n_end)
+                                                    reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
+                                        }
+                                    }
+                                }
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TNA; ++j) {
+                            const int n = nw + j * 32 + l32e;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int t = tw + i * 32 + 8 * (r >> 2) + 4 * ge + (r & 3);
+                                if (t < a.T && n < n_end) y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
+                            }
+                        }
+                }
+            }
+            // The next tile's first fragments (its stage 0 has landed: the barrier of this tile's last
+            // stage waited for it), read once this tile's results have left the registers.
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) first_reads(cb0n, (P + nk) & 1, done);
+        };
+
+        if (tna >= 3) tile(ic<3>{});
+        else tile(ic<2>{});
+
+        if (!more) break;
+        P = (P + nk) & 1;
+        cur_t0 = nxt_t0; cur_n0 = nxt_n0; cur_nc = nxt_nc; cur_w = nxt_w;
+    }
+    wait_vm<0>();
+}
+
+}  // namespace
+
+// Tile plan of the persistent kernel for a [T, N] output with K_b base columns on `cus` compute
+// units, or false if the shape is better served by the per-tile kernels (too few tiles to give every
+// CU one, or too shallow).
+bool plan_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p) {
+    if (cus < kXcds || cus % kXcds) return false;
+    if (K_b < 4 * 2 * BKB || (N & 1)) return false;     // at least four integer stages; fp16 arrays copied as dwords
+    const int tiles_m = (T + BM - 1) / BM;
+    const int nb = (N + 31) / 32;                       // 32-channel blocks
+    const int tn_min = (nb + 2 * TNX - 1) / (2 * TNX);  // tiles per row panel at full width
+    if ((long)tiles_m * tn_min < cus) return false;
+    // Candidate tile counts: from full width down to four blocks per tile.  Estimated time of a
+    // launch in units of one block's K loop: the busiest CU's blocks (its tiles, each `base` wide plus
+    // its share of the wider ones) plus a fixed cost per tile.
+    const int tn_max = nb / 4 > tn_min ? nb / 4 : tn_min;
+    double best = 1e30;
+    int best_tn = tn_min;
+    for (int tn = tn_min; tn <= tn_max; ++tn) {
+        const int base = nb / tn, rem = nb % tn;
+        if (base + (rem ? 1 : 0) > 2 * TNX) continue;
+        const long tiles = (long)tiles_m * tn;
+        const long r = (tiles + cus - 1) / cus;         // tiles of the busiest CU
+        const double blocks = (double)(r * base + (r * rem + tn - 1) / tn);
+        // (last term: among equal estimates, the tile count that leaves the fewest CUs without a tile in
+        // the last round)
+        const double cost = blocks + 0.35 * (double)r + 1e-3 * (double)(r * cus - tiles) / (double)cus;
+        if (cost < best - 1e-9) { best = cost; best_tn = tn; }
+    }
+    p->tiles_m = tiles_m;
+    p->tn = best_tn;
+    p->base = nb / best_tn;
+    p->rem = nb % best_tn;
+    p->grid = cus;
+    return best < 1e29;
+}
+
+hipError_t launch_gemm_stream(const GemmArgs& a, const StreamPlan& p, hipStream_t stream) {
+    const bool raw = a.y == nullptr;
+    if (!raw) hipLaunchKernelGGL(gemm_stream_kernel<0>, dim3(p.grid), dim3(NT), 0, stream, a, p);
+    else if (a.code_sum && a.w_code_sum) hipLaunchKernelGGL(gemm_stream_kernel<2>, dim3(p.grid), dim3(NT), 0, stream, a, p);
+    else hipLaunchKernelGGL(gemm_stream_kernel<1>, dim3(p.grid), dim3(NT), 0, stream, a, p);
+    return hipGetLastError();
+}
+
+}  // namespace quik

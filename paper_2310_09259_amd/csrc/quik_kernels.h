@@ -59,9 +59,19 @@ struct WeightReduceArgs {
     int32_t* w_code_sum;  // [N], may be null
 };
 
+// Tile plan of the persistent 4-bit GEMM (quik_gemm_stream.hip): every token-row panel of 256 rows is
+// cut into `tn` tiles along the output channels, `rem` of them `base + 1` blocks of 32 channels wide
+// and the others `base`, spread evenly; `grid` resident workgroups walk through the tiles.
+struct StreamPlan {
+    int tiles_m, tn, base, rem, grid;
+};
+
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+hipError_t launch_gemm_tiles(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
+bool plan_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p);
+hipError_t launch_gemm_stream(const GemmArgs& a, const StreamPlan& p, hipStream_t stream);
 // FP6 path (quik_gemm_fp6.hip): xq / w_q of GemmArgs are panel buffers [stage][row][48 bytes]; ldq / ldw unused
 hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_pack_fp6(const void* w_q, int ldw, int N, int K_b, void* w6, hipStream_t stream);
