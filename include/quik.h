@@ -214,6 +214,28 @@ int quik_int_gemm(const void *xq, int ldq, const void *w_q, int ldw,
                   void *stream);
 
 /*
+ * Test hook (host only, no GPU call): how quik_gemm_dequant and quik_debug_int_gemm
+ * lay a 4-bit [T, N] output with K_b base columns over a GPU with `cus` compute
+ * units.  Returns 0 if the persistent kernel cannot run the shape (plan untouched);
+ * 1 if it can and is the automatic choice; 2 if it can but the per-tile kernels are
+ * estimated to be at least as fast and are used.  For 1 and 2 the persistent
+ * kernel's tile plan is written to plan[0..4] (HOST pointer): 256-row token panels,
+ * tiles per panel, the width of the narrower tiles in 32-channel blocks, the number
+ * of tiles one block wider (spread evenly), resident workgroups.
+ * QUIK_EINVAL / QUIK_ENULL on invalid input.
+ */
+int quik_debug_gemm_plan(int T, int N, int K_b, int cus, int *plan);
+
+/*
+ * Test hook: which kernel family the 4-bit GEMM entry points use from now on, in
+ * this process: 0 = automatic (the default), 1 = the persistent kernel wherever
+ * quik_debug_gemm_plan returns 1 or 2, 2 = the per-tile kernels always.  Results
+ * are the same either way.  Not synchronised with calls in flight on other
+ * threads.  Returns QUIK_OK or QUIK_EINVAL.
+ */
+int quik_debug_set_gemm_path(int mode);
+
+/*
  * The whole layer: quik_quantize into `workspace`, then quik_gemm_dequant
  * (Algorithm 1, "QUIK Matmul").  Two kernel launches on `stream`.
  *

@@ -42,6 +42,10 @@ def load() -> C.CDLL:
         lib.quik_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.quik_workspace_regions.restype = i
         lib.quik_workspace_regions.argtypes = [i, i, i, i, i, vp, vp]
+        lib.quik_debug_gemm_plan.restype = i
+        lib.quik_debug_gemm_plan.argtypes = [i, i, i, i, vp]
+        lib.quik_debug_set_gemm_path.restype = i
+        lib.quik_debug_set_gemm_path.argtypes = [i]
         lib.quik_quantize_workspace_bytes.restype = C.c_size_t
         lib.quik_quantize_workspace_bytes.argtypes = [i, i]
         lib.quik_w_reduced_bytes.restype = C.c_size_t
@@ -167,6 +171,21 @@ def quik_check_outlier_idx_host(idx_host, K: int) -> int:
     import numpy as np
     a = np.ascontiguousarray(idx_host, dtype=np.int32)
     return load().quik_check_outlier_idx_host(a.ctypes.data_as(C.c_void_p), int(a.size), K)
+
+
+def quik_debug_gemm_plan(T: int, N: int, K_b: int, cus: int):
+    """Host-only: None if the persistent 4-bit kernel cannot run this shape on `cus` compute units, else
+    (choice, (tiles_m, tn, base, rem, grid)): choice 1 = it is used, 2 = the per-tile kernels are."""
+    plan = (C.c_int * 5)()
+    rc = load().quik_debug_gemm_plan(T, N, K_b, cus, C.cast(plan, C.c_void_p))
+    if rc < 0:
+        _check(rc, "quik_debug_gemm_plan")
+    return (rc, tuple(plan)) if rc > 0 else None
+
+
+def quik_debug_set_gemm_path(mode: int):
+    """0 automatic, 1 persistent 4-bit kernel wherever it can run, 2 per-tile kernels only."""
+    _check(load().quik_debug_set_gemm_path(mode), "quik_debug_set_gemm_path")
 
 
 def quik_quantize_workspace_bytes(T: int, bits: int) -> int:

@@ -123,6 +123,22 @@ int quik_workspace_regions(int T, int K, int N, int n_out, int bits, size_t* off
     return QUIK_OK;
 }
 
+int quik_debug_gemm_plan(int T, int N, int K_b, int cus, int* plan) {
+    if (T <= 0 || N <= 0 || K_b <= 0 || (K_b & 1) || K_b >= kMaxKb || cus <= 0) return QUIK_EINVAL;
+    if (!plan) return QUIK_ENULL;
+    quik::StreamPlan p;
+    const int c = quik::choose_gemm_stream(T, N, K_b, cus, &p);
+    if (c == 0) return 0;
+    plan[0] = p.tiles_m; plan[1] = p.tn; plan[2] = p.base; plan[3] = p.rem; plan[4] = p.grid;
+    return c;
+}
+
+int quik_debug_set_gemm_path(int mode) {
+    if (mode < 0 || mode > 2) return QUIK_EINVAL;
+    quik::set_gemm_path(mode);
+    return QUIK_OK;
+}
+
 size_t quik_quantize_workspace_bytes(int T, int bits) {
     if (T <= 0 || (bits != 4 && bits != 8)) return 0;
     return side_bytes(T, bits);

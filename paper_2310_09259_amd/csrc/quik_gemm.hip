@@ -953,11 +953,36 @@ static int compute_units() {
     return cached[dev];
 }
 
+// Estimated time of the per-tile kernels' launch for a 4-bit [T, N] output on `cus` compute units, in the
+// unit of plan_gemm_stream's estimate (one 32-channel block of a 256-row tile through the K loop): the
+// rounds and relative round times of dispatch() below.
+static double tiles_estimate(int T, int N, int cus) {
+    auto rounds = [&](int bm, int bn) { return (double)((((long)(T + bm - 1) / bm) * ((N + bn - 1) / bn) + cus - 1) / cus); };
+    const double a = 4.0 * rounds(256, 128), b = 4.0 * 1.42 * rounds(256, 192), c = 4.0 * 1.42 * rounds(192, 256);
+    return a < b ? (a < c ? a : c) : (b < c ? b : c);
+}
+
+static int g_gemm_path = 0;     // 0: automatic; 1: the persistent kernel wherever it can run; 2: never
+void set_gemm_path(int mode) { g_gemm_path = mode; }
+
+// 0: the persistent kernel cannot run this shape; 1: it can and is the automatic choice; 2: it can, but
+// the per-tile kernels are estimated to be at least as fast.  The persistent kernel wins where whole
+// rounds of fixed tiles leave CUs idle (the LLaMA-7B up-projection at 2048 tokens: 464 tiles of
+// 256 x 192 on 256 CUs); block for block its K loop is about as fast as the per-tile kernels', and with
+// few K stages per tile its longer prologue shows.
+int choose_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* plan) {
+    if (!plan_gemm_stream(T, N, K_b, cus, plan)) return 0;
+    const long tiles = (long)plan->tiles_m * plan->tn;
+    const long r = (tiles + cus - 1) / cus;
+    const double blocks = (double)(r * plan->base + (r * plan->rem + plan->tn - 1) / plan->tn);
+    return (K_b >= 2048 && blocks <= 0.97 * tiles_estimate(T, N, cus)) ? 1 : 2;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
-    if (a.bits == 4 && !a.fp_only) {
-        // large token counts: the persistent kernel with balanced tile widths
+    if (a.bits == 4 && !a.fp_only && g_gemm_path != 2) {
         StreamPlan plan;
-        if (plan_gemm_stream(a.T, a.N, a.K_b, compute_units(), &plan)) return launch_gemm_stream(a, plan, stream);
+        const int c = choose_gemm_stream(a.T, a.N, a.K_b, compute_units(), &plan);
+        if (c == 1 || (c == 2 && g_gemm_path == 1)) return launch_gemm_stream(a, plan, stream);
     }
     return launch_gemm_tiles(a, stream);
 }

@@ -288,16 +288,15 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
     int cur_t0 = 0, cur_n0 = 0, cur_nc = 0, cur_w = 0, nxt_t0 = 0, nxt_n0 = 0, nxt_nc = 0, nxt_w = 0;
     if (!geo(0, cur_t0, cur_n0, cur_nc, cur_w)) return;
 
-    // ---- first tile: its first two stages
-    {
-        Copy c0;
-        prep_copy(c0, cur_t0, cur_n0, cur_nc, false, 0, true);
+    // ---- first tile: its first two stages.  `rf` describes the stage copied last and is carried from
+    // stage to stage (see prep_refill).
+    Copy rf;
+    prep_copy(rf, cur_t0, cur_n0, cur_nc, false, 0, true);
 #pragma unroll
-        for (int d = 0; d < LPS; ++d) issue_copy(c0, 0, d);
-        prep_copy(c0, cur_t0, cur_n0, cur_nc, false, 1, true);
+    for (int d = 0; d < LPS; ++d) issue_copy(rf, 0, d);
+    prep_copy(rf, cur_t0, cur_n0, cur_nc, false, 1, true);
 #pragma unroll
-        for (int d = 0; d < LPS; ++d) issue_copy(c0, 1, d);
-    }
+    for (int d = 0; d < LPS; ++d) issue_copy(rf, 1, d);
     wait_vm<LPS>();                                       // stage 0 has landed
     __syncthreads();
     {
@@ -314,12 +313,19 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
         if (more) wave_cols(nxt_w, cb0n, tnan);
 
         // What goes into the slot that the barrier of stage v frees: stage v + 2 of this tile, else a stage of
-        // the next tile (the ring simply runs on).
+        // the next tile (the ring simply runs on).  Descriptors and lane offsets are rebuilt only where they
+        // change -- at the first stage of an operand kind or tile, and at a last, partial stage (lanes beyond
+        // the data are masked) -- which is a handful of times per tile; every other stage just moves the
+        // offset inside the rows.  (Rebuilding them at every stage costs about a hundred scalar
+        // instructions per wave right behind the barrier, where all eight waves would do it at once.)
         auto prep_refill = [&](Copy& r, int v) QUIK_INLINE {
             const int u = v + 2;
             const bool next = u >= nk, fp = !next && u >= nk_int;
             const int j = next ? u - nk : (fp ? u - nk_int : u);
-            prep_copy(r, next ? nxt_t0 : cur_t0, next ? nxt_n0 : cur_n0, next ? nxt_nc : cur_nc, fp, j, !next || more);
+            if (j == 0 || (j + 1) * BKB > (fp ? fp_bytes : int_bytes))
+                prep_copy(r, next ? nxt_t0 : cur_t0, next ? nxt_n0 : cur_n0, next ? nxt_nc : cur_nc, fp, j, !next || more);
+            else
+                r.so = (uint32_t)(j * BKB);
         };
 
         auto tile = [&](auto tna_c) QUIK_INLINE {
@@ -346,7 +352,6 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
             // the last integer stage that is an fp16 stage, or the next tile: its fragments are simply not
             // used as integers).
             auto int_stage = [&](int s, int slot) QUIK_INLINE {
-                Copy rf;
 #pragma unroll
                 for (int ks = 0; ks < KSUB; ++ks) {
                     const int par = ks & 1;                           // raw set of this sub-step; the other holds the next one
@@ -481,7 +486,6 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                 }
                 auto fp_stage = [&](auto last_c, int f, int slot) QUIK_INLINE {
                     constexpr bool LAST = decltype(last_c)::value != 0;
-                    Copy rf;
 #pragma unroll
                     for (int ks = 0; ks < KSUB; ++ks) {
                         const int tks = (ks + 2) % KSUB;
@@ -609,11 +613,11 @@ bool plan_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p) {
     const int tiles_m = (T + BM - 1) / BM;
     const int nb = (N + 31) / 32;                       // 32-channel blocks
     const int tn_min = (nb + 2 * TNX - 1) / (2 * TNX);  // tiles per row panel at full width
-    if ((long)tiles_m * tn_min < cus) return false;
     // Candidate tile counts: from full width down to four blocks per tile.  Estimated time of a
     // launch in units of one block's K loop: the busiest CU's blocks (its tiles, each `base` wide plus
     // its share of the wider ones) plus a fixed cost per tile.
     const int tn_max = nb / 4 > tn_min ? nb / 4 : tn_min;
+    if ((long)tiles_m * tn_max < cus) return false;     // even the narrowest tiles leave CUs without one
     double best = 1e30;
     int best_tn = tn_min;
     for (int tn = tn_min; tn <= tn_max; ++tn) {

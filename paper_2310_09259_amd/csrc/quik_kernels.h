@@ -71,6 +71,8 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_gemm_tiles(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
 bool plan_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p);
+int choose_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p);   // 0 cannot, 1 chosen, 2 possible but not chosen
+void set_gemm_path(int mode);                                           // test hook: 0 automatic, 1 persistent wherever possible, 2 per-tile
 hipError_t launch_gemm_stream(const GemmArgs& a, const StreamPlan& p, hipStream_t stream);
 // FP6 path (quik_gemm_fp6.hip): xq / w_q of GemmArgs are panel buffers [stage][row][48 bytes]; ldq / ldw unused
 hipError_t launch_gemm_fp6(const GemmArgs& a, hipStream_t stream);

@@ -134,6 +134,67 @@ def test_side_buffer_sizes_and_workspace_regions(lib):
     assert reg(0, 4096, 11008, 256, 4, C.cast(off, C.c_void_p), C.cast(C.pointer(ldq), C.c_void_p)) == -1
 
 
+def _plan(lib, T, N, K_b, cus=256):
+    plan = (C.c_int * 5)()
+    fn = lib.quik_debug_gemm_plan
+    fn.argtypes = [C.c_int] * 4 + [C.c_void_p]
+    rc = fn(T, N, K_b, cus, C.cast(plan, C.c_void_p))
+    return rc, tuple(plan)
+
+
+def _tiles_of_workgroup(plan, b):
+    """Widths (in 32-channel blocks) of the tiles workgroup b walks through: the tile list is cut into
+    eight contiguous ranges (one per XCD, workgroup b belongs to XCD b % 8) and the workgroups of an XCD
+    take its tiles round robin; tile id -> channel panel id / tiles_m, whose width is base or base + 1."""
+    tiles_m, tn, base, rem, grid = plan
+    total, per_xcd = tiles_m * tn, grid // 8
+    x, local = b % 8, b // 8
+    q, r = divmod(total, 8)
+    first = x * (q + 1) if x < r else r * (q + 1) + (x - r) * q
+    count = q + (1 if x < r else 0)
+    out = []
+    while local < count:
+        nt = (first + local) // tiles_m
+        out.append(base + ((nt + 1) * rem) // tn - (nt * rem) // tn)
+        local += per_xcd
+    return out
+
+
+def test_persistent_kernel_plan_covers_the_output_and_balances_the_cus(lib):
+    """Host logic of the persistent 4-bit kernel's tile plan, on the benchmark shapes (256 CUs)."""
+    for T, N, K_b in ((2048, 11008, 3840), (2048, 4096, 10752), (4096, 15360, 4864), (4096, 28672, 7936),
+                      (1030, 9990, 1064), (1024, 15360, 4864)):
+        rc, plan = _plan(lib, T, N, K_b)
+        assert rc in (1, 2), (T, N, K_b)                           # the persistent kernel can run the shape
+        tiles_m, tn, base, rem, grid = plan
+        nb = (N + 31) // 32
+        assert tiles_m == (T + 255) // 256 and grid == 256
+        assert tn * base + rem == nb and 0 <= rem < tn            # the tiles of a panel cover its blocks exactly
+        assert 1 <= base and base + (1 if rem else 0) <= 6         # no tile wider than six blocks
+        loads = [sum(_tiles_of_workgroup(plan, b)) for b in range(grid)]
+        assert sum(loads) == tiles_m * nb                          # every tile belongs to exactly one workgroup
+        assert min(loads) > 0
+        # the busiest CU is within one tile's width of the ideal share (the old fixed 256 x 192 tiling of
+        # the first shape gave 12 blocks to most CUs for an ideal of 10.75)
+        assert max(loads) <= -(-tiles_m * nb // grid) + 6
+    # the headline shape is where fixed tiles waste most (464 tiles of 256 x 192 on 256 CUs = 12 blocks for the
+    # busiest CU): the persistent kernel is the automatic choice and gives no CU more than 11
+    rc, plan = _plan(lib, 2048, 11008, 3840)
+    assert rc == 1 and max(sum(_tiles_of_workgroup(plan, b)) for b in range(256)) == 11
+    # one 256 x 128 tile per CU already balances the down-projection; few K stages per tile: per-tile kernels
+    assert _plan(lib, 2048, 4096, 10752)[0] == 2 and _plan(lib, 1030, 9990, 1064)[0] == 2
+    # shapes the persistent kernel cannot run: too few tiles for the chip, shallow K, odd N
+    assert _plan(lib, 16, 15360, 4864)[0] == 0
+    assert _plan(lib, 2048, 11008, 512)[0] == 0
+    assert _plan(lib, 2048, 11007, 3840)[0] == 0
+    assert _plan(lib, 2048, 11008, 3840, cus=0)[0] == -1
+    assert _plan(lib, 2048, 11008, 3841)[0] == -1
+    fn = lib.quik_debug_gemm_plan
+    assert fn(2048, 11008, 3840, 256, None) == -2
+    assert lib.quik_debug_set_gemm_path(3) == -1 and lib.quik_debug_set_gemm_path(-1) == -1
+    assert lib.quik_debug_set_gemm_path(1) == 0 and lib.quik_debug_set_gemm_path(0) == 0
+
+
 def test_fp6_sizes_and_bad_arguments(lib):
     vp, i = C.c_void_p, C.c_int
     lib.quik_workspace_bytes_fp6.restype = C.c_size_t

@@ -320,6 +320,160 @@ def test_full_size_workloads(api, oracle, name):
         assert np.array_equal(got, ref.acc), f"{int((got != ref.acc).sum())} accumulators differ (side data)"
 
 
+@pytest.fixture
+def persistent_path(api):
+    """Routes every 4-bit shape the persistent kernel can run to it (by itself the library picks it only
+    where it is estimated to be faster, which leaves out the small shapes an oracle can check)."""
+    api.quik_debug_set_gemm_path(1)
+    yield
+    api.quik_debug_set_gemm_path(0)
+
+
+# Shapes the persistent 4-bit kernel can run (at least one 256-row tile per CU, K_b >= 1024): ragged in
+# T and N, a packed row that is not a multiple of 16 bytes (the last 16-byte piece of a weight row ends
+# in pad bytes), odd and even numbers of K stages, a last partial K stage, many narrow tiles.
+STREAM_INT_SHAPES = [(1030, 9990, 1064), (2304, 5440, 2048), (600, 22016, 1320), (513, 16384, 1024)]
+
+
+@pytest.mark.parametrize("widening", ["plain", "corrected"])
+@pytest.mark.parametrize("T,N,K_b", STREAM_INT_SHAPES)
+def test_persistent_kernel_accumulators_are_bit_exact(api, oracle, persistent_path, T, N, K_b, widening):
+    """INT32 accumulators of the persistent kernel, both operand widenings, weight pad bytes 0xFF; the
+    oracle runs on one random row of every 32-row block and on the first and last row."""
+    import torch
+    rng = np.random.default_rng(T + 3 * N + 5 * K_b)
+    q = rng.integers(-8, 8, size=(T, K_b)).astype(np.int8)
+    w = rng.integers(-8, 8, size=(N, K_b)).astype(np.int8)
+    q[0, :] = -8
+    w[0, :] = -8
+    q[T - 1, :] = 7
+    w[N - 1, :] = -8
+    assert api.quik_debug_gemm_plan(T, N, K_b, 256) is not None
+    ld = api.quik_packed_row_bytes(K_b, 4) + 16          # a stride larger than the padded row, too
+    xq = to_dev(expected_xq(oracle, q, 4, ld))
+    wp = np.full((N, ld), 0xFF, np.uint8)
+    wp[:, : K_b // 2] = oracle.pack(w, 4)
+    wpd = to_dev(wp)
+    side = w_red = None
+    if widening == "corrected":
+        w_red = api.quik_weight_reduce(wpd, to_dev(np.ones(N, np.float16)), K_b, 4)
+        side = to_dev(q[:, 0::2].astype(np.int32).sum(axis=1).astype(np.int32)).view(torch.uint8)
+    acc = api.quik_debug_int_gemm(xq, wpd, K_b, 4, workspace=side, w_reduced=w_red)
+    _sync()
+    sel = _sampled_rows(T, N)
+    got = acc[torch.from_numpy(sel).cuda()].cpu().numpy()
+    want = oracle.int_gemm(q[sel], w, 4)
+    assert np.array_equal(got, want), f"{int((got != want).sum())} accumulators differ"
+
+
+STREAM_LINEAR_SHAPES = [
+    # (shape, bias, extra columns of the output buffer's row stride)
+    (synth.LayerShape("stream_ragged_partial_fp_stage", 1030, 1104, 9990, 40, 4, seed=81), False, 0),
+    (synth.LayerShape("stream_no_outliers_bias", 2304, 2048, 5440, 0, 4, seed=82), True, 0),
+    (synth.LayerShape("stream_scalar_stores", 600, 1448, 22016, 128, 4, seed=83), True, 3),
+    (synth.LayerShape("stream_padded_rows", 520, 1288, 16390, 256, 4, seed=84), False, 10),
+]
+
+
+@pytest.mark.parametrize("shp,bias,ld_extra", STREAM_LINEAR_SHAPES, ids=lambda v: getattr(v, "name", str(v)))
+def test_persistent_kernel_output_matches_oracle(api, oracle, persistent_path, shp, bias, ld_extra):
+    """Fused output of the persistent kernel on shapes with ragged edges: with and without outlier
+    columns and bias, 16-byte aligned output rows and rows that need element stores; nothing is written
+    beyond column N.  Oracle on sampled rows (tokens are independent)."""
+    import torch
+    assert api.quik_debug_gemm_plan(shp.T, shp.N, shp.K_b, 256) is not None
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    b = np.random.default_rng(shp.seed).standard_normal(shp.N).astype(np.float16) if bias else None
+    ybig = torch.full((shp.T, shp.N + ld_extra), -3.0, dtype=torch.float16, device="cuda")
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, 4)
+    api.quik_linear(d["x"], d["idx"], 4, d["w_q"], d["w_scale"], w_red, d["w_out"],
+                    bias=to_dev(b) if bias else None, out=ybig[:, : shp.N])
+    _sync()
+    sel = _sampled_rows(shp.T, shp.seed)
+    ref = oracle.linear(inp.x[sel], inp.outlier_idx, 4, inp.w_packed, inp.w_scale, inp.w_out, bias=b)
+    yh = ybig[torch.from_numpy(sel).cuda()].cpu().numpy()
+    ok, worst = output_within_tolerance(yh[:, : shp.N], ref.y)
+    assert ok, f"fp16 output outside 5e-3 (worst error / tolerance = {worst:.2f})"
+    assert worst > 0
+    if ld_extra:
+        assert bool((ybig[:, shp.N:] == -3.0).all())
+
+
+CANARY_SHAPES = [
+    synth.LayerShape("canary_small_t", 20, 1024, 200, 64, 4, seed=91),        # K-split kernel
+    synth.LayerShape("canary_tiles", 300, 1096, 333, 32, 4, seed=92),         # per-tile kernel, ragged everything
+    synth.LayerShape("canary_w8a8", 130, 1000, 140, 24, 8, seed=93),
+    synth.LayerShape("canary_persistent", 1030, 1104, 9990, 40, 4, seed=94),  # persistent kernel
+]
+
+
+@pytest.mark.parametrize("shp", CANARY_SHAPES, ids=lambda s: s.name)
+def test_nothing_is_written_outside_the_documented_extents(api, oracle, persistent_path, shp):
+    """Every output buffer sits inside a larger one filled with a canary byte: rows before the first and
+    after the last, columns beyond the logical width (where the row stride is the caller's), the bytes
+    behind scale / zero / the quantization workspace / the layer workspace must come back untouched.
+    (Inside a row of xq the bytes up to the stride are documented to be written: zeros.)"""
+    import torch
+    CAN = 0xA5
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    T, K, N, n_out, bits = shp.T, shp.K, shp.N, shp.n_out, shp.bits
+    ldq = api.quik_packed_row_bytes(shp.K_b, bits)
+
+    def canary(nbytes):
+        return torch.full((nbytes,), CAN, dtype=torch.uint8, device="cuda")
+
+    def untouched(t):
+        return bool((t == CAN).all())
+
+    # ---- quik_quantize
+    xq_buf = canary((T + 2) * (ldq + 16)).view(T + 2, ldq + 16)
+    sc_buf, ze_buf = canary((T + 32) * 4), canary((T + 32) * 4)
+    xo_buf = canary((T + 2) * (n_out + 8) * 2).view(torch.float16).view(T + 2, n_out + 8)
+    qws = api.quik_quantize_workspace_bytes(T, bits)
+    side_buf = canary(qws + 256)
+    out = (xq_buf[1: T + 1], sc_buf[64: 64 + 4 * T].view(torch.float32), ze_buf[64: 64 + 4 * T].view(torch.float32),
+           xo_buf[1: T + 1, :n_out], side_buf[:qws])
+    xq, scale, zero, x_out, side = api.quik_quantize(d["x"], d["idx"], bits, out=out)
+    _sync()
+    q, s_, z_, xo = oracle.quantize(inp.x, inp.outlier_idx, bits)
+    assert np.array_equal(xq[:, :ldq].cpu().numpy(), expected_xq(oracle, q, bits, ldq))
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), s_.view(np.uint32))
+    assert np.array_equal(x_out.cpu().numpy().view(np.uint16), xo.view(np.uint16))
+    assert untouched(xq_buf[0]) and untouched(xq_buf[T + 1]), "xq: rows outside [0, T)"
+    assert untouched(sc_buf[:64]) and untouched(sc_buf[64 + 4 * T:]), "scale"
+    assert untouched(ze_buf[:64]) and untouched(ze_buf[64 + 4 * T:]), "zero"
+    xo_bytes = xo_buf.view(torch.uint8).view(T + 2, (n_out + 8) * 2)
+    assert untouched(xo_bytes[0]) and untouched(xo_bytes[T + 1]) and untouched(xo_bytes[:, n_out * 2:]), "x_out"
+    assert untouched(side_buf[qws:]), "quantization workspace"
+
+    # ---- quik_gemm_dequant on those outputs, y inside a larger buffer
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, bits)
+    y_buf = canary((T + 2) * (N + 8) * 2).view(torch.float16).view(T + 2, N + 8)
+    api.quik_gemm_dequant(xq, scale, zero, x_out if n_out else None, shp.K_b, bits, d["w_q"], d["w_scale"], w_red,
+                          d["w_out"], out=y_buf[1: T + 1, :N], workspace=side)
+    _sync()
+    ref = oracle.linear(inp.x, inp.outlier_idx, bits, inp.w_packed, inp.w_scale, inp.w_out)
+    ok, worst = output_within_tolerance(y_buf[1: T + 1, :N].cpu().numpy(), ref.y)
+    assert ok, worst
+    y_bytes = y_buf.view(torch.uint8).view(T + 2, (N + 8) * 2)
+    assert untouched(y_bytes[0]) and untouched(y_bytes[T + 1]) and untouched(y_bytes[:, N * 2:]), "y"
+
+    # ---- quik_linear with a workspace of exactly the reported size
+    need = api.quik_workspace_bytes(T, K, N, n_out, bits)
+    ws_buf = canary(need + 512)
+    y_buf = canary((T + 2) * (N + 8) * 2).view(torch.float16).view(T + 2, N + 8)
+    api.quik_linear(d["x"], d["idx"], bits, d["w_q"], d["w_scale"], w_red, d["w_out"], out=y_buf[1: T + 1, :N],
+                    workspace=ws_buf[:need])
+    _sync()
+    ok, worst = output_within_tolerance(y_buf[1: T + 1, :N].cpu().numpy(), ref.y)
+    assert ok, worst
+    y_bytes = y_buf.view(torch.uint8).view(T + 2, (N + 8) * 2)
+    assert untouched(y_bytes[0]) and untouched(y_bytes[T + 1]) and untouched(y_bytes[:, N * 2:]), "y (quik_linear)"
+    assert untouched(ws_buf[need:]), "layer workspace"
+
+
 def test_prepared_call_matches_direct_call(api, oracle):
     """The marshal-once form of quik_linear enqueues exactly the same work."""
     shp = synth.LayerShape("prepared", 90, 1024, 200, 64, 4, seed=47)
