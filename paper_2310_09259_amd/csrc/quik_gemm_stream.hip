@@ -249,28 +249,26 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
     };
 
     // Raw fragments of two sub-steps (32 packed bytes of every row = 64 columns each; words 0, 1 of a
-    // fragment feed the first half of a sub-step, words 2, 3 the second) and the widened operands: the
-    // activation operands of both halves, and two weight operands that take turns -- a weight fragment is
-    // widened while the two MFMAs of the fragment before it issue.
+    // fragment feed the first half of a sub-step, words 2, 3 the second) and two sets of widened operands:
+    // while the MFMAs of a sub-step read one set, the next sub-step's raw words are widened into the other,
+    // a word or two per MFMA slot, so no MFMA ever waits for an operand made just before it.
     uint4 R[2][TM + TNX];
-    v4i Aop[2][TM], Bop[2];
+    v4i U[2][TM + TNX][2];
     auto read_frag = [&](int set, int f, int ks) QUIK_INLINE {
         const uint32_t off = (f < TM) ? rdA[ks] + (uint32_t)(f * 4096) : rdB[ks] + (uint32_t)((f - TM) * 4096);
         R[set][f] = *reinterpret_cast<const uint4*>(lds + off);
     };
-    // words 2 * half, 2 * half + 1 of fragment f of raw set `rset`, widened into `dst`
-    auto widen_pair = [&](v4i& dst, int rset, int f, int half) QUIK_INLINE {
+    // word w (fragment w / 4, word w % 4) of raw set `rset`, widened into operand set `set`
+    auto widen_word = [&](int set, int rset, int w) QUIK_INLINE {
         constexpr uint32_t M = 0xF0F0F0F0u;
-        const bool act = f < TM;                         // activations: even k in the high nibble
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const uint32_t x = half == 0 ? (kk == 0 ? R[rset][f].x : R[rset][f].y) : (kk == 0 ? R[rset][f].z : R[rset][f].w);
-            const uint32_t hi = x & M;                   // 16 * signed high nibble
-            const uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)   // low nibble + 8
-                                     : ((x << 4) & M);                     // 16 * signed low nibble
-            dst[kk * 2] = (int)(act ? hi : lo);
-            dst[kk * 2 + 1] = (int)(act ? lo : hi);
-        }
+        const int f = w >> 2, k = w & 3;
+        const bool act = f < TM;                             // activations: even k in the high nibble
+        const uint32_t x = (k == 0) ? R[rset][f].x : (k == 1) ? R[rset][f].y : (k == 2) ? R[rset][f].z : R[rset][f].w;
+        const uint32_t hi = x & M;                           // 16 * signed high nibble
+        const uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)   // low nibble + 8
+                                 : ((x << 4) & M);                     // 16 * signed low nibble
+        U[set][f][k >> 1][(k & 1) * 2] = (int)(act ? hi : lo);
+        U[set][f][k >> 1][(k & 1) * 2 + 1] = (int)(act ? lo : hi);
     };
     // a tile's first two sub-steps' fragments (its stage 0, in ring slot `slot`), and the operands its
     // first half sub-step starts with
@@ -281,8 +279,7 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
 #pragma unroll
             for (int f = 0; f < TM + TNX; ++f) read_frag(q, f, q);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) widen_pair(Aop[0][i], 0, i, 0);
-        widen_pair(Bop[0], 0, TM, 0);
+        for (int w = 0; w < (TM + TNX) * 4; ++w) widen_word(0, 0, w);
     };
 
     int cur_t0 = 0, cur_n0 = 0, cur_nc = 0, cur_w = 0, nxt_t0 = 0, nxt_n0 = 0, nxt_nc = 0, nxt_w = 0;
@@ -332,7 +329,7 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
             constexpr int TNA = decltype(tna_c)::value;
             constexpr int NFA = TM + TNA;
             constexpr int MH = TM * TNA;                              // MFMAs per half sub-step
-            static_assert(2 * MH >= LPS && MH >= NFA && TNA >= TM, "copy, read and widening work is spread over the MFMA slots");
+            static_assert(2 * MH >= LPS && 2 * MH >= NFA, "copy, read and widening work is spread over the MFMA slots");
 
             v16i acc[TM][TNA];
 #pragma unroll
@@ -343,14 +340,12 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                     for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
             // One integer stage (stage s of the tile, in ring slot `slot`).  The refill of the slot it frees
-            // is spread over the MFMA slots after the barrier.  A half sub-step issues its MFMAs weight
-            // fragment by weight fragment (two MFMAs each); meanwhile the next weight fragment (in the order
-            // j0h0, j1h0, .., j0h1, .., then the next sub-step's) is widened into the weight operand not in
-            // use, the activation operands of the other half are widened, and, in the second half, the raw
-            // registers that are done are refilled from LDS with the fragments of the sub-step after the
-            // next -- which, in the last two sub-steps, belongs to the next stage in the other slot (after
-            // the last integer stage that is an fp16 stage, or the next tile: its fragments are simply not
-            // used as integers).
+            // is spread over the MFMA slots after the barrier.  A sub-step issues its MFMAs from one operand
+            // set; meanwhile the next sub-step's raw fragments are widened into the other set and the raw
+            // registers of this sub-step (widened during the one before) are refilled from LDS with the
+            // fragments of the sub-step after the next -- which, in the last two sub-steps, belongs to the
+            // next stage in the other slot (after the last integer stage that is an fp16 stage, or the next
+            // tile: its fragments are simply not used as integers).
             auto int_stage = [&](int s, int slot) QUIK_INLINE {
 #pragma unroll
                 for (int ks = 0; ks < KSUB; ++ks) {
@@ -369,23 +364,14 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
 #pragma unroll
                     for (int hm = 0; hm < 2 * MH; ++hm) {
                         const int h = hm / MH, m = hm % MH, j = m / TM, i = m % TM;
-                        const int seq = h * TNA + j;                  // this weight fragment's place in the sub-step
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Aop[h][i], Bop[seq & 1], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(U[par][i][h], U[par][TM + j][h], acc[i][j], 0, 0, 0);
                         if (ks == 2 && hm < LPS) issue_copy(rf, slot, hm);
-                        if (i == 0) {
-                            // the weight fragment after this one
-                            const int nseq = seq + 1;
-                            if (nseq < 2 * TNA) widen_pair(Bop[nseq & 1], par, TM + nseq % TNA, nseq / TNA);
-                            else widen_pair(Bop[0], par ^ 1, TM, 0);
-                        } else if (j < TM) {
-                            // activation fragment j of the other half: this sub-step's second half, or the next
-                            // sub-step's first
-                            if (h == 0) widen_pair(Aop[1][j], par, j, 1);
-                            else widen_pair(Aop[0][j], par ^ 1, j, 0);
-                        }
-                        // second half: every raw register of this sub-step has been widened by the time its
-                        // turn comes here (activations in the first half, weight fragment j at MFMA 2 j - 2)
-                        if (h == 1 && m < NFA) read_frag(par, m, tks);
+                        // the next sub-step's operands, a word or two per MFMA slot
+#pragma unroll
+                        for (int w = 0; w < NFA * 4; ++w)
+                            if (w * (2 * MH) / (NFA * 4) == hm) widen_word(par ^ 1, par ^ 1, w);
+                        // this sub-step's raw registers were widened during the sub-step before
+                        if (hm < NFA) read_frag(par, hm, tks);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
