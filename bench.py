@@ -26,8 +26,10 @@ PEAK_SP24_TOPS = 10000.0     # 2:4-sparse int8 matrix rate counted in dense-equi
                              # dense int8 figure (the sparse instruction does a 64-column step in the time
                              # of a dense 32-column one)
 PEAK_HBM_GBS = 8000.0
-# profiles/gemm_kernel_llama7b_up.md: (47796 KiB * 2.0 + 44033 KiB * 1.0) * 1024
-TRAFFIC_BYTES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
+# profiles/gemm_stream_kernel_llama7b_up.md: (53394 KiB * 2.0 + 45640 KiB * 1.0) * 1024 for the persistent kernel;
+# (47796 KiB * 2.0 + 44033 KiB * 1.0) * 1024 for the per-tile kernel (--gemm-path tiles)
+TRAFFIC_BYTES = {"llama7b_up": int((53394 * 2.0 + 45640) * 1024)}
+TRAFFIC_BYTES_TILES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
 # profiles/gemm_sp24_kernel_llama7b_up.md: the sparse GEMM, same factors
 TRAFFIC_BYTES_SP24 = {"llama7b_up": int((47721 * 2.0 + 44034) * 1024)}
 
@@ -210,6 +212,9 @@ def main():
     ap.add_argument("--only", choices=["layer", "gemm", "quantize", "gemm_fp6", "gemm_sp24", "copy"], default=None,
                     help="launch just this kernel (or the two of the layer) --steps times after --warmup "
                          "launches and exit: a short command line for rocprofv3 counter runs")
+    ap.add_argument("--gemm-path", choices=["auto", "persistent", "tiles"], default="auto",
+                    help="4-bit GEMM kernel family: the library's own choice (default), the persistent kernel "
+                         "wherever it can run, or the per-tile kernels only (for profiles of either one)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (a kernel of known "
                          "traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
@@ -225,6 +230,7 @@ def main():
     from paper_2310_09259_amd import api, synth
 
     api.load()                      # fails loudly if the HIP library is missing
+    api.quik_debug_set_gemm_path({"auto": 0, "persistent": 1, "tiles": 2}[args.gemm_path])
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     shp = synth.CONFIGS[args.workload]
@@ -404,14 +410,28 @@ def main():
                 "weight_bytes_per_element": 0.5, "activation_bytes_per_element": 0.5}
         del w24, ws24, q24, w_qs, inp_s
 
-    ms_fp16 = None
+    ms_fp16 = ms_lib_int8 = None
     if not args.no_fp16:
         wf = (torch.randn((N, K), device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
         ms_fp16 = _kernel_ms(lambda: torch.nn.functional.linear(x, wf), torch, it)
         del wf
+        # context for the roofline fraction: the vendor library's plain int8 GEMM (operands already one
+        # byte per value, no widening, no epilogue, no outlier product) on the integer part's shape
+        try:
+            ai = torch.randint(-8, 8, (T, K_b), dtype=torch.int8, device=dev)
+            wi = torch.randint(-8, 8, (N, K_b), dtype=torch.int8, device=dev)
+            ms_lib_int8 = _kernel_ms(lambda: torch._int_mm(ai, wi.t()), torch, it)
+            del ai, wi
+        except Exception:                                    # shapes the library call does not take
+            ms_lib_int8 = None
 
     ops_layer = 2.0 * T * K * N
     ops_int = 2.0 * T * K_b * N
+    # which kernel family the library picks for this shape (host logic of the library, asked through the ABI)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    plan = api.quik_debug_gemm_plan(T, N, K_b, cus) if (bits == 4 and not mixed) else None
+    persistent = plan is not None and args.gemm_path != "tiles" and (plan[0] == 1 or args.gemm_path == "persistent")
+    gemm_kernel_name = "gemm_stream_kernel" if persistent else "gemm_kernel"
     tops = ops_layer / (ms_step * 1e-3) / 1e12
     gemm_tops = ops_int / (ms_gemm * 1e-3) / 1e12
     out = {
@@ -427,6 +447,9 @@ def main():
         "frac_int8_mfma_peak_layer": tops / PEAK_INT8_TOPS,
         "speedup_vs_fp16_gemm": (ms_fp16 / ms_step) if ms_fp16 else None,
         "fp16_gemm_ms": ms_fp16,
+        "library_int8_gemm": None if ms_lib_int8 is None else {
+            "ms": ms_lib_int8, "frac_int8_mfma_peak": ops_int / (ms_lib_int8 * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+            "what": "torch._int_mm (hipBLASLt) on [T, K_b] x [K_b, N] int8: context, not part of the path"},
         "kernels_ms": {"quik_quantize": ms_quant, "quik_gemm_dequant": ms_gemm,
                        "quik_linear_events": ms_layer_ev},
         "fusion_ablation_ms": None if no_ablation else {
@@ -446,14 +469,14 @@ def main():
                            "what": "quik_debug_mfma_probe (independent 32x32x32 int8 matrix instructions, "
                                    "register-resident) and quik_debug_copy_probe (512 MiB streaming copy, "
                                    "read + write bytes)"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel (INT GEMM + dequant + outlier GEMM)",
+        "roofline": {"bound": "mfma", "kernel": gemm_kernel_name + " (INT GEMM + dequant + outlier GEMM)",
                      "achieved": gemm_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": gemm_tops / PEAK_INT8_TOPS,
                      "frac_of_measured_mfma_peak": gemm_tops / measured_mfma_tops,
                      # HBM-side bytes per launch from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
                      # (factors from a 256 MiB copy; see profiles/), measured for the default
                      # workload only
-                     "traffic": TRAFFIC_BYTES.get(args.workload),
+                     "traffic": (TRAFFIC_BYTES if persistent else TRAFFIC_BYTES_TILES).get(args.workload),
                      "algorithmic_ops_per_launch": ops_int},
     }
     if fp6 is not None:
