@@ -17,6 +17,16 @@ LIB = os.path.join(HERE, "libquik_oracle.so")
 
 FLAGS = ["-O3", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
          "-fno-fast-math", "-Wall", "-Wextra"]
+# QUIK_ORACLE_SANITIZE=1: an AddressSanitizer + UndefinedBehaviorSanitizer build under another name, for
+#   QUIK_ORACLE_SANITIZE=1 ASAN_OPTIONS=detect_leaks=0 \
+#   LD_PRELOAD="$(gcc -print-file-name=libasan.so) $(gcc -print-file-name=libubsan.so)" \
+#   python -m pytest tests/test_oracle_pins.py -m "not gpu"
+# (same arithmetic flags; -O1 so that reports name source lines)
+SANITIZE = os.environ.get("QUIK_ORACLE_SANITIZE") == "1"
+if SANITIZE:
+    FLAGS = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+             *[f for f in FLAGS if f != "-O3"]]
+    LIB = os.path.join(HERE, "libquik_oracle_san.so")
 
 
 def build(force: bool = True) -> str:
