@@ -885,7 +885,7 @@ hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
     // at least one tile per CU to pay off; otherwise 128 x 128 tiles with two workgroups per CU.
     const long big_tiles = (long)((a.T + 255) / 256) * ((a.N + 127) / 128);
     if (big_tiles < 256) return launch_cfg<BITS, WBITS, 128, 128, 2, 2, 128, 2, 2, 8, MODE>(a, stream);
-    if constexpr (MODE == 0 && BITS == WBITS) {
+    if constexpr (BITS == WBITS) {   // every MODE: the accumulator hook runs the tiles of the fused call
         // One workgroup per CU, so a launch runs in ceil(tiles / 256) rounds.  Tiles of 1.5x the area
         // (64 x 96 or 96 x 64 per wave: 17 % fewer LDS fragment reads and widening operations per
         // MFMA, a third fewer per-tile prologues and epilogues) take 1.42x as long per round

@@ -117,6 +117,9 @@ INT_GEMM_SHAPES = [
     (16, 512, 480, 8), (150, 140, 1000, 8), (257, 129, 4864, 8),
     # enough 256 x 128 tiles to take the eight-wave configuration, ragged in T and N, K tail
     (520, 11000, 480, 4), (770, 5500, 224, 8),
+    # the 1.5x-area tiles (256 x 192 for the shape above, 192 x 256 for this one): the accumulator hook
+    # takes the tile choice of the fused call in every mode
+    (576, 16640, 224, 4),
     # small-T paths: K-split kernel (T <= 32; K shorter than four stages, ragged N), 64 x 64 and
     # 128 x 64 tile configurations
     (32, 100, 160, 4), (7, 333, 2432, 4), (20, 95, 4864, 8), (50, 200, 992, 4), (64, 130, 480, 8),
@@ -634,3 +637,45 @@ def test_random_shapes_match_oracle(api, oracle, seed):
     assert np.array_equal(acc.cpu().numpy(), ref.acc), what
     ok, worst = output_within_tolerance(y.cpu().numpy(), ref.y)
     assert ok, f"{what}: output outside 5e-3 ({worst:.2f}x)"
+
+
+# Kernel forms that run more than one workgroup per CU (the forms in which a register allocation that ends
+# on a partial share of the SIMD's file has produced wrong bytes now and then): every one of them many times
+# in a row on shapes with several workgroups per CU; the first result is checked against the oracle, every
+# later one must equal it bit for bit.
+REPEAT_SHAPES = [
+    synth.LayerShape("rep_64x64", 60, 1024, 3000, 64, 4, seed=101),           # 64 x 64 tiles, deep ring
+    synth.LayerShape("rep_128x64", 120, 1024, 3000, 64, 4, seed=102),         # 128 x 64 tiles
+    synth.LayerShape("rep_128x128", 700, 1024, 2900, 64, 4, seed=103),        # 128 x 128 tiles, two per CU
+    synth.LayerShape("rep_128x128_w8a8", 700, 1024, 2900, 64, 8, seed=104),
+    synth.LayerShape("rep_ksplit", 24, 2048, 4000, 64, 4, seed=105),          # K-split kernel
+]
+
+
+@pytest.mark.parametrize("shp", REPEAT_SHAPES, ids=lambda s: s.name)
+def test_repeated_calls_of_multi_workgroup_forms_are_bit_identical(api, oracle, shp):
+    inp = synth.make_inputs(shp)
+    d = upload(inp)
+    ref = oracle.linear(inp.x, inp.outlier_idx, shp.bits, inp.w_packed, inp.w_scale, inp.w_out)
+    w_red = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
+    first = {}
+    for rep in range(8):
+        got = {"layer": api.quik_linear(d["x"], d["idx"], shp.bits, d["w_q"], d["w_scale"], w_red, d["w_out"])}
+        for version in (1, 2):                                     # the unfused kernels
+            got[f"ablation_v{version}"], _ = api.quik_linear_ablation(version, d["x"], d["idx"], shp.bits, d["w_q"],
+                                                                      d["w_scale"], w_red, d["w_out"])
+        got["w_reduced"] = api.quik_weight_reduce(d["w_q"], d["w_scale"], shp.K_b, shp.bits)
+        if shp.bits == 4:
+            got["w6"] = api.quik_weight_pack_fp6(d["w_q"], shp.K_b)
+            got["xq6"] = api.quik_quantize_fp6(d["x"], d["idx"])[0]
+            got["xq24"] = api.quik_quantize_sp24(d["x"], d["idx"])[0]
+        _sync()
+        got = {k: v.cpu().numpy().view(np.uint8) for k, v in got.items()}
+        if rep == 0:
+            first = got
+            for name in ("layer", "ablation_v1", "ablation_v2"):
+                ok, worst = output_within_tolerance(got[name].view(np.float16), ref.y)
+                assert ok, (name, worst)
+        else:
+            for k, v in got.items():
+                assert np.array_equal(v, first[k]), f"{k}: call {rep} differs from call 0"
