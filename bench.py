@@ -25,10 +25,11 @@ PEAK_FP6_TOPS = 10100.0      # dense FP6 / FP4 matrix rate, MI355X data sheet (1
 PEAK_SP24_TOPS = 10000.0     # 2:4-sparse int8 matrix rate counted in dense-equivalent operations: twice the
                              # dense int8 figure (the sparse instruction does a 64-column step in the time
                              # of a dense 32-column one)
+PEAK_FP16_TFLOPS = 2500.0   # dense fp16 matrix rate, MI355X data sheet
 PEAK_HBM_GBS = 8000.0
-# profiles/gemm_stream_kernel_llama7b_up.md: (53394 KiB * 2.0 + 45640 KiB * 1.0) * 1024 for the persistent kernel;
+# profiles/gemm_stream_kernel_llama7b_up.md: (46381 KiB * 2.0 + 45498 KiB * 1.0) * 1024 for the persistent kernel;
 # (47796 KiB * 2.0 + 44033 KiB * 1.0) * 1024 for the per-tile kernel (--gemm-path tiles)
-TRAFFIC_BYTES = {"llama7b_up": int((53394 * 2.0 + 45640) * 1024)}
+TRAFFIC_BYTES = {"llama7b_up": int((46381 * 2.0 + 45498) * 1024)}
 TRAFFIC_BYTES_TILES = {"llama7b_up": int((47796 * 2.0 + 44033) * 1024)}
 # profiles/gemm_sp24_kernel_llama7b_up.md: the sparse GEMM, same factors
 TRAFFIC_BYTES_SP24 = {"llama7b_up": int((47721 * 2.0 + 44034) * 1024)}
@@ -473,6 +474,10 @@ def main():
                      "achieved": gemm_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": gemm_tops / PEAK_INT8_TOPS,
                      "frac_of_measured_mfma_peak": gemm_tops / measured_mfma_tops,
+                     # the kernel's two contractions against their own peaks: time at 100 % of the int8 rate for
+                     # the integer part plus time at 100 % of the fp16 rate for the outlier part, over the time taken
+                     "frac_roof_int8_plus_fp16": (ops_int / (PEAK_INT8_TOPS * 1e12) + 2.0 * T * n_out * N / (PEAK_FP16_TFLOPS * 1e12))
+                                                 / (ms_gemm * 1e-3),
                      # HBM-side bytes per launch from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
                      # (factors from a 256 MiB copy; see profiles/), measured for the default
                      # workload only

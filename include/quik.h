@@ -227,6 +227,17 @@ int quik_int_gemm(const void *xq, int ldq, const void *w_q, int ldw,
 int quik_debug_gemm_plan(int T, int N, int K_b, int cus, int *plan);
 
 /*
+ * Test hook (host only): the k-th output tile (k = 0, 1, ...) that resident workgroup
+ * `workgroup` (0 .. plan[4]-1) of the persistent kernel computes for the shape of
+ * quik_debug_gemm_plan: tile[0] = first token row, tile[1] = first output channel,
+ * tile[2] = number of channels (HOST pointer; the tile has 256 token rows, fewer at
+ * the end of T).  Returns 1, or 0 if the workgroup has fewer than k + 1 tiles (tile
+ * untouched), or QUIK_EINVAL (also when the persistent kernel cannot run the shape) /
+ * QUIK_ENULL.
+ */
+int quik_debug_gemm_tile(int T, int N, int K_b, int cus, int workgroup, int k, int *tile);
+
+/*
  * Test hook: which kernel family the 4-bit GEMM entry points use from now on, in
  * this process: 0 = automatic (the default), 1 = the persistent kernel wherever
  * quik_debug_gemm_plan returns 1 or 2, 2 = the per-tile kernels always.  Results

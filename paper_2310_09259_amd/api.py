@@ -44,6 +44,8 @@ def load() -> C.CDLL:
         lib.quik_workspace_regions.argtypes = [i, i, i, i, i, vp, vp]
         lib.quik_debug_gemm_plan.restype = i
         lib.quik_debug_gemm_plan.argtypes = [i, i, i, i, vp]
+        lib.quik_debug_gemm_tile.restype = i
+        lib.quik_debug_gemm_tile.argtypes = [i, i, i, i, i, i, vp]
         lib.quik_debug_set_gemm_path.restype = i
         lib.quik_debug_set_gemm_path.argtypes = [i]
         lib.quik_quantize_workspace_bytes.restype = C.c_size_t

@@ -133,6 +133,20 @@ int quik_debug_gemm_plan(int T, int N, int K_b, int cus, int* plan) {
     return c;
 }
 
+int quik_debug_gemm_tile(int T, int N, int K_b, int cus, int workgroup, int k, int* tile) {
+    if (T <= 0 || N <= 0 || K_b <= 0 || (K_b & 1) || K_b >= kMaxKb || cus <= 0 || workgroup < 0 || k < 0) return QUIK_EINVAL;
+    if (!tile) return QUIK_ENULL;
+    quik::StreamPlan p;
+    if (quik::choose_gemm_stream(T, N, K_b, cus, &p) == 0 || workgroup >= p.grid) return QUIK_EINVAL;
+    int nt, m, b0, w;
+    if (!quik::stream_tile(p, workgroup, k, &nt, &m)) return 0;
+    quik::stream_panel(p, nt, &b0, &w);
+    tile[0] = m * quik::kStreamRows;
+    tile[1] = b0 * 32;
+    tile[2] = (w * 32 < N - b0 * 32) ? w * 32 : N - b0 * 32;
+    return 1;
+}
+
 int quik_debug_set_gemm_path(int mode) {
     if (mode < 0 || mode > 2) return QUIK_EINVAL;
     quik::set_gemm_path(mode);

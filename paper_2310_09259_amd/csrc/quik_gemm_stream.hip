@@ -47,7 +47,7 @@ using namespace gemm_dev;
 template <int V> using ic = std::integral_constant<int, V>;
 #define QUIK_INLINE __attribute__((always_inline))
 
-constexpr int BM = 256;                 // token rows per tile
+constexpr int BM = kStreamRows;         // token rows per tile
 constexpr int TNX = 3;                  // most 32-channel blocks per wave
 constexpr int BNX = 2 * TNX * 32;       // widest tile
 constexpr int BKB = 128;                // bytes of every packed row per stage (256 columns)
@@ -117,23 +117,15 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
         return ln;
     };
 
-    // ---- this workgroup's tiles
-    const int xcd = blockIdx.x % kXcds, cu = blockIdx.x / kXcds, per_xcd = gridDim.x / kXcds;
-    const int total = p.tiles_m * p.tn;
-    const int tq = total / kXcds, tr = total % kXcds;
-    const int first = (xcd < tr) ? xcd * (tq + 1) : tr * (tq + 1) + (xcd - tr) * tq;
-    const int count = tq + (xcd < tr ? 1 : 0);
+    // ---- this workgroup's tiles (stream_tile in quik_kernels.h has the order)
     // k-th tile of this workgroup: first token row, first channel, channels that exist, width in blocks
     // (plain scalars on purpose: a struct selected at run time ends up in scratch memory)
     auto geo = [&](int k, int& t0, int& n0, int& ncols, int& w) QUIK_INLINE -> bool {
-        const int local = cu + k * per_xcd;
-        if (local >= count) return false;
-        const int id = first + local;
-        const int nt = id / p.tiles_m, m = id % p.tiles_m;
-        const int lo = (nt * p.rem) / p.tn, hi = ((nt + 1) * p.rem) / p.tn;
+        int nt, m, b0;
+        if (!stream_tile(p, (int)blockIdx.x, k, &nt, &m)) return false;
+        stream_panel(p, nt, &b0, &w);
         t0 = m * BM;
-        n0 = (nt * p.base + lo) * 32;
-        w = p.base + hi - lo;
+        n0 = b0 * 32;
         ncols = min(w * 32, a.N - n0);
         return true;
     };

@@ -65,6 +65,45 @@ struct WeightReduceArgs {
 struct StreamPlan {
     int tiles_m, tn, base, rem, grid;
 };
+constexpr int kStreamRows = 256;       // token rows per tile
+constexpr int kStreamXcds = 8;         // workgroup b runs on XCD b % 8
+
+// The k-th tile of workgroup `block`: channel panel nt (of p.tn) and token panel m (of p.tiles_m), or false
+// if the workgroup has fewer tiles.  The tile list (channel panels outermost, the token panels of a channel
+// panel adjacent) is cut into one contiguous range per XCD.  Plain order inside a range: a round of the
+// XCD's workgroups takes consecutive tiles, i.e. a few channel panels with all their token panels, and
+// every round streams all activations through the XCD's L2 again.  When the range is a whole number of
+// channel panels and of rounds, a round instead takes ALL channel panels of the range with a slice of the
+// token panels (the activations pass through the L2 once per launch, the XCD's smaller share of the
+// weights once per round); from round to round a workgroup moves on by 1/rounds of the range's channel
+// panels, so that it meets the narrower and the wider tiles like in the plain order.
+__host__ __device__ inline bool stream_tile(const StreamPlan& p, int block, int k, int* nt, int* m) {
+    const int xcd = block % kStreamXcds, wg = block / kStreamXcds, per_xcd = p.grid / kStreamXcds;
+    const int total = p.tiles_m * p.tn;
+    const int tq = total / kStreamXcds, tr = total % kStreamXcds;
+    const int first = (xcd < tr) ? xcd * (tq + 1) : tr * (tq + 1) + (xcd - tr) * tq;
+    const int count = tq + (xcd < tr ? 1 : 0);
+    const int local = wg + k * per_xcd;
+    if (k < 0 || local >= count) return false;
+    const int rounds = (count + per_xcd - 1) / per_xcd;
+    const bool blocked = rounds > 1 && first % p.tiles_m == 0 && count % p.tiles_m == 0 &&
+                         count == rounds * per_xcd && p.tiles_m % rounds == 0 && (count / p.tiles_m) % rounds == 0;
+    if (blocked) {
+        const int m_per_round = p.tiles_m / rounds, panels = count / p.tiles_m;
+        *nt = first / p.tiles_m + (wg / m_per_round + k * (panels / rounds)) % panels;
+        *m = k * m_per_round + wg % m_per_round;
+    } else {
+        *nt = (first + local) / p.tiles_m;
+        *m = (first + local) % p.tiles_m;
+    }
+    return true;
+}
+// first channel block and width (in 32-channel blocks) of channel panel nt
+__host__ __device__ inline void stream_panel(const StreamPlan& p, int nt, int* block0, int* width) {
+    const int lo = (nt * p.rem) / p.tn, hi = ((nt + 1) * p.rem) / p.tn;
+    *block0 = nt * p.base + lo;
+    *width = p.base + hi - lo;
+}
 
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);

@@ -142,22 +142,20 @@ def _plan(lib, T, N, K_b, cus=256):
     return rc, tuple(plan)
 
 
-def _tiles_of_workgroup(plan, b):
-    """Widths (in 32-channel blocks) of the tiles workgroup b walks through: the tile list is cut into
-    eight contiguous ranges (one per XCD, workgroup b belongs to XCD b % 8) and the workgroups of an XCD
-    take its tiles round robin; tile id -> channel panel id / tiles_m, whose width is base or base + 1."""
-    tiles_m, tn, base, rem, grid = plan
-    total, per_xcd = tiles_m * tn, grid // 8
-    x, local = b % 8, b // 8
-    q, r = divmod(total, 8)
-    first = x * (q + 1) if x < r else r * (q + 1) + (x - r) * q
-    count = q + (1 if x < r else 0)
-    out = []
-    while local < count:
-        nt = (first + local) // tiles_m
-        out.append(base + ((nt + 1) * rem) // tn - (nt * rem) // tn)
-        local += per_xcd
-    return out
+def _tiles_of_workgroup(lib, T, N, K_b, b, cus=256):
+    """The tiles (first token row, first channel, channels) workgroup b of the persistent kernel walks through,
+    as the library's own tile order gives them."""
+    fn = lib.quik_debug_gemm_tile
+    fn.argtypes = [C.c_int] * 6 + [C.c_void_p]
+    out, k = [], 0
+    while True:
+        tile = (C.c_int * 3)()
+        rc = fn(T, N, K_b, cus, b, k, C.cast(tile, C.c_void_p))
+        assert rc in (0, 1)
+        if rc == 0:
+            return out
+        out.append(tuple(tile))
+        k += 1
 
 
 def test_persistent_kernel_plan_covers_the_output_and_balances_the_cus(lib):
@@ -171,16 +169,31 @@ def test_persistent_kernel_plan_covers_the_output_and_balances_the_cus(lib):
         assert tiles_m == (T + 255) // 256 and grid == 256
         assert tn * base + rem == nb and 0 <= rem < tn            # the tiles of a panel cover its blocks exactly
         assert 1 <= base and base + (1 if rem else 0) <= 6         # no tile wider than six blocks
-        loads = [sum(_tiles_of_workgroup(plan, b)) for b in range(grid)]
-        assert sum(loads) == tiles_m * nb                          # every tile belongs to exactly one workgroup
+        tiles = [_tiles_of_workgroup(lib, T, N, K_b, b) for b in range(grid)]
+        # every (token panel, channel range) of the output belongs to exactly one workgroup, channel ranges of a
+        # token panel tile [0, N) without gaps, widths are whole blocks of 32 channels (the last one cut at N)
+        flat = sorted(t for ts in tiles for t in ts)
+        assert len(flat) == len(set(flat)) == tiles_m * tn
+        for mp in range(tiles_m):
+            row = [t for t in flat if t[0] == mp * 256]
+            assert len(row) == tn and row[0][1] == 0
+            for a, b2 in zip(row, row[1:]):
+                assert a[1] + a[2] == b2[1] and a[2] % 32 == 0 and base * 32 <= a[2] <= (base + 1) * 32
+            assert row[-1][1] + row[-1][2] == N
+        loads = [sum(-(-t[2] // 32) for t in ts) for ts in tiles]
+        assert sum(loads) == tiles_m * nb                          # every block belongs to exactly one workgroup
         assert min(loads) > 0
         # the busiest CU is within one tile's width of the ideal share (the old fixed 256 x 192 tiling of
         # the first shape gave 12 blocks to most CUs for an ideal of 10.75)
         assert max(loads) <= -(-tiles_m * nb // grid) + 6
     # the headline shape is where fixed tiles waste most (464 tiles of 256 x 192 on 256 CUs = 12 blocks for the
-    # busiest CU): the persistent kernel is the automatic choice and gives no CU more than 11
+    # busiest CU): the persistent kernel is the automatic choice and gives no CU more than 11; an XCD's
+    # workgroups take all of its eight channel panels with four of the eight token panels per round
     rc, plan = _plan(lib, 2048, 11008, 3840)
-    assert rc == 1 and max(sum(_tiles_of_workgroup(plan, b)) for b in range(256)) == 11
+    per_wg = [_tiles_of_workgroup(lib, 2048, 11008, 3840, b) for b in range(256)]
+    assert rc == 1 and max(sum(-(-t[2] // 32) for t in ts) for ts in per_wg) == 11
+    first_round_xcd0 = [per_wg[b][0] for b in range(0, 256, 8)]
+    assert len({t[1] for t in first_round_xcd0}) == 8 and {t[0] for t in first_round_xcd0} == {0, 256, 512, 768}
     # one 256 x 128 tile per CU already balances the down-projection; few K stages per tile: per-tile kernels
     assert _plan(lib, 2048, 4096, 10752)[0] == 2 and _plan(lib, 1030, 9990, 1064)[0] == 2
     # shapes the persistent kernel cannot run: too few tiles for the chip, shallow K, odd N
