@@ -604,8 +604,7 @@ bool plan_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p) {
         const long tiles = (long)tiles_m * tn;
         const long r = (tiles + cus - 1) / cus;         // tiles of the busiest CU
         const double blocks = (double)(r * base + (r * rem + tn - 1) / tn);
-        // (last term: among equal estimates, the tile count that leaves the fewest CUs without a tile in
-        // the last round)
+        // (last term: among equal estimates, the tile count that leaves the fewest CUs one tile short)
         const double cost = blocks + 0.35 * (double)r + 1e-3 * (double)(r * cus - tiles) / (double)cus;
         if (cost < best - 1e-9) { best = cost; best_tn = tn; }
     }
