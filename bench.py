@@ -186,6 +186,41 @@ def run_only(args, api, torch, shp, x, idx, w_q, w_scale, w_red, w_out, y, ws, s
     print(json.dumps({"only": args.only, "workload": shp.name, "launches": args.steps, "ms_per_launch": ms}))
 
 
+def run_mix_probe(api, torch):
+    """What each kind of instruction of the 4-bit GEMM's K loop costs the matrix pipe: the probe's rate for
+    the matrix instruction alone and with vector operations, LDS reads, global -> LDS copies and barriers
+    added at the K loop's counts, and the clock the chip held under each load."""
+    dev = torch.device("cuda:0")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    src = torch.randint(0, 255, (32 << 20,), dtype=torch.uint8, device=dev)
+    clocks = torch.zeros(2, dtype=torch.int64, device=dev)
+    iters = 4000
+    names = {1: "changing random operands", 2: "4 vector ops per MFMA", 4: "5 LDS reads per 12 MFMAs",
+             8: "2 copies per 12 MFMAs", 16: "barrier per 48 MFMAs"}
+    rows = []
+    base = None
+    _preheat(lambda: api.quik_debug_mix_probe(0, cus, iters, sink), torch)
+    for mix in (0, 1, 3, 5, 9, 17, 7, 11, 13, 15, 31):
+        call = lambda: api.quik_debug_mix_probe(mix, cus, iters, sink, src if mix & 8 else None, clocks)
+        ops = call()
+        ms = _kernel_ms(call, torch, 30)
+        torch.cuda.synchronize()
+        ck = clocks.cpu().numpy()
+        tops = ops / (ms * 1e-3) / 1e12
+        if base is None:
+            base = tops
+        rows.append({"mix": mix, "what": "MFMA alone, constant operands (small values)" if mix == 0 else
+                     " + ".join(n for b, n in names.items() if mix & b),
+                     "TOPS": tops, "frac_of_5_POPS": tops / PEAK_INT8_TOPS, "time_vs_first_row": base / tops,
+                     "ns_per_mfma_per_simd": ms * 1e6 / (iters * 12 * 2),
+                     # the shader clock held during the loop of wave 0 of workgroup 0: ticks of s_memtime per tick of
+                     # the 100 MHz s_memrealtime over the same interval
+                     "clock_MHz": 100.0 * float(ck[0]) / float(ck[1]) if ck[1] else None})
+    print(json.dumps({"probe": "quik_debug_mix_probe", "workgroups": cus, "waves_per_workgroup": 8,
+                      "mfma_per_iteration": 12, "iterations": iters, "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -216,6 +251,9 @@ def main():
     ap.add_argument("--gemm-path", choices=["auto", "persistent", "tiles"], default="auto",
                     help="4-bit GEMM kernel family: the library's own choice (default), the persistent kernel "
                          "wherever it can run, or the per-tile kernels only (for profiles of either one)")
+    ap.add_argument("--mix-probe", action="store_true",
+                    help="instead of the layer: the K loop's instruction mix around the int8 matrix instruction, "
+                         "one ingredient at a time (quik_debug_mix_probe); one JSON line with a row per mix")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (a kernel of known "
                          "traffic, to scale the FETCH_SIZE / WRITE_SIZE counters of a --pmc run)")
@@ -232,6 +270,9 @@ def main():
 
     api.load()                      # fails loudly if the HIP library is missing
     api.quik_debug_set_gemm_path({"auto": 0, "persistent": 1, "tiles": 2}[args.gemm_path])
+    if args.mix_probe:
+        run_mix_probe(api, torch)
+        return
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     shp = synth.CONFIGS[args.workload]

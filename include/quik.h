@@ -453,6 +453,26 @@ int quik_debug_mfma_probe(int workgroups, int iters, int32_t *sink, void *stream
 int quik_debug_copy_probe(const void *src, void *dst, size_t bytes, void *stream);
 
 /*
+ * Measurement probe: the instruction mix of the 4-bit GEMM's K loop around the int8 matrix
+ * instruction, one ingredient at a time and free of data dependences, to show what each kind of
+ * instruction costs the matrix pipe.  `workgroups` workgroups of eight waves (one per CU on a 256-CU
+ * chip with workgroups = 256); every wave issues 12 * iters matrix instructions
+ * (2 * 32 * 32 * 32 * 12 * 8 * workgroups * iters integer operations) plus, per bit of `mix`:
+ *   1  operands of pseudo-random bytes that change from one matrix instruction to the next (else
+ *      constant operands of small values, most bytes zero)
+ *   2  four vector bit operations per matrix instruction
+ *   4  five 16-byte-per-lane LDS reads per 12 matrix instructions
+ *   8  two global -> LDS copies of 16 bytes per lane per 12 matrix instructions, out of `src`
+ *      (DEVICE, 16-byte aligned, src_bytes >= 16 MiB; read only)
+ *  16  a workgroup barrier per 48 matrix instructions
+ * clocks (DEVICE uint64 [2], or NULL): ticks of the s_memtime and of the s_memrealtime counter over
+ * the loop of workgroup 0 (for comparing loads with each other).  `sink` as above.
+ * QUIK_EINVAL for mix outside 0..31 or bad sizes, QUIK_ENULL, QUIK_EALIGN.
+ */
+int quik_debug_mix_probe(int mix, int workgroups, int iters, int32_t *sink, const void *src, size_t src_bytes,
+                         unsigned long long *clocks, void *stream);
+
+/*
  * Host-side validator for an outlier index list (HOST pointer): returns QUIK_OK
  * if all n_out entries are unique and inside [0, K), QUIK_EINVAL otherwise.
  */

@@ -111,6 +111,8 @@ def load() -> C.CDLL:
         lib.quik_linear_fp6.argtypes = [vp, i, i, i, vp, i, vp, vp, f, vp, i, vp, i, vp, i, vp, C.c_size_t, vp]
         lib.quik_debug_mfma_probe.restype = i
         lib.quik_debug_mfma_probe.argtypes = [i, i, vp, vp]
+        lib.quik_debug_mix_probe.restype = i
+        lib.quik_debug_mix_probe.argtypes = [i, i, i, vp, vp, C.c_size_t, vp, vp]
         lib.quik_debug_copy_probe.restype = i
         lib.quik_debug_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
         lib.quik_check_outlier_idx_host.restype = i
@@ -162,6 +164,14 @@ def quik_debug_mfma_probe(workgroups: int, iters: int, sink):
     """Enqueue the int8 matrix-instruction probe; returns the integer operations it performs."""
     _check(load().quik_debug_mfma_probe(workgroups, iters, _ptr(sink), _stream()), "quik_debug_mfma_probe")
     return 2.0 * 32 * 32 * 32 * 16 * workgroups * iters
+
+
+def quik_debug_mix_probe(mix: int, workgroups: int, iters: int, sink, src=None, clocks=None):
+    """Enqueue the K-loop instruction-mix probe (see include/quik.h for the bits of `mix`); returns the
+    integer operations it performs.  clocks: int64 device tensor [2] or None."""
+    _check(load().quik_debug_mix_probe(mix, workgroups, iters, _ptr(sink), _ptr(src), _nbytes(src), _ptr(clocks),
+                                       _stream()), "quik_debug_mix_probe")
+    return 2.0 * 32 * 32 * 32 * 12 * 8 * workgroups * iters
 
 
 def quik_debug_copy_probe(src, dst):

@@ -708,6 +708,21 @@ int quik_debug_mfma_probe(int workgroups, int iters, int32_t* sink, void* stream
                : QUIK_ELAUNCH;
 }
 
+int quik_debug_mix_probe(int mix, int workgroups, int iters, int32_t* sink, const void* src, size_t src_bytes,
+                         unsigned long long* clocks, void* stream) {
+    if (mix < 0 || mix > 31 || workgroups <= 0 || workgroups > 4096 || iters <= 0) return QUIK_EINVAL;
+    if (!sink) return QUIK_ENULL;
+    if (mix & 8) {
+        if (!src) return QUIK_ENULL;
+        if (src_bytes < (size_t(16) << 20)) return QUIK_EINVAL;
+        if (!aligned16(src)) return QUIK_EALIGN;
+    }
+    return quik::launch_mix_probe(mix, workgroups, iters, sink, src, (mix & 8) ? src_bytes : 0, clocks,
+                                  static_cast<hipStream_t>(stream)) == hipSuccess
+               ? QUIK_OK
+               : QUIK_ELAUNCH;
+}
+
 int quik_debug_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
     if (bytes == 0 || bytes % 16) return QUIK_EINVAL;
     if (!src || !dst) return QUIK_ENULL;

@@ -125,6 +125,8 @@ hipError_t launch_weight_pack_sp24(const void* w_q, int ldw, int N, int K_b, voi
 // measurement probes (quik_probe.hip)
 hipError_t launch_mfma_probe(int workgroups, int iters, int* sink, hipStream_t stream);
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t stream);
+hipError_t launch_mix_probe(int mix, int workgroups, int iters, int* sink, const void* src, size_t src_bytes,
+                            unsigned long long* clocks, hipStream_t stream);
 
 // unfused stages (fusion ablation)
 hipError_t launch_unfused_quantize(const QuantizeArgs& a, void* x_base, int ldb, float* row_min,
