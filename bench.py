@@ -376,6 +376,16 @@ def main():
     probe_ops = api.quik_debug_mfma_probe(2048, 2000, sink)
     ms_probe = _kernel_ms(lambda: api.quik_debug_mfma_probe(2048, 2000, sink), torch, 20)
     measured_mfma_tops = probe_ops / (ms_probe * 1e-3) / 1e12
+    # the same instruction on operands of pseudo-random bytes (the chip lowers its clock under them), and with
+    # the K loop's other instructions beside it (vector operations, LDS reads, copies, barriers; no dependences)
+    cus_ = torch.cuda.get_device_properties(0).multi_processor_count
+    mix_src = torch.randint(0, 255, (32 << 20,), dtype=torch.uint8, device=dev)
+    mix_tops = {}
+    for mix in (1, 31):
+        mix_ops = api.quik_debug_mix_probe(mix, cus_, 2000, sink, mix_src if mix & 8 else None)
+        ms_mix = _kernel_ms(lambda: api.quik_debug_mix_probe(mix, cus_, 2000, sink, mix_src if mix & 8 else None), torch, 20)
+        mix_tops[mix] = mix_ops / (ms_mix * 1e-3) / 1e12
+    del mix_src
     src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(1)
     dst = torch.empty_like(src)
     ms_copy = _kernel_ms(lambda: api.quik_debug_copy_probe(src, dst), torch, 20)
@@ -507,14 +517,21 @@ def main():
                                   "frac_of_measured_copy": quant_bytes / (ms_quant_cold * 1e-3) / 1e9 / measured_hbm_gbs,
                                   "what": f"rotation of {n_rot} distinct input/output sets "
                                           f"({n_rot * quant_bytes / 2**20:.0f} MiB): served by HBM"}},
-        "measured_peaks": {"int8_mfma_TOPS": measured_mfma_tops, "copy_GBs": measured_hbm_gbs,
-                           "what": "quik_debug_mfma_probe (independent 32x32x32 int8 matrix instructions, "
-                                   "register-resident) and quik_debug_copy_probe (512 MiB streaming copy, "
-                                   "read + write bytes)"},
+        "measured_peaks": {"int8_mfma_TOPS": measured_mfma_tops,
+                           "int8_mfma_TOPS_random_operands": mix_tops[1],
+                           "int8_mfma_TOPS_k_loop_mix": mix_tops[31],
+                           "copy_GBs": measured_hbm_gbs,
+                           "what": "quik_debug_mfma_probe (independent 32x32x32 int8 matrix instructions on "
+                                   "register-resident operands of small values), quik_debug_mix_probe 1 (the same on "
+                                   "operands of pseudo-random bytes) and 31 (with the vector, LDS, copy and barrier "
+                                   "instructions of the GEMM's K loop beside them, no dependences), "
+                                   "quik_debug_copy_probe (512 MiB streaming copy, read + write bytes)"},
         "roofline": {"bound": "mfma", "kernel": gemm_kernel_name + " (INT GEMM + dequant + outlier GEMM)",
                      "achieved": gemm_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": gemm_tops / PEAK_INT8_TOPS,
                      "frac_of_measured_mfma_peak": gemm_tops / measured_mfma_tops,
+                     "frac_of_measured_mfma_peak_random_operands": gemm_tops / mix_tops[1],
+                     "frac_of_measured_k_loop_mix": gemm_tops / mix_tops[31],
                      # the kernel's two contractions against their own peaks: time at 100 % of the int8 rate for
                      # the integer part plus time at 100 % of the fp16 rate for the outlier part, over the time taken
                      "frac_roof_int8_plus_fp16": (ops_int / (PEAK_INT8_TOPS * 1e12) + 2.0 * T * n_out * N / (PEAK_FP16_TFLOPS * 1e12))
