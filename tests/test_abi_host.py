@@ -208,6 +208,21 @@ def test_persistent_kernel_plan_covers_the_output_and_balances_the_cus(lib):
     assert lib.quik_debug_set_gemm_path(1) == 0 and lib.quik_debug_set_gemm_path(0) == 0
 
 
+def test_mix_probe_rejects_bad_arguments(lib):
+    vp, i = C.c_void_p, C.c_int
+    fn = lib.quik_debug_mix_probe
+    fn.argtypes = [i, i, i, vp, vp, C.c_size_t, vp, vp]
+    p, u, null = vp(0x1000), vp(0x1004), vp(0)
+    assert fn(32, 256, 10, p, null, 0, null, null) == -1          # mix outside 0 .. 31
+    assert fn(-1, 256, 10, p, null, 0, null, null) == -1
+    assert fn(0, 0, 10, p, null, 0, null, null) == -1
+    assert fn(0, 256, 0, p, null, 0, null, null) == -1
+    assert fn(0, 256, 10, null, null, 0, null, null) == -2         # sink NULL
+    assert fn(8, 256, 10, p, null, 32 << 20, null, null) == -2     # copies asked for, no source
+    assert fn(8, 256, 10, p, p, 1 << 20, null, null) == -1         # source too small
+    assert fn(8, 256, 10, p, u, 32 << 20, null, null) == -3        # source misaligned
+
+
 def test_fp6_sizes_and_bad_arguments(lib):
     vp, i = C.c_void_p, C.c_int
     lib.quik_workspace_bytes_fp6.restype = C.c_size_t

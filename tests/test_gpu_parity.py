@@ -679,3 +679,24 @@ def test_repeated_calls_of_multi_workgroup_forms_are_bit_identical(api, oracle, 
         else:
             for k, v in got.items():
                 assert np.array_equal(v, first[k]), f"{k}: call {rep} differs from call 0"
+
+
+def test_measurement_probes_run(api):
+    """The probes behind `measured_peaks` are not part of the layer, but bench.py depends on them: every
+    instruction mix launches, finishes and reports its two clock counters."""
+    import torch
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    src = torch.zeros(16 << 20, dtype=torch.uint8, device="cuda")
+    clocks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    for mix in (0, 1, 7, 8, 16, 31):
+        clocks.zero_()
+        ops = api.quik_debug_mix_probe(mix, 64, 50, sink, src if mix & 8 else None, clocks)
+        _sync()
+        assert ops == 2.0 * 32 * 32 * 32 * 12 * 8 * 64 * 50
+        c = clocks.cpu().numpy()
+        assert c[0] > 0 and c[1] > 0, (mix, c)
+    assert api.quik_debug_mfma_probe(64, 50, sink) > 0
+    dst = torch.empty_like(src)
+    api.quik_debug_copy_probe(src, dst)
+    _sync()
+    assert int(sink.item()) == 0 and bool((dst == 0).all())
