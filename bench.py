@@ -353,6 +353,17 @@ def main():
                                              w_scale, w_red, w_out, None, y, side)
     ms_quant = _kernel_ms(quant_call, torch, it)
     ms_gemm = _kernel_ms(gemm_call, torch, it)
+    # The same GEMM launch on operands without entropy (every packed byte 0x88 = all codes zero in the
+    # activations' and the weights' nibble order alike): same instruction stream, same bytes moved.  The chip
+    # holds a higher clock when the operand bits do not toggle; the difference to ms_gemm is what the
+    # benchmark's uniformly random codes cost in clock, not in work.
+    ms_gemm_flat = None
+    if not mixed:
+        xq_flat, wq_flat = torch.full_like(xq, 0x88), torch.full_like(w_q, 0x88)
+        flat_call = api.prepare_gemm_dequant(xq_flat, scale, zero, x_out if n_out else None, K_b, bits, wq_flat,
+                                             w_scale, w_red, w_out, None, y, side)
+        ms_gemm_flat = _kernel_ms(flat_call, torch, it)
+        del xq_flat, wq_flat, flat_call
     ms_layer_ev = _kernel_ms(step, torch, it)
 
     # the quantization kernel on inputs that are NOT cache-resident: a rotation of distinct input and
@@ -532,6 +543,10 @@ def main():
                      "frac_of_measured_mfma_peak": gemm_tops / measured_mfma_tops,
                      "frac_of_measured_mfma_peak_random_operands": gemm_tops / mix_tops[1],
                      "frac_of_measured_k_loop_mix": gemm_tops / mix_tops[31],
+                     "same_launch_on_constant_operands": None if ms_gemm_flat is None else {
+                         "ms": ms_gemm_flat, "frac": ops_int / (ms_gemm_flat * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+                         "what": "every packed operand byte 0x88 (all codes zero): the clock the chip holds depends "
+                                 "on how much the operand bits toggle"},
                      # the kernel's two contractions against their own peaks: time at 100 % of the int8 rate for
                      # the integer part plus time at 100 % of the fp16 rate for the outlier part, over the time taken
                      "frac_roof_int8_plus_fp16": (ops_int / (PEAK_INT8_TOPS * 1e12) + 2.0 * T * n_out * N / (PEAK_FP16_TFLOPS * 1e12))
