@@ -526,7 +526,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             if (t < a.T) {
                 __half* dst = y + (size_t)t * a.ldy + n;
                 if (n + 8 <= a.N) {
-                    *reinterpret_cast<uint4*>(dst) = v;
+                    store16_through(dst, v);
                 } else {
                     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll

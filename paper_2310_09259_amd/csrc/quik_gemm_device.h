@@ -5,6 +5,8 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
+#include "quik_store_device.h"
+
 namespace quik {
 namespace gemm_dev {
 

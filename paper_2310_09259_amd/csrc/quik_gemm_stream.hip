@@ -537,7 +537,7 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                                     if (t < a.T) {
                                         __half* dst = y + (size_t)t * a.ldy + n;
                                         if (n + 8 <= n_end) {
-                                            *reinterpret_cast<uint4*>(dst) = v;
+                                            store16_through(dst, v);
                                         } else {
                                             const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll

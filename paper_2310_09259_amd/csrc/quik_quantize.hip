@@ -39,6 +39,7 @@
 
 #include "quik_kernels.h"
 #include "quik_quant_device.h"
+#include "quik_store_device.h"
 #include "quik_fp6_device.h"
 #include "quik_sp24_device.h"
 
@@ -439,19 +440,19 @@ __global__ __launch_bounds__(kBlock, (NCH >= 4 ? 2 : 3)) void quantize_rows_kern
                 uint4 v = src[i];
                 if constexpr (FP6) {                   // piece i of the image = piece i % 3 of stage i / 3
                     const int st = i / 3, c = i - 3 * st;
-                    dst[((size_t)st * T + t) * 3 + c] = v;
+                    store16_through(dst + ((size_t)st * T + t) * 3 + c, v);
                     continue;
                 }
                 if constexpr (SP24) {                  // piece i of the image = piece i % 2 of stage i / 2
                     v = make_uint4(sp24::act_word(v.x), sp24::act_word(v.y), sp24::act_word(v.z), sp24::act_word(v.w));
-                    dst[((size_t)(i >> 1) * T + t) * 2 + (i & 1)] = v;
+                    store16_through(dst + ((size_t)(i >> 1) * T + t) * 2 + (i & 1), v);
                     continue;
                 }
                 if constexpr (BITS == 4 && FMT == 0) {
                     auto sw = [](uint32_t w) { return ((w & 0x0F0F0F0Fu) << 4) | ((w >> 4) & 0x0F0F0F0Fu); };
                     v = make_uint4(sw(v.x), sw(v.y), sw(v.z), sw(v.w));
                 }
-                dst[i] = v;
+                store16_through(dst + i, v);
             }
             // ---- pass 3: move the outlier columns
 #pragma unroll
@@ -633,7 +634,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kernel(
                     auto sw = [](uint32_t w) { return ((w & 0x0F0F0F0Fu) << 4) | ((w >> 4) & 0x0F0F0F0Fu); };
                     v = make_uint4(sw(v.x), sw(v.y), sw(v.z), sw(v.w));
                 }
-                dst[i] = v;
+                store16_through(dst + i, v);
             }
             // ---- pass 3: move the outlier columns
             for (int j = lt; j < n_out; j += TPR) {
