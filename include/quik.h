@@ -465,9 +465,13 @@ int quik_debug_copy_probe(const void *src, void *dst, size_t bytes, void *stream
  *   8  two global -> LDS copies of 16 bytes per lane per 12 matrix instructions, out of `src`
  *      (DEVICE, 16-byte aligned, src_bytes >= 16 MiB; read only)
  *  16  a workgroup barrier per 48 matrix instructions
+ *  32  (only together with 1) the changing operands are bytes as the GEMM's nibble widening makes
+ *      them: half of the operand words vary in the high nibble of every byte only, the other half
+ *      in the low nibble only.  The clock the chip sustains depends on how many operand bits toggle,
+ *      so the rates with this bit set are the ceiling for the GEMM's own operands.
  * clocks (DEVICE uint64 [2], or NULL): ticks of the s_memtime and of the s_memrealtime counter over
  * the loop of workgroup 0 (for comparing loads with each other).  `sink` as above.
- * QUIK_EINVAL for mix outside 0..31 or bad sizes, QUIK_ENULL, QUIK_EALIGN.
+ * QUIK_EINVAL for mix outside 0..63, for bit 32 without bit 1, or bad sizes; QUIK_ENULL, QUIK_EALIGN.
  */
 int quik_debug_mix_probe(int mix, int workgroups, int iters, int32_t *sink, const void *src, size_t src_bytes,
                          unsigned long long *clocks, void *stream);

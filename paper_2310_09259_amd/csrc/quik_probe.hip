@@ -42,6 +42,10 @@ __global__ __launch_bounds__(256) void mfma_i8_probe_kernel(int iters, int* sink
 //   8  two global -> LDS copies of 16 bytes per lane per iteration (the operand copies' count), out of a
 //      512 KB window of `src` that the CUs of an XCD share (L2-resident)
 //  16  a workgroup barrier every fourth iteration (one per K stage)
+//  32  (with 1) the changing operands are bytes of the kind the GEMM's nibble widening makes: in one
+//      operand's even words and the other's odd words only the high nibble of a byte varies (16 x a signed
+//      code), in the remaining words only the low nibble (a code + 8).  The clock the chip holds depends on
+//      how many operand bits toggle, so this -- not bit 1 alone -- is the ceiling for the GEMM's own operands.
 // clocks[0], clocks[1]: the shader clock counter and the 100 MHz real-time counter over the loop of
 // workgroup 0 (their ratio is the clock the chip held under this load).
 constexpr int kMixWaves = 8, kMixMfma = 12, kMixAcc = 6;
@@ -50,7 +54,7 @@ template <int MIX>
 __global__ __launch_bounds__(kMixWaves * 64, 1) void mfma_mix_probe_kernel(int iters, int* sink, const uint8_t* src,
                                                                          uint32_t src_bytes, unsigned long long* clocks) {
     using namespace gemm_dev;
-    constexpr bool TOGGLE = MIX & 1, VALU = MIX & 2, LDSR = MIX & 4, COPY = MIX & 8, BARRIER = MIX & 16;
+    constexpr bool TOGGLE = MIX & 1, VALU = MIX & 2, LDSR = MIX & 4, COPY = MIX & 8, BARRIER = MIX & 16, NIBBLE = MIX & 32;
     constexpr int NL = 5, ND = 2, WINDOW = 512 * 1024;
     asm volatile("" ::: "v255");       // a wave owns half of its SIMD's register file: claim it whole (see build.py)
     __shared__ __align__(1024) uint8_t frag[64 * 1024];
@@ -73,6 +77,10 @@ __global__ __launch_bounds__(kMixWaves * 64, 1) void mfma_mix_probe_kernel(int i
             const uint32_t h = (uint32_t)(lane * 4 + e + 1) * 0x9E3779B1u;
             a[q][e] = TOGGLE ? (int)(h * (2 * q + 3)) : (e == 0 ? lane : e);
             b[q][e] = TOGGLE ? (int)((h ^ 0x5bd1e995u) * (2 * q + 5)) : (e == 3 ? (int)blockIdx.x : 4 + e);
+            if constexpr (TOGGLE && NIBBLE) {
+                a[q][e] &= (e & 1) ? 0x0F0F0F0F : (int)0xF0F0F0F0u;
+                b[q][e] &= (e & 1) ? (int)0xF0F0F0F0u : 0x0F0F0F0F;
+            }
         }
     uint32_t x[8];
 #pragma unroll
@@ -158,12 +166,12 @@ hipError_t launch_mix_probe(int mix, int workgroups, int iters, int* sink, const
 #define QUIK_MIX_CASE(M) \
     case M: hipLaunchKernelGGL(mfma_mix_probe_kernel<M>, dim3(workgroups), dim3(kMixWaves * 64), 0, stream, iters, sink, s8, nb, clocks); break;
     switch (mix) {
-        QUIK_MIX_CASE(0) QUIK_MIX_CASE(1) QUIK_MIX_CASE(2) QUIK_MIX_CASE(3) QUIK_MIX_CASE(4) QUIK_MIX_CASE(5)
-        QUIK_MIX_CASE(6) QUIK_MIX_CASE(7) QUIK_MIX_CASE(8) QUIK_MIX_CASE(9) QUIK_MIX_CASE(10) QUIK_MIX_CASE(11)
-        QUIK_MIX_CASE(12) QUIK_MIX_CASE(13) QUIK_MIX_CASE(14) QUIK_MIX_CASE(15) QUIK_MIX_CASE(16) QUIK_MIX_CASE(17)
-        QUIK_MIX_CASE(18) QUIK_MIX_CASE(19) QUIK_MIX_CASE(20) QUIK_MIX_CASE(21) QUIK_MIX_CASE(22) QUIK_MIX_CASE(23)
-        QUIK_MIX_CASE(24) QUIK_MIX_CASE(25) QUIK_MIX_CASE(26) QUIK_MIX_CASE(27) QUIK_MIX_CASE(28) QUIK_MIX_CASE(29)
-        QUIK_MIX_CASE(30) QUIK_MIX_CASE(31)
+        QUIK_MIX_CASE(0) QUIK_MIX_CASE(1) QUIK_MIX_CASE(2) QUIK_MIX_CASE(3) QUIK_MIX_CASE(4) QUIK_MIX_CASE(5) QUIK_MIX_CASE(6) QUIK_MIX_CASE(7)
+        QUIK_MIX_CASE(8) QUIK_MIX_CASE(9) QUIK_MIX_CASE(10) QUIK_MIX_CASE(11) QUIK_MIX_CASE(12) QUIK_MIX_CASE(13) QUIK_MIX_CASE(14) QUIK_MIX_CASE(15)
+        QUIK_MIX_CASE(16) QUIK_MIX_CASE(17) QUIK_MIX_CASE(18) QUIK_MIX_CASE(19) QUIK_MIX_CASE(20) QUIK_MIX_CASE(21) QUIK_MIX_CASE(22) QUIK_MIX_CASE(23)
+        QUIK_MIX_CASE(24) QUIK_MIX_CASE(25) QUIK_MIX_CASE(26) QUIK_MIX_CASE(27) QUIK_MIX_CASE(28) QUIK_MIX_CASE(29) QUIK_MIX_CASE(30) QUIK_MIX_CASE(31)
+        QUIK_MIX_CASE(33) QUIK_MIX_CASE(35) QUIK_MIX_CASE(37) QUIK_MIX_CASE(39) QUIK_MIX_CASE(41) QUIK_MIX_CASE(43) QUIK_MIX_CASE(45) QUIK_MIX_CASE(47)
+        QUIK_MIX_CASE(49) QUIK_MIX_CASE(51) QUIK_MIX_CASE(53) QUIK_MIX_CASE(55) QUIK_MIX_CASE(57) QUIK_MIX_CASE(59) QUIK_MIX_CASE(61) QUIK_MIX_CASE(63)
         default: return hipErrorInvalidValue;
     }
 #undef QUIK_MIX_CASE
