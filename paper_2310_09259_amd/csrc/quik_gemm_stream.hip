@@ -45,6 +45,7 @@ namespace {
 using namespace gemm_dev;
 
 template <int V> using ic = std::integral_constant<int, V>;
+typedef float v4f __attribute__((ext_vector_type(4)));
 #define QUIK_INLINE __attribute__((always_inline))
 
 constexpr int BM = kStreamRows;         // token rows per tile
@@ -52,6 +53,7 @@ constexpr int TNX = 3;                  // most 32-channel blocks per wave
 constexpr int BNX = 2 * TNX * 32;       // widest tile
 constexpr int BKB = 128;                // bytes of every packed row per stage (256 columns)
 constexpr int TM = 2;                   // 32-row blocks per wave
+constexpr int IB = 2 * TM;              // 16 x 16 accumulator blocks per wave along the token rows
 constexpr int NWAVES = 8, NT = NWAVES * 64;
 constexpr int CPR = BKB / 16, RPI = 64 / CPR;
 constexpr int IROWS = NWAVES * RPI;     // rows between a wave's consecutive copy instructions
@@ -214,22 +216,24 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
     // the end of that phase, which keeps the reads behind it.
     auto tie = [&](uint32_t& addr, uint32_t dep) QUIK_INLINE { asm volatile("" : "+v"(addr) : "v"(dep)); };
 
-    // ---- fragment addresses: one register per operand and sub-step (row l of the wave's first block,
-    // swizzled 16-byte slot of k-group kg); the 32-row block is an immediate.  Registers 0, 1 point into
-    // ring slot `slot`, registers 2, 3 into the other one: a stage flips the register of sub-step q to its
-    // own slot right before it reads that sub-step (see int_stage).
+    // ---- fragment addresses: one register per operand and sub-step.  The matrix instruction is the
+    // 16 x 16 x 64 one: lane (l = lane % 16, g = lane / 16) supplies the 16 int8 values of k-group g for row
+    // (or channel) l of a 16-row block, i.e. 8 packed bytes: bytes 8g .. 8g + 7 of the sub-step's 32 bytes
+    // of that row.  A register holds the address for the wave's first block; the block is an immediate.
+    // Registers 0, 1 point into ring slot `slot`, registers 2, 3 into the other one: a stage flips the
+    // register of sub-step q to its own slot right before it reads that sub-step (see int_stage).
     uint32_t rdA[KSUB], rdB[KSUB];
     auto set_rd = [&](int cb0, int slot, uint32_t dep) QUIK_INLINE {
         uint32_t lnu = (uint32_t)lane;
         tie(lnu, dep);
         const int ln = (int)lnu;
-        const int l = ln & 31, kg = (ln >> 5) & 1;
+        const int l = ln & 15, g = (ln >> 4) & 3;
         const int ra = wm * TM * 32 + l, rb = cb0 * 32 + l;
 #pragma unroll
         for (int ks = 0; ks < KSUB; ++ks) {
             const int so = (ks < 2 ? slot : slot ^ 1) * SLOT_STRIDE;
-            rdA[ks] = OFF_A + so + ra * BKB + (((ks * 2 + kg) ^ swz<BKB>(ra)) << 4);
-            rdB[ks] = OFF_B + so + rb * BKB + (((ks * 2 + kg) ^ swz<BKB>(rb)) << 4);
+            rdA[ks] = OFF_A + so + ra * BKB + (((ks * 2 + (g >> 1)) ^ swz<BKB>(ra)) << 4) + (g & 1) * 8;
+            rdB[ks] = OFF_B + so + rb * BKB + (((ks * 2 + (g >> 1)) ^ swz<BKB>(rb)) << 4) + (g & 1) * 8;
         }
     };
     // first block and block count of this wave in a tile of width w (tiles narrower than four blocks
@@ -240,38 +244,39 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
         tna = wn ? we / 2 : (we + 1) / 2;
     };
 
-    // Raw fragments of two sub-steps (32 packed bytes of every row = 64 columns each; words 0, 1 of a
-    // fragment feed the first half of a sub-step, words 2, 3 the second) and two sets of widened operands:
-    // while the MFMAs of a sub-step read one set, the next sub-step's raw words are widened into the other,
-    // a word or two per MFMA slot, so no MFMA ever waits for an operand made just before it.
-    uint4 R[2][TM + TNX];
-    v4i U[2][TM + TNX][2];
+    // Raw fragments of two sub-steps (a fragment: 8 packed bytes per lane = 16 columns of one row of a 16-row
+    // block) and two sets of widened operands (a fragment widens to the 16 int8 values one matrix instruction
+    // takes from the lane): while the MFMAs of a sub-step read one set, the next sub-step's raw words are
+    // widened into the other, a word per MFMA slot, so no MFMA ever waits for an operand made just before it.
+    constexpr int NFX = IB + 2 * TNX;
+    uint2 R[2][NFX];
+    v4i U[2][NFX];
     auto read_frag = [&](int set, int f, int ks) QUIK_INLINE {
-        const uint32_t off = (f < TM) ? rdA[ks] + (uint32_t)(f * 4096) : rdB[ks] + (uint32_t)((f - TM) * 4096);
-        R[set][f] = *reinterpret_cast<const uint4*>(lds + off);
+        const uint32_t off = (f < IB) ? rdA[ks] + (uint32_t)(f * 16 * BKB) : rdB[ks] + (uint32_t)((f - IB) * 16 * BKB);
+        R[set][f] = *reinterpret_cast<const uint2*>(lds + off);
     };
-    // word w (fragment w / 4, word w % 4) of raw set `rset`, widened into operand set `set`
+    // word w (fragment w / 2, word w % 2) of raw set `rset`, widened into operand set `set`
     auto widen_word = [&](int set, int rset, int w) QUIK_INLINE {
         constexpr uint32_t M = 0xF0F0F0F0u;
-        const int f = w >> 2, k = w & 3;
-        const bool act = f < TM;                             // activations: even k in the high nibble
-        const uint32_t x = (k == 0) ? R[rset][f].x : (k == 1) ? R[rset][f].y : (k == 2) ? R[rset][f].z : R[rset][f].w;
+        const int f = w >> 1, k = w & 1;
+        const bool act = f < IB;                             // activations: even k in the high nibble
+        const uint32_t x = k ? R[rset][f].y : R[rset][f].x;
         const uint32_t hi = x & M;                           // 16 * signed high nibble
         const uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)   // low nibble + 8
                                  : ((x << 4) & M);                     // 16 * signed low nibble
-        U[set][f][k >> 1][(k & 1) * 2] = (int)(act ? hi : lo);
-        U[set][f][k >> 1][(k & 1) * 2 + 1] = (int)(act ? lo : hi);
+        U[set][f][2 * k] = (int)(act ? hi : lo);
+        U[set][f][2 * k + 1] = (int)(act ? lo : hi);
     };
     // a tile's first two sub-steps' fragments (its stage 0, in ring slot `slot`), and the operands its
-    // first half sub-step starts with
+    // first sub-step starts with
     auto first_reads = [&](int cb0, int slot, uint32_t dep) QUIK_INLINE {
         set_rd(cb0, slot, dep);
 #pragma unroll
         for (int q = 0; q < 2; ++q)
 #pragma unroll
-            for (int f = 0; f < TM + TNX; ++f) read_frag(q, f, q);
+            for (int f = 0; f < NFX; ++f) read_frag(q, f, q);
 #pragma unroll
-        for (int w = 0; w < (TM + TNX) * 4; ++w) widen_word(0, 0, w);
+        for (int w = 0; w < NFX * 2; ++w) widen_word(0, 0, w);
     };
 
     int cur_t0 = 0, cur_n0 = 0, cur_nc = 0, cur_w = 0, nxt_t0 = 0, nxt_n0 = 0, nxt_nc = 0, nxt_w = 0;
@@ -319,25 +324,28 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
 
         auto tile = [&](auto tna_c) QUIK_INLINE {
             constexpr int TNA = decltype(tna_c)::value;
-            constexpr int NFA = TM + TNA;
-            constexpr int MH = TM * TNA;                              // MFMAs per half sub-step
-            static_assert(2 * MH >= LPS && 2 * MH >= NFA, "copy, read and widening work is spread over the MFMA slots");
+            constexpr int JB = 2 * TNA;                               // 16-channel accumulator blocks per wave
+            constexpr int NFA = IB + JB;                              // fragments per sub-step
+            constexpr int NMF = IB * JB;                              // MFMAs per sub-step
+            constexpr int CS = NMF / 8;                               // a copy instruction every CS-th MFMA slot
+            static_assert(NMF >= NFA * 2 && 8 >= LPS, "copy, read and widening work is spread over the MFMA slots");
 
-            v16i acc[TM][TNA];
+            v4i acc[IB][JB];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < IB; ++i)
 #pragma unroll
-                for (int j = 0; j < TNA; ++j)
+                for (int j = 0; j < JB; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+                    for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
 
             // One integer stage (stage s of the tile, in ring slot `slot`).  The refill of the slot it frees
-            // is spread over the MFMA slots after the barrier.  A sub-step issues its MFMAs from one operand
-            // set; meanwhile the next sub-step's raw fragments are widened into the other set and the raw
-            // registers of this sub-step (widened during the one before) are refilled from LDS with the
-            // fragments of the sub-step after the next -- which, in the last two sub-steps, belongs to the
-            // next stage in the other slot (after the last integer stage that is an fp16 stage, or the next
-            // tile: its fragments are simply not used as integers).
+            // is spread over the MFMA slots after the barrier.  A sub-step (32 packed bytes of every row) is
+            // one 16 x 16 x 64 instruction per accumulator block, issued from one operand set; meanwhile the
+            // next sub-step's raw fragments are widened into the other set and the raw registers of this
+            // sub-step (widened during the one before) are refilled from LDS with the fragments of the
+            // sub-step after the next -- which, in the last two sub-steps, belongs to the next stage in the
+            // other slot (after the last integer stage that is an fp16 stage, or the next tile: its
+            // fragments are simply not used as integers).
             auto int_stage = [&](int s, int slot) QUIK_INLINE {
 #pragma unroll
                 for (int ks = 0; ks < KSUB; ++ks) {
@@ -354,16 +362,16 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                     rdB[tks] ^= SLOT_STRIDE;
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int hm = 0; hm < 2 * MH; ++hm) {
-                        const int h = hm / MH, m = hm % MH, j = m / TM, i = m % TM;
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(U[par][i][h], U[par][TM + j][h], acc[i][j], 0, 0, 0);
-                        if (ks == 2 && hm < LPS) issue_copy(rf, slot, hm);
-                        // the next sub-step's operands, a word or two per MFMA slot
+                    for (int hm = 0; hm < NMF; ++hm) {
+                        const int j = hm / IB, i = hm % IB;
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(U[par][i], U[par][IB + j], acc[i][j], 0, 0, 0);
+                        if (ks == 2 && hm % CS == 0 && hm / CS < LPS) issue_copy(rf, slot, hm / CS);
+                        // the next sub-step's operands, a word per MFMA slot
 #pragma unroll
-                        for (int w = 0; w < NFA * 4; ++w)
-                            if (w * (2 * MH) / (NFA * 4) == hm) widen_word(par ^ 1, par ^ 1, w);
+                        for (int w = 0; w < NFA * 2; ++w)
+                            if (w * NMF / (NFA * 2) == hm) widen_word(par ^ 1, par ^ 1, w);
                         // this sub-step's raw registers were widened during the sub-step before
-                        if (hm < NFA) read_frag(par, hm, tks);
+                        if (hm >= NMF / 3 && hm - NMF / 3 < NFA) read_frag(par, hm - NMF / 3, tks);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -380,18 +388,18 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
             // once, before the tile loop, and keep dozens of registers alive through the K loops.  An
             // opaque copy of the lane id per tile keeps that arithmetic here.
             const int lane_e = opaque_lane();
-            const int l32e = lane_e & 31, ge = lane_e >> 5;
+            const int l16e = lane_e & 15, ge = lane_e >> 4;     // accumulator block: channel l16e, token rows 4 ge .. 4 ge + 3
             const int tw = cur_t0 + wm * TM * 32, nw = cur_n0 + cb0 * 32, n_end = cur_n0 + cur_nc;
             uint32_t done = 0;                            // a value from the end of this tile's output
             if constexpr (RAW) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < IB; ++i)
 #pragma unroll
-                    for (int j = 0; j < TNA; ++j) {
-                        const int n = nw + j * 32 + l32e;
+                    for (int j = 0; j < JB; ++j) {
+                        const int n = nw + j * 16 + l16e;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int t = tw + i * 32 + 8 * (r >> 2) + 4 * ge + (r & 3);
+                        for (int r = 0; r < 4; ++r) {
+                            const int t = tw + i * 16 + 4 * ge + r;
                             if (t < a.T && n < n_end) {
                                 int v = acc[i][j][r] >> SHIFT;
                                 if constexpr (ASYM) v -= 8 * (a.code_sum[t] + a.w_code_sum[n]);
@@ -403,99 +411,114 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                 // Dequantization: the raw accumulator is 16 x the integer dot product plus
                 // 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes the latter, the
                 // conversion to binary32 is exact, and 2^-4 rides on the weight scale.
-                float c_sw[TNA], c_wr[TNA], c_bv[TNA];
-                int c_nc[TNA];
+                float c_sw[JB], c_wr[JB], c_bv[JB];
+                int c_nc[JB];
 #pragma unroll
-                for (int j = 0; j < TNA; ++j) {
-                    const int col = (cb0 + j) * 32 + l32e;            // inside the tile
+                for (int j = 0; j < JB; ++j) {
+                    const int col = cb0 * 32 + j * 16 + l16e;         // inside the tile
                     c_sw[j] = __half2float(*reinterpret_cast<const __half*>(prm + PRM_WSCALE + col * 2)) *
                               (1.0f / (float)(1 << SHIFT));           // exact power-of-two factor
                     c_bv[j] = a.bias ? __half2float(*reinterpret_cast<const __half*>(prm + PRM_BIAS + col * 2)) : 0.0f;
                     c_wr[j] = *reinterpret_cast<const float*>(prm + PRM_WRED + col * 4);
                     c_nc[j] = -128 * *reinterpret_cast<const int*>(prm + PRM_WCSUM + col * 4);
                 }
-                // Per-token parameters of eight rows at a time (group gq = row block i, row quad rq), read one
-                // group ahead of their use; tied to the results of the group before, or the scheduler would
-                // hoist all 24 reads (96 registers) to the top.
+                // Per-token parameters of the four rows a lane holds of a 16-row block, read one block ahead of
+                // their use; tied to the results of the block before, or the scheduler would hoist all reads
+                // to the top.
                 uint32_t dq_dep = 0;
-                v16f cf[TM][TNA];
+                v4f cf[IB][JB];
                 float4 sa4[2], z4[2];
                 int4 cs4[2];
-                auto load_group = [&](int gq) QUIK_INLINE {
-                    const int lr = wm * TM * 32 + (gq >> 2) * 32 + 8 * (gq & 3) + 4 * ge;
+                auto load_group = [&](int i) QUIK_INLINE {
+                    const int lr = wm * TM * 32 + i * 16 + 4 * ge;
                     uint32_t o = (uint32_t)lr * 4u;
                     tie(o, dq_dep);
-                    sa4[gq & 1] = *reinterpret_cast<const float4*>(prm + PRM_SCALE + o);
-                    z4[gq & 1] = *reinterpret_cast<const float4*>(prm + PRM_ZERO + o);
-                    cs4[gq & 1] = *reinterpret_cast<const int4*>(prm + PRM_CSUM + o);
+                    sa4[i & 1] = *reinterpret_cast<const float4*>(prm + PRM_SCALE + o);
+                    z4[i & 1] = *reinterpret_cast<const float4*>(prm + PRM_ZERO + o);
+                    cs4[i & 1] = *reinterpret_cast<const int4*>(prm + PRM_CSUM + o);
                 };
                 load_group(0);
 #pragma unroll
-                for (int gq = 0; gq < TM * 4; ++gq) {
-                    const int i = gq >> 2, rq = gq & 3, b = gq & 1;
-                    if (gq + 1 < TM * 4) load_group(gq + 1);
+                for (int i = 0; i < IB; ++i) {
+                    const int b = i & 1;
+                    if (i + 1 < IB) load_group(i + 1);
                     const float sa_[4] = {sa4[b].x, sa4[b].y, sa4[b].z, sa4[b].w};
                     const float sh_[4] = {z4[b].x + 8.0f * sa4[b].x, z4[b].y + 8.0f * sa4[b].y, z4[b].z + 8.0f * sa4[b].z,
                                           z4[b].w + 8.0f * sa4[b].w};    // zeroAct + halfRange * scaleAct
                     const int ct_[4] = {-128 * cs4[b].x, -128 * cs4[b].y, -128 * cs4[b].z, -128 * cs4[b].w};
 #pragma unroll
-                    for (int j = 0; j < TNA; ++j)
+                    for (int j = 0; j < JB; ++j)
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr) {
-                            const int r = rq * 4 + rr;
-                            const int ai = acc[i][j][r] + ct_[rr] + c_nc[j];
-                            cf[i][j][r] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j],
-                                                         __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
+                            const int ai = acc[i][j][rr] + ct_[rr] + c_nc[j];
+                            cf[i][j][rr] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j],
+                                                          __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
                         }
-                    dq_dep = __float_as_uint(cf[i][TNA - 1][rq * 4 + 3]);
+                    dq_dep = __float_as_uint(cf[i][JB - 1][3]);
                 }
 
-                // fp16 outlier stages on the dequantized tile (stage nk_int + f of the tile).  The first two
-                // sub-steps of the first one are read again here (the last integer stage has read them, but
-                // keeping them in registers across the dequantization costs more than this read).
-                // LAST: the tile's last stage -- no look-ahead into the next tile, whose waves' column blocks
-                // may differ.
+                // fp16 outlier stages on the dequantized tile (stage nk_int + f of the tile): two k-steps of 32
+                // columns (64 bytes of every row) per stage, one 16 x 16 x 32 instruction per accumulator block
+                // and k-step; lane (l, g) supplies columns 8g .. 8g + 7 of the k-step, one 16-byte piece.  The
+                // two operand sets of the integer phase (free now) hold the stage's two k-steps; a set is
+                // refilled with the same k-step of the next stage once its MFMAs are issued.
+                // The barrier sits after the first k-step's MFMAs: every read of this stage was issued during
+                // the stage before, so its slot is free, and the reads that follow go to the next stage,
+                // which must have landed.  LAST: the tile's last stage -- no look-ahead into the next tile,
+                // whose waves' column blocks may differ.
+                uint32_t fpA[2], fpB[2];
+                {
+                    uint32_t lnu = (uint32_t)lane;
+                    tie(lnu, dq_dep);
+                    const int l = (int)lnu & 15, g = ((int)lnu >> 4) & 3;
+                    const int ra = wm * TM * 32 + l, rb = cb0 * 32 + l;
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    tie(rdA[q], dq_dep);
-                    tie(rdB[q], dq_dep);
-#pragma unroll
-                    for (int f = 0; f < NFA; ++f) read_frag(q, f, q);
+                    for (int kk = 0; kk < 2; ++kk) {
+                        fpA[kk] = OFF_A + slot * SLOT_STRIDE + ra * BKB + (((kk * 4 + g) ^ swz<BKB>(ra)) << 4);
+                        fpB[kk] = OFF_B + slot * SLOT_STRIDE + rb * BKB + (((kk * 4 + g) ^ swz<BKB>(rb)) << 4);
+                    }
                 }
-                auto fp_stage = [&](auto last_c, int f, int slot) QUIK_INLINE {
-                    constexpr bool LAST = decltype(last_c)::value != 0;
+                auto read_fp = [&](auto kk_c) QUIK_INLINE {
+                    constexpr int KK = decltype(kk_c)::value;
 #pragma unroll
-                    for (int ks = 0; ks < KSUB; ++ks) {
-                        const int tks = (ks + 2) % KSUB;
-                        if (ks == 2) {
-                            wait_vm<0>();
-                            __syncthreads();
-                            prep_refill(rf, nk_int + f);
-                        }
-                        rdA[tks] ^= SLOT_STRIDE;
-                        rdB[tks] ^= SLOT_STRIDE;
-                        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                        for (int m = 0; m < MH; ++m) {
-                            const int i = m / TNA, j = m % TNA;
-                            cf[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, R[ks & 1][i]),
-                                                                             __builtin_bit_cast(v8h, R[ks & 1][TM + j]),
-                                                                             cf[i][j], 0, 0, 0);
-                            // the refill, spread over the MFMAs of the two sub-steps after the barrier
-                            if (ks >= 2) {
-#pragma unroll
-                                for (int d = 0; d < LPS; ++d)
-                                    if (d * 2 * MH / LPS == (ks - 2) * MH + m) issue_copy(rf, slot, d);
-                            }
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        // this sub-step's raw registers are free now
-                        if (ks + 2 < KSUB || !LAST) {
-#pragma unroll
-                            for (int q = 0; q < NFA; ++q) read_frag(ks & 1, q, tks);
-                        }
+                    for (int f = 0; f < NFA; ++f) {
+                        const uint32_t off = (f < IB) ? fpA[KK] + (uint32_t)(f * 16 * BKB) : fpB[KK] + (uint32_t)((f - IB) * 16 * BKB);
+                        U[KK][f] = *reinterpret_cast<const v4i*>(lds + off);
                     }
                 };
+                auto fp_mfmas = [&](auto kk_c, int slot_, bool copies) QUIK_INLINE {
+                    constexpr int KK = decltype(kk_c)::value;
+#pragma unroll
+                    for (int m = 0; m < NMF; ++m) {
+                        const int j = m / IB, i = m % IB;
+                        cf[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, U[KK][i]),
+                                                                         __builtin_bit_cast(v8h, U[KK][IB + j]), cf[i][j], 0, 0, 0);
+                        // the refill, spread over the MFMAs of the k-step after the barrier
+                        if (KK == 1 && m % CS == 0 && m / CS < LPS) issue_copy(rf, slot_, m / CS);
+                    }
+                    (void)copies;
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                auto fp_stage = [&](auto last_c, int f, int slot_) QUIK_INLINE {
+                    constexpr bool LAST = decltype(last_c)::value != 0;
+                    fp_mfmas(ic<0>{}, slot_, false);
+                    wait_vm<0>();
+                    __syncthreads();
+                    prep_refill(rf, nk_int + f);
+#pragma unroll
+                    for (int kk = 0; kk < 2; ++kk) {
+                        fpA[kk] ^= SLOT_STRIDE;
+                        fpB[kk] ^= SLOT_STRIDE;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (!LAST) read_fp(ic<0>{});
+                    fp_mfmas(ic<1>{}, slot_, true);
+                    if constexpr (!LAST) read_fp(ic<1>{});
+                };
+                // (unconditional: a conditional definition would keep the sets' registers occupied from the top
+                // of the epilogue)
+                read_fp(ic<0>{});
+                read_fp(ic<1>{});
                 for (int f = 0; f + 1 < nk_fp; ++f) {
                     fp_stage(ic<0>{}, f, slot);
                     slot ^= 1;
@@ -503,9 +526,9 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                 if (nk_fp > 0) fp_stage(ic<1>{}, nk_fp - 1, slot);
                 __builtin_amdgcn_sched_barrier(0);
 
-                // Output: a lane owns one column of sixteen rows of every 32 x 32 block, so direct stores
-                // would be 2 bytes per lane.  Each wave parks sixteen rows of its fp16 tile at a time in
-                // its own LDS buffer and writes them out as 16-byte pieces, whole row segments per store
+                // Output: a lane owns four rows of one column of every 16 x 16 block, so direct stores would be
+                // 2 bytes per lane.  Each wave parks the sixteen rows of a block row of its fp16 tile in its own
+                // LDS buffer and writes them out as 16-byte pieces, whole row segments per store
                 // instruction.  Needs 16-byte aligned output rows; otherwise the direct path below.
                 __half* __restrict__ y = static_cast<__half*>(a.y);
                 const bool vec_ok = ((reinterpret_cast<uintptr_t>(a.y) & 15u) == 0) && (a.ldy % 8 == 0);
@@ -515,50 +538,47 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                     constexpr int RPS = 64 / CH;                 // rows per store instruction
                     const int prow = lane_e / CH, pch = lane_e % CH;
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < IB; ++i) {               // rows 16 i .. 16 i + 15 of the wave's tile
 #pragma unroll
-                        for (int hf = 0; hf < 2; ++hf) {         // rows 16 hf .. 16 hf + 15 of block row i
+                        for (int j = 0; j < JB; ++j)
 #pragma unroll
-                            for (int j = 0; j < TNA; ++j)
+                            for (int r = 0; r < 4; ++r) {
+                                const int row = 4 * ge + r;      // inside the 16 rows
+                                *reinterpret_cast<__half*>(wbuf + row * PARK_ROW_BYTES + (j * 16 + l16e) * 2) =
+                                    __float2half(cf[i][j][r]);
+                            }
 #pragma unroll
-                                for (int rr = 0; rr < 8; ++rr) {
-                                    const int r = hf * 8 + rr;
-                                    const int row = 8 * (rr >> 2) + 4 * ge + (rr & 3);     // inside the 16 rows
-                                    *reinterpret_cast<__half*>(wbuf + row * PARK_ROW_BYTES + (j * 32 + l32e) * 2) =
-                                        __float2half(cf[i][j][r]);
-                                }
+                        for (int q = 0; q < (PARK_ROWS + RPS - 1) / RPS; ++q) {
+                            const int row = q * RPS + prow;
+                            if (prow < RPS && row < PARK_ROWS) {
+                                const uint4 v = *reinterpret_cast<const uint4*>(wbuf + row * PARK_ROW_BYTES + pch * 16);
+                                done = v.x;
+                                const int t = tw + i * 16 + row, n = nw + pch * 8;
+                                if (t < a.T) {
+                                    __half* dst = y + (size_t)t * a.ldy + n;
+                                    if (n + 8 <= n_end) {
+                                        store16_through(dst, v);
+                                    } else {
+                                        const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                            for (int q = 0; q < (PARK_ROWS + RPS - 1) / RPS; ++q) {
-                                const int row = q * RPS + prow;
-                                if (prow < RPS && row < PARK_ROWS) {
-                                    const uint4 v = *reinterpret_cast<const uint4*>(wbuf + row * PARK_ROW_BYTES + pch * 16);
-                                    done = v.x;
-                                    const int t = tw + i * 32 + hf * 16 + row, n = nw + pch * 8;
-                                    if (t < a.T) {
-                                        __half* dst = y + (size_t)t * a.ldy + n;
-                                        if (n + 8 <= n_end) {
-                                            store16_through(dst, v);
-                                        } else {
-                                            const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                                            for (int e = 0; e < 8; ++e)
-                                                if (n + e < n_end)
-                                                    reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
-                                        }
+                                        for (int e = 0; e < 8; ++e)
+                                            if (n + e < n_end)
+                                                reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
                                     }
                                 }
                             }
-                            __builtin_amdgcn_sched_barrier(0);
                         }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 } else {
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < IB; ++i)
 #pragma unroll
-                        for (int j = 0; j < TNA; ++j) {
-                            const int n = nw + j * 32 + l32e;
+                        for (int j = 0; j < JB; ++j) {
+                            const int n = nw + j * 16 + l16e;
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int t = tw + i * 32 + 8 * (r >> 2) + 4 * ge + (r & 3);
+                            for (int r = 0; r < 4; ++r) {
+                                const int t = tw + i * 16 + 4 * ge + r;
                                 if (t < a.T && n < n_end) y[(size_t)t * a.ldy + n] = __float2half(cf[i][j][r]);
                             }
                         }
