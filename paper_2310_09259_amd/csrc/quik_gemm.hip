@@ -966,16 +966,18 @@ static int g_gemm_path = 0;     // 0: automatic; 1: the persistent kernel wherev
 void set_gemm_path(int mode) { g_gemm_path = mode; }
 
 // 0: the persistent kernel cannot run this shape; 1: it can and is the automatic choice; 2: it can, but
-// the per-tile kernels are estimated to be at least as fast.  The persistent kernel wins where whole
-// rounds of fixed tiles leave CUs idle (the LLaMA-7B up-projection at 2048 tokens: 464 tiles of
-// 256 x 192 on 256 CUs); block for block its K loop is about as fast as the per-tile kernels', and with
-// few K stages per tile its longer prologue shows.
+// the per-tile kernels are estimated to be at least as fast.  Measured on the LLaMA shapes, in the unit of
+// tiles_estimate: a block of the persistent kernel costs 0.91 - 0.95 where its tiles are five or six blocks
+// wide (its K loop runs on the 16 x 16 x 64 matrix instruction, under which the chip keeps its clock; whole
+// rounds of fixed 256 x 192 tiles cost 0.947 per block, so it also wins 4 % where those balance perfectly),
+// and 1.04 where the tiles are four blocks wide (a wave then holds two column blocks: more fragment reads
+// and widening per MFMA than the per-tile 256 x 128 form) or K is shallow (its longer per-tile epilogue).
 int choose_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* plan) {
     if (!plan_gemm_stream(T, N, K_b, cus, plan)) return 0;
     const long tiles = (long)plan->tiles_m * plan->tn;
     const long r = (tiles + cus - 1) / cus;
     const double blocks = (double)(r * plan->base + (r * plan->rem + plan->tn - 1) / plan->tn);
-    return (K_b >= 2048 && blocks <= 0.97 * tiles_estimate(T, N, cus)) ? 1 : 2;
+    return (K_b >= 2048 && plan->base >= 5 && 0.94 * blocks <= tiles_estimate(T, N, cus)) ? 1 : 2;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream) {

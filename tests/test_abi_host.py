@@ -194,8 +194,13 @@ def test_persistent_kernel_plan_covers_the_output_and_balances_the_cus(lib):
     assert rc == 1 and max(sum(-(-t[2] // 32) for t in ts) for ts in per_wg) == 11
     first_round_xcd0 = [per_wg[b][0] for b in range(0, 256, 8)]
     assert len({t[1] for t in first_round_xcd0}) == 8 and {t[0] for t in first_round_xcd0} == {0, 256, 512, 768}
-    # one 256 x 128 tile per CU already balances the down-projection; few K stages per tile: per-tile kernels
+    # one 256 x 128 tile per CU already balances the down-projection, four-block tiles at 1024 tokens of the
+    # 13B QKV shape, few K stages per tile: per-tile kernels
     assert _plan(lib, 2048, 4096, 10752)[0] == 2 and _plan(lib, 1030, 9990, 1064)[0] == 2
+    assert _plan(lib, 1024, 15360, 4864)[0] == 2
+    # whole rounds of six-block tiles either way (13B QKV at 4096 tokens), and the 70B up-projection: the
+    # persistent kernel's K loop is the faster one
+    assert _plan(lib, 4096, 15360, 4864)[0] == 1 and _plan(lib, 4096, 28672, 7936)[0] == 1
     # shapes the persistent kernel cannot run: too few tiles for the chip, shallow K, odd N
     assert _plan(lib, 16, 15360, 4864)[0] == 0
     assert _plan(lib, 2048, 11008, 512)[0] == 0
