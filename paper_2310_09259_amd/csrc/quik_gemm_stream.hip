@@ -1,9 +1,14 @@
 // Persistent form of the 4-bit integer GEMM + dequantization epilogue + fp16 outlier GEMM for
 // large token counts (Algorithm 1 of arXiv 2310.09259: "INTmatmul", "Dequantization", "FPmatmul"
 // and the final add; epilogue fusion as in Section 3.4).  Same arithmetic, operand formats and
-// widening as gemm_kernel in quik_gemm.hip (see the header of that file); what differs is how the
-// work is laid over the chip:
+// widening as gemm_kernel in quik_gemm.hip (see the header of that file); what differs is the matrix
+// instruction and how the work is laid over the chip:
 //
+//  * The integer product runs on v_mfma_i32_16x16x64_i8 and the outlier product on
+//    v_mfma_f32_16x16x32_f16 (16 x 16 accumulator blocks: a lane holds four token rows of one channel).
+//    On MI355X the chip holds its full clock under these where it lowers it under the 32 x 32 forms on
+//    the same operand bytes; the price is twice the matrix instructions and 8-byte instead of 16-byte
+//    fragment reads for the same bytes.
 //  * One workgroup of eight waves per CU stays resident and walks through a list of output tiles
 //    (256 token rows x 128 / 160 / 192 output channels).  The two-slot stage ring keeps running
 //    across the tile boundary: while a tile's last two stages are multiplied, the slots they free
