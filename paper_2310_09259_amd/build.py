@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libquik.so")
-SOURCES = ["quik_api.hip", "quik_quantize.hip", "quik_gemm.hip", "quik_gemm_stream.hip", "quik_gemm_fp6.hip", "quik_gemm_sp24.hip",
+SOURCES = ["quik_api.hip", "quik_quantize.hip", "quik_gemm.hip", "quik_gemm_tiles16.hip", "quik_gemm_stream.hip", "quik_gemm_fp6.hip", "quik_gemm_sp24.hip",
            "quik_unfused.hip", "quik_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
