@@ -266,9 +266,13 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
         const int f = w >> 1, k = w & 1;
         const bool act = f < IB;                             // activations: even k in the high nibble
         const uint32_t x = k ? R[rset][f].y : R[rset][f].x;
-        const uint32_t hi = x & M;                           // 16 * signed high nibble
-        const uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)   // low nibble + 8
-                                 : ((x << 4) & M);                     // 16 * signed low nibble
+        uint32_t hi = x & M;                                 // 16 * signed high nibble
+        uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)         // low nibble + 8
+                           : ((x << 4) & M);                           // 16 * signed low nibble
+        // A use right here: the operands of a stage's third sub-step are first read behind the stage
+        // barrier's branches, and without it the compiler sinks their widening out of the MFMA slots of the
+        // second sub-step into one burst behind the barrier.
+        asm volatile("" : "+v"(hi), "+v"(lo));
         U[set][f][2 * k] = (int)(act ? hi : lo);
         U[set][f][2 * k + 1] = (int)(act ? lo : hi);
     };
