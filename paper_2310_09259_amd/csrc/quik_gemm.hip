@@ -897,11 +897,12 @@ hipError_t dispatch(const GemmArgs& a, hipStream_t stream) {
         if (cost_b < cost_a && cost_b <= cost_c) return launch_cfg<BITS, WBITS, 256, 192, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
         if (cost_c < cost_a) return launch_cfg<BITS, WBITS, 192, 256, 2, 4, 128, 2, 1, 4, MODE>(a, stream);
     }
-    // Equal 4-bit widths run this tile on the 16 x 16 matrix instructions (quik_gemm_tiles16.hip), under which
-    // the chip keeps its clock: 2 - 6 % faster here, where two waves share every SIMD.  The smaller tiles
+    // Equal widths run this tile on the 16 x 16 matrix instructions (quik_gemm_tiles16.hip), under which the
+    // chip keeps its clock: 2 - 6 % faster here with 4-bit operands, where two waves share every SIMD, 10 %
+    // with 8-bit ones (full bytes cost the 32 x 32 form most clock).  The smaller tiles
     // above mostly run one wave per SIMD, which the 16 x 16 form's doubled instruction count slows down
     // (128 tokens of the 13B QKV shape: +7 %), and the larger ones do not fit the register file in that form.
-    if constexpr (BITS == 4 && WBITS == 4) return launch_gemm_tiles16(a, stream);
+    if constexpr (BITS == WBITS) return launch_gemm_tiles16(a, stream);
     else return launch_cfg<BITS, WBITS, 256, 128, 4, 2, 128, 2, 1, 4, MODE>(a, stream);
 }
 

@@ -1,19 +1,19 @@
-// Per-tile form of the 4-bit integer GEMM + dequantization epilogue + fp16 outlier GEMM on the
+// Per-tile form of the integer GEMM + dequantization epilogue + fp16 outlier GEMM on the
 // 16 x 16 matrix instructions (Algorithm 1 of arXiv 2310.09259: "INTmatmul", "Dequantization",
 // "FPmatmul" and the final add; epilogue fusion as in Section 3.4).
 //
 // Same data path, operand formats, widenings, stage ring, tile shapes and epilogue arithmetic as
 // gemm_kernel in quik_gemm.hip (see the header of that file; the output is bit-identical), for equal
-// 4-bit widths only.  What differs is the matrix instruction: v_mfma_i32_16x16x64_i8 for the integer
-// product and v_mfma_f32_16x16x32_f16 for the outlier product.  On MI355X the chip holds its full clock
-// under these, where it lowers it under the 32 x 32 forms on the same operand bytes (measured: 8 % on the
-// LLaMA-7B down-projection at 2048 tokens).
+// operand widths (4 + 4 or 8 + 8 bits).  What differs is the matrix instruction: v_mfma_i32_16x16x64_i8
+// for the integer product and v_mfma_f32_16x16x32_f16 for the outlier product.  On MI355X the chip holds
+// its full clock under these, where it lowers it under the 32 x 32 forms on the same operand bytes.
 //
 // Layout.  Lane (l = lane % 16, g = lane / 16) supplies the 16 int8 values of k-group g for token row
 // (or channel) l of a 16-row block: 8 packed bytes, bytes 8g .. 8g + 7 of the sub-step's 32 bytes of
 // that row, read with ds_read_b64 and widened into the four registers of one operand.  It holds, in the
 // four registers of a 16 x 16 accumulator block, channel l of token rows 4g .. 4g + 3.  An fp16 k-step
-// is 32 columns (64 bytes of a row): lane (l, g) supplies columns 8g .. 8g + 7, one 16-byte piece.
+// is 32 columns (64 bytes of a row): lane (l, g) supplies columns 8g .. 8g + 7, one 16-byte piece; an
+// 8-bit integer k-step is 64 bytes of a row likewise, the 16-byte piece being the operand itself.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
@@ -33,10 +33,10 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 // buffers, GM = m-tiles per group of the tile order (0: plain column sweep).
 // MODE 0: fused epilogue (single-AND widening + correction); MODE 1: raw INT32 accumulators, symmetric
 // widening; MODE 2: raw accumulators, single-AND widening + correction.
-template <int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
+template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
 __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
-    constexpr bool ASYM = MODE != 1;
+    constexpr bool ASYM = (BITS == 4) && (MODE != 1);
     // Every form claims the full share of the register file its launch bounds give it (two waves per
     // SIMD: 256 registers), so that the top of the allocation is never a live register: the
     // row-quantization kernel misread such a register on MI355X when its allocation ended below its share.
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
     static_assert(A_INSTR >= 1 && B_INSTR >= 1, "tile too small for the wave count");
     constexpr int LPS = A_INSTR + B_INSTR;
     constexpr int KSUB = BKB / 32;
-    constexpr int SHIFT = ASYM ? 4 : 8;
+    constexpr int SHIFT = (BITS == 4) ? (ASYM ? 4 : 8) : 0;
     constexpr int A_BYTES = BM * BKB, B_BYTES = BN * BKB, ST_BYTES = A_BYTES + B_BYTES;
     constexpr int NF = IB + JB;                          // fragments per sub-step
     constexpr int SLOTS = IB * JB;                       // MFMAs per sub-step
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
     }
     const int t0 = tile_m * BM, n0 = tile_n * BN;
 
-    const int row_bytes = a.K_b / 2;
+    const int row_bytes = a.K_b * BITS / 8;
     const int int_bytes = (row_bytes + 15) & ~15;
     const int nk_int = a.fp_only ? 0 : (row_bytes + BKB - 1) / BKB;
     const int fp_bytes = a.n_out * 2;
@@ -167,7 +167,8 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
             const bool ok = (tid + q * NT < BM) && t < a.T;
             p_s[q] = ok ? a.scale[t] : 0.0f;
             p_z[q] = ok ? a.zero[t] : 0.0f;
-            p_c[q] = (ok && !a.fp_only) ? a.code_sum[t] : 0;
+            p_c[q] = 0;
+            if constexpr (ASYM) p_c[q] = (ok && !a.fp_only) ? a.code_sum[t] : 0;
         }
         const __half* __restrict__ wsc = static_cast<const __half*>(a.w_scale);
         const __half* __restrict__ bias = static_cast<const __half*>(a.bias);
@@ -177,7 +178,8 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
             c_sw[j] = __half2float(wsc[n]) * (1.0f / (float)(1 << SHIFT));   // exact power-of-two factor
             c_bv[j] = bias ? __half2float(bias[n]) : 0.0f;
             c_wr[j] = a.w_reduced[n];
-            c_nc[j] = a.fp_only ? 0 : -128 * a.w_code_sum[n];
+            c_nc[j] = 0;
+            if constexpr (ASYM) c_nc[j] = a.fp_only ? 0 : -128 * a.w_code_sum[n];
             if (a.fp_only) { c_sw[j] = 0.0f; c_bv[j] = 0.0f; c_wr[j] = 0.0f; }
         }
     }
@@ -192,40 +194,11 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
             const int r = tid + q * NT;
             if (r < BM) {
                 lds_sa[r] = p_s[q];                                          // scaleAct
-                lds_sh[r] = p_z[q] + 8.0f * p_s[q];                          // zeroAct + halfRange * scaleAct
-                lds_ct[r] = -128 * p_c[q];                                   // in raw accumulator units
+                lds_sh[r] = p_z[q] + (float)(1 << (BITS - 1)) * p_s[q];      // zeroAct + halfRange * scaleAct
+                if constexpr (ASYM) lds_ct[r] = -128 * p_c[q];               // in raw accumulator units
             }
         }
     }
-
-    // fragment addresses inside a stage buffer: row l of 16-row block f, sub-step ks, k-group g
-    uint32_t rd[NF][KSUB];
-#pragma unroll
-    for (int f = 0; f < NF; ++f) {
-        int r = (f < IB) ? (wm * IB * 16 + f * 16 + l16) : (wn * JB * 16 + (f - IB) * 16 + l16);
-        uint32_t base = (f < IB ? 0 : A_BYTES) + r * BKB;
-#pragma unroll
-        for (int ks = 0; ks < KSUB; ++ks) rd[f][ks] = base + (((ks * 2 + (g >> 1)) ^ swz<BKB>(r)) << 4) + (g & 1) * 8;
-    }
-
-    uint2 R[RD][NF];
-    v4i U[2][NF];
-    auto read_frag = [&](int set, int f, const uint8_t* stage, int ks) {
-        R[set][f] = *reinterpret_cast<const uint2*>(stage + rd[f][ks]);
-    };
-    // word w (fragment w / 2, word w % 2) of raw set `rset`, widened into operand set `set`: slot 0 of a
-    // word pair holds the even k of the word, slot 1 the odd k
-    auto widen_word = [&](int set, int rset, int w) {
-        constexpr uint32_t M = 0xF0F0F0F0u;
-        const int f = w >> 1, k = w & 1;
-        const bool act = f < IB;                         // activations: even k in the high nibble
-        const uint32_t x = k ? R[rset][f].y : R[rset][f].x;
-        const uint32_t hi = x & M;                       // 16 * signed high nibble
-        const uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)   // low nibble + 8
-                                 : ((x << 4) & M);                     // 16 * signed low nibble
-        U[set][f][2 * k] = (int)(act ? hi : lo);
-        U[set][f][2 * k + 1] = (int)(act ? lo : hi);
-    };
 
     v4i acc[IB][JB];
 #pragma unroll
@@ -241,55 +214,136 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
         __syncthreads();
     };
 
-    // sub-step ks of stage s.  PLAIN: the DMA into the freed buffer is a full int stage and is spread over
-    // the MFMA slots that follow the barrier; otherwise it is issued in one go.
-    auto substep = [&](int s, int ks, bool plain) {
-        const int par = ks & 1;
-        if (ks == BAR_KS) {
-            stage_barrier();
-            if (!plain) issue_any(s + NST);
-        }
-        const int ts = (ks + LA < KSUB) ? s : s + 1, tks = (ks + LA) % KSUB;
-        const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
-        const int rnext = (ks + 1) % RD, rload = (ks + LA) % RD;
-        __builtin_amdgcn_sched_barrier(0);
+    v4i U[2][NF];
+    // 16-byte fragments of a 64-byte k-step (an fp16 k-step of 32 columns; an 8-bit integer k-step of 64):
+    // row l of 16-row block f, k-step kk of a stage, k-group g
+    uint32_t fpo[NF][2];
 #pragma unroll
-        for (int m = 0; m < SLOTS; ++m) {
-            const int j = m / IB, i = m % IB;
-            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(U[par][i], U[par][IB + j], acc[i][j], 0, 0, 0);
-            if (plain && ks == BAR_KS) {
-                constexpr int PER = (SLOTS >= LPS) ? SLOTS / LPS : 1;
-                if (m % PER == 0 && m / PER < LPS) issue_one(s + NST, m / PER);
-                if (SLOTS < LPS && m == SLOTS - 1)
-                    for (int d = SLOTS; d < LPS; ++d) issue_one(s + NST, d);
-            }
+    for (int f = 0; f < NF; ++f) {
+        int r = (f < IB) ? (wm * IB * 16 + f * 16 + l16) : (wn * JB * 16 + (f - IB) * 16 + l16);
+        uint32_t base = (f < IB ? 0 : A_BYTES) + r * BKB;
 #pragma unroll
-            for (int w = 0; w < WORDS; ++w)
-                if (w * SLOTS / WORDS == m) widen_word(par ^ 1, rnext, w);
-            if (m >= RO && m - RO < NF) read_frag(rload, m - RO, tgt, tks);
-            if (SLOTS - RO < NF && m == SLOTS - 1)
-                for (int f = SLOTS - RO; f < NF; ++f) read_frag(rload, f, tgt, tks);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        for (int kk = 0; kk < 2; ++kk) fpo[f][kk] = base + (((kk * 4 + g) ^ swz<BKB>(r)) << 4);
+    }
+    auto read_fp = [&](int kk, int st) {
+        const uint8_t* stage = lds + (st % NST) * ST_BYTES;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) U[kk][f] = *reinterpret_cast<const v4i*>(stage + fpo[f][kk]);
     };
 
-    wait_vm<(NST - 1) * LPS>();          // stage 0 landed
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < LA; ++q)
-#pragma unroll
-        for (int f = 0; f < NF; ++f) read_frag(q, f, lds, q);
-#pragma unroll
-    for (int w = 0; w < WORDS; ++w) widen_word(0, 0, w);
-
     int s = 0;
-    for (; s + NST < nk_int - 1; ++s) {
+    if constexpr (BITS == 4) {
+        // fragment addresses inside a stage buffer: row l of 16-row block f, sub-step ks, k-group g
+        uint32_t rd[NF][KSUB];
+    #pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            int r = (f < IB) ? (wm * IB * 16 + f * 16 + l16) : (wn * JB * 16 + (f - IB) * 16 + l16);
+            uint32_t base = (f < IB ? 0 : A_BYTES) + r * BKB;
+    #pragma unroll
+            for (int ks = 0; ks < KSUB; ++ks) rd[f][ks] = base + (((ks * 2 + (g >> 1)) ^ swz<BKB>(r)) << 4) + (g & 1) * 8;
+        }
+
+        uint2 R[RD][NF];
+        auto read_frag = [&](int set, int f, const uint8_t* stage, int ks) {
+            R[set][f] = *reinterpret_cast<const uint2*>(stage + rd[f][ks]);
+        };
+        // word w (fragment w / 2, word w % 2) of raw set `rset`, widened into operand set `set`: slot 0 of a
+        // word pair holds the even k of the word, slot 1 the odd k
+        auto widen_word = [&](int set, int rset, int w) {
+            constexpr uint32_t M = 0xF0F0F0F0u;
+            const int f = w >> 1, k = w & 1;
+            const bool act = f < IB;                         // activations: even k in the high nibble
+            const uint32_t x = k ? R[rset][f].y : R[rset][f].x;
+            const uint32_t hi = x & M;                       // 16 * signed high nibble
+            const uint32_t lo = ASYM ? ((x ^ 0x08080808u) & 0x0F0F0F0Fu)   // low nibble + 8
+                                     : ((x << 4) & M);                     // 16 * signed low nibble
+            U[set][f][2 * k] = (int)(act ? hi : lo);
+            U[set][f][2 * k + 1] = (int)(act ? lo : hi);
+        };
+
+        // sub-step ks of stage s.  PLAIN: the DMA into the freed buffer is a full int stage and is spread over
+        // the MFMA slots that follow the barrier; otherwise it is issued in one go.
+        auto substep = [&](int s, int ks, bool plain) {
+            const int par = ks & 1;
+            if (ks == BAR_KS) {
+                stage_barrier();
+                if (!plain) issue_any(s + NST);
+            }
+            const int ts = (ks + LA < KSUB) ? s : s + 1, tks = (ks + LA) % KSUB;
+            const uint8_t* tgt = lds + (ts % NST) * ST_BYTES;
+            const int rnext = (ks + 1) % RD, rload = (ks + LA) % RD;
+            __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+            for (int m = 0; m < SLOTS; ++m) {
+                const int j = m / IB, i = m % IB;
+                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(U[par][i], U[par][IB + j], acc[i][j], 0, 0, 0);
+                if (plain && ks == BAR_KS) {
+                    constexpr int PER = (SLOTS >= LPS) ? SLOTS / LPS : 1;
+                    if (m % PER == 0 && m / PER < LPS) issue_one(s + NST, m / PER);
+                    if (SLOTS < LPS && m == SLOTS - 1)
+                        for (int d = SLOTS; d < LPS; ++d) issue_one(s + NST, d);
+                }
+    #pragma unroll
+                for (int w = 0; w < WORDS; ++w)
+                    if (w * SLOTS / WORDS == m) widen_word(par ^ 1, rnext, w);
+                if (m >= RO && m - RO < NF) read_frag(rload, m - RO, tgt, tks);
+                if (SLOTS - RO < NF && m == SLOTS - 1)
+                    for (int f = SLOTS - RO; f < NF; ++f) read_frag(rload, f, tgt, tks);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+
+        wait_vm<(NST - 1) * LPS>();          // stage 0 landed
+        __syncthreads();
+    #pragma unroll
+        for (int q = 0; q < LA; ++q)
+    #pragma unroll
+            for (int f = 0; f < NF; ++f) read_frag(q, f, lds, q);
+    #pragma unroll
+        for (int w = 0; w < WORDS; ++w) widen_word(0, 0, w);
+
+        for (; s + NST < nk_int - 1; ++s) {
+    #pragma unroll
+            for (int ks = 0; ks < KSUB; ++ks) substep(s, ks, true);
+        }
+        for (; s < nk_int; ++s) {
+    #pragma unroll
+            for (int ks = 0; ks < KSUB; ++ks) substep(s, ks, false);
+        }
+    } else {
+        // 8-bit operands go from LDS into the matrix instruction as they are: lane (l, g) supplies bytes
+        // 16g .. 16g + 15 of a 64-byte k-step, two k-steps per stage.  The two operand sets hold the stage's
+        // two k-steps; a set is refilled with the same k-step of the next stage once its MFMAs are issued.
+        // The stage barrier sits after the first k-step's MFMAs: every read of this stage was issued during
+        // the stage before, so its buffer is free, and the reads that follow go to the next stage.
+        auto int8_mfmas = [&](int kk, int s_, bool copies) {
 #pragma unroll
-        for (int ks = 0; ks < KSUB; ++ks) substep(s, ks, true);
-    }
-    for (; s < nk_int; ++s) {
-#pragma unroll
-        for (int ks = 0; ks < KSUB; ++ks) substep(s, ks, false);
+            for (int m = 0; m < SLOTS; ++m) {
+                const int j = m / IB, i = m % IB;
+                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(U[kk][i], U[kk][IB + j], acc[i][j], 0, 0, 0);
+                if (copies) {
+                    constexpr int PER = (SLOTS >= LPS) ? SLOTS / LPS : 1;
+                    if (m % PER == 0 && m / PER < LPS) issue_one(s_ + NST, m / PER);
+                    if (SLOTS < LPS && m == SLOTS - 1)
+                        for (int d = SLOTS; d < LPS; ++d) issue_one(s_ + NST, d);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto int8_stage = [&](int s_, bool plain) {
+            int8_mfmas(0, s_, false);
+            stage_barrier();
+            if (!plain) issue_any(s_ + NST);
+            read_fp(0, s_ + 1);
+            int8_mfmas(1, s_, plain);
+            read_fp(1, s_ + 1);
+        };
+        wait_vm<(NST - 1) * LPS>();          // stage 0 landed
+        __syncthreads();
+        read_fp(0, 0);
+        read_fp(1, 0);
+        for (; s + NST < nk_int - 1; ++s) int8_stage(s, true);
+        for (; s < nk_int; ++s) int8_stage(s, false);
     }
 
     const int tw = t0 + wm * IB * 16, nw = n0 + wn * JB * 16;
@@ -312,23 +366,27 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
             }
         return;
     }
-    // Dequantization.  The raw accumulator is 16 times the integer dot product plus
-    // 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes that, the conversion to binary32
-    // is exact (at most 24 significant bits), and 2^-4 rides on the weight scale.
+    // Dequantization.  The raw accumulator is 2^SHIFT times the integer dot product plus, for the
+    // single-AND widening, 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes that, the
+    // conversion to binary32 is exact (at most 24 significant bits), and 2^-SHIFT rides on the weight scale.
     v4f cf[IB][JB];
 #pragma unroll
     for (int i = 0; i < IB; ++i) {
         const int lr = wm * IB * 16 + i * 16 + 4 * g;
         const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
         const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
-        const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[lr]);
         const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
-        const int ct_[4] = {ct4.x, ct4.y, ct4.z, ct4.w};
+        int ct_[4] = {0, 0, 0, 0};
+        if constexpr (ASYM) {
+            const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[lr]);
+            ct_[0] = ct4.x; ct_[1] = ct4.y; ct_[2] = ct4.z; ct_[3] = ct4.w;
+        }
 #pragma unroll
         for (int j = 0; j < JB; ++j)
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                const int ai = acc[i][j][rr] + ct_[rr] + c_nc[j];
+                int ai = acc[i][j][rr];
+                if constexpr (ASYM) ai = ai + ct_[rr] + c_nc[j];
                 cf[i][j][rr] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j], __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
             }
     }
@@ -338,19 +396,6 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
     // k-step of the next stage once its MFMAs are issued.  The stage barrier sits after the first k-step's
     // MFMAs: every read of this stage was issued during the stage before, so its buffer is free, and the
     // reads that follow go to the next stage, which must have landed.
-    uint32_t fpo[NF][2];
-#pragma unroll
-    for (int f = 0; f < NF; ++f) {
-        int r = (f < IB) ? (wm * IB * 16 + f * 16 + l16) : (wn * JB * 16 + (f - IB) * 16 + l16);
-        uint32_t base = (f < IB ? 0 : A_BYTES) + r * BKB;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) fpo[f][kk] = base + (((kk * 4 + g) ^ swz<BKB>(r)) << 4);
-    }
-    auto read_fp = [&](int kk, int st) {
-        const uint8_t* stage = lds + (st % NST) * ST_BYTES;
-#pragma unroll
-        for (int f = 0; f < NF; ++f) U[kk][f] = *reinterpret_cast<const v4i*>(stage + fpo[f][kk]);
-    };
     auto fp_mfmas = [&](int kk) {
 #pragma unroll
         for (int m = 0; m < SLOTS; ++m) {
@@ -359,7 +404,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
                                                              __builtin_bit_cast(v8h, U[kk][IB + j]), cf[i][j], 0, 0, 0);
         }
     };
-    if (s < nk) {
+    if (BITS == 4 && s < nk) {           // (the 8-bit loop has already read them)
         read_fp(0, s);
         read_fp(1, s);
     }
@@ -435,24 +480,28 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
         }
 }
 
-template <int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
+template <int BITS, int BM, int BN, int WM, int WN, int BKB, int NST, int OCC, int GM, int MODE>
 hipError_t launch_cfg(const GemmArgs& a, hipStream_t stream) {
     int tiles = ((a.T + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_tiles16_kernel<BM, BN, WM, WN, BKB, NST, OCC, GM, MODE>), dim3(tiles),
+    hipLaunchKernelGGL((gemm_tiles16_kernel<BITS, BM, BN, WM, WN, BKB, NST, OCC, GM, MODE>), dim3(tiles),
                        dim3(WM * WN * 64), 0, stream, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// 4-bit activations and weights, 256 x 128 tiles: eight waves, one workgroup per CU.  (The kernel is written
-// for any tile of gemm_kernel's; the smaller ones mostly run one wave per SIMD, which this form's doubled
-// instruction count slows down, and 64 x 96 or 96 x 64 per wave do not fit the register file in it.)
+// Equal operand widths, 256 x 128 tiles: eight waves, one workgroup per CU.  (The kernel is written for any
+// tile of gemm_kernel's; the smaller ones mostly run one wave per SIMD, which this form's doubled instruction
+// count slows down, and 64 x 96 or 96 x 64 per wave do not fit the register file in it.)
 hipError_t launch_gemm_tiles16(const GemmArgs& a, hipStream_t stream) {
     const bool raw = a.y == nullptr;
-    if (!raw) return launch_cfg<256, 128, 4, 2, 128, 2, 1, 4, 0>(a, stream);
-    if (a.code_sum && a.w_code_sum) return launch_cfg<256, 128, 4, 2, 128, 2, 1, 4, 2>(a, stream);
-    return launch_cfg<256, 128, 4, 2, 128, 2, 1, 4, 1>(a, stream);
+    if (a.bits == 8) {
+        if (!raw) return launch_cfg<8, 256, 128, 4, 2, 128, 2, 1, 4, 0>(a, stream);
+        return launch_cfg<8, 256, 128, 4, 2, 128, 2, 1, 4, 1>(a, stream);
+    }
+    if (!raw) return launch_cfg<4, 256, 128, 4, 2, 128, 2, 1, 4, 0>(a, stream);
+    if (a.code_sum && a.w_code_sum) return launch_cfg<4, 256, 128, 4, 2, 128, 2, 1, 4, 2>(a, stream);
+    return launch_cfg<4, 256, 128, 4, 2, 128, 2, 1, 4, 1>(a, stream);
 }
 
 }  // namespace quik

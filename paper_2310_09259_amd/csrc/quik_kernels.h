@@ -108,7 +108,7 @@ __host__ __device__ inline void stream_panel(const StreamPlan& p, int nt, int* b
 hipError_t launch_quantize(const QuantizeArgs& a, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_gemm_tiles(const GemmArgs& a, hipStream_t stream);
-// equal 4-bit widths, 256 x 128 tiles: the per-tile kernel on 16 x 16 matrix instructions (quik_gemm_tiles16.hip)
+// equal operand widths, 256 x 128 tiles: the per-tile kernel on 16 x 16 matrix instructions (quik_gemm_tiles16.hip)
 hipError_t launch_gemm_tiles16(const GemmArgs& a, hipStream_t stream);
 hipError_t launch_weight_reduce(const WeightReduceArgs& a, hipStream_t stream);
 bool plan_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p);
