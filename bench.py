@@ -494,7 +494,9 @@ def main():
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     plan = api.quik_debug_gemm_plan(T, N, K_b, cus) if (bits == 4 and not mixed) else None
     persistent = plan is not None and args.gemm_path != "tiles" and (plan[0] == 1 or args.gemm_path == "persistent")
-    gemm_kernel_name = "gemm_stream_kernel" if persistent else "gemm_kernel"
+    # per-tile family: gemm_tiles16_kernel runs the 256 x 128 tiles of equal operand widths, gemm_kernel /
+    # gemm_skinny the other tiles (the dispatch in quik_gemm.hip decides)
+    gemm_kernel_name = "gemm_stream_kernel" if persistent else "gemm_kernel|gemm_tiles16_kernel"
     tops = ops_layer / (ms_step * 1e-3) / 1e12
     gemm_tops = ops_int / (ms_gemm * 1e-3) / 1e12
     out = {
