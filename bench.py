@@ -196,12 +196,13 @@ def run_mix_probe(api, torch):
     src = torch.randint(0, 255, (32 << 20,), dtype=torch.uint8, device=dev)
     clocks = torch.zeros(2, dtype=torch.int64, device=dev)
     iters = 4000
-    names = {1: "changing random operands", 32: "as widened nibbles (4 varying bits per byte)", 2: "4 vector ops per MFMA",
+    names = {1: "changing random operands", 32: "as widened nibbles (4 varying bits per byte)",
+             64: "on the 16x16x64 instruction (two per 32x32x32-equivalent, 8-byte LDS reads)", 2: "4 vector ops per MFMA",
              4: "5 LDS reads per 12 MFMAs", 8: "2 copies per 12 MFMAs", 16: "barrier per 48 MFMAs"}
     rows = []
     base = None
     _preheat(lambda: api.quik_debug_mix_probe(0, cus, iters, sink), torch)
-    for mix in (0, 1, 3, 5, 9, 17, 7, 11, 13, 15, 31, 33, 35, 37, 41, 47, 63):
+    for mix in (0, 1, 3, 5, 9, 17, 7, 11, 13, 15, 31, 33, 35, 37, 41, 47, 63, 97, 127):
         call = lambda: api.quik_debug_mix_probe(mix, cus, iters, sink, src if mix & 8 else None, clocks)
         ops = call()
         ms = _kernel_ms(call, torch, 30)
@@ -392,7 +393,7 @@ def main():
     cus_ = torch.cuda.get_device_properties(0).multi_processor_count
     mix_src = torch.randint(0, 255, (32 << 20,), dtype=torch.uint8, device=dev)
     mix_tops = {}
-    for mix in (1, 31, 33, 63):
+    for mix in (1, 31, 33, 63, 97, 127):
         mix_ops = api.quik_debug_mix_probe(mix, cus_, 2000, sink, mix_src if mix & 8 else None)
         ms_mix = _kernel_ms(lambda: api.quik_debug_mix_probe(mix, cus_, 2000, sink, mix_src if mix & 8 else None), torch, 20)
         mix_tops[mix] = mix_ops / (ms_mix * 1e-3) / 1e12
@@ -535,12 +536,15 @@ def main():
                            "int8_mfma_TOPS_k_loop_mix": mix_tops[31],
                            "int8_mfma_TOPS_nibble_operands": mix_tops[33],
                            "int8_mfma_TOPS_k_loop_mix_nibble_operands": mix_tops[63],
+                           "int8_mfma_16x16x64_TOPS_nibble_operands": mix_tops[97],
+                           "int8_mfma_16x16x64_TOPS_k_loop_mix_nibble_operands": mix_tops[127],
                            "copy_GBs": measured_hbm_gbs,
                            "what": "quik_debug_mfma_probe (independent 32x32x32 int8 matrix instructions on "
                                    "register-resident operands of small values), quik_debug_mix_probe 1 (the same on "
                                    "operands of pseudo-random bytes) and 31 (with the vector, LDS, copy and barrier "
                                    "instructions of the GEMM's K loop beside them, no dependences), 33 and 63 (as 1 and 31 "
-                                   "on operand bytes of the kind the GEMM's nibble widening makes -- the ceiling for its own operands), "
+                                   "on operand bytes of the kind the GEMM's nibble widening makes -- the ceiling for its own operands), 97 and 127 "
+                                   "(as 33 and 63 on the 16 x 16 x 64 instruction of the persistent kernel), "
                                    "quik_debug_copy_probe (512 MiB streaming copy, read + write bytes)"},
         "roofline": {"bound": "mfma", "kernel": gemm_kernel_name + " (INT GEMM + dequant + outlier GEMM)",
                      "achieved": gemm_tops, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
@@ -549,6 +553,8 @@ def main():
                      "frac_of_measured_mfma_peak_random_operands": gemm_tops / mix_tops[1],
                      "frac_of_measured_k_loop_mix": gemm_tops / mix_tops[31],
                      "frac_of_measured_k_loop_mix_nibble_operands": gemm_tops / mix_tops[63],
+                     # the persistent kernel's own instruction shape (the per-tile 32 x 32 forms: the row above)
+                     "frac_of_measured_k_loop_mix_16x16x64": gemm_tops / mix_tops[127],
                      "same_launch_on_constant_operands": None if ms_gemm_flat is None else {
                          "ms": ms_gemm_flat, "frac": ops_int / (ms_gemm_flat * 1e-3) / 1e12 / PEAK_INT8_TOPS,
                          "what": "every packed operand byte 0x88 (all codes zero): the clock the chip holds depends "

@@ -469,9 +469,12 @@ int quik_debug_copy_probe(const void *src, void *dst, size_t bytes, void *stream
  *      them: half of the operand words vary in the high nibble of every byte only, the other half
  *      in the low nibble only.  The clock the chip sustains depends on how many operand bits toggle,
  *      so the rates with this bit set are the ceiling for the GEMM's own operands.
+ *  64  the same work on the 16 x 16 x 64 int8 matrix instruction (two in place of every 32 x 32 x 32 one,
+ *      ten 8-byte LDS reads in place of five 16-byte ones): the persistent kernel's instruction.  Only as
+ *      mix = 97 (matrix instructions alone on widened-nibble operands) and mix = 127 (the whole mix).
  * clocks (DEVICE uint64 [2], or NULL): ticks of the s_memtime and of the s_memrealtime counter over
  * the loop of workgroup 0 (for comparing loads with each other).  `sink` as above.
- * QUIK_EINVAL for mix outside 0..63, for bit 32 without bit 1, or bad sizes; QUIK_ENULL, QUIK_EALIGN.
+ * QUIK_EINVAL for mix outside 0..63, 97, 127, for bit 32 without bit 1, or bad sizes; QUIK_ENULL, QUIK_EALIGN.
  */
 int quik_debug_mix_probe(int mix, int workgroups, int iters, int32_t *sink, const void *src, size_t src_bytes,
                          unsigned long long *clocks, void *stream);

@@ -710,7 +710,9 @@ int quik_debug_mfma_probe(int workgroups, int iters, int32_t* sink, void* stream
 
 int quik_debug_mix_probe(int mix, int workgroups, int iters, int32_t* sink, const void* src, size_t src_bytes,
                          unsigned long long* clocks, void* stream) {
-    if (mix < 0 || mix > 63 || ((mix & 32) && !(mix & 1)) || workgroups <= 0 || workgroups > 4096 || iters <= 0) return QUIK_EINVAL;
+    if (mix < 0 || (mix > 63 && mix != 97 && mix != 127) || ((mix & 32) && !(mix & 1)) || workgroups <= 0 || workgroups > 4096 ||
+        iters <= 0)
+        return QUIK_EINVAL;
     if (!sink) return QUIK_ENULL;
     if (mix & 8) {
         if (!src) return QUIK_ENULL;

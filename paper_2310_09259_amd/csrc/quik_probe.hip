@@ -46,6 +46,9 @@ __global__ __launch_bounds__(256) void mfma_i8_probe_kernel(int iters, int* sink
 //      operand's even words and the other's odd words only the high nibble of a byte varies (16 x a signed
 //      code), in the remaining words only the low nibble (a code + 8).  The clock the chip holds depends on
 //      how many operand bits toggle, so this -- not bit 1 alone -- is the ceiling for the GEMM's own operands.
+//  64  (with 1 and 32) the same work on v_mfma_i32_16x16x64_i8, the persistent kernel's instruction: two of
+//      them in place of every 32 x 32 x 32 one, and ten 8-byte LDS reads in place of five 16-byte ones.
+//      Built for mix 97 (matrix instructions alone) and 127 (the whole K-loop mix).
 // clocks[0], clocks[1]: the shader clock counter and the 100 MHz real-time counter over the loop of
 // workgroup 0 (their ratio is the clock the chip held under this load).
 constexpr int kMixWaves = 8, kMixMfma = 12, kMixAcc = 6;
@@ -54,7 +57,8 @@ template <int MIX>
 __global__ __launch_bounds__(kMixWaves * 64, 1) void mfma_mix_probe_kernel(int iters, int* sink, const uint8_t* src,
                                                                          uint32_t src_bytes, unsigned long long* clocks) {
     using namespace gemm_dev;
-    constexpr bool TOGGLE = MIX & 1, VALU = MIX & 2, LDSR = MIX & 4, COPY = MIX & 8, BARRIER = MIX & 16, NIBBLE = MIX & 32;
+    constexpr bool TOGGLE = MIX & 1, VALU = MIX & 2, LDSR = MIX & 4, COPY = MIX & 8, BARRIER = MIX & 16, NIBBLE = MIX & 32,
+                   X16 = MIX & 64;
     constexpr int NL = 5, ND = 2, WINDOW = 512 * 1024;
     asm volatile("" ::: "v255");       // a wave owns half of its SIMD's register file: claim it whole (see build.py)
     __shared__ __align__(1024) uint8_t frag[64 * 1024];
@@ -62,7 +66,7 @@ __global__ __launch_bounds__(kMixWaves * 64, 1) void mfma_mix_probe_kernel(int i
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     for (int i = threadIdx.x; i < 16 * 1024; i += blockDim.x) reinterpret_cast<int*>(frag)[i] = i * 0x9E3779B1u;
     __syncthreads();
-    v16i acc[kMixAcc];
+    v16i acc[kMixAcc];              // the 16 x 16 form uses them as 4 x kMixAcc blocks of four registers
 #pragma unroll
     for (int j = 0; j < kMixAcc; ++j)
 #pragma unroll
@@ -89,7 +93,11 @@ __global__ __launch_bounds__(kMixWaves * 64, 1) void mfma_mix_probe_kernel(int i
     const int l = lane & 31, kg = lane >> 5;
     const uint32_t faddr = lds_addr(frag) + (uint32_t)(wave * 4096 + l * 128 + ((kg ^ swz<128>(l)) << 4));
     typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
     u4 rr[NL];
+    u2 rh[2 * NL];
+#pragma unroll
+    for (int q = 0; q < 2 * NL; ++q) rh[q] = u2{0, 0};
 #pragma unroll
     for (int q = 0; q < NL; ++q) rr[q] = u4{0, 0, 0, 0};
     const v4i rs = make_rsrc(src, src_bytes);
@@ -101,13 +109,28 @@ __global__ __launch_bounds__(kMixWaves * 64, 1) void mfma_mix_probe_kernel(int i
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int m = 0; m < kMixMfma; ++m) {
-            acc[m % kMixAcc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[m % 4], b[(m + m / 4) % 4], acc[m % kMixAcc], 0, 0, 0);
+            if constexpr (X16) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {        // blocks 2 * (m / kMixAcc) + h of accumulator m % kMixAcc
+                    const int q0 = 8 * (m / kMixAcc) + 4 * h;
+                    v16i& c = acc[m % kMixAcc];
+                    v4i d = v4i{c[q0], c[q0 + 1], c[q0 + 2], c[q0 + 3]};
+                    d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[m % 4], b[(m + m / 4 + h) % 4], d, 0, 0, 0);
+                    c[q0] = d[0]; c[q0 + 1] = d[1]; c[q0 + 2] = d[2]; c[q0 + 3] = d[3];
+                }
+            } else {
+                acc[m % kMixAcc] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[m % 4], b[(m + m / 4) % 4], acc[m % kMixAcc], 0, 0, 0);
+            }
             if constexpr (VALU) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) asm volatile("v_and_b32 %0, 0xf0f0f0f0, %0" : "+v"(x[(m * 4 + v) % 8]));
             }
             if constexpr (LDSR) {
-                if (m < NL) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rr[m]) : "v"(faddr), "n"((m % 8) * 4096 % 32768));
+                if constexpr (X16) {
+                    if (m < 2 * NL) asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(rh[m < 2 * NL ? m : 0]) : "v"(faddr), "n"((m % 16) * 2048 % 32768));
+                } else {
+                    if (m < NL) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(rr[m]) : "v"(faddr), "n"((m % 8) * 4096 % 32768));
+                }
             }
             if constexpr (COPY) {
                 if (m < ND) dma16(rs, ring_base + (uint32_t)((((it & 3) * ND + m) * kMixWaves + wave) * 1024) % 65536u,
@@ -127,6 +150,8 @@ __global__ __launch_bounds__(kMixWaves * 64, 1) void mfma_mix_probe_kernel(int i
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int q = 0; q < NL; ++q) asm volatile("" ::"v"(rr[q]));
+#pragma unroll
+            for (int q = 0; q < 2 * NL; ++q) asm volatile("" ::"v"(rh[q]));
         }
     }
     if constexpr (COPY) wait_vm<0>();
@@ -172,6 +197,7 @@ hipError_t launch_mix_probe(int mix, int workgroups, int iters, int* sink, const
         QUIK_MIX_CASE(24) QUIK_MIX_CASE(25) QUIK_MIX_CASE(26) QUIK_MIX_CASE(27) QUIK_MIX_CASE(28) QUIK_MIX_CASE(29) QUIK_MIX_CASE(30) QUIK_MIX_CASE(31)
         QUIK_MIX_CASE(33) QUIK_MIX_CASE(35) QUIK_MIX_CASE(37) QUIK_MIX_CASE(39) QUIK_MIX_CASE(41) QUIK_MIX_CASE(43) QUIK_MIX_CASE(45) QUIK_MIX_CASE(47)
         QUIK_MIX_CASE(49) QUIK_MIX_CASE(51) QUIK_MIX_CASE(53) QUIK_MIX_CASE(55) QUIK_MIX_CASE(57) QUIK_MIX_CASE(59) QUIK_MIX_CASE(61) QUIK_MIX_CASE(63)
+        QUIK_MIX_CASE(97) QUIK_MIX_CASE(127)
         default: return hipErrorInvalidValue;
     }
 #undef QUIK_MIX_CASE

@@ -218,7 +218,8 @@ def test_mix_probe_rejects_bad_arguments(lib):
     fn = lib.quik_debug_mix_probe
     fn.argtypes = [i, i, i, vp, vp, C.c_size_t, vp, vp]
     p, u, null = vp(0x1000), vp(0x1004), vp(0)
-    assert fn(64, 256, 10, p, null, 0, null, null) == -1          # mix outside 0 .. 63
+    assert fn(64, 256, 10, p, null, 0, null, null) == -1          # mix outside 0 .. 63, 97, 127
+    assert fn(96, 256, 10, p, null, 0, null, null) == -1 and fn(128, 256, 10, p, null, 0, null, null) == -1
     assert fn(32, 256, 10, p, null, 0, null, null) == -1          # nibble operands without changing operands
     assert fn(-1, 256, 10, p, null, 0, null, null) == -1
     assert fn(0, 0, 10, p, null, 0, null, null) == -1

@@ -688,7 +688,7 @@ def test_measurement_probes_run(api):
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     src = torch.zeros(16 << 20, dtype=torch.uint8, device="cuda")
     clocks = torch.zeros(2, dtype=torch.int64, device="cuda")
-    for mix in (0, 1, 7, 8, 16, 31, 33, 63):
+    for mix in (0, 1, 7, 8, 16, 31, 33, 63, 97, 127):
         clocks.zero_()
         ops = api.quik_debug_mix_probe(mix, 64, 50, sink, src if mix & 8 else None, clocks)
         _sync()
