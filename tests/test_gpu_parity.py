@@ -120,6 +120,8 @@ INT_GEMM_SHAPES = [
     # the 1.5x-area tiles (256 x 192 for the shape above, 192 x 256 for this one): the accumulator hook
     # takes the tile choice of the fused call in every mode
     (576, 16640, 224, 4),
+    # one round of 256 x 128 tiles: the 16 x 16 per-tile kernel, both widths, K tail
+    (1000, 8190, 368, 4), (1000, 8190, 232, 8),
     # small-T paths: K-split kernel (T <= 32; K shorter than four stages, ragged N), 64 x 64 and
     # 128 x 64 tile configurations
     (32, 100, 160, 4), (7, 333, 2432, 4), (20, 95, 4864, 8), (50, 200, 992, 4), (64, 130, 480, 8),
@@ -215,6 +217,10 @@ LINEAR_SHAPES = [
     # 1.5x-area tiles: 256 x 192 is picked for the two shapes above; 192 x 256 for these
     synth.LayerShape("tiles_192x256", 576, 256, 16640, 32, 4, seed=49),
     synth.LayerShape("tiles_192x256_w8a8_ragged", 570, 256, 16630, 24, 8, seed=50),
+    # exactly one round of 256 x 128 tiles beats the larger tiles: the per-tile kernel on the 16 x 16 matrix
+    # instructions (4-bit and 8-bit forms), ragged T, N and K
+    synth.LayerShape("tiles16_256x128_ragged", 1000, 392, 8184, 24, 4, seed=55),
+    synth.LayerShape("tiles16_256x128_w8a8_ragged", 1000, 280, 8184, 40, 8, seed=56),
     # small-T paths
     synth.LayerShape("t32_ragged_n", 32, 1024, 333, 64, 4, seed=40),
     synth.LayerShape("t5_w8a8", 5, 512, 200, 16, 8, seed=44),
@@ -408,6 +414,8 @@ CANARY_SHAPES = [
     synth.LayerShape("canary_tiles", 300, 1096, 333, 32, 4, seed=92),         # per-tile kernel, ragged everything
     synth.LayerShape("canary_w8a8", 130, 1000, 140, 24, 8, seed=93),
     synth.LayerShape("canary_persistent", 1030, 1104, 9990, 40, 4, seed=94),  # persistent kernel
+    synth.LayerShape("canary_tiles16", 1000, 392, 8190, 24, 4, seed=95),      # 16 x 16 per-tile kernel
+    synth.LayerShape("canary_tiles16_w8a8", 1000, 280, 8190, 40, 8, seed=96),
 ]
 
 
