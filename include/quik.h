@@ -233,7 +233,9 @@ int quik_debug_gemm_plan(int T, int N, int K_b, int cus, int *plan);
  * tile[2] = number of channels (HOST pointer; the tile has 256 token rows, fewer at
  * the end of T).  Returns 1, or 0 if the workgroup has fewer than k + 1 tiles (tile
  * untouched), or QUIK_EINVAL (also when the persistent kernel cannot run the shape) /
- * QUIK_ENULL.
+ * QUIK_ENULL.  The kernel walks its tiles with divisors prepared on the host; the hook
+ * evaluates that walk and its definition with plain divisions, and returns
+ * QUIK_EUNSUPPORTED should the two ever differ.
  */
 int quik_debug_gemm_tile(int T, int N, int K_b, int cus, int workgroup, int k, int *tile);
 

@@ -138,8 +138,12 @@ int quik_debug_gemm_tile(int T, int N, int K_b, int cus, int workgroup, int k, i
     if (!tile) return QUIK_ENULL;
     quik::StreamPlan p;
     if (quik::choose_gemm_stream(T, N, K_b, cus, &p) == 0 || workgroup >= p.grid) return QUIK_EINVAL;
-    int nt, m, b0, w;
-    if (!quik::stream_tile(p, workgroup, k, &nt, &m)) return 0;
+    int nt, m, b0, w, nt_ref = -1, m_ref = -1;
+    const bool any = quik::stream_tile(p, workgroup, k, &nt, &m);
+    // the walk on the plan's prepared divisors against its definition with plain divisions
+    if (any != quik::stream_tile_reference(p, workgroup, k, &nt_ref, &m_ref) || (any && (nt != nt_ref || m != m_ref)))
+        return QUIK_EUNSUPPORTED;
+    if (!any) return 0;
     quik::stream_panel(p, nt, &b0, &w);
     tile[0] = m * quik::kStreamRows;
     tile[1] = b0 * 32;

@@ -469,12 +469,8 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                 // fp16 outlier stages on the dequantized tile (stage nk_int + f of the tile): two k-steps of 32
                 // columns (64 bytes of every row) per stage, one 16 x 16 x 32 instruction per accumulator block
                 // and k-step; lane (l, g) supplies columns 8g .. 8g + 7 of the k-step, one 16-byte piece.  The
-                // two operand sets of the integer phase (free now) hold the stage's two k-steps; a set is
-                // refilled with the same k-step of the next stage once its MFMAs are issued.
-                // The barrier sits after the first k-step's MFMAs: every read of this stage was issued during
-                // the stage before, so its slot is free, and the reads that follow go to the next stage,
-                // which must have landed.  LAST: the tile's last stage -- no look-ahead into the next tile,
-                // whose waves' column blocks may differ.
+                // two operand sets of the integer phase (free now) hold one k-step each; while one feeds the
+                // MFMAs, the other is refilled.
                 uint32_t fpA[2], fpB[2];
                 {
                     uint32_t lnu = (uint32_t)lane;
@@ -487,47 +483,50 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                         fpB[kk] = OFF_B + slot * SLOT_STRIDE + rb * BKB + (((kk * 4 + g) ^ swz<BKB>(rb)) << 4);
                     }
                 }
-                auto read_fp = [&](auto kk_c) QUIK_INLINE {
+                auto read_fp_frag = [&](auto kk_c, int f) QUIK_INLINE {
                     constexpr int KK = decltype(kk_c)::value;
-#pragma unroll
-                    for (int f = 0; f < NFA; ++f) {
-                        const uint32_t off = (f < IB) ? fpA[KK] + (uint32_t)(f * 16 * BKB) : fpB[KK] + (uint32_t)((f - IB) * 16 * BKB);
-                        U[KK][f] = *reinterpret_cast<const v4i*>(lds + off);
-                    }
+                    const uint32_t off = (f < IB) ? fpA[KK] + (uint32_t)(f * 16 * BKB) : fpB[KK] + (uint32_t)((f - IB) * 16 * BKB);
+                    U[KK][f] = *reinterpret_cast<const v4i*>(lds + off);
                 };
-                auto fp_mfmas = [&](auto kk_c, int slot_, bool copies) QUIK_INLINE {
+                // k-step KK of a stage: its MFMAs from set KK, and beside them, a fragment per MFMA slot, the
+                // reads that refill the other set -- the stage's second k-step during the first, the next
+                // stage's first k-step (other slot) during the second, together with the refill copies.
+                auto fp_mfmas = [&](auto kk_c, int slot_, bool reads) QUIK_INLINE {
                     constexpr int KK = decltype(kk_c)::value;
 #pragma unroll
                     for (int m = 0; m < NMF; ++m) {
                         const int j = m / IB, i = m % IB;
                         cf[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, U[KK][i]),
                                                                          __builtin_bit_cast(v8h, U[KK][IB + j]), cf[i][j], 0, 0, 0);
-                        // the refill, spread over the MFMAs of the k-step after the barrier
                         if (KK == 1 && m % CS == 0 && m / CS < LPS) issue_copy(rf, slot_, m / CS);
+                        if (m < NFA && reads) read_fp_frag(ic<KK ^ 1>{}, m);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    (void)copies;
-                    __builtin_amdgcn_sched_barrier(0);
                 };
+                // The barrier sits between the k-steps: every read of this stage has been issued by then (and is
+                // waited for), so its slot is free, and the reads that follow go to the next stage, which must
+                // have landed.  LAST: the tile's last stage -- no look-ahead into the next tile, whose waves'
+                // column blocks may differ.
                 auto fp_stage = [&](auto last_c, int f, int slot_) QUIK_INLINE {
                     constexpr bool LAST = decltype(last_c)::value != 0;
-                    fp_mfmas(ic<0>{}, slot_, false);
+                    fp_mfmas(ic<0>{}, slot_, true);
                     wait_vm<0>();
                     __syncthreads();
                     prep_refill(rf, nk_int + f);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fp_mfmas(ic<1>{}, slot_, !LAST);
 #pragma unroll
                     for (int kk = 0; kk < 2; ++kk) {
                         fpA[kk] ^= SLOT_STRIDE;
                         fpB[kk] ^= SLOT_STRIDE;
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (!LAST) read_fp(ic<0>{});
-                    fp_mfmas(ic<1>{}, slot_, true);
-                    if constexpr (!LAST) read_fp(ic<1>{});
                 };
-                // (unconditional: a conditional definition would keep the sets' registers occupied from the top
-                // of the epilogue)
-                read_fp(ic<0>{});
-                read_fp(ic<1>{});
+                // the first stage's first k-step (unconditional: a conditional definition would keep the set's
+                // registers occupied from the top of the epilogue); from here on set 0 is read in the other slot
+#pragma unroll
+                for (int f = 0; f < NFA; ++f) read_fp_frag(ic<0>{}, f);
+                fpA[0] ^= SLOT_STRIDE;
+                fpB[0] ^= SLOT_STRIDE;
                 for (int f = 0; f + 1 < nk_fp; ++f) {
                     fp_stage(ic<0>{}, f, slot);
                     slot ^= 1;
@@ -642,7 +641,7 @@ bool plan_gemm_stream(int T, int N, int K_b, int cus, StreamPlan* p) {
     p->base = nb / best_tn;
     p->rem = nb % best_tn;
     p->grid = cus;
-    return best < 1e29;
+    return best < 1e29 && finish_stream_plan(p);
 }
 
 hipError_t launch_gemm_stream(const GemmArgs& a, const StreamPlan& p, hipStream_t stream) {

@@ -62,11 +62,30 @@ struct WeightReduceArgs {
 // Tile plan of the persistent 4-bit GEMM (quik_gemm_stream.hip): every token-row panel of 256 rows is
 // cut into `tn` tiles along the output channels, `rem` of them `base + 1` blocks of 32 channels wide
 // and the others `base`, spread evenly; `grid` resident workgroups walk through the tiles.
+// The fields after `grid` are derived from the first five by finish_stream_plan(): whatever the walk over
+// the tiles would have to divide by is prepared on the host (a division of two run-time scalars costs a
+// workgroup some three hundred clocks, and the walk needs seventeen of them per tile).
 struct StreamPlan {
     int tiles_m, tn, base, rem, grid;
+    int per_xcd, tq, tr;                    // workgroups per XCD; tiles per XCD: tq, and one more on the first tr XCDs
+    int blocked_mask;                       // bit x: XCD x walks its range in the blocked order (see stream_tile)
+    int mpr[2], panels[2], inc[2];          // blocked order, XCDs with tq + 1 tiles [0] / with tq tiles [1]
+    unsigned long long mg_tiles_m, mg_tn, mg_mpr[2], mg_panels[2];   // stream_magic() of these divisors
 };
 constexpr int kStreamRows = 256;       // token rows per tile
 constexpr int kStreamXcds = 8;         // workgroup b runs on XCD b % 8
+constexpr int kStreamMagicBits = 40;
+constexpr int kStreamMagicRange = 1 << 20;   // stream_div is exact for x, d below this
+
+// x / d for 0 <= x, 1 <= d below kStreamMagicRange, with mg = stream_magic(d) = ceil(2^40 / d): mg * d =
+// 2^40 + e with e < d, so x * mg / 2^40 exceeds x / d by x * e / (d * 2^40) < x / 2^40 < 1 / d, too little to
+// carry the fraction of x / d (at most (d - 1) / d) to the next integer.
+inline unsigned long long stream_magic(int d) {
+    return d > 0 ? ((1ull << kStreamMagicBits) + (unsigned long long)d - 1) / (unsigned long long)d : 0;
+}
+__host__ __device__ inline int stream_div(int x, unsigned long long mg) {
+    return (int)(((unsigned long long)(unsigned)x * mg) >> kStreamMagicBits);
+}
 
 // The k-th tile of workgroup `block`: channel panel nt (of p.tn) and token panel m (of p.tiles_m), or false
 // if the workgroup has fewer tiles.  The tile list (channel panels outermost, the token panels of a channel
@@ -77,7 +96,14 @@ constexpr int kStreamXcds = 8;         // workgroup b runs on XCD b % 8
 // token panels (the activations pass through the L2 once per launch, the XCD's smaller share of the
 // weights once per round); from round to round a workgroup moves on by 1/rounds of the range's channel
 // panels, so that it meets the narrower and the wider tiles like in the plain order.
-__host__ __device__ inline bool stream_tile(const StreamPlan& p, int block, int k, int* nt, int* m) {
+// stream_tile_reference spells this out with plain divisions (host: tests and finish_stream_plan);
+// stream_tile is the same function on the plan's prepared values, for host and device.
+inline bool stream_range_blocked(const StreamPlan& p, int first, int count, int per_xcd) {
+    const int rounds = (count + per_xcd - 1) / per_xcd;
+    return rounds > 1 && first % p.tiles_m == 0 && count % p.tiles_m == 0 && count == rounds * per_xcd &&
+           p.tiles_m % rounds == 0 && (count / p.tiles_m) % rounds == 0;
+}
+inline bool stream_tile_reference(const StreamPlan& p, int block, int k, int* nt, int* m) {
     const int xcd = block % kStreamXcds, wg = block / kStreamXcds, per_xcd = p.grid / kStreamXcds;
     const int total = p.tiles_m * p.tn;
     const int tq = total / kStreamXcds, tr = total % kStreamXcds;
@@ -85,10 +111,8 @@ __host__ __device__ inline bool stream_tile(const StreamPlan& p, int block, int 
     const int count = tq + (xcd < tr ? 1 : 0);
     const int local = wg + k * per_xcd;
     if (k < 0 || local >= count) return false;
-    const int rounds = (count + per_xcd - 1) / per_xcd;
-    const bool blocked = rounds > 1 && first % p.tiles_m == 0 && count % p.tiles_m == 0 &&
-                         count == rounds * per_xcd && p.tiles_m % rounds == 0 && (count / p.tiles_m) % rounds == 0;
-    if (blocked) {
+    if (stream_range_blocked(p, first, count, per_xcd)) {
+        const int rounds = (count + per_xcd - 1) / per_xcd;
         const int m_per_round = p.tiles_m / rounds, panels = count / p.tiles_m;
         *nt = first / p.tiles_m + (wg / m_per_round + k * (panels / rounds)) % panels;
         *m = k * m_per_round + wg % m_per_round;
@@ -98,9 +122,55 @@ __host__ __device__ inline bool stream_tile(const StreamPlan& p, int block, int 
     }
     return true;
 }
+// fills the derived fields; false if a quantity leaves the range of stream_div
+inline bool finish_stream_plan(StreamPlan* p) {
+    const int per_xcd = p->grid / kStreamXcds;
+    const long total = (long)p->tiles_m * p->tn;
+    if (per_xcd < 1 || total >= kStreamMagicRange / 2 || (long)p->tn * p->tn >= kStreamMagicRange) return false;
+    p->per_xcd = per_xcd;
+    p->tq = (int)(total / kStreamXcds);
+    p->tr = (int)(total % kStreamXcds);
+    p->blocked_mask = 0;
+    for (int c = 0; c < 2; ++c) { p->mpr[c] = p->panels[c] = p->inc[c] = 1; }
+    for (int xcd = 0; xcd < kStreamXcds; ++xcd) {
+        const int c = xcd < p->tr ? 0 : 1;
+        const int first = c == 0 ? xcd * (p->tq + 1) : p->tr * (p->tq + 1) + (xcd - p->tr) * p->tq;
+        const int count = p->tq + (c == 0 ? 1 : 0);
+        if (count < 1 || !stream_range_blocked(*p, first, count, per_xcd)) continue;
+        const int rounds = (count + per_xcd - 1) / per_xcd;
+        p->blocked_mask |= 1 << xcd;
+        p->mpr[c] = p->tiles_m / rounds;
+        p->panels[c] = count / p->tiles_m;
+        p->inc[c] = p->panels[c] / rounds;
+    }
+    p->mg_tiles_m = stream_magic(p->tiles_m);
+    p->mg_tn = stream_magic(p->tn);
+    for (int c = 0; c < 2; ++c) { p->mg_mpr[c] = stream_magic(p->mpr[c]); p->mg_panels[c] = stream_magic(p->panels[c]); }
+    return true;
+}
+__host__ __device__ inline bool stream_tile(const StreamPlan& p, int block, int k, int* nt, int* m) {
+    const int xcd = block % kStreamXcds, wg = block / kStreamXcds;
+    const bool lo = xcd < p.tr;
+    const int first = lo ? xcd * (p.tq + 1) : p.tr * (p.tq + 1) + (xcd - p.tr) * p.tq;
+    const int count = p.tq + (lo ? 1 : 0);
+    const int local = wg + k * p.per_xcd;
+    if (k < 0 || local >= count) return false;
+    if ((p.blocked_mask >> xcd) & 1) {
+        const int mpr = lo ? p.mpr[0] : p.mpr[1], panels = lo ? p.panels[0] : p.panels[1], inc = lo ? p.inc[0] : p.inc[1];
+        const int q = stream_div(wg, lo ? p.mg_mpr[0] : p.mg_mpr[1]);
+        const int x = q + k * inc;                                     // < 2 * panels
+        *nt = stream_div(first, p.mg_tiles_m) + x - stream_div(x, lo ? p.mg_panels[0] : p.mg_panels[1]) * panels;
+        *m = k * mpr + wg - q * mpr;
+    } else {
+        const int idx = first + local, q = stream_div(idx, p.mg_tiles_m);
+        *nt = q;
+        *m = idx - q * p.tiles_m;
+    }
+    return true;
+}
 // first channel block and width (in 32-channel blocks) of channel panel nt
 __host__ __device__ inline void stream_panel(const StreamPlan& p, int nt, int* block0, int* width) {
-    const int lo = (nt * p.rem) / p.tn, hi = ((nt + 1) * p.rem) / p.tn;
+    const int lo = stream_div(nt * p.rem, p.mg_tn), hi = stream_div((nt + 1) * p.rem, p.mg_tn);   // x / p.tn
     *block0 = nt * p.base + lo;
     *width = p.base + hi - lo;
 }

@@ -158,6 +158,29 @@ def _tiles_of_workgroup(lib, T, N, K_b, b, cus=256):
         k += 1
 
 
+def test_persistent_kernel_tile_walk_matches_its_definition_on_random_shapes(lib):
+    """The kernel finds its tiles with divisions replaced by multiplications with host-prepared constants; the
+    hook fails (rc < 0, caught in _tiles_of_workgroup) if that walk ever differs from the definition with plain
+    divisions.  Random shapes and CU counts, every workgroup, every tile; the tiles must also cover the output
+    exactly once."""
+    rng = np.random.default_rng(20231009)
+    seen = 0
+    for _ in range(60):
+        cus = int(rng.choice([8, 16, 64, 104, 256, 304]))
+        T = int(rng.integers(1, 9000))
+        N = 2 * int(rng.integers(64, 20000))
+        K_b = 2 * int(rng.integers(512, 6000))
+        rc, plan = _plan(lib, T, N, K_b, cus)
+        if rc == 0:
+            continue
+        tiles_m, tn, base, rem, grid = plan
+        flat = [t for b in range(grid) for t in _tiles_of_workgroup(lib, T, N, K_b, b, cus)]
+        assert len(flat) == len(set(flat)) == tiles_m * tn, (T, N, K_b, cus)
+        assert sum(-(-t[2] // 32) for t in flat) == tiles_m * ((N + 31) // 32), (T, N, K_b, cus)
+        seen += 1
+    assert seen >= 20
+
+
 def test_persistent_kernel_plan_covers_the_output_and_balances_the_cus(lib):
     """Host logic of the persistent 4-bit kernel's tile plan, on the benchmark shapes (256 CUs)."""
     for T, N, K_b in ((2048, 11008, 3840), (2048, 4096, 10752), (4096, 15360, 4864), (4096, 28672, 7936),
