@@ -68,7 +68,7 @@ constexpr int A_BYTES = BM * BKB, B_BYTES = BNX * BKB;
 // LDS map.  The two ring slots of an operand are SLOT_STRIDE apart (a power of two, so that a fragment
 // address switches slots with one XOR); the gaps hold the epilogue parameters:
 //   0       weights, slot 0 (24 KB)      24576  parameters (7 KB)
-//   32768   weights, slot 1              57344  (free)
+//   32768   weights, slot 1              57344  code sums of the tile that starts next (2 KB)
 //   65536   activations, slot 0 (32 KB)  98304  activations, slot 1
 //   131072  per-wave output buffers
 constexpr int SLOT_STRIDE = 32768;
@@ -83,6 +83,9 @@ constexpr int PRM_SCALE = 0, PRM_ZERO = BM * 4, PRM_CSUM = 2 * BM * 4;
 constexpr int PRM_WSCALE = 3 * BM * 4, PRM_WRED = PRM_WSCALE + 1024, PRM_WCSUM = PRM_WRED + 1024,
               PRM_BIAS = PRM_WCSUM + 1024;
 static_assert(OFF_PRM + PRM_BIAS + 1024 <= SLOT_STRIDE, "parameters do not fit the gap");
+// code sums of the next tile's BM token rows and (up to) 256 channels: they are the accumulators' initial value
+constexpr int OFF_SUMS = SLOT_STRIDE + B_BYTES, SUMS_CS = 0, SUMS_WCS = BM * 4;
+static_assert(OFF_SUMS + SUMS_WCS + 1024 <= OFF_A, "code sums do not fit the gap");
 constexpr int SMEM_BYTES = OFF_PARK + NWAVES * PARK_BYTES;
 static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 static_assert(KSUB == 4, "the stage code below is written for four sub-steps");
@@ -197,11 +200,9 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                 const uint32_t o = (uint32_t)wave_u * 256u;
                 dma4(make_rsrc(a.scale + t0, rows * 4), pb + PRM_SCALE + o, l4 + o);
                 dma4(make_rsrc(a.zero + t0, rows * 4), pb + PRM_ZERO + o, l4 + o);
-                dma4(make_rsrc(a.code_sum + t0, rows * 4), pb + PRM_CSUM + o, l4 + o);
             } else if (wave_u < 7) {                       // 64 channels each
                 const uint32_t o = (uint32_t)(wave_u - 4) * 256u;
                 dma4(make_rsrc(a.w_reduced + n0, cols * 4), pb + PRM_WRED + o, l4 + o);
-                dma4(make_rsrc(a.w_code_sum + n0, cols * 4), pb + PRM_WCSUM + o, l4 + o);
             } else {                                       // fp16 arrays: 128 channels per instruction
                 const __half* ws = static_cast<const __half*>(a.w_scale) + n0;
                 const __half* bs = a.bias ? static_cast<const __half*>(a.bias) + n0 : ws;
@@ -211,6 +212,21 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                     dma4(make_rsrc(ws, cols * 2), pb + PRM_WSCALE + h * 256, l4 + h * 256);
                     dma4(make_rsrc(bs, bb), pb + PRM_BIAS + h * 256, l4 + h * 256);
                 }
+            }
+        }
+    };
+
+    // the code sums of a tile (the one that starts next), global -> LDS; `on` false: no such tile, zeros arrive
+    auto issue_sums = [&](int t0, int n0, int ncols, bool on) QUIK_INLINE {
+        if constexpr (ASYM) {
+            const uint32_t sb = lds_base + OFF_SUMS;
+            const uint32_t l4 = (uint32_t)opaque_lane() * 4u;
+            if (wave_u < 4) {                              // 64 token rows each
+                const uint32_t o = (uint32_t)wave_u * 256u;
+                dma4(make_rsrc(a.code_sum + t0, on ? (size_t)(a.T - t0) * 4 : 0), sb + SUMS_CS + o, l4 + o);
+            } else if (wave_u < 7) {                       // 64 channels each
+                const uint32_t o = (uint32_t)(wave_u - 4) * 256u;
+                dma4(make_rsrc(a.w_code_sum + n0, on ? (size_t)ncols * 4 : 0), sb + SUMS_WCS + o, l4 + o);
             }
         }
     };
@@ -293,6 +309,7 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
 
     // ---- first tile: its first two stages.  `rf` describes the stage copied last and is carried from
     // stage to stage (see prep_refill).
+    issue_sums(cur_t0, cur_n0, cur_nc, true);            // (first: the wait for stage 0 below then covers it)
     Copy rf;
     prep_copy(rf, cur_t0, cur_n0, cur_nc, false, 0, true);
 #pragma unroll
@@ -339,13 +356,36 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
             constexpr int CS = NMF / 8;                               // a copy instruction every CS-th MFMA slot
             static_assert(NMF >= NFA * 2 && 8 >= LPS, "copy, read and widening work is spread over the MFMA slots");
 
+            // The accumulators start at -128 * (code_sum[t] + w_code_sum[n]): the single-AND widening leaves
+            // 16 x the integer dot product plus 128 times these sums, so that the K loop ends on 16 x the dot
+            // product itself (two's complement, nothing overflows on the way).  The sums were copied to LDS
+            // two stages before the previous tile's K loop ended (before the first stage for the first tile).
             v4i acc[IB][JB];
-#pragma unroll
-            for (int i = 0; i < IB; ++i)
+            if constexpr (ASYM) {
+                const int lane_i = opaque_lane();
+                const int l16i = lane_i & 15, gi = lane_i >> 4;
+                const uint8_t* sums = smem + OFF_SUMS;
+                int nw[JB];
 #pragma unroll
                 for (int j = 0; j < JB; ++j)
+                    nw[j] = -128 * *reinterpret_cast<const int*>(sums + SUMS_WCS + (cb0 * 32 + j * 16 + l16i) * 4);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
+                for (int i = 0; i < IB; ++i) {
+                    const int4 cs = *reinterpret_cast<const int4*>(sums + SUMS_CS + (wm * TM * 32 + i * 16 + 4 * gi) * 4);
+                    const int nc[4] = {-128 * cs.x, -128 * cs.y, -128 * cs.z, -128 * cs.w};
+#pragma unroll
+                    for (int j = 0; j < JB; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[i][j][r] = nc[r] + nw[j];
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < IB; ++i)
+#pragma unroll
+                    for (int j = 0; j < JB; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
+            }
 
             // One integer stage (stage s of the tile, in ring slot `slot`).  The refill of the slot it frees
             // is spread over the MFMA slots after the barrier.  A sub-step (32 packed bytes of every row) is
@@ -364,7 +404,10 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                         wait_vm<0>();
                         __syncthreads();          // stage s + 1 has landed for everybody; nobody reads this stage's slot any more
                         prep_refill(rf, s);
-                        if (s == nk_int - 2) issue_params(cur_t0, cur_n0, cur_nc);
+                        if (s == nk_int - 2) {
+                            issue_params(cur_t0, cur_n0, cur_nc);
+                            issue_sums(nxt_t0, nxt_n0, nxt_nc, more);
+                        }
                     }
                     // sub-step tks was last read in the other slot
                     rdA[tks] ^= SLOT_STRIDE;
@@ -410,18 +453,14 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                         for (int r = 0; r < 4; ++r) {
                             const int t = tw + i * 16 + 4 * ge + r;
                             if (t < a.T && n < n_end) {
-                                int v = acc[i][j][r] >> SHIFT;
-                                if constexpr (ASYM) v -= 8 * (a.code_sum[t] + a.w_code_sum[n]);
-                                a.acc[(size_t)t * a.ldacc + n] = v;
+                                a.acc[(size_t)t * a.ldacc + n] = acc[i][j][r] >> SHIFT;   // exact: a multiple of 2^SHIFT
                             }
                         }
                     }
             } else {
-                // Dequantization: the raw accumulator is 16 x the integer dot product plus
-                // 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes the latter, the
-                // conversion to binary32 is exact, and 2^-4 rides on the weight scale.
+                // Dequantization: the accumulator is 16 x the integer dot product, its conversion to binary32
+                // is exact, and 2^-4 rides on the weight scale.
                 float c_sw[JB], c_wr[JB], c_bv[JB];
-                int c_nc[JB];
 #pragma unroll
                 for (int j = 0; j < JB; ++j) {
                     const int col = cb0 * 32 + j * 16 + l16e;         // inside the tile
@@ -429,7 +468,6 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                               (1.0f / (float)(1 << SHIFT));           // exact power-of-two factor
                     c_bv[j] = a.bias ? __half2float(*reinterpret_cast<const __half*>(prm + PRM_BIAS + col * 2)) : 0.0f;
                     c_wr[j] = *reinterpret_cast<const float*>(prm + PRM_WRED + col * 4);
-                    c_nc[j] = -128 * *reinterpret_cast<const int*>(prm + PRM_WCSUM + col * 4);
                 }
                 // Per-token parameters of the four rows a lane holds of a 16-row block, read one block ahead of
                 // their use; tied to the results of the block before, or the scheduler would hoist all reads
@@ -437,14 +475,12 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                 uint32_t dq_dep = 0;
                 v4f cf[IB][JB];
                 float4 sa4[2], z4[2];
-                int4 cs4[2];
                 auto load_group = [&](int i) QUIK_INLINE {
                     const int lr = wm * TM * 32 + i * 16 + 4 * ge;
                     uint32_t o = (uint32_t)lr * 4u;
                     tie(o, dq_dep);
                     sa4[i & 1] = *reinterpret_cast<const float4*>(prm + PRM_SCALE + o);
                     z4[i & 1] = *reinterpret_cast<const float4*>(prm + PRM_ZERO + o);
-                    cs4[i & 1] = *reinterpret_cast<const int4*>(prm + PRM_CSUM + o);
                 };
                 load_group(0);
 #pragma unroll
@@ -454,13 +490,11 @@ __global__ __launch_bounds__(NT, 1) void gemm_stream_kernel(GemmArgs a, StreamPl
                     const float sa_[4] = {sa4[b].x, sa4[b].y, sa4[b].z, sa4[b].w};
                     const float sh_[4] = {z4[b].x + 8.0f * sa4[b].x, z4[b].y + 8.0f * sa4[b].y, z4[b].z + 8.0f * sa4[b].z,
                                           z4[b].w + 8.0f * sa4[b].w};    // zeroAct + halfRange * scaleAct
-                    const int ct_[4] = {-128 * cs4[b].x, -128 * cs4[b].y, -128 * cs4[b].z, -128 * cs4[b].w};
 #pragma unroll
                     for (int j = 0; j < JB; ++j)
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr) {
-                            const int ai = acc[i][j][rr] + ct_[rr] + c_nc[j];
-                            cf[i][j][rr] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j],
+                            cf[i][j][rr] = __builtin_fmaf((float)acc[i][j][rr], sa_[rr] * c_sw[j],
                                                           __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
                         }
                     dq_dep = __float_as_uint(cf[i][JB - 1][3]);
