@@ -71,11 +71,12 @@ template <int BITS, int WBITS, int BM, int BN, int WM, int WN, int BKB, int NST,
 __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
     constexpr bool RAW = MODE != 0;
     constexpr bool ASYM = (BITS == 4) && (MODE != 1);
-    // The accumulator-only forms are small enough for their register allocation to end anywhere; they
-    // claim the full 256 of their launch bounds so that the top of the allocation is never a live
-    // register (the row-quantization kernel misread such a register on MI355X when its allocation left
-    // part of the SIMD's file free).
-    if constexpr (RAW) asm volatile("" ::: "v255");
+    // Every form runs two waves per SIMD (WM * WN * OCC = 8 waves per CU, and the stage buffers leave no room
+    // for more workgroups), so each claims the full 256 registers of its share: the top of the allocation is
+    // then never a live register (the row-quantization kernel misread such a register on MI355X when its
+    // allocation left part of the SIMD's file free).
+    static_assert(WM * WN * OCC == 8, "two waves per SIMD");
+    asm volatile("" ::: "v255");
     // Mixed layers: a stage still covers BKB activation bytes = BKB k, which is only BKB/2 packed
     // weight bytes.  The weight nibbles are widened to 16x int8 (even / odd k of a word in two
     // registers); the int8 activations are brought into the same k order with two byte permutes
@@ -353,13 +354,31 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
         }
     };
 
+    // With the single-AND widening and the fused epilogue the accumulators start at
+    // -128 * (code_sum[t] + w_code_sum[n]) instead of zero, so that the K loop ends on 16 x the integer dot
+    // product (the widening leaves it plus 128 times these sums; two's complement, nothing overflows on the way).
     v16i acc[TM][TN];
+    if constexpr (ASYM && !RAW) {
+        __syncthreads();                                  // lds_ct is complete (the first stages are in flight)
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int rq = 0; rq < 4; ++rq) {
+                const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[wm * TM * 32 + i * 32 + 8 * rq + 4 * g]);
+                const int ct_[4] = {ct4.x, ct4.y, ct4.z, ct4.w};
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) acc[i][j][rq * 4 + rr] = ct_[rr] + c_nc[j];
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    }
 
     // stage barrier of iteration s: stage s+1 has landed for everybody, and nobody reads stage s any more
     auto stage_barrier = [&]() {
@@ -440,10 +459,8 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             }
         return;
     }
-    // Dequantization.  The raw accumulator is 2^SHIFT times the integer dot product plus, for the
-    // single-AND widening, 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes that,
-    // the conversion to binary32 is exact (at most 24 significant bits), and 2^-SHIFT rides on the
-    // weight scale.
+    // Dequantization.  The accumulator is 2^SHIFT times the integer dot product, its conversion to binary32
+    // is exact (at most 24 significant bits), and 2^-SHIFT rides on the weight scale.
     v16f cf[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -453,19 +470,12 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_kernel(GemmArgs a) {
             const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
             const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
             const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
-            int ct_[4] = {0, 0, 0, 0};
-            if constexpr (ASYM) {
-                const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[lr]);
-                ct_[0] = ct4.x; ct_[1] = ct4.y; ct_[2] = ct4.z; ct_[3] = ct4.w;
-            }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
                     const int r = rq * 4 + rr;
-                    int ai = acc[i][j][r];
-                    if constexpr (ASYM) ai = ai + ct_[rr] + c_nc[j];
-                    cf[i][j][r] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j],
+                    cf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], sa_[rr] * c_sw[j],
                                                  __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
                 }
         }

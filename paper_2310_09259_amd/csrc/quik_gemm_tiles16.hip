@@ -200,13 +200,29 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
         }
     }
 
+    // With the single-AND widening and the fused epilogue the accumulators start at
+    // -128 * (code_sum[t] + w_code_sum[n]) instead of zero, so that the K loop ends on 16 x the integer dot
+    // product (the widening leaves it plus 128 times these sums; two's complement, nothing overflows on the way).
     v4i acc[IB][JB];
+    if constexpr (ASYM && !RAW) {
+        __syncthreads();                                  // lds_ct is complete (the first stages are in flight)
 #pragma unroll
-    for (int i = 0; i < IB; ++i)
+        for (int i = 0; i < IB; ++i) {
+            const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[wm * IB * 16 + i * 16 + 4 * g]);
+            const int ct_[4] = {ct4.x, ct4.y, ct4.z, ct4.w};
 #pragma unroll
-        for (int j = 0; j < JB; ++j)
+            for (int j = 0; j < JB; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = ct_[r] + c_nc[j];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < IB; ++i)
+#pragma unroll
+            for (int j = 0; j < JB; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
+    }
 
     // stage barrier of iteration s: stage s+1 has landed for everybody, and nobody reads stage s any more
     auto stage_barrier = [&]() {
@@ -366,9 +382,8 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
             }
         return;
     }
-    // Dequantization.  The raw accumulator is 2^SHIFT times the integer dot product plus, for the
-    // single-AND widening, 128 * (code_sum[t] + w_code_sum[n]); one three-operand add removes that, the
-    // conversion to binary32 is exact (at most 24 significant bits), and 2^-SHIFT rides on the weight scale.
+    // Dequantization.  The accumulator is 2^SHIFT times the integer dot product, its conversion to binary32 is
+    // exact (at most 24 significant bits), and 2^-SHIFT rides on the weight scale.
     v4f cf[IB][JB];
 #pragma unroll
     for (int i = 0; i < IB; ++i) {
@@ -376,18 +391,11 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void gemm_tiles16_kernel(GemmArg
         const float4 sa4 = *reinterpret_cast<const float4*>(&lds_sa[lr]);
         const float4 sh4 = *reinterpret_cast<const float4*>(&lds_sh[lr]);
         const float sa_[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, sh_[4] = {sh4.x, sh4.y, sh4.z, sh4.w};
-        int ct_[4] = {0, 0, 0, 0};
-        if constexpr (ASYM) {
-            const int4 ct4 = *reinterpret_cast<const int4*>(&lds_ct[lr]);
-            ct_[0] = ct4.x; ct_[1] = ct4.y; ct_[2] = ct4.z; ct_[3] = ct4.w;
-        }
 #pragma unroll
         for (int j = 0; j < JB; ++j)
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                int ai = acc[i][j][rr];
-                if constexpr (ASYM) ai = ai + ct_[rr] + c_nc[j];
-                cf[i][j][rr] = __builtin_fmaf((float)ai, sa_[rr] * c_sw[j], __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
+                cf[i][j][rr] = __builtin_fmaf((float)acc[i][j][rr], sa_[rr] * c_sw[j], __builtin_fmaf(sh_[rr], c_wr[j], c_bv[j]));
             }
     }
 
