@@ -67,7 +67,7 @@ constexpr int KSUB = BKB / 32;
 constexpr int A_BYTES = BM * BKB, B_BYTES = BNX * BKB;
 // LDS map.  The two ring slots of an operand are SLOT_STRIDE apart (a power of two, so that a fragment
 // address switches slots with one XOR); the gaps hold the epilogue parameters:
-//   0       weights, slot 0 (24 KB)      24576  parameters (7 KB)
+//   0       weights, slot 0 (24 KB)      24576  parameters (5 KB)
 //   32768   weights, slot 1              57344  code sums of the tile that starts next (2 KB)
 //   65536   activations, slot 0 (32 KB)  98304  activations, slot 1
 //   131072  per-wave output buffers
@@ -76,12 +76,11 @@ constexpr int OFF_B = 0, OFF_A = 65536;
 static_assert(B_BYTES <= SLOT_STRIDE && A_BYTES <= SLOT_STRIDE, "ring slots overlap");
 constexpr int PARK_ROWS = 16, PARK_ROW_BYTES = TNX * 64 + 16, PARK_BYTES = PARK_ROWS * PARK_ROW_BYTES;
 constexpr int OFF_PARK = OFF_A + 2 * SLOT_STRIDE;
-// parameter area: three per-token arrays of BM words, then four per-channel arrays of 256 words
+// parameter area: two per-token arrays of BM words, then three per-channel arrays of 256 words
 // (weight scale and bias are fp16: 96 words used)
 constexpr int OFF_PRM = B_BYTES;
-constexpr int PRM_SCALE = 0, PRM_ZERO = BM * 4, PRM_CSUM = 2 * BM * 4;
-constexpr int PRM_WSCALE = 3 * BM * 4, PRM_WRED = PRM_WSCALE + 1024, PRM_WCSUM = PRM_WRED + 1024,
-              PRM_BIAS = PRM_WCSUM + 1024;
+constexpr int PRM_SCALE = 0, PRM_ZERO = BM * 4;
+constexpr int PRM_WSCALE = 2 * BM * 4, PRM_WRED = PRM_WSCALE + 1024, PRM_BIAS = PRM_WRED + 1024;
 static_assert(OFF_PRM + PRM_BIAS + 1024 <= SLOT_STRIDE, "parameters do not fit the gap");
 // code sums of the next tile's BM token rows and (up to) 256 channels: they are the accumulators' initial value
 constexpr int OFF_SUMS = SLOT_STRIDE + B_BYTES, SUMS_CS = 0, SUMS_WCS = BM * 4;
