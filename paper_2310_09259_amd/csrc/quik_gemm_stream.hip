@@ -29,9 +29,13 @@
 //  * One stage body serves every integer stage of a tile, whatever ring slot it sits in: the two slots
 //    of an operand lie 32 KB apart, and the fragment address registers are flipped between them
 //    (one XOR each per stage) right before the reads that need the other slot.
-//  * The epilogue parameters (per token: scale, zero, code sum; per channel: weight scale, wReduced,
-//    code sum, bias) are copied global -> LDS by the same DMA path as the operands, two stages
-//    before they are needed, so they never occupy registers during the K loop.
+//  * The epilogue parameters (per token: scale, zero; per channel: weight scale, wReduced, bias) are
+//    copied global -> LDS by the same DMA path as the operands, two stages before they are needed, so
+//    they never occupy registers during the K loop.  With them come the code sums (per token, per
+//    channel) of the tile that starts next: its accumulators start at -128 times their sum, which is
+//    what the single-AND widening adds to 16 x the dot product, so the K loop ends on the latter.
+//  * Which tile comes next is computed without run-time divisions: the plan carries the divisors of
+//    that walk as multipliers prepared on the host (stream_tile in quik_kernels.h).
 //  * The output tile leaves through a small per-wave LDS buffer, sixteen rows at a time, so the
 //    stage ring is never needed for it.
 #include <hip/hip_runtime.h>
