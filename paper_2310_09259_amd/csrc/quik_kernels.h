@@ -126,7 +126,9 @@ inline bool stream_tile_reference(const StreamPlan& p, int block, int k, int* nt
 inline bool finish_stream_plan(StreamPlan* p) {
     const int per_xcd = p->grid / kStreamXcds;
     const long total = (long)p->tiles_m * p->tn;
-    if (per_xcd < 1 || total >= kStreamMagicRange / 2 || (long)p->tn * p->tn >= kStreamMagicRange) return false;
+    if (per_xcd < 1 || per_xcd >= kStreamMagicRange || total >= kStreamMagicRange / 2 ||
+        (long)p->tn * p->tn >= kStreamMagicRange)
+        return false;
     p->per_xcd = per_xcd;
     p->tq = (int)(total / kStreamXcds);
     p->tr = (int)(total % kStreamXcds);
